@@ -1,0 +1,372 @@
+"""Pins for the fp64 oracle (CPU only).
+
+Each pin checks oracle/spkv_oracle.py against something other than itself:
+hand-derived fixtures, pure-Python brute force, a library attention routine,
+limiting cases and closed forms.  The last test plants mistakes into copies of
+the oracle and requires that the pins catch every one of them.
+"""
+
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle.spkv_oracle import SPKVOracle, threshold_logit
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "rational_weight_cases.json")
+
+
+# --------------------------------------------------------------------- helpers
+def _random_problem(rng, B, Hq, Hkv, D, lens, mu=0.0):
+    total = sum(lens)
+    k = rng.standard_normal((total, Hkv, D))
+    v = rng.standard_normal((total, Hkv, D))
+    f = (rng.standard_normal((total, Hkv)) + mu).astype(np.float32)
+    q = rng.standard_normal((B, Hq, D))
+    cu = np.concatenate([[0], np.cumsum(lens)]).tolist()
+    return q, k, v, f, cu
+
+
+def _build(cls, B, Hq, Hkv, D, w, tau, k, v, f, cu, sm_scale=None):
+    o = cls(B, Hq, Hkv, D, window=w, tau=tau, sm_scale=sm_scale, store_dtype=np.float64)
+    o.append(k, v, f, cu)
+    return o
+
+
+# ------------------------------------------------- pin 1: hand-derived fixtures
+def pin_golden(cls):
+    for case in json.load(open(GOLDEN)):
+        D, T = case["D"], len(case["weights"])
+        scale = case["sm_scale"] if case["sm_scale"] is not None else 1.0 / math.sqrt(D)
+        k = np.zeros((T, 1, D))
+        v = np.zeros((T, 1, D))
+        k[:, 0, 0] = [math.log(wt) / scale for wt in case["weights"]]
+        v[:, 0, 0] = case["values"]
+        f = np.array(case["logits"], np.float32).reshape(T, 1)
+        q = np.zeros((1, 1, D))
+        q[0, 0, 0] = 1.0
+        o = _build(cls, 1, 1, 1, D, case["window"], case["tau"], k, v, f, [0, T],
+                   sm_scale=case["sm_scale"])
+        out, lse = o.decode(q)
+        want = Fraction(*case["out"])
+        assert abs(out[0, 0, 0] - float(want)) < 1e-12, case["name"]
+        assert np.all(out[0, 0, 1:] == 0.0), case["name"]
+        assert abs(lse[0, 0] - math.log(case["lse_exp"])) < 1e-12, case["name"]
+        assert o.kept_positions(0, 0).tolist() == case["kept"], case["name"]
+        assert o.kept_len().tolist() == [[len(case["kept"])]], case["name"]
+
+
+# --------------------------------------------------- pin 2: brute force (loops)
+def _brute_force(q, k, v, f, cu, Hq, Hkv, D, w, theta, scale):
+    """Hand-written loops over the definition: enumerate the available set of
+    the newest query of every sequence and sum exp-weighted values."""
+    B = len(cu) - 1
+    G = Hq // Hkv
+    out = [[[0.0] * D for _ in range(Hq)] for _ in range(B)]
+    lse = [[0.0] * Hq for _ in range(B)]
+    kept = {}
+    for b in range(B):
+        rows = list(range(cu[b], cu[b + 1]))
+        T = len(rows)
+        t = T - 1
+        for h in range(Hkv):
+            avail = []
+            kept[(b, h)] = []
+            for s in range(T):
+                gate_on = float(f[rows[s]][h]) >= float(theta)
+                in_win = 0 <= t - s < w
+                if gate_on or in_win:
+                    avail.append(s)
+                if gate_on and not in_win:
+                    kept[(b, h)].append(s)
+            for g in range(G):
+                j = h * G + g
+                scores = [scale * math.fsum(q[b][j][d] * k[rows[s]][h][d] for d in range(D))
+                          for s in avail]
+                mx = max(scores)
+                ws = [math.exp(x - mx) for x in scores]
+                z = math.fsum(ws)
+                for d in range(D):
+                    out[b][j][d] = math.fsum(wt * v[rows[s]][h][d]
+                                             for wt, s in zip(ws, avail)) / z
+                lse[b][j] = mx + math.log(z)
+    return np.array(out), np.array(lse), kept
+
+
+def pin_brute_force(cls):
+    rng = np.random.default_rng(7)
+    cases = [  # B, Hq, Hkv, D, w, tau, lens
+        (1, 1, 1, 4, 1, 0.5, [9]),
+        (2, 4, 2, 4, 2, 0.5, [16, 5]),
+        (3, 4, 1, 4, 4, 0.3, [3, 4, 13]),
+        (2, 6, 3, 4, 4, 0.7, [5, 16]),
+        (1, 2, 2, 4, 16, 0.5, [16]),
+    ]
+    for (B, Hq, Hkv, D, w, tau, lens) in cases:
+        q, k, v, f, cu = _random_problem(rng, B, Hq, Hkv, D, lens)
+        o = _build(cls, B, Hq, Hkv, D, w, tau, k, v, f, cu)
+        out, lse = o.decode(q)
+        theta = math.log(float(np.float32(tau)) / (1.0 - float(np.float32(tau))))
+        bo, bl, bkept = _brute_force(q.tolist(), k.tolist(), v.tolist(), f.tolist(), cu,
+                                     Hq, Hkv, D, w, np.float32(theta), 1.0 / math.sqrt(D))
+        np.testing.assert_allclose(out, bo, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(lse, bl, rtol=1e-12, atol=1e-13)
+        for b in range(B):
+            for h in range(Hkv):
+                assert o.kept_positions(b, h).tolist() == bkept[(b, h)]
+
+
+# ------------------------- pin 3: library routine under the paper's mask (SDPA)
+def _sdpa_last_row(q_last, k, v, gate, w, scale, Hq, Hkv, mode):
+    """Full T x T masked attention with torch's fp64 SDPA for one sequence;
+    returns the last query row.  mode: 'gated' (window OR gate, causal),
+    'causal' (is_causal=True, no mask tensor), 'window' (banded causal)."""
+    T, D = k.shape[0], k.shape[2]
+    G = Hq // Hkv
+    kt = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]  # [1,Hq,T,D]
+    vt = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    gen = torch.Generator().manual_seed(1)
+    qt = torch.randn(1, Hq, T, D, dtype=torch.float64, generator=gen)
+    qt[0, :, T - 1, :] = torch.from_numpy(q_last)
+    if mode == "causal":
+        o = F.scaled_dot_product_attention(qt, kt, vt, is_causal=True, scale=scale)
+    else:
+        qi = torch.arange(T)[:, None]
+        ki = torch.arange(T)[None, :]
+        causal = ki <= qi
+        in_window = causal & ((qi - ki) < w)
+        if mode == "window":
+            mask = in_window[None, None].expand(1, Hq, T, T)
+        else:
+            gt = torch.from_numpy(gate).T.repeat_interleave(G, dim=0)   # [Hq, T] bool
+            mask = (in_window[None] | (causal[None] & gt[:, None, :]))[None]
+        o = F.scaled_dot_product_attention(qt, kt, vt, attn_mask=mask, scale=scale)
+    return o[0, :, T - 1, :].numpy()
+
+
+def pin_sdpa(cls):
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, D, w, tau = 2, 8, 2, 16, 8, 0.5
+    lens = [50, 23]
+    q, k, v, f, cu = _random_problem(rng, B, Hq, Hkv, D, lens, mu=-0.5)
+    o = _build(cls, B, Hq, Hkv, D, w, tau, k, v, f, cu)
+    out, _ = o.decode(q)
+    for b in range(B):
+        sl = slice(cu[b], cu[b + 1])
+        sig = 1.0 / (1.0 + np.exp(-f[sl].astype(np.float64)))
+        ref = _sdpa_last_row(q[b], k[sl], v[sl], sig >= tau, w, 1.0 / math.sqrt(D),
+                             Hq, Hkv, "gated")
+        np.testing.assert_allclose(out[b], ref, rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------- pin 4: limiting thresholds (tau)
+def pin_tau_limits(cls):
+    rng = np.random.default_rng(13)
+    B, Hq, Hkv, D, w = 2, 4, 2, 8, 4
+    lens = [30, 3]
+    q, k, v, f, cu = _random_problem(rng, B, Hq, Hkv, D, lens)
+    for tau, mode in ((-math.inf, "causal"), (0.0, "causal"), (math.inf, "window"),
+                      (1.0, "window")):
+        o = _build(cls, B, Hq, Hkv, D, w, tau, k, v, f, cu)
+        out, _ = o.decode(q)
+        for b in range(B):
+            sl = slice(cu[b], cu[b + 1])
+            ref = _sdpa_last_row(q[b], k[sl], v[sl], None, w, 1.0 / math.sqrt(D),
+                                 Hq, Hkv, mode)
+            np.testing.assert_allclose(out[b], ref, rtol=1e-10, atol=1e-12)
+        kl = o.kept_len()
+        for b in range(B):
+            want = max(0, lens[b] - w) if mode == "causal" else 0
+            assert kl[b].tolist() == [want] * Hkv
+            if mode == "causal":
+                assert o.kept_positions(b, 0).tolist() == list(range(want))
+
+
+# --------------------------------------------------------- pin 5: closed forms
+def pin_closed_forms(cls):
+    rng = np.random.default_rng(17)
+    # (a) all keys identical, V = identity: out reads off the available set.
+    T, w = 12, 3
+    f = np.array([1, -1, 1, -1, -1, 1, -1, -1, 1, -1, -1, -1], np.float32).reshape(T, 1)
+    k = np.ones((T, 1, T)) * 0.25
+    v = np.eye(T).reshape(T, 1, T)
+    q = rng.standard_normal((1, 2, T))
+    o = _build(cls, 1, 2, 1, T, w, 0.5, k, v, f, [0, T])
+    out, lse = o.decode(q)
+    avail = [0, 2, 5, 8, 9, 10, 11]         # gated {0,2,5,8} plus window {9,10,11}
+    want = np.zeros(T)
+    want[avail] = 1.0 / len(avail)
+    for j in range(2):
+        np.testing.assert_allclose(out[0, j], want, rtol=0, atol=1e-15)
+        score = (1.0 / math.sqrt(T)) * 0.25 * q[0, j].sum()
+        assert abs(lse[0, j] - (score + math.log(len(avail)))) < 1e-12
+    assert o.kept_positions(0, 0).tolist() == [0, 2, 5, 8]
+    # (b) constant V rows -> that constant, whatever the weights.
+    q, k, v, f, cu = _random_problem(rng, 1, 2, 2, 8, [40])
+    v[:] = np.linspace(-1, 1, 8)[None, None, :]
+    out, _ = _build(cls, 1, 2, 2, 8, 4, 0.5, k, v, f, cu).decode(q)
+    np.testing.assert_allclose(out[0, 0], np.linspace(-1, 1, 8), atol=1e-14)
+    # (c) one available key with an overwhelming score -> its V row; the same
+    #     key gated off and outside the window -> no influence at all.
+    q, k, v, f, cu = _random_problem(rng, 1, 1, 1, 8, [20])
+    k[5, 0] = 200.0 * q[0, 0] / np.linalg.norm(q[0, 0])
+    f[5, 0] = 3.0
+    out, _ = _build(cls, 1, 1, 1, 8, 4, 0.5, k, v, f, cu).decode(q)
+    np.testing.assert_allclose(out[0, 0], v[5, 0], atol=1e-9)
+    f[5, 0] = -3.0
+    out_off, _ = _build(cls, 1, 1, 1, 8, 4, 0.5, k, v, f, cu).decode(q)
+    k[5, 0] = 0.0
+    out_zero, _ = _build(cls, 1, 1, 1, 8, 4, 0.5, k, v, f, cu).decode(q)
+    np.testing.assert_array_equal(out_off, out_zero)
+
+
+# ------------------------------------- pin 6: counting, via the sigmoid domain
+def pin_count_invariant(cls):
+    rng = np.random.default_rng(19)
+    B, Hkv, D, w = 3, 4, 4, 16
+    lens = [300, 16, 17]
+    for tau in (0.2, 0.5, 0.8):
+        q, k, v, f, cu = _random_problem(rng, B, Hkv, Hkv, D, lens)
+        o = _build(cls, B, Hkv, Hkv, D, w, tau, k, v, f, cu)
+        u = 1.0 / (1.0 + np.exp(-f.astype(np.float64)))          # Eq. 1
+        assert np.all(np.abs(u - tau) > 1e-6)                    # no borderline draws
+        kl = o.kept_len()
+        gate_on = 0
+        for b in range(B):
+            ub = u[cu[b]:cu[b + 1]]
+            n_out = max(0, lens[b] - w)
+            for h in range(Hkv):
+                z = ub[:, h] >= tau                                  # Eq. 2
+                assert kl[b, h] == int(z[:n_out].sum())
+                assert o.kept_positions(b, h).tolist() == np.nonzero(z[:n_out])[0].tolist()
+                gate_on += int(z.sum())
+        st = o.stats()
+        assert st["kept_tokens"] == int(kl.sum())
+        assert st["gate_on_tokens"] == gate_on
+        assert st["evicted_tokens"] == sum(max(0, n - w) for n in lens) * Hkv
+        assert st["window_tokens"] == sum(min(n, w) for n in lens) * Hkv
+        assert abs(st["density_all"] - gate_on / (sum(lens) * Hkv)) < 1e-15     # Eq. 8
+        assert st["kept_kv_bytes"] == (st["kept_tokens"] + st["window_tokens"]) * 4 * D
+        assert st["dense_kv_bytes"] == sum(lens) * Hkv * 4 * D
+
+
+# ------------------------- pin 7: state machine (incremental == bulk, monotone)
+def pin_incremental(cls):
+    rng = np.random.default_rng(23)
+    B, Hq, Hkv, D, w = 2, 4, 2, 4, 4
+    lens = [11, 7]
+    q, k, v, f, cu = _random_problem(rng, B, Hq, Hkv, D, lens)
+    bulk = _build(cls, B, Hq, Hkv, D, w, 0.5, k, v, f, cu)
+    inc = cls(B, Hq, Hkv, D, window=w, tau=0.5, store_dtype=np.float64)
+    for step in range(max(lens)):
+        rows = [cu[b] + step for b in range(B) if step < lens[b]]
+        c = [0] + list(np.cumsum([1 if step < lens[b] else 0 for b in range(B)]))
+        inc.append(k[rows], v[rows], f[rows], c)
+    o1, l1 = bulk.decode(q)
+    o2, l2 = inc.decode(q)
+    np.testing.assert_array_equal(o1, o2)
+    np.testing.assert_array_equal(l1, l2)
+    assert bulk.kept_len().tolist() == inc.kept_len().tolist()
+    # raising tau keeps a subset
+    lo = _build(cls, B, Hq, Hkv, D, w, 0.3, k, v, f, cu)
+    hi = _build(cls, B, Hq, Hkv, D, w, 0.7, k, v, f, cu)
+    for b in range(B):
+        for h in range(Hkv):
+            assert set(hi.kept_positions(b, h)) <= set(lo.kept_positions(b, h))
+
+
+def pin_threshold(cls=None):
+    assert threshold_logit(0.5) == np.float32(0.0)
+    assert threshold_logit(0.0) == -np.inf and threshold_logit(-1.0) == -np.inf
+    assert threshold_logit(1.0) == np.inf and threshold_logit(math.inf) == np.inf
+    for tau in (0.01, 0.1, 0.3, 0.7, 0.9, 0.99):
+        th = float(threshold_logit(tau))
+        assert abs(1.0 / (1.0 + math.exp(-th)) - tau) < 1e-6      # sigmoid(theta) = tau
+        assert threshold_logit(tau).dtype == np.float32
+
+
+PINS = [pin_golden, pin_brute_force, pin_sdpa, pin_tau_limits, pin_closed_forms,
+        pin_count_invariant, pin_incremental]
+
+
+@pytest.mark.parametrize("pin", PINS + [pin_threshold], ids=lambda p: p.__name__)
+def test_pin(pin):
+    pin(SPKVOracle)
+
+
+# ----------------------------------------------------------- planted mistakes
+class _WindowOffByOne(SPKVOracle):           # window of w+1 keys
+    def available(self, b, h):
+        T = self.seq_len(b)
+        return ((T - 1 - np.arange(T)) <= self.w) | self.gate(b, h)
+
+
+class _StrictGate(SPKVOracle):               # u > tau instead of u >= tau
+    def gate(self, b, h):
+        return self._f(b)[:, h] > self.theta
+
+
+class _NoScale(SPKVOracle):                  # forgets 1/sqrt(d)
+    def __init__(self, *a, **kw):
+        super().__init__(*a, **kw)
+        if kw.get("sm_scale") is None:
+            self.scale = 1.0
+
+
+class _KeptOffByOne(SPKVOracle):             # long-term list one position early
+    def kept_positions(self, b, h):
+        n = max(0, self.seq_len(b) - self.w + 1)
+        return np.nonzero(self.gate(b, h)[:n])[0].astype(np.int32)
+
+
+class _GateIgnored(SPKVOracle):              # window only
+    def available(self, b, h):
+        T = self.seq_len(b)
+        return (T - 1 - np.arange(T)) < self.w
+
+
+class _WrongGroup(SPKVOracle):               # query head j reads KV head j % H_kv
+    def decode(self, q, workers=1):
+        q = np.asarray(q, np.float64)
+        perm = [g * self.Hkv + h for h in range(self.Hkv) for g in range(self.G)]
+        out, lse = super().decode(q[:, perm, :])
+        inv = np.argsort(perm)
+        return out[:, inv, :], lse[:, inv]
+
+
+class _TransposedPV(SPKVOracle):             # weights applied with K instead of V
+    def _decode_pair(self, b, h, q_bh):
+        out, lse = super()._decode_pair(b, h, q_bh)
+        K = self._k(b)[:, h, :].astype(np.float64)
+        V = self._v(b)[:, h, :].astype(np.float64)
+        avail = self.available(b, h)
+        x = self.scale * (K @ q_bh.T)
+        x[~avail] = -np.inf
+        e = np.exp(x - x.max(axis=0))
+        return (e.T @ K) / e.sum(axis=0)[:, None], lse
+
+
+class _ThresholdSignFlipped(SPKVOracle):         # theta with the wrong sign
+    def __init__(self, *a, **kw):
+        super().__init__(*a, **kw)
+        self.theta = np.float32(-self.theta)
+
+
+MUTANTS = [_WindowOffByOne, _StrictGate, _NoScale, _KeptOffByOne, _GateIgnored,
+           _WrongGroup, _TransposedPV, _ThresholdSignFlipped]
+
+
+@pytest.mark.parametrize("mutant", MUTANTS, ids=lambda m: m.__name__)
+def test_planted_mistake_is_caught(mutant):
+    caught = []
+    for pin in PINS:
+        try:
+            pin(mutant)
+        except AssertionError:
+            caught.append(pin.__name__)
+    assert caught, f"no pin catches {mutant.__name__}"
