@@ -1,0 +1,173 @@
+/*
+ * spkv.h -- C ABI of the Self-Pruned KV (SP-KV) decode path for AMD MI355X (gfx950).
+ *
+ * The library keeps, for one attention layer, the two-part KV cache of SP-KV
+ * (paper Sec. 2.1 and appendix "Inference Kernels"):
+ *
+ *   - a local window: the w most recent key/value pairs of every sequence, always
+ *     attended (window indicator 1[0 <= t - s < w]; w = 128 by default), held in a
+ *     ring buffer with the pair's utility logit beside it;
+ *   - a long-term cache per (sequence, KV head): the pairs that have left the window
+ *     and whose utility passed the threshold, z_s = 1[u_s >= tau] (Eq. 2), stored
+ *     compacted in ascending position in fixed-size pages; pairs with z_s = 0 are
+ *     dropped when they leave the window.
+ *
+ * and computes one decode step of gated attention (Eq. 3-5): the newest token of every
+ * sequence attends to its window and to its heads' long-term caches,
+ *   o_t = sum_s softmax_s(<q_t, k_s> * sm_scale) v_s   over available s.
+ *
+ * Conventions
+ *   - Every pointer documented "device" is GPU memory owned by the caller (for example a
+ *     PyTorch tensor) and must be 16-byte aligned; "host" pointers are ordinary memory.
+ *     The library allocates no device memory: the cache lives in an arena the caller
+ *     provides and keeps alive until spkv_cache_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls that
+ *     enqueue work return without waiting for it; calls documented "synchronises" wait
+ *     for `stream`.  One cache must be driven from one stream at a time.
+ *   - Tensors are dense, row-major, innermost dimension last.  K, V and Q are bf16
+ *     (bit pattern in uint16_t); utility logits are fp32 pre-sigmoid values f with
+ *     u = sigmoid(f) (Eq. 1).  Query head j reads KV head j / (n_q_heads / n_kv_heads).
+ *   - The gate is evaluated on the logit: z = 1[f >= theta], theta = log(tau / (1 - tau))
+ *     computed in fp64 from the fp32 tau and rounded once to fp32.  This is Eq. 2 moved
+ *     through the (strictly increasing) sigmoid.  tau <= 0 keeps every pair, tau >= 1
+ *     keeps none.  NaN logits are dropped.
+ *   - All functions return SPKV_OK (0) or a negative SPKV_E_* code; nothing is thrown and
+ *     a failed call leaves the cache unchanged unless stated otherwise.
+ */
+#ifndef SPKV_H
+#define SPKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPKV_OK            0
+#define SPKV_E_INVAL      -1   /* null pointer, bad shape, misaligned pointer, bad option   */
+#define SPKV_E_STATE      -2   /* decode on a sequence that holds no token yet              */
+#define SPKV_E_CAPACITY   -3   /* page pool, page table or max_context would overflow       */
+#define SPKV_E_HIP        -4   /* a HIP runtime call or kernel launch failed                */
+#define SPKV_E_NOMEM      -5   /* host allocation failed                                    */
+#define SPKV_E_DEVICE     -6   /* a kernel flagged an internal inconsistency (see stats)    */
+
+#define SPKV_MAX_BATCH     512 /* sequences per cache                                       */
+#define SPKV_PAGE_TOKENS   64  /* key/value pairs per long-term page                        */
+
+typedef struct spkv_cache spkv_cache_t;   /* opaque host object */
+
+typedef struct spkv_config {
+    int32_t batch;          /* sequences, 1 .. SPKV_MAX_BATCH                               */
+    int32_t n_q_heads;      /* query heads; a multiple of n_kv_heads, group size <= 16      */
+    int32_t n_kv_heads;     /* KV heads (one gate per KV head, listing appendix)            */
+    int32_t head_dim;       /* 64 or 128                                                    */
+    int32_t window;         /* w >= 1 (Sec. 2.1; 128 in the paper's main setting)           */
+    int32_t page_tokens;    /* 0 or SPKV_PAGE_TOKENS                                        */
+    float   tau;            /* gate threshold on the sigmoid (Eq. 2); 0.5 in the paper      */
+    int32_t max_context;    /* largest number of tokens any one sequence will hold          */
+    int64_t max_total_kept_tokens; /* long-term capacity summed over all (sequence, head)   */
+} spkv_config_t;
+
+typedef struct spkv_stats {
+    int64_t total_tokens;      /* sum over sequences of tokens appended                     */
+    int64_t evicted_tokens;    /* sum over (seq, head) of tokens that have left the window  */
+    int64_t window_tokens;     /* sum over (seq, head) of min(T, w)                         */
+    int64_t kept_tokens;       /* sum over (seq, head) of long-term entries                 */
+    int64_t gate_on_tokens;    /* sum over (seq, head, position) of z (Eq. 8 numerator)     */
+    double  density_evicted;   /* kept / evicted: the density the text reports (Eq. 8 note) */
+    double  density_all;       /* gate_on / (n_kv_heads * total_tokens): Eq. 8 literally    */
+    int64_t kept_kv_bytes;     /* (kept + window) * 2 * head_dim * 2: bytes a step must read*/
+    int64_t dense_kv_bytes;    /* total_tokens * n_kv_heads * 2 * head_dim * 2              */
+    int64_t pool_pages_used;
+    int64_t pool_pages_total;
+    int64_t arena_bytes;
+    int32_t device_error;      /* nonzero if a kernel ever flagged an inconsistency         */
+    int32_t n_work_items;      /* split-K work items of the current schedule                */
+} spkv_stats_t;
+
+/* Options for spkv_cache_set_option. */
+#define SPKV_OPT_ITEM_TARGET    1  /* split-K work items to aim for per decode, 1..16384     */
+#define SPKV_OPT_KERNEL_TIMING  2  /* 1: bracket every split-K kernel launch with HIP events */
+
+/* Bytes of device arena a cache with this configuration needs (0 if cfg is invalid).
+ * Host-only; touches no device.  Capacity rule: the long-term cache can hold
+ * max_total_kept_tokens pairs in total plus one partly filled page per (seq, head). */
+size_t spkv_cache_required_bytes(const spkv_config_t* cfg);
+
+/* Create a cache inside `dev_arena` (device, 256-byte aligned, >= required bytes) and
+ * enqueue on `stream` the fill that zeroes it.  The arena stays owned by the caller and
+ * must outlive the cache.  *out receives the handle.  (Sec. 2.1; appendix "Inference
+ * Kernels": window ring + per-head long-term pages.) */
+int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_bytes,
+                      void* stream, spkv_cache_t** out);
+
+/* Free the host object.  Synchronises nothing; the caller frees the arena afterwards. */
+int spkv_cache_destroy(spkv_cache_t* cache);
+
+/* Forget every token (all sequences back to length 0); enqueues the zero fill. */
+int spkv_cache_reset(spkv_cache_t* cache, void* stream);
+
+/* Write path (Eq. 1-2; appendix "Inference Kernels").  Appends, for each sequence b,
+ * the tokens in rows cu_seqlens[b] .. cu_seqlens[b+1]-1 (in position order):
+ *   k, v         device bf16  [total_tokens, n_kv_heads, head_dim]
+ *   util_logits  device fp32  [total_tokens, n_kv_heads]   (pre-sigmoid f)
+ *   cu_seqlens   host   int32 [batch + 1], cu_seqlens[0] = 0, non-decreasing
+ * Each new pair is written into its sequence's window ring together with its logit; a
+ * pair pushed out of the window (position s when position s + w arrives) is appended to
+ * its head's long-term cache if f_s >= theta and dropped otherwise.  A decode step is the
+ * case cu_seqlens = 0, 1, .., batch (one token per sequence; sequences may also get 0).
+ * Larger calls take a bulk path (ballot/prefix-sum stream compaction, stable order).
+ * Errors: SPKV_E_CAPACITY if any sequence would exceed max_context, or if the pool could
+ * overflow even when every pushed-out pair were kept, judged after refreshing the host's
+ * bound from the device counters (synchronises only in that case); then nothing is
+ * written.  Feed long prompts in chunks so that this worst case fits. */
+int spkv_append(spkv_cache_t* cache, const void* k, const void* v, const float* util_logits,
+                const int32_t* cu_seqlens, void* stream);
+
+/* Read path (Eq. 3-5).  For every sequence, the newest appended token attends to its
+ * window and to its heads' long-term caches:
+ *   q    device bf16 [batch, n_q_heads, head_dim]   (query of the newest token)
+ *   out  device bf16 [batch, n_q_heads, head_dim]
+ *   lse  device fp32 [batch, n_q_heads] or NULL: log sum_s exp(sm_scale * <q, k_s>)
+ *   sm_scale <= 0 selects 1 / sqrt(head_dim)
+ * Call after spkv_append of the same step, so that the query's own key is in the window.
+ * Errors: SPKV_E_STATE if some sequence holds no token. */
+int spkv_decode_attention(spkv_cache_t* cache, const void* q, void* out, float* lse,
+                          float sm_scale, void* stream);
+
+/* Gate density and sizes (Eq. 8).  Synchronises `stream`.  kept_len (host int32
+ * [batch * n_kv_heads], or NULL) receives the long-term length of every (seq, head). */
+int spkv_cache_stats(spkv_cache_t* cache, spkv_stats_t* stats, int32_t* kept_len, void* stream);
+
+/* Positions held by the long-term cache of (sequence b, KV head h), ascending, into
+ * pos (host int32 [cap]); *n receives the count (the call fails with SPKV_E_INVAL if
+ * cap is too small, after setting *n).  Synchronises `stream`. */
+int spkv_cache_kept_positions(spkv_cache_t* cache, int32_t b, int32_t h, int32_t* pos,
+                              int32_t cap, int32_t* n, void* stream);
+
+/* The fp32 threshold theta the gate compares logits against. */
+int spkv_cache_threshold_logit(const spkv_cache_t* cache, float* theta);
+
+/* Tuning and instrumentation; see SPKV_OPT_*. */
+int spkv_cache_set_option(spkv_cache_t* cache, int32_t option, int64_t value);
+
+/* With SPKV_OPT_KERNEL_TIMING on: durations (milliseconds, HIP events recorded on the
+ * launch stream immediately before and after the split-K decode kernel) of the launches
+ * since the last call, oldest first, at most cap; *n receives the count.  Synchronises
+ * those events. */
+int spkv_cache_read_kernel_timing(spkv_cache_t* cache, float* ms, int32_t cap, int32_t* n);
+
+/* Element offset (in bf16 elements from the start of a 64-pair page) at which the cache
+ * stores head-dim element d of the pair with in-page index kidx; is_v selects the value
+ * (1) or the key (0).  Returns -1 for arguments out of range.  Host-only; lets tests check
+ * that the page layout is a bijection and matches the MFMA operand order. */
+int64_t spkv_debug_layout_offset(int32_t head_dim, int32_t is_v, int32_t kidx, int32_t d);
+
+/* Static text for an error code. */
+const char* spkv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPKV_H */

@@ -182,8 +182,10 @@ class SPKVOracle:
         )
 
     # ------------------------------------------------------------------- read
-    def _decode_pair(self, b, h, q_bh):
-        """q_bh: [G, D] fp64 -> (out [G, D], lse [G]) for the newest position."""
+    def decode_pair(self, b, h, q_bh):
+        """One (sequence, KV head): q_bh [G, D] (the group's query heads) ->
+        (out [G, D], lse [G]) for the newest position, in fp64."""
+        q_bh = np.asarray(q_bh, dtype=np.float64)
         K = self._k(b)[:, h, :].astype(np.float64)       # [T, D]
         V = self._v(b)[:, h, :].astype(np.float64)
         avail = self.available(b, h)
@@ -213,7 +215,7 @@ class SPKVOracle:
         def job(bh):
             b, h = bh
             g0 = h * self.G
-            o, l = self._decode_pair(b, h, q[b, g0:g0 + self.G, :])
+            o, l = self.decode_pair(b, h, q[b, g0:g0 + self.G, :])
             out[b, g0:g0 + self.G, :] = o
             lse[b, g0:g0 + self.G] = l
 

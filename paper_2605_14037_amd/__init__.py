@@ -1,0 +1,12 @@
+"""SP-KV decode path for AMD MI355X: ctypes binding over the C-ABI library libspkv.so.
+
+Importing the package loads nothing; the library is loaded on first use and a missing
+library is an error (there is no fallback path).  Build it with
+`python -m paper_2605_14037_amd.build` or `__graft_entry__.build()`.
+"""
+
+from .binding import (  # noqa: F401
+    SPKVCache, SPKVConfig, SPKVStats, SPKVError, load_library, library_path,
+    required_bytes, strerror, layout_offset, EXPORTED_SYMBOLS,
+    OPT_ITEM_TARGET, OPT_KERNEL_TIMING,
+)

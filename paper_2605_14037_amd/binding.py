@@ -1,0 +1,226 @@
+"""Thin ctypes binding of include/spkv.h: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch supplies device
+memory (the arena and the tensors) and the current stream.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+OK, E_INVAL, E_STATE, E_CAPACITY, E_HIP, E_NOMEM, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
+OPT_ITEM_TARGET, OPT_KERNEL_TIMING = 1, 2
+MAX_BATCH, PAGE_TOKENS = 512, 64
+
+EXPORTED_SYMBOLS = [
+    "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_reset",
+    "spkv_append", "spkv_decode_attention", "spkv_cache_stats", "spkv_cache_kept_positions",
+    "spkv_cache_threshold_logit", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
+    "spkv_debug_layout_offset", "spkv_strerror",
+]
+
+
+class SPKVConfig(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("window", C.c_int32), ("page_tokens", C.c_int32),
+                ("tau", C.c_float), ("max_context", C.c_int32),
+                ("max_total_kept_tokens", C.c_int64)]
+
+
+class SPKVStats(C.Structure):
+    _fields_ = [("total_tokens", C.c_int64), ("evicted_tokens", C.c_int64),
+                ("window_tokens", C.c_int64), ("kept_tokens", C.c_int64),
+                ("gate_on_tokens", C.c_int64), ("density_evicted", C.c_double),
+                ("density_all", C.c_double), ("kept_kv_bytes", C.c_int64),
+                ("dense_kv_bytes", C.c_int64), ("pool_pages_used", C.c_int64),
+                ("pool_pages_total", C.c_int64), ("arena_bytes", C.c_int64),
+                ("device_error", C.c_int32), ("n_work_items", C.c_int32)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class SPKVError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+def library_path():
+    return os.path.join(HERE, "libspkv.so")
+
+
+def load_library():
+    """Load libspkv.so once and declare the prototypes of include/spkv.h."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it first "
+                           "(python -m paper_2605_14037_amd.build); there is no fallback path")
+    lib = C.CDLL(path)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    P = C.POINTER
+    lib.spkv_cache_required_bytes.restype = C.c_size_t
+    lib.spkv_cache_required_bytes.argtypes = [P(SPKVConfig)]
+    lib.spkv_cache_create.restype = C.c_int
+    lib.spkv_cache_create.argtypes = [P(SPKVConfig), vp, C.c_size_t, vp, P(vp)]
+    lib.spkv_cache_destroy.restype = C.c_int
+    lib.spkv_cache_destroy.argtypes = [vp]
+    lib.spkv_cache_reset.restype = C.c_int
+    lib.spkv_cache_reset.argtypes = [vp, vp]
+    lib.spkv_append.restype = C.c_int
+    lib.spkv_append.argtypes = [vp, vp, vp, vp, P(i32), vp]
+    lib.spkv_decode_attention.restype = C.c_int
+    lib.spkv_decode_attention.argtypes = [vp, vp, vp, vp, f32, vp]
+    lib.spkv_cache_stats.restype = C.c_int
+    lib.spkv_cache_stats.argtypes = [vp, P(SPKVStats), P(i32), vp]
+    lib.spkv_cache_kept_positions.restype = C.c_int
+    lib.spkv_cache_kept_positions.argtypes = [vp, i32, i32, P(i32), i32, P(i32), vp]
+    lib.spkv_cache_threshold_logit.restype = C.c_int
+    lib.spkv_cache_threshold_logit.argtypes = [vp, P(f32)]
+    lib.spkv_cache_set_option.restype = C.c_int
+    lib.spkv_cache_set_option.argtypes = [vp, i32, i64]
+    lib.spkv_cache_read_kernel_timing.restype = C.c_int
+    lib.spkv_cache_read_kernel_timing.argtypes = [vp, P(f32), i32, P(i32)]
+    lib.spkv_debug_layout_offset.restype = i64
+    lib.spkv_debug_layout_offset.argtypes = [i32, i32, i32, i32]
+    lib.spkv_strerror.restype = C.c_char_p
+    lib.spkv_strerror.argtypes = [C.c_int]
+    _LIB = lib
+    return lib
+
+
+def strerror(code):
+    return load_library().spkv_strerror(int(code)).decode()
+
+
+def required_bytes(cfg: SPKVConfig) -> int:
+    return int(load_library().spkv_cache_required_bytes(C.byref(cfg)))
+
+
+def layout_offset(head_dim, is_v, kidx, d) -> int:
+    return int(load_library().spkv_debug_layout_offset(head_dim, int(is_v), kidx, d))
+
+
+def _check(code, where):
+    if code != OK:
+        raise SPKVError(code, where)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_ptr(t: torch.Tensor, dtype, shape, name):
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: need a contiguous cuda {dtype} tensor of shape {tuple(shape)}, "
+                         f"got {t.dtype} {tuple(t.shape)} on {t.device}")
+    return C.c_void_p(t.data_ptr())
+
+
+class SPKVCache:
+    """One attention layer's SP-KV cache on the current CUDA (HIP) device."""
+
+    def __init__(self, batch, n_q_heads, n_kv_heads, head_dim, max_context,
+                 max_total_kept_tokens, window=128, tau=0.5, device="cuda"):
+        self.lib = load_library()
+        self.cfg = SPKVConfig(batch, n_q_heads, n_kv_heads, head_dim, window, 0, tau,
+                              max_context, max_total_kept_tokens)
+        nbytes = required_bytes(self.cfg)
+        if nbytes == 0:
+            raise SPKVError(E_INVAL, "spkv_cache_required_bytes")
+        self.device = torch.device(device)
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.handle = C.c_void_p()
+        _check(self.lib.spkv_cache_create(C.byref(self.cfg), C.c_void_p(self.arena.data_ptr()),
+                                          nbytes, _stream(), C.byref(self.handle)),
+               "spkv_cache_create")
+
+    def close(self):
+        if getattr(self, "handle", None) is not None and self.handle.value:
+            torch.cuda.synchronize(self.device)
+            self.lib.spkv_cache_destroy(self.handle)
+            self.handle = C.c_void_p()
+        self.arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- write path
+    def append(self, k, v, util_logits, cu_seqlens):
+        cfg = self.cfg
+        total = int(cu_seqlens[-1])
+        cu = (C.c_int32 * (cfg.batch + 1))(*[int(x) for x in cu_seqlens])
+        if total == 0:
+            _check(self.lib.spkv_append(self.handle, None, None, None, cu, _stream()), "spkv_append")
+            return
+        kp = _dev_ptr(k, torch.bfloat16, (total, cfg.n_kv_heads, cfg.head_dim), "k")
+        vp = _dev_ptr(v, torch.bfloat16, (total, cfg.n_kv_heads, cfg.head_dim), "v")
+        fp = _dev_ptr(util_logits, torch.float32, (total, cfg.n_kv_heads), "util_logits")
+        _check(self.lib.spkv_append(self.handle, kp, vp, fp, cu, _stream()), "spkv_append")
+
+    # ---- read path
+    def decode_attention(self, q, out=None, lse=None, sm_scale=0.0, want_lse=False):
+        cfg = self.cfg
+        shape = (cfg.batch, cfg.n_q_heads, cfg.head_dim)
+        qp = _dev_ptr(q, torch.bfloat16, shape, "q")
+        if out is None:
+            out = torch.empty(shape, dtype=torch.bfloat16, device=q.device)
+        op = _dev_ptr(out, torch.bfloat16, shape, "out")
+        if lse is None and want_lse:
+            lse = torch.empty(shape[:2], dtype=torch.float32, device=q.device)
+        lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
+        _check(self.lib.spkv_decode_attention(self.handle, qp, op, lp, float(sm_scale), _stream()),
+               "spkv_decode_attention")
+        return (out, lse) if lse is not None else out
+
+    # ---- bookkeeping
+    def reset(self):
+        _check(self.lib.spkv_cache_reset(self.handle, _stream()), "spkv_cache_reset")
+
+    def stats(self, with_kept_len=False):
+        st = SPKVStats()
+        n = self.cfg.batch * self.cfg.n_kv_heads
+        buf = (C.c_int32 * n)()
+        _check(self.lib.spkv_cache_stats(self.handle, C.byref(st), buf, _stream()),
+               "spkv_cache_stats")
+        if with_kept_len:
+            return st, [list(buf[b * self.cfg.n_kv_heads:(b + 1) * self.cfg.n_kv_heads])
+                        for b in range(self.cfg.batch)]
+        return st
+
+    def kept_positions(self, b, h):
+        cap = max(1, self.cfg.max_context)
+        buf = (C.c_int32 * cap)()
+        n = C.c_int32()
+        _check(self.lib.spkv_cache_kept_positions(self.handle, b, h, buf, cap, C.byref(n),
+                                                  _stream()), "spkv_cache_kept_positions")
+        return list(buf[:n.value])
+
+    def threshold_logit(self):
+        th = C.c_float()
+        _check(self.lib.spkv_cache_threshold_logit(self.handle, C.byref(th)),
+               "spkv_cache_threshold_logit")
+        return th.value
+
+    def set_option(self, option, value):
+        _check(self.lib.spkv_cache_set_option(self.handle, option, int(value)),
+               "spkv_cache_set_option")
+
+    def read_kernel_timing(self, cap=8192):
+        buf = (C.c_float * cap)()
+        n = C.c_int32()
+        _check(self.lib.spkv_cache_read_kernel_timing(self.handle, buf, cap, C.byref(n)),
+               "spkv_cache_read_kernel_timing")
+        return list(buf[:n.value])

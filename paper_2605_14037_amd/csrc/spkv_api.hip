@@ -1,0 +1,436 @@
+// Host side of the SP-KV C ABI: configuration checks, arena carving, the host's
+// conservative capacity bound (the "safe budget" idea of the paper's appendix "Inference
+// Kernels": capacity is checked on the host without reading the device until a worst-case
+// bound trips), and kernel launches.  See include/spkv.h for the contract.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "spkv_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kDefaultItemTarget = 4096;
+constexpr int kMaxTimedLaunches = 8192;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Carve {
+    size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, err_flag, page_table, pool,
+        pos_pool, seg_count, bulk_info, n_items, items, item_start, part_acc, part_ml,
+        pos_scratch, total;
+    int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items;
+};
+
+bool config_ok(const spkv_config_t* c) {
+    if (c == nullptr) return false;
+    if (c->batch < 1 || c->batch > SPKV_MAX_BATCH) return false;
+    if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads != 0) return false;
+    if (c->n_q_heads / c->n_kv_heads > 16) return false;
+    if ((int64_t)c->batch * c->n_kv_heads > 16384) return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->window < 1 || c->window > (1 << 20)) return false;
+    if (c->page_tokens != 0 && c->page_tokens != SPKV_PAGE_TOKENS) return false;
+    if (std::isnan(c->tau)) return false;
+    if (c->max_context < 1 || c->max_context > (1 << 30)) return false;
+    if (c->max_total_kept_tokens < 0 || c->max_total_kept_tokens > ((int64_t)1 << 40)) return false;
+    return true;
+}
+
+bool carve(const spkv_config_t* c, Carve* out) {
+    if (!config_ok(c)) return false;
+    Carve k{};
+    k.n_pairs = c->batch * c->n_kv_heads;
+    k.G = c->n_q_heads / c->n_kv_heads;
+    k.n_ring_pages = (c->window + kPageTokens - 1) / kPageTokens;
+    const int64_t max_evicted = c->max_context > c->window ? c->max_context - c->window : 0;
+    k.pt_cap = (int)((max_evicted + kPageTokens - 1) / kPageTokens) + 1;
+    const int64_t n_pages = (c->max_total_kept_tokens + kPageTokens - 1) / kPageTokens + k.n_pairs;
+    if (n_pages > ((int64_t)1 << 30)) return false;
+    k.n_pages = (int)n_pages;
+    k.n_seg_cap = (int)((max_evicted + kSegTokens - 1) / kSegTokens) + 1;
+    k.max_items = kMaxItemTarget + k.n_pairs;
+    const size_t page_bytes = (size_t)spkv_page_elems(c->head_dim) * 2;
+    size_t off = 0;
+    auto take = [&off](size_t bytes) {
+        const size_t at = off;
+        off += align_up(bytes);
+        return at;
+    };
+    k.ring = take((size_t)k.n_pairs * k.n_ring_pages * page_bytes);
+    k.ring_logit = take((size_t)k.n_pairs * c->window * 4);
+    k.t_pair = take((size_t)k.n_pairs * 4);
+    k.kept_len = take((size_t)k.n_pairs * 4);
+    k.gate_on = take((size_t)k.n_pairs * 4);
+    k.pool_next = take(4);
+    k.err_flag = take(4);
+    k.page_table = take((size_t)k.n_pairs * k.pt_cap * 4);
+    k.pool = take((size_t)k.n_pages * page_bytes);
+    k.pos_pool = take((size_t)k.n_pages * kPageTokens * 4);
+    k.seg_count = take((size_t)k.n_pairs * k.n_seg_cap * 4);
+    k.bulk_info = take((size_t)k.n_pairs * 16);
+    k.n_items = take(4);
+    k.items = take((size_t)k.max_items * 16);
+    k.item_start = take((size_t)(k.n_pairs + 1) * 4);
+    k.part_acc = take((size_t)k.max_items * k.G * c->head_dim * 4);
+    k.part_ml = take((size_t)k.max_items * k.G * 2 * 4);
+    k.pos_scratch = take((size_t)k.pt_cap * kPageTokens * 4);
+    k.total = off;
+    *out = k;
+    return true;
+}
+
+float logit_threshold(float tau) {
+    const double t = (double)tau;
+    if (t <= 0.0) return -INFINITY;
+    if (t >= 1.0) return INFINITY;
+    return (float)std::log(t / (1.0 - t));
+}
+
+int64_t pages_for(int64_t len) { return (len + kPageTokens - 1) / kPageTokens; }
+
+}  // namespace
+
+struct spkv_cache {
+    spkv_config_t cfg;
+    Carve carve;
+    SpkvView view;
+    char* arena;
+    size_t arena_bytes;
+    std::vector<int32_t> T;       // tokens per sequence (exact: the host sees every append)
+    std::vector<int32_t> L_ub;    // per (seq, head): upper bound of the long-term length
+    int64_t pages_ub;             // sum of pages_for(L_ub): upper bound of pool pages in use
+    int item_target;
+    bool timing;
+    std::vector<hipEvent_t> events;   // pairs (before, after)
+    int n_timed;
+};
+
+namespace {
+
+// Read the exact long-term lengths back and tighten the host's bound.  Synchronises.
+int refresh_bound(spkv_cache* c, hipStream_t s, int32_t* kept_len_out) {
+    std::vector<int32_t> len(c->carve.n_pairs);
+    if (hipStreamSynchronize(s) != hipSuccess) return SPKV_E_HIP;
+    if (hipMemcpy(len.data(), c->view.kept_len, len.size() * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return SPKV_E_HIP;
+    int64_t pages = 0;
+    for (int p = 0; p < c->carve.n_pairs; ++p) {
+        c->L_ub[p] = len[p];
+        pages += pages_for(len[p]);
+    }
+    c->pages_ub = pages;
+    if (kept_len_out != nullptr) std::memcpy(kept_len_out, len.data(), len.size() * 4);
+    return SPKV_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int64_t half_pages_ub(const spkv_cache* c) {
+    int64_t hp = 0;
+    const int Hkv = c->cfg.n_kv_heads;
+    for (int p = 0; p < c->carve.n_pairs; ++p) {
+        const int Tw = std::min(c->T[p / Hkv], c->cfg.window);
+        hp += (c->L_ub[p] + kHalfTokens - 1) / kHalfTokens + (Tw + kHalfTokens - 1) / kHalfTokens;
+    }
+    return hp;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t spkv_cache_required_bytes(const spkv_config_t* cfg) {
+    Carve k;
+    return carve(cfg, &k) ? k.total : 0;
+}
+
+int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_bytes, void* stream,
+                      spkv_cache_t** out) {
+    if (out == nullptr) return SPKV_E_INVAL;
+    *out = nullptr;
+    Carve k;
+    if (!carve(cfg, &k)) return SPKV_E_INVAL;
+    if (dev_arena == nullptr || (reinterpret_cast<uintptr_t>(dev_arena) % kAlign) != 0 ||
+        arena_bytes < k.total)
+        return SPKV_E_INVAL;
+    spkv_cache* c = new (std::nothrow) spkv_cache();
+    if (c == nullptr) return SPKV_E_NOMEM;
+    c->cfg = *cfg;
+    c->cfg.page_tokens = SPKV_PAGE_TOKENS;
+    c->carve = k;
+    c->arena = static_cast<char*>(dev_arena);
+    c->arena_bytes = k.total;
+    c->T.assign(cfg->batch, 0);
+    c->L_ub.assign(k.n_pairs, 0);
+    c->pages_ub = 0;
+    c->item_target = kDefaultItemTarget;
+    c->timing = false;
+    c->n_timed = 0;
+    SpkvView& v = c->view;
+    v.B = cfg->batch;
+    v.Hq = cfg->n_q_heads;
+    v.Hkv = cfg->n_kv_heads;
+    v.G = k.G;
+    v.D = cfg->head_dim;
+    v.w = cfg->window;
+    v.n_pairs = k.n_pairs;
+    v.n_ring_pages = k.n_ring_pages;
+    v.pt_cap = k.pt_cap;
+    v.n_pages = k.n_pages;
+    v.n_seg_cap = k.n_seg_cap;
+    v.max_items = k.max_items;
+    v.theta = logit_threshold(cfg->tau);
+    char* a = c->arena;
+    v.ring = reinterpret_cast<uint16_t*>(a + k.ring);
+    v.ring_logit = reinterpret_cast<float*>(a + k.ring_logit);
+    v.t_pair = reinterpret_cast<int32_t*>(a + k.t_pair);
+    v.kept_len = reinterpret_cast<int32_t*>(a + k.kept_len);
+    v.gate_on = reinterpret_cast<int32_t*>(a + k.gate_on);
+    v.pool_next = reinterpret_cast<int32_t*>(a + k.pool_next);
+    v.err_flag = reinterpret_cast<int32_t*>(a + k.err_flag);
+    v.page_table = reinterpret_cast<int32_t*>(a + k.page_table);
+    v.pool = reinterpret_cast<uint16_t*>(a + k.pool);
+    v.pos_pool = reinterpret_cast<int32_t*>(a + k.pos_pool);
+    v.seg_count = reinterpret_cast<int32_t*>(a + k.seg_count);
+    v.bulk_info = reinterpret_cast<int32_t*>(a + k.bulk_info);
+    v.n_items = reinterpret_cast<int32_t*>(a + k.n_items);
+    v.items = reinterpret_cast<int4*>(a + k.items);
+    v.item_start = reinterpret_cast<int32_t*>(a + k.item_start);
+    v.part_acc = reinterpret_cast<float*>(a + k.part_acc);
+    v.part_ml = reinterpret_cast<float*>(a + k.part_ml);
+    v.pos_scratch = reinterpret_cast<int32_t*>(a + k.pos_scratch);
+    if (spkv_launch_fill_zero(c->arena, c->arena_bytes, static_cast<hipStream_t>(stream)) !=
+        hipSuccess) {
+        delete c;
+        return SPKV_E_HIP;
+    }
+    *out = c;
+    return SPKV_OK;
+}
+
+int spkv_cache_destroy(spkv_cache_t* c) {
+    if (c == nullptr) return SPKV_E_INVAL;
+    for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+    delete c;
+    return SPKV_OK;
+}
+
+int spkv_cache_reset(spkv_cache_t* c, void* stream) {
+    if (c == nullptr) return SPKV_E_INVAL;
+    if (spkv_launch_fill_zero(c->arena, c->arena_bytes, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return SPKV_E_HIP;
+    std::fill(c->T.begin(), c->T.end(), 0);
+    std::fill(c->L_ub.begin(), c->L_ub.end(), 0);
+    c->pages_ub = 0;
+    return SPKV_OK;
+}
+
+int spkv_append(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
+                const int32_t* cu_seqlens, void* stream) {
+    if (c == nullptr || cu_seqlens == nullptr) return SPKV_E_INVAL;
+    const int B = c->cfg.batch, Hkv = c->cfg.n_kv_heads, w = c->cfg.window;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (cu_seqlens[0] != 0) return SPKV_E_INVAL;
+    int n_max = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t n = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+        if (n < 0) return SPKV_E_INVAL;
+        if ((int64_t)c->T[b] + n > c->cfg.max_context) return SPKV_E_CAPACITY;
+        if (n > n_max) n_max = (int)n;
+    }
+    if (n_max == 0) return SPKV_OK;
+    if (k == nullptr || v == nullptr || util_logits == nullptr) return SPKV_E_INVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(util_logits)) return SPKV_E_INVAL;
+
+    // Worst case for the pool: every pair pushed out of the window by this call is kept.
+    for (int attempt = 0;; ++attempt) {
+        int64_t pages = c->pages_ub;
+        for (int b = 0; b < B; ++b) {
+            const int n = cu_seqlens[b + 1] - cu_seqlens[b];
+            const int64_t ev = std::max<int64_t>(0, (int64_t)c->T[b] + n - w) -
+                               std::max<int64_t>(0, (int64_t)c->T[b] - w);
+            if (ev == 0) continue;
+            for (int h = 0; h < Hkv; ++h) {
+                const int64_t L = c->L_ub[b * Hkv + h];
+                pages += pages_for(L + ev) - pages_for(L);
+            }
+        }
+        if (pages <= c->carve.n_pages) break;
+        if (attempt == 1) return SPKV_E_CAPACITY;
+        const int rc = refresh_bound(c, s, nullptr);
+        if (rc != SPKV_OK) return rc;
+    }
+
+    SpkvCu cu;
+    std::memcpy(cu.v, cu_seqlens, (size_t)(B + 1) * 4);
+    const uint16_t* kk = static_cast<const uint16_t*>(k);
+    const uint16_t* vv = static_cast<const uint16_t*>(v);
+    hipError_t e = (n_max == 1)
+                       ? spkv_launch_append_step(c->view, kk, vv, util_logits, cu, s)
+                       : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, s);
+    if (e != hipSuccess) return SPKV_E_HIP;
+
+    for (int b = 0; b < B; ++b) {
+        const int n = cu_seqlens[b + 1] - cu_seqlens[b];
+        const int64_t ev = std::max<int64_t>(0, (int64_t)c->T[b] + n - w) -
+                           std::max<int64_t>(0, (int64_t)c->T[b] - w);
+        c->T[b] += n;
+        if (ev == 0) continue;
+        for (int h = 0; h < Hkv; ++h) {
+            int32_t& L = c->L_ub[b * Hkv + h];
+            c->pages_ub += pages_for(L + ev) - pages_for(L);
+            L += (int32_t)ev;
+        }
+    }
+    if (spkv_launch_schedule(c->view, c->item_target, s) != hipSuccess) return SPKV_E_HIP;
+    return SPKV_OK;
+}
+
+int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse, float sm_scale,
+                          void* stream) {
+    if (c == nullptr || q == nullptr || out == nullptr) return SPKV_E_INVAL;
+    if (!aligned16(q) || !aligned16(out) || (lse != nullptr && !aligned16(lse))) return SPKV_E_INVAL;
+    for (int b = 0; b < c->cfg.batch; ++b)
+        if (c->T[b] == 0) return SPKV_E_STATE;
+    if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (c->timing && c->n_timed < kMaxTimedLaunches) {
+        if ((size_t)(2 * c->n_timed + 2) > c->events.size()) {
+            hipEvent_t a, b2;
+            if (hipEventCreate(&a) != hipSuccess) return SPKV_E_HIP;
+            if (hipEventCreate(&b2) != hipSuccess) {
+                (void)hipEventDestroy(a);
+                return SPKV_E_HIP;
+            }
+            c->events.push_back(a);
+            c->events.push_back(b2);
+        }
+        ev0 = c->events[2 * c->n_timed];
+        ev1 = c->events[2 * c->n_timed + 1];
+        c->n_timed += 1;
+    }
+    const int64_t hp = half_pages_ub(c);
+    const int grid = (int)std::min<int64_t>(hp, c->item_target) + c->carve.n_pairs;
+    if (spkv_launch_decode(c->view, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
+                           lse, sm_scale, grid, ev0, ev1, s) != hipSuccess)
+        return SPKV_E_HIP;
+    return SPKV_OK;
+}
+
+int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void* stream) {
+    if (c == nullptr || st == nullptr) return SPKV_E_INVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int n_pairs = c->carve.n_pairs, Hkv = c->cfg.n_kv_heads, w = c->cfg.window;
+    std::vector<int32_t> len(n_pairs), gate(n_pairs);
+    int rc = refresh_bound(c, s, len.data());
+    if (rc != SPKV_OK) return rc;
+    int32_t pool_next = 0, err = 0, n_items = 0;
+    if (hipMemcpy(gate.data(), c->view.gate_on, (size_t)n_pairs * 4, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(&pool_next, c->view.pool_next, 4, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(&err, c->view.err_flag, 4, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(&n_items, c->view.n_items, 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return SPKV_E_HIP;
+    std::memset(st, 0, sizeof(*st));
+    for (int b = 0; b < c->cfg.batch; ++b) {
+        st->total_tokens += c->T[b];
+        st->evicted_tokens += (int64_t)std::max(0, c->T[b] - w) * Hkv;
+        st->window_tokens += (int64_t)std::min(c->T[b], w) * Hkv;
+    }
+    for (int p = 0; p < n_pairs; ++p) {
+        st->kept_tokens += len[p];
+        st->gate_on_tokens += gate[p];
+    }
+    st->density_evicted = st->evicted_tokens ? (double)st->kept_tokens / (double)st->evicted_tokens : 0.0;
+    st->density_all = st->total_tokens ? (double)st->gate_on_tokens / ((double)st->total_tokens * Hkv) : 0.0;
+    const int64_t row_bytes = (int64_t)2 * c->cfg.head_dim * 2;
+    st->kept_kv_bytes = (st->kept_tokens + st->window_tokens) * row_bytes;
+    st->dense_kv_bytes = st->total_tokens * Hkv * row_bytes;
+    st->pool_pages_used = pool_next;
+    st->pool_pages_total = c->carve.n_pages;
+    st->arena_bytes = (int64_t)c->arena_bytes;
+    st->device_error = err;
+    st->n_work_items = n_items;
+    if (kept_len != nullptr) std::memcpy(kept_len, len.data(), (size_t)n_pairs * 4);
+    return err ? SPKV_E_DEVICE : SPKV_OK;
+}
+
+int spkv_cache_kept_positions(spkv_cache_t* c, int32_t b, int32_t h, int32_t* pos, int32_t cap,
+                              int32_t* n, void* stream) {
+    if (c == nullptr || n == nullptr || b < 0 || b >= c->cfg.batch || h < 0 ||
+        h >= c->cfg.n_kv_heads || cap < 0)
+        return SPKV_E_INVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int pair = b * c->cfg.n_kv_heads + h;
+    if (spkv_launch_gather_positions(c->view, pair, s) != hipSuccess) return SPKV_E_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return SPKV_E_HIP;
+    int32_t L = 0;
+    if (hipMemcpy(&L, c->view.kept_len + pair, 4, hipMemcpyDeviceToHost) != hipSuccess) return SPKV_E_HIP;
+    *n = L;
+    if (L > cap || (L > 0 && pos == nullptr)) return SPKV_E_INVAL;
+    if (L > 0 &&
+        hipMemcpy(pos, c->view.pos_scratch, (size_t)L * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return SPKV_E_HIP;
+    return SPKV_OK;
+}
+
+int spkv_cache_threshold_logit(const spkv_cache_t* c, float* theta) {
+    if (c == nullptr || theta == nullptr) return SPKV_E_INVAL;
+    *theta = c->view.theta;
+    return SPKV_OK;
+}
+
+int spkv_cache_set_option(spkv_cache_t* c, int32_t option, int64_t value) {
+    if (c == nullptr) return SPKV_E_INVAL;
+    switch (option) {
+        case SPKV_OPT_ITEM_TARGET:
+            if (value < 1 || value > kMaxItemTarget) return SPKV_E_INVAL;
+            c->item_target = (int)value;
+            return SPKV_OK;
+        case SPKV_OPT_KERNEL_TIMING:
+            c->timing = value != 0;
+            c->n_timed = 0;
+            return SPKV_OK;
+        default:
+            return SPKV_E_INVAL;
+    }
+}
+
+int spkv_cache_read_kernel_timing(spkv_cache_t* c, float* ms, int32_t cap, int32_t* n) {
+    if (c == nullptr || n == nullptr || cap < 0 || (cap > 0 && ms == nullptr)) return SPKV_E_INVAL;
+    const int count = std::min<int>(c->n_timed, cap);
+    for (int i = 0; i < count; ++i) {
+        if (hipEventSynchronize(c->events[2 * i + 1]) != hipSuccess) return SPKV_E_HIP;
+        if (hipEventElapsedTime(&ms[i], c->events[2 * i], c->events[2 * i + 1]) != hipSuccess)
+            return SPKV_E_HIP;
+    }
+    *n = count;
+    c->n_timed = 0;
+    return SPKV_OK;
+}
+
+int64_t spkv_debug_layout_offset(int32_t head_dim, int32_t is_v, int32_t kidx, int32_t d) {
+    if ((head_dim != 64 && head_dim != 128) || kidx < 0 || kidx >= kPageTokens || d < 0 ||
+        d >= head_dim)
+        return -1;
+    return is_v ? spkv_v_off(head_dim, kidx, d) : spkv_k_off(head_dim, kidx, d);
+}
+
+const char* spkv_strerror(int code) {
+    switch (code) {
+        case SPKV_OK: return "ok";
+        case SPKV_E_INVAL: return "invalid argument";
+        case SPKV_E_STATE: return "decode on a sequence that holds no token";
+        case SPKV_E_CAPACITY: return "cache capacity (pool pages, page table or max_context) exceeded";
+        case SPKV_E_HIP: return "HIP runtime error";
+        case SPKV_E_NOMEM: return "host allocation failed";
+        case SPKV_E_DEVICE: return "kernel flagged an inconsistent cache state";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

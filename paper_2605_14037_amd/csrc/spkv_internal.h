@@ -1,0 +1,57 @@
+// Shared between the host API (spkv_api.hip) and the kernels (spkv_kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/spkv.h"
+#include "spkv_layout.h"
+
+constexpr int kSegTokens = 1024;      // bulk append: tokens per compaction segment
+constexpr int kMaxItemTarget = 16384;
+
+// Device-side view of one cache: plain pointers into the caller's arena.
+struct SpkvView {
+    int32_t B, Hq, Hkv, G, D, w;
+    int32_t n_pairs;        // B * Hkv
+    int32_t n_ring_pages;   // ceil(w / 64) pages per (seq, head) ring
+    int32_t pt_cap;         // page-table entries per (seq, head)
+    int32_t n_pages;        // pages in the long-term pool
+    int32_t n_seg_cap;      // bulk-append segments per (seq, head)
+    int32_t max_items;      // capacity of the work-item table / partials
+    float   theta;          // gate threshold on the logit
+
+    uint16_t* ring;         // [n_pairs][n_ring_pages] pages (K and V interleaved by half)
+    float*    ring_logit;   // [n_pairs][w]
+    int32_t*  t_pair;       // [n_pairs] tokens appended so far (same for all heads of a seq)
+    int32_t*  kept_len;     // [n_pairs] long-term length L
+    int32_t*  gate_on;      // [n_pairs] count of appended tokens with gate on
+    int32_t*  pool_next;    // [1] next free pool page
+    int32_t*  err_flag;     // [1] set by kernels on an impossible state
+    int32_t*  page_table;   // [n_pairs][pt_cap] logical page -> pool page
+    uint16_t* pool;         // [n_pages] pages
+    int32_t*  pos_pool;     // [n_pages][64] position of every long-term entry
+    int32_t*  seg_count;    // [n_pairs][n_seg_cap] bulk scratch: kept per segment, then offsets
+    int32_t*  bulk_info;    // [n_pairs][4] bulk scratch: T_old, first long-term index of new tokens
+    int32_t*  n_items;      // [1] work items in the current schedule
+    int4*     items;        // [max_items] {pair, first half-page, end half-page, 0}
+    int32_t*  item_start;   // [n_pairs + 1] first item of every pair
+    float*    part_acc;     // [max_items][G][D] un-normalised partial outputs
+    float*    part_ml;      // [max_items][G][2] running max (log2 domain) and sum
+    int32_t*  pos_scratch;  // [pt_cap * 64] gather buffer for kept positions
+};
+
+// cu_seqlens travels to the append kernels by value in the kernel-argument block.
+struct SpkvCu {
+    int32_t v[SPKV_MAX_BATCH + 1];
+};
+
+hipError_t spkv_launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const SpkvCu& cu, hipStream_t s);
+hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const SpkvCu& cu, int n_max, hipStream_t s);
+hipError_t spkv_launch_schedule(const SpkvView& v, int item_target, hipStream_t s);
+hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
+                              float sm_scale, int grid_items, hipEvent_t ev0, hipEvent_t ev1,
+                              hipStream_t s);
+hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s);

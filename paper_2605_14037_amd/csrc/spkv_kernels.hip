@@ -1,0 +1,608 @@
+// HIP kernels of the SP-KV decode path for gfx950 (MI355X, wave64, MFMA).
+//
+//   write path : spkv_append_step (one token per sequence, fused evict + append),
+//                spkv_bulk_count / spkv_bulk_ring / spkv_bulk_scatter (many tokens:
+//                ballot + mbcnt stream compaction, stable order)
+//   scheduler  : spkv_schedule (split every head's kept list into equal work items)
+//   read path  : spkv_decode_split (split-K flash decoding on MFMA, one wave per item),
+//                spkv_decode_combine (log-sum-exp merge of the partials)
+//
+// Gate: Eq. 2 of the paper taken on the logit, z = 1[f >= theta].  Availability:
+// Eq. 3-4; the window ring holds exactly the keys with 0 <= t - s < w and the long-term
+// pages exactly the gated-on keys with t - s >= w, so the two sets are disjoint and their
+// union is the available set of Eq. 5.
+#include "spkv_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) float f32x8;
+
+#define SPKV_NEG_INF (-__builtin_inff())
+
+// ------------------------------------------------------------------ small helpers
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+__device__ __forceinline__ int mbcnt64(unsigned long long mask) {
+    return __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+}
+
+__device__ __forceinline__ uint16_t* ring_page(const SpkvView& v, int pair, int rp) {
+    return v.ring + ((size_t)pair * v.n_ring_pages + rp) * (size_t)spkv_page_elems(v.D);
+}
+
+__device__ __forceinline__ uint16_t* pool_page(const SpkvView& v, int page) {
+    return v.pool + (size_t)page * (size_t)spkv_page_elems(v.D);
+}
+
+// One wave copies row `sk` of page `sp` to row `dk` of page `dp` (both in page layout).
+template <int D>
+__device__ __forceinline__ void copy_row_paged(const uint16_t* sp, int sk, uint16_t* dp, int dk,
+                                               int lane) {
+#pragma unroll
+    for (int d = lane; d < D; d += 64) dp[spkv_v_off(D, dk, d)] = sp[spkv_v_off(D, sk, d)];
+    if (lane < D / 8)
+        *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk, lane * 8)) =
+            *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, lane * 8));
+}
+
+// One wave copies a dense (row-major) K row and V row into row `dk` of page `dp`.
+template <int D>
+__device__ __forceinline__ void copy_row_dense(const uint16_t* krow, const uint16_t* vrow,
+                                               uint16_t* dp, int dk, int lane) {
+#pragma unroll
+    for (int d = lane; d < D; d += 64) dp[spkv_v_off(D, dk, d)] = vrow[d];
+    if (lane < D / 8)
+        *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk, lane * 8)) =
+            *reinterpret_cast<const uint4*>(krow + lane * 8);
+}
+
+// ------------------------------------------------------------------------ zero fill
+__global__ __launch_bounds__(256) void spkv_fill_zero(uint4* p, size_t n16) {
+    const uint4 z = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = z;
+}
+
+hipError_t spkv_launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    spkv_fill_zero<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(static_cast<uint4*>(p), n16);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------- write path, one token per sequence
+// Appendix "Inference Kernels": write the new pair into the next ring slot; if the slot
+// held a pair (window full), that pair leaves the window: keep it (append to the head's
+// long-term pages, allocating a page with one atomic when a page boundary is crossed) if
+// its stored logit passes the gate, else drop it.  One workgroup of D threads per
+// (sequence, KV head); thread d moves V element d, threads < D/8 move one 16-byte K chunk.
+template <int D>
+__global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t* __restrict__ k,
+                                                      const uint16_t* __restrict__ vv,
+                                                      const float* __restrict__ f, SpkvCu cu) {
+    const int pair = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row = cu.v[b];
+    if (cu.v[b + 1] - row == 0) return;
+    const int tid = threadIdx.x;
+    const int T = v.t_pair[pair];
+    const int slot = T % v.w;
+    uint16_t* rp = ring_page(v, pair, slot >> 6);
+    const int rk = slot & 63;
+    __shared__ int s_page;
+
+    if (T >= v.w) {
+        const float f_old = v.ring_logit[(size_t)pair * v.w + slot];
+        if (f_old >= v.theta) {                                   // Eq. 2 on the logit
+            const int L = v.kept_len[pair];
+            const int lp = L >> 6, gk = L & 63;
+            if (tid == 0) {
+                int page;
+                if (lp >= v.pt_cap) {
+                    page = -1;
+                } else if (gk == 0) {
+                    page = atomicAdd(v.pool_next, 1);
+                    if (page >= v.n_pages) page = -1;
+                    else v.page_table[(size_t)pair * v.pt_cap + lp] = page;
+                } else {
+                    page = v.page_table[(size_t)pair * v.pt_cap + lp];
+                }
+                if (page < 0) *v.err_flag = 1;
+                s_page = page;
+            }
+            __syncthreads();
+            const int page = s_page;
+            if (page >= 0) {
+                uint16_t* gp = pool_page(v, page);
+                gp[spkv_v_off(D, gk, tid)] = rp[spkv_v_off(D, rk, tid)];
+                if (tid < D / 8)
+                    *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) =
+                        *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
+                if (tid == 0) {
+                    v.pos_pool[(size_t)page * kPageTokens + gk] = T - v.w;
+                    v.kept_len[pair] = L + 1;
+                }
+            }
+        }
+    }
+    const size_t src = ((size_t)row * v.Hkv + h) * D;
+    rp[spkv_v_off(D, rk, tid)] = vv[src + tid];
+    if (tid < D / 8)
+        *reinterpret_cast<uint4*>(rp + spkv_k_off(D, rk, tid * 8)) =
+            *reinterpret_cast<const uint4*>(k + src + tid * 8);
+    if (tid == 0) {
+        const float fn = f[(size_t)row * v.Hkv + h];
+        v.ring_logit[(size_t)pair * v.w + slot] = fn;
+        v.t_pair[pair] = T + 1;
+        if (fn >= v.theta) v.gate_on[pair] += 1;
+    }
+}
+
+hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const SpkvCu& cu, hipStream_t s) {
+    if (v.D == 128)
+        spkv_append_step<128><<<dim3(v.n_pairs), dim3(128), 0, s>>>(v, k, vv, f, cu);
+    else
+        spkv_append_step<64><<<dim3(v.n_pairs), dim3(64), 0, s>>>(v, k, vv, f, cu);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------- write path, many tokens (bulk)
+// For (sequence, head) with n new tokens, T_old stored: positions that leave the window
+// are [max(0, T_old - w), T_old + n - w).  Those below T_old sit in the ring (<= w of
+// them, handled by spkv_bulk_ring); the others are new tokens j in [0, n - w) that enter
+// and leave the window within this call (handled per 1024-token segment).  The last
+// min(n, w) new tokens land in the ring.  Long-term order is ascending position:
+// ring-evicted first, then new tokens, ranks from ballot + mbcnt prefix sums.
+
+// Stage 1: per (segment, pair) count of new tokens j < n - w that pass the gate.
+__global__ __launch_bounds__(256) void spkv_bulk_count(SpkvView v, const float* __restrict__ f,
+                                                       SpkvCu cu) {
+    const int pair = blockIdx.y, seg = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int n = cu.v[b + 1] - cu.v[b];
+    const int n_ev = max(0, n - v.w);
+    const int j0 = seg * kSegTokens;
+    if (j0 >= n_ev) return;
+    const int j1 = min(n_ev, j0 + kSegTokens);
+    __shared__ int s_wave[4];
+    int cnt = 0;
+    for (int base = j0; base < j1; base += 256) {
+        const int j = base + (int)threadIdx.x;
+        const bool flag = j < j1 && f[((size_t)cu.v[b] + j) * v.Hkv + h] >= v.theta;
+        cnt += __popcll(__ballot(flag));
+    }
+    if (lane_id() == 0) s_wave[threadIdx.x >> 6] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        v.seg_count[(size_t)pair * v.n_seg_cap + seg] = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+}
+
+// Stage 2: one workgroup per pair.  Compacts the pairs leaving the ring, turns the
+// segment counts into offsets, allocates every page the call needs with one atomic,
+// and publishes the new lengths.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
+    const int pair = blockIdx.x;
+    const int b = pair / v.Hkv;
+    const int n = cu.v[b + 1] - cu.v[b];
+    if (n == 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int T_old = v.t_pair[pair], T_new = T_old + n, L_old = v.kept_len[pair];
+    const int r0 = max(0, T_old - v.w);
+    const int r1 = min(T_old, max(0, T_new - v.w));
+    const int nr = max(0, r1 - r0);
+    const int n_ev = max(0, n - v.w);
+    const int nseg = (n_ev + kSegTokens - 1) / kSegTokens;
+    const float* rl = v.ring_logit + (size_t)pair * v.w;
+    __shared__ int s_wave[4];
+    __shared__ int s_first, s_need, s_base, s_ok;
+
+    int cnt = 0;
+    for (int base = 0; base < nr; base += 256) {
+        const int idx = base + tid;
+        const bool flag = idx < nr && rl[(r0 + idx) % v.w] >= v.theta;
+        cnt += __popcll(__ballot(flag));
+    }
+    if (lane == 0) s_wave[wave] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+        const int ring_kept = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+        int acc = 0;
+        int32_t* sc = v.seg_count + (size_t)pair * v.n_seg_cap;
+        for (int sgi = 0; sgi < nseg; ++sgi) {
+            const int c = sc[sgi];
+            sc[sgi] = acc;
+            acc += c;
+        }
+        const int total_new = ring_kept + acc;
+        const int first = (L_old + kPageTokens - 1) / kPageTokens;
+        const int last = (L_old + total_new + kPageTokens - 1) / kPageTokens;
+        const int need = last - first;
+        int base = 0, ok = 1;
+        if (last > v.pt_cap) ok = 0;
+        if (ok && need > 0) {
+            base = atomicAdd(v.pool_next, need);
+            if (base + need > v.n_pages) ok = 0;
+        }
+        if (!ok) *v.err_flag = 1;
+        s_first = first;
+        s_need = ok ? need : 0;
+        s_base = base;
+        s_ok = ok;
+        int32_t* bi = v.bulk_info + (size_t)pair * 4;
+        bi[0] = T_old;
+        bi[1] = L_old + ring_kept;
+        bi[2] = ok;
+        if (ok) v.kept_len[pair] = L_old + total_new;
+    }
+    __syncthreads();
+    const int ok = s_ok;
+    for (int i = tid; i < s_need; i += 256)
+        v.page_table[(size_t)pair * v.pt_cap + s_first + i] = s_base + i;
+    __threadfence_block();
+    __syncthreads();
+
+    int carry = 0;
+    for (int base = 0; base < nr; base += 256) {
+        const int idx = base + tid;
+        const bool flag = idx < nr && rl[(r0 + idx) % v.w] >= v.theta;
+        const unsigned long long mask = __ballot(flag);
+        __syncthreads();
+        if (lane == 0) s_wave[wave] = __popcll(mask);
+        __syncthreads();
+        int woff = 0, ctot = 0;
+        for (int i = 0; i < 4; ++i) {
+            if (i < wave) woff += s_wave[i];
+            ctot += s_wave[i];
+        }
+        if (ok) {
+            unsigned long long m = mask;
+            int c = 0;
+            while (m) {
+                const int bit = __ffsll((long long)m) - 1;
+                m &= m - 1;
+                const int s = r0 + base + wave * 64 + bit;
+                const int slot = s % v.w;
+                const int gi = L_old + carry + woff + c;
+                ++c;
+                const int page = v.page_table[(size_t)pair * v.pt_cap + (gi >> 6)];
+                copy_row_paged<D>(ring_page(v, pair, slot >> 6), slot & 63, pool_page(v, page),
+                                  gi & 63, lane);
+                if (lane == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = s;
+            }
+        }
+        carry += ctot;
+    }
+    if (tid == 0) v.t_pair[pair] = T_new;
+}
+
+// Stage 3: per (segment, pair).  Recomputes the keep flags of the segment's tokens,
+// ranks them (ballot + mbcnt within a wave, popcount prefix across the 16 wave-steps of
+// the segment, segment offset from stage 2) and copies kept rows into the long-term pages;
+// writes the last min(n, w) tokens into the ring.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint16_t* __restrict__ k,
+                                                         const uint16_t* __restrict__ vv,
+                                                         const float* __restrict__ f, SpkvCu cu) {
+    const int pair = blockIdx.y, seg = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b];
+    const int n = cu.v[b + 1] - row0;
+    const int j0 = seg * kSegTokens;
+    if (j0 >= n) return;
+    const int32_t* bi = v.bulk_info + (size_t)pair * 4;
+    if (bi[2] == 0) return;
+    const int T_old = bi[0], Lbase = bi[1];
+    const int n_ev = max(0, n - v.w);
+    const int seg_off = (j0 < n_ev) ? v.seg_count[(size_t)pair * v.n_seg_cap + seg] : 0;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ int s_cnt[16];
+
+    unsigned long long masks[4];
+    int gate_cnt = 0;
+#pragma unroll
+    for (int gi = 0; gi < 4; ++gi) {
+        const int g = wave * 4 + gi;
+        const int j = j0 + g * 64 + lane;
+        const bool on = j < n && f[((size_t)row0 + j) * v.Hkv + h] >= v.theta;
+        gate_cnt += __popcll(__ballot(on));
+        masks[gi] = __ballot(on && j < n_ev);
+        if (lane == 0) s_cnt[g] = __popcll(masks[gi]);
+    }
+    if (lane == 0 && gate_cnt) atomicAdd(v.gate_on + pair, gate_cnt);
+    __syncthreads();
+
+    for (int gi = 0; gi < 4; ++gi) {
+        const int g = wave * 4 + gi;
+        const int jg = j0 + g * 64;
+        if (jg >= n) break;
+        int prefix = 0;
+        for (int i = 0; i < g; ++i) prefix += s_cnt[i];
+        unsigned long long m = masks[gi];
+        int c = 0;
+        while (m) {
+            const int bit = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const int j = jg + bit;
+            const int gidx = Lbase + seg_off + prefix + c;
+            ++c;
+            const int page = v.page_table[(size_t)pair * v.pt_cap + (gidx >> 6)];
+            const size_t src = ((size_t)(row0 + j) * v.Hkv + h) * D;
+            copy_row_dense<D>(k + src, vv + src, pool_page(v, page), gidx & 63, lane);
+            if (lane == 0) v.pos_pool[(size_t)page * kPageTokens + (gidx & 63)] = T_old + j;
+        }
+        const int ja = max(jg, n_ev), jb = min(n, jg + 64);
+        for (int j = ja; j < jb; ++j) {
+            const int slot = (T_old + j) % v.w;
+            const size_t src = ((size_t)(row0 + j) * v.Hkv + h) * D;
+            copy_row_dense<D>(k + src, vv + src, ring_page(v, pair, slot >> 6), slot & 63, lane);
+            if (lane == 0)
+                v.ring_logit[(size_t)pair * v.w + slot] = f[((size_t)row0 + j) * v.Hkv + h];
+        }
+    }
+}
+
+hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const SpkvCu& cu, int n_max, hipStream_t s) {
+    const int n_ev_max = n_max - v.w;
+    if (n_ev_max > 0) {
+        const int segs = (n_ev_max + kSegTokens - 1) / kSegTokens;
+        spkv_bulk_count<<<dim3(segs, v.n_pairs), dim3(256), 0, s>>>(v, f, cu);
+    }
+    const int segs_all = (n_max + kSegTokens - 1) / kSegTokens;
+    if (v.D == 128) {
+        spkv_bulk_ring<128><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu);
+        spkv_bulk_scatter<128><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu);
+    } else {
+        spkv_bulk_ring<64><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu);
+        spkv_bulk_scatter<64><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------- scheduler
+// Work unit: a half-page (32 keys).  Pair p has ceil(L/32) long-term half-pages followed
+// by ceil(min(T, w)/32) ring half-pages.  All pairs are cut into items of about
+// total / item_target half-pages, each pair split evenly, so that the split-K grid is
+// balanced over the kept lengths whatever their spread.
+__device__ __forceinline__ int pair_half_pages(const SpkvView& v, int p) {
+    const int L = v.kept_len[p];
+    const int Tw = min(v.t_pair[p], v.w);
+    return ((L + kHalfTokens - 1) >> 5) + ((Tw + kHalfTokens - 1) >> 5);
+}
+
+__global__ __launch_bounds__(256) void spkv_schedule(SpkvView v, int item_target) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ long long s_red[4];
+    __shared__ int s_w[4];
+    long long local = 0;
+    for (int p = tid; p < v.n_pairs; p += 256) local += pair_half_pages(v, p);
+    for (int o = 32; o > 0; o >>= 1) local += __shfl_xor(local, o);
+    if (lane == 0) s_red[wave] = local;
+    __syncthreads();
+    const long long total = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+    int cb = (int)((total + item_target - 1) / item_target);
+    if (cb < 1) cb = 1;
+
+    int carry = 0;
+    for (int base = 0; base < v.n_pairs; base += 256) {
+        const int p = base + tid;
+        const int nhp = p < v.n_pairs ? pair_half_pages(v, p) : 0;
+        const int it = (nhp + cb - 1) / cb;
+        int incl = it;                                   // inclusive scan inside the wave
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        __syncthreads();
+        if (lane == 63) s_w[wave] = incl;
+        __syncthreads();
+        int woff = 0, ctot = 0;
+        for (int i = 0; i < 4; ++i) {
+            if (i < wave) woff += s_w[i];
+            ctot += s_w[i];
+        }
+        const int excl = carry + woff + incl - it;
+        if (p < v.n_pairs) {
+            v.item_start[p] = excl;
+            for (int j = 0; j < it; ++j) {
+                if (excl + j >= v.max_items) { *v.err_flag = 2; break; }
+                const int hb = (int)((long long)nhp * j / it);
+                const int he = (int)((long long)nhp * (j + 1) / it);
+                v.items[excl + j] = make_int4(p, hb, he, 0);
+            }
+        }
+        carry += ctot;
+    }
+    if (tid == 0) {
+        v.item_start[v.n_pairs] = carry;
+        *v.n_items = min(carry, v.max_items);
+    }
+}
+
+hipError_t spkv_launch_schedule(const SpkvView& v, int item_target, hipStream_t s) {
+    spkv_schedule<<<dim3(1), dim3(256), 0, s>>>(v, item_target);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------- split-K decode
+// One wavefront per work item.  For each half-page (32 keys) of the item:
+//   S[key][head]   = K[key][:] . Q[head][:]          2 x D/32 MFMA 16x16x32 (bf16 -> fp32)
+//   online softmax in the log2 domain (running max m, sum l), weights rounded to bf16
+//   O[d][head]    += V[key][d] * P[key][head]        D/16 MFMA 16x16x32
+// The G <= 16 query heads of the GQA group are the N = 16 columns of every MFMA, so each
+// K/V tile is read exactly once per group.  Every wave-wide load is 1 KB contiguous.
+template <int D>
+__global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
+                                                        float scale_log2e) {
+    constexpr int NS = D / 32;   // head-dim slabs of one K tile
+    constexpr int NB = D / 16;   // 16-wide output blocks
+    const int item = blockIdx.x;
+    if (item >= *v.n_items) return;
+    const int4 it = v.items[item];
+    const int pair = it.x, hp0 = it.y, hp1 = it.z;
+    const int L = v.kept_len[pair];
+    const int Tw = min(v.t_pair[pair], v.w);
+    const int ghp = (L + kHalfTokens - 1) >> 5;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int lane = threadIdx.x, kc = lane >> 4, n = lane & 15;
+
+    bf16x8 qb[NS];
+    {
+        const uint16_t* qrow = q + ((size_t)b * v.Hq + (size_t)h * v.G + n) * D + kc * 8;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            uint4 raw = {0u, 0u, 0u, 0u};
+            if (n < v.G) raw = *reinterpret_cast<const uint4*>(qrow + sl * 32);
+            qb[sl] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    f32x4 acc[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m = SPKV_NEG_INF, l = 0.f;
+
+    for (int hp = hp0; hp < hp1; ++hp) {
+        const uint16_t* base;
+        int nvalid;
+        if (hp < ghp) {
+            const int page = v.page_table[(size_t)pair * v.pt_cap + (hp >> 1)];
+            base = pool_page(v, page) + (hp & 1) * (2 * kHalfTokens * D);
+            nvalid = min(kHalfTokens, L - hp * kHalfTokens);
+        } else {
+            const int r = hp - ghp;
+            base = ring_page(v, pair, r >> 1) + (r & 1) * (2 * kHalfTokens * D);
+            nvalid = min(kHalfTokens, Tw - r * kHalfTokens);
+        }
+        const uint16_t* kp = base + lane * 8;
+        const uint16_t* vp = base + kHalfTokens * D + lane * 8;
+        bf16x8 ka[2][NS], va[NB];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl)
+                ka[t][sl] = *reinterpret_cast<const bf16x8*>(kp + (t * (D / 8) + sl * 4) * 128);
+#pragma unroll
+        for (int db = 0; db < NB; ++db)
+            va[db] = *reinterpret_cast<const bf16x8*>(vp + db * 512);
+
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][sl], qb[sl], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][sl], qb[sl], s1, 0, 0, 0);
+        }
+        // Lane (kc, n) now holds, for head n, the keys r = 16 t + 4 kc + i of the half-page.
+        float x[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[i] = s0[i] * scale_log2e;
+            x[4 + i] = s1[i] * scale_log2e;
+        }
+        if (nvalid < kHalfTokens) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int r = (e >> 2) * 16 + kc * 4 + (e & 3);
+                if (r >= nvalid) x[e] = SPKV_NEG_INF;
+            }
+        }
+        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                         fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        f32x8 p;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
+            psum += p[e];
+        }
+        l = l * alpha + psum;
+        if (__ballot(m_new != m) != 0ull) {
+#pragma unroll
+            for (int db = 0; db < NB; ++db) acc[db] *= alpha;
+        }
+        m = m_new;
+        const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+#pragma unroll
+        for (int db = 0; db < NB; ++db)
+            acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[db], pb, acc[db], 0, 0, 0);
+    }
+
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (n < v.G) {
+        float* pa = v.part_acc + ((size_t)item * v.G + n) * D + kc * 4;
+#pragma unroll
+        for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[db];
+        if (kc == 0) {
+            float* pm = v.part_ml + ((size_t)item * v.G + n) * 2;
+            pm[0] = m;
+            pm[1] = l;
+        }
+    }
+}
+
+// Merge the partials of one (sequence, query head): with M = max_i m_i,
+//   out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i,  lse = (M + log2(sum)) ln 2.
+template <int D>
+__global__ __launch_bounds__(D) void spkv_decode_combine(SpkvView v, uint16_t* __restrict__ out,
+                                                         float* __restrict__ lse) {
+    const int pair = blockIdx.x / v.G, g = blockIdx.x - pair * v.G;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int d = threadIdx.x;
+    const int i0 = v.item_start[pair], i1 = min(v.item_start[pair + 1], v.max_items);
+    float M = SPKV_NEG_INF;
+    for (int i = i0; i < i1; ++i) M = fmaxf(M, v.part_ml[((size_t)i * v.G + g) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int i = i0; i < i1; ++i) {
+        const float* pm = v.part_ml + ((size_t)i * v.G + g) * 2;
+        const float wgt = __builtin_amdgcn_exp2f(pm[0] - M);
+        den += wgt * pm[1];
+        num += wgt * v.part_acc[((size_t)i * v.G + g) * D + d];
+    }
+    const size_t o = ((size_t)b * v.Hq + (size_t)h * v.G + g);
+    const __bf16 r = (__bf16)(num / den);
+    out[o * D + d] = __builtin_bit_cast(uint16_t, r);
+    if (lse != nullptr && d == 0) lse[o] = (M + __builtin_log2f(den)) * 0.6931471805599453f;
+}
+
+hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
+                              float sm_scale, int grid_items, hipEvent_t ev0, hipEvent_t ev1,
+                              hipStream_t s) {
+    const float scale_log2e = sm_scale * 1.4426950408889634f;
+    hipError_t e;
+    if (ev0 != nullptr && (e = hipEventRecord(ev0, s)) != hipSuccess) return e;
+    if (v.D == 128)
+        spkv_decode_split<128><<<dim3(grid_items), dim3(64), 0, s>>>(v, q, scale_log2e);
+    else
+        spkv_decode_split<64><<<dim3(grid_items), dim3(64), 0, s>>>(v, q, scale_log2e);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
+    if (v.D == 128)
+        spkv_decode_combine<128><<<dim3(v.n_pairs * v.G), dim3(128), 0, s>>>(v, out, lse);
+    else
+        spkv_decode_combine<64><<<dim3(v.n_pairs * v.G), dim3(64), 0, s>>>(v, out, lse);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------ kept positions (debug)
+__global__ __launch_bounds__(256) void spkv_gather_positions(SpkvView v, int pair) {
+    const int L = v.kept_len[pair];
+    for (int gi = blockIdx.x * blockDim.x + threadIdx.x; gi < L; gi += gridDim.x * blockDim.x) {
+        const int page = v.page_table[(size_t)pair * v.pt_cap + (gi >> 6)];
+        v.pos_scratch[gi] = v.pos_pool[(size_t)page * kPageTokens + (gi & 63)];
+    }
+}
+
+hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s) {
+    spkv_gather_positions<<<dim3(64), dim3(256), 0, s>>>(v, pair);
+    return hipGetLastError();
+}

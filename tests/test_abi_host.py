@@ -1,0 +1,105 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/spkv.h declares,
+validates configurations, and its page layout is the MFMA operand order it claims."""
+
+import ctypes as C
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_14037_amd as spkv
+from oracle.spkv_oracle import threshold_logit
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "spkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spkv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = spkv.load_library()
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert getattr(lib, n) is not None, n
+    assert sorted(spkv.EXPORTED_SYMBOLS) == names
+
+
+def test_strerror_covers_all_codes():
+    texts = {spkv.strerror(c) for c in range(0, -7, -1)}
+    assert len(texts) == 7 and "unknown error" not in texts
+    assert spkv.strerror(-99) == "unknown error"
+
+
+def _cfg(**kw):
+    base = dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=64, window=128, page_tokens=0,
+                tau=0.5, max_context=4096, max_total_kept_tokens=8192)
+    base.update(kw)
+    return spkv.SPKVConfig(**base)
+
+
+def test_required_bytes_validates_and_grows():
+    base = spkv.required_bytes(_cfg())
+    assert base > 0 and base % 256 == 0
+    assert spkv.required_bytes(_cfg(max_total_kept_tokens=16384)) > base
+    assert spkv.required_bytes(_cfg(batch=4)) > base
+    for bad in (dict(batch=0), dict(batch=513), dict(n_q_heads=7), dict(head_dim=96),
+                dict(window=0), dict(page_tokens=32), dict(tau=float("nan")),
+                dict(max_context=0), dict(max_total_kept_tokens=-1),
+                dict(n_q_heads=34, n_kv_heads=2)):
+        assert spkv.required_bytes(_cfg(**bad)) == 0, bad
+    # the pool term: 64 pairs * (K row + V row) per page
+    more = spkv.required_bytes(_cfg(max_total_kept_tokens=8192 + 64 * 100))
+    assert more - base >= 100 * 64 * 2 * 64 * 2
+
+
+def test_create_rejects_bad_arguments_without_a_gpu():
+    lib = spkv.load_library()
+    h = C.c_void_p()
+    cfg = _cfg()
+    assert lib.spkv_cache_create(C.byref(cfg), None, 1 << 30, None, C.byref(h)) == -1
+    assert lib.spkv_cache_create(C.byref(cfg), C.c_void_p(256), 16, None, C.byref(h)) == -1
+    assert lib.spkv_cache_create(C.byref(cfg), C.c_void_p(8), 1 << 30, None, C.byref(h)) == -1
+    bad = _cfg(head_dim=32)
+    assert lib.spkv_cache_create(C.byref(bad), C.c_void_p(256), 1 << 30, None, C.byref(h)) == -1
+    assert lib.spkv_cache_destroy(None) == -1
+    assert lib.spkv_decode_attention(None, None, None, None, 0.0, None) == -1
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_page_layout_is_a_bijection_in_mfma_operand_order(D):
+    n = 64 * D
+    koff = np.array([[spkv.layout_offset(D, 0, kidx, d) for d in range(D)] for kidx in range(64)])
+    voff = np.array([[spkv.layout_offset(D, 1, kidx, d) for d in range(D)] for kidx in range(64)])
+    both = np.concatenate([koff.ravel(), voff.ravel()])
+    assert sorted(both.tolist()) == list(range(2 * n))            # K and V tile the page exactly
+    for half in range(2):
+        lo = half * 2 * 32 * D
+        ks = koff[half * 32:(half + 1) * 32]
+        vs = voff[half * 32:(half + 1) * 32]
+        assert ks.min() == lo and ks.max() == lo + 32 * D - 1     # K block, then V block
+        assert vs.min() == lo + 32 * D and vs.max() == lo + 64 * D - 1
+        # K tile (t, slab): lane (kc, kk) holds d = 32 slab + 8 kc + e of key 16 t + kk at
+        # byte 16 * lane of a 1 KB tile.
+        for t in range(2):
+            for slab in range(D // 32):
+                tile = lo + (t * (D // 8) + slab * 4) * 128
+                for lane in range(64):
+                    kc, kk = lane // 16, lane % 16
+                    for e in range(8):
+                        assert koff[half * 32 + 16 * t + kk, 32 * slab + 8 * kc + e] == tile + lane * 8 + e
+        # V tile db: lane (kc, dr) holds keys 16 t + 4 kc + i (element 4 t + i) of d = 16 db + dr.
+        for db in range(D // 16):
+            tile = lo + 32 * D + db * 512
+            for lane in range(64):
+                kc, dr = lane // 16, lane % 16
+                for t in range(2):
+                    for i in range(4):
+                        assert voff[half * 32 + 16 * t + 4 * kc + i, 16 * db + dr] == tile + lane * 8 + 4 * t + i
+    assert spkv.layout_offset(D, 0, 64, 0) == -1 and spkv.layout_offset(D, 1, 0, D) == -1
+    assert spkv.layout_offset(96, 0, 0, 0) == -1

@@ -1,0 +1,231 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element.
+
+Kept positions, lengths and stats must match bit for bit; outputs within
+|gpu - ref| <= 1e-2 + 1e-2 |ref| (bf16 inputs, fp32 accumulation, bf16 output)."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_14037_amd as spkv
+from oracle.spkv_oracle import SPKVOracle, threshold_logit
+from paper_2605_14037_amd.inputs import (TokenStream, small_workload, to_numpy_f32, workload)
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg1_every_step():
+    """Config 1: prefill 2048 tokens, then 64 append+decode steps, all checked."""
+    m = H.run_workload(workload("cfg1"), chunk=512)
+    assert len(m) == 64
+
+
+@pytest.mark.parametrize("ctx,w", [(1, 128), (5, 128), (127, 128), (128, 128), (129, 128),
+                                   (200, 128), (31, 32), (33, 32), (700, 100), (90, 1),
+                                   (300, 8), (1000, 512), (64, 64), (65, 64)])
+def test_window_edges(ctx, w):
+    """T < w, T = w, T = w + 1, windows that are not a multiple of the 32-key half-page."""
+    wl = small_workload("edge", 2, 8, 2, 64, [ctx, max(1, ctx // 2)], [[0.5, 0.2]], window=w,
+                        decode_steps=3, seed=ctx * 1000 + w)
+    H.run_workload(wl, chunk=4096)
+
+
+@pytest.mark.parametrize("D,Hq,Hkv", [(64, 2, 2), (64, 8, 2), (128, 32, 8), (128, 8, 1),
+                                      (128, 16, 1), (64, 16, 2)])
+def test_head_shapes(D, Hq, Hkv):
+    """head_dim 64 / 128 and group sizes 1, 4, 8, 16."""
+    wl = small_workload("heads", 3, Hq, Hkv, D, [900, 130, 417], 0.3, decode_steps=2,
+                        seed=D + Hq + Hkv)
+    H.run_workload(wl, chunk=512)
+
+
+@pytest.mark.parametrize("tau,keep", [(0.0, 0.5), (1.0, 0.5), (0.3, 0.5), (0.9, 0.6),
+                                      (0.5, 1.0), (0.5, 0.0)])
+def test_thresholds_all_and_none(tau, keep):
+    """tau <= 0 keeps everything (dense cache), tau >= 1 keeps nothing (window only)."""
+    wl = small_workload("tau", 2, 8, 2, 128, [1500, 777], keep, tau=tau, decode_steps=2,
+                        seed=int(tau * 100) + int(keep * 10))
+    H.run_workload(wl, chunk=1024)
+
+
+def test_threshold_value_matches_oracle_bits():
+    for tau in (0.01, 0.1, 0.3, 0.5, 0.7, 0.9, 0.99, 0.0, 1.0):
+        c = spkv.SPKVCache(1, 1, 1, 64, 256, 256, tau=tau)
+        assert np.float32(c.threshold_logit()).tobytes() == threshold_logit(tau).tobytes(), tau
+        c.close()
+
+
+def test_gate_equality_is_kept():
+    """A logit exactly equal to theta passes the gate (Eq. 2 uses >=)."""
+    B, Hq, Hkv, D, w = 1, 1, 1, 64, 4
+    T = 40
+    g = torch.Generator(device="cuda").manual_seed(5)
+    k = torch.randn(T, Hkv, D, generator=g, device="cuda").to(torch.bfloat16)
+    v = torch.randn(T, Hkv, D, generator=g, device="cuda").to(torch.bfloat16)
+    f = torch.full((T, Hkv), -1.0, device="cuda")
+    f[3] = 0.0
+    f[7] = -0.0
+    f[9] = float("nan")
+    cache = spkv.SPKVCache(B, Hq, Hkv, D, 64, 64, window=w, tau=0.5)
+    oracle = SPKVOracle(B, Hq, Hkv, D, window=w, tau=0.5)
+    H.feed(cache, oracle, k, v, f, [0, T])
+    assert cache.kept_positions(0, 0) == [3, 7] == oracle.kept_positions(0, 0).tolist()
+    q = torch.randn(B, Hq, D, generator=g, device="cuda").to(torch.bfloat16)
+    H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0])
+    cache.close()
+
+
+def test_incremental_equals_bulk():
+    """Appending one token at a time and in bulk build the same cache."""
+    wl = small_workload("inc", 2, 8, 2, 64, [333, 150], 0.4, seed=77)
+    stream = TokenStream(wl, device="cuda")
+    k, v, f, cu = stream.next_tokens(wl.ctx_lens)
+    bulk, inc, mixed = H.make_cache(wl), H.make_cache(wl), H.make_cache(wl)
+    bulk.append(k, v, f, cu)
+    for step in range(max(wl.ctx_lens)):
+        rows = [cu[b] + step for b in range(wl.batch) if step < wl.ctx_lens[b]]
+        c = np.concatenate([[0], np.cumsum([1 if step < n else 0 for n in wl.ctx_lens])]).tolist()
+        inc.append(k[rows].contiguous(), v[rows].contiguous(), f[rows].contiguous(), c)
+    # mixed: ragged chunks of 1, 70, 129, 2, rest
+    done = [0, 0]
+    for n in (1, 70, 129, 2, 10 ** 6):
+        counts = [min(n, wl.ctx_lens[b] - done[b]) for b in range(2)]
+        rows = [cu[b] + done[b] + i for b in range(2) for i in range(counts[b])]
+        c = [0, counts[0], counts[0] + counts[1]]
+        if rows:
+            mixed.append(k[rows].contiguous(), v[rows].contiguous(), f[rows].contiguous(), c)
+        done = [done[b] + counts[b] for b in range(2)]
+    q = stream.next_query()
+    outs = [c.decode_attention(q, want_lse=True) for c in (bulk, inc, mixed)]
+    oracle = H.make_oracle(wl)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    for c in (bulk, inc, mixed):
+        H.check_state(c, oracle, wl)
+    for o, l in outs:
+        assert torch.equal(o, outs[0][0]) and torch.equal(l, outs[0][1])
+    H.check_output(outs[0][0], oracle.decode(to_numpy_f32(q))[0])
+    for c in (bulk, inc, mixed):
+        c.close()
+
+
+def test_sequences_that_skip_a_step():
+    """cu_seqlens may give a sequence no token in a step."""
+    wl = small_workload("skip", 3, 4, 2, 64, [140, 150, 160], 0.5, seed=3)
+    stream = TokenStream(wl, device="cuda")
+    cache, oracle = H.make_cache(wl, extra_context=16), H.make_oracle(wl)
+    H.prefill(cache, oracle, stream, wl, 64)
+    for counts in ([1, 0, 1], [0, 0, 1], [1, 1, 0], [0, 0, 0], [1, 1, 1]):
+        k, v, f, cu = stream.next_tokens(counts)
+        H.feed(cache, oracle, k, v, f, cu)
+        q = stream.next_query()
+        H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0], str(counts))
+        H.check_state(cache, oracle, wl, label=str(counts))
+    cache.close()
+
+
+def test_peaked_scores():
+    """Queries scaled x4: a few keys dominate and outputs are O(1)."""
+    wl = small_workload("peaked", 2, 8, 2, 128, [3000, 1000], 0.25, decode_steps=2, seed=9)
+    m = H.run_workload(wl, chunk=1024, q_gain=4.0)
+    assert all(x["rel_l2"] < H.REL_L2_MAX for x in m)
+
+
+def test_split_count_invariance():
+    """The number of split-K work items does not change indices, and changes outputs only
+    by fp32 rounding."""
+    wl = small_workload("split", 2, 8, 2, 128, [6000, 2500], 0.3, seed=21)
+    stream = TokenStream(wl, device="cuda")
+    k, v, f, cu = stream.next_tokens(wl.ctx_lens)
+    q = stream.next_query()
+    oracle = H.make_oracle(wl)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    ref = oracle.decode(to_numpy_f32(q))[0]
+    outs = []
+    for target in (1, 2, 7, 64, 4096, 16384):
+        cache = H.make_cache(wl)
+        cache.set_option(spkv.OPT_ITEM_TARGET, target)
+        cache.append(k, v, f, cu)
+        out = cache.decode_attention(q)
+        st = H.check_state(cache, oracle, wl, label=f"target {target}")
+        assert st.n_work_items >= wl.batch * wl.n_kv_heads
+        if target == 1:
+            assert st.n_work_items == wl.batch * wl.n_kv_heads
+        H.check_output(out, ref, f"target {target}")
+        outs.append(out.float())
+        cache.close()
+    for o in outs[1:]:
+        assert (o - outs[0]).abs().max().item() <= 2e-2 * max(1.0, outs[0].abs().max().item())
+
+
+def test_errors_from_the_host_side():
+    wl = small_workload("err", 2, 4, 2, 64, [10, 10], 1.0, seed=1)
+    stream = TokenStream(wl, device="cuda")
+    cache = spkv.SPKVCache(2, 4, 2, 64, max_context=300, max_total_kept_tokens=64, window=16,
+                           tau=0.0)
+    q = stream.next_query()
+    with pytest.raises(spkv.SPKVError) as e:                 # nothing appended yet
+        cache.decode_attention(q)
+    assert e.value.code == -2
+    k, v, f, cu = stream.next_tokens([200, 0])
+    with pytest.raises(spkv.SPKVError) as e:                 # 184 pairs pushed out, all kept, pool holds 64 (+1 page/pair)
+        cache.append(k, v, f, cu)
+    assert e.value.code == -3
+    k2, v2, f2, cu2 = stream.next_tokens([301, 1])
+    with pytest.raises(spkv.SPKVError) as e:                 # beyond max_context
+        cache.append(k2, v2, f2, cu2)
+    assert e.value.code == -3
+    st = cache.stats()
+    assert st.total_tokens == 0 and st.kept_tokens == 0      # failed calls changed nothing
+    k3, v3, f3, cu3 = stream.next_tokens([40, 30])
+    cache.append(k3, v3, f3, cu3)
+    oracle = SPKVOracle(2, 4, 2, 64, window=16, tau=0.0)
+    oracle.append(to_numpy_f32(k3), to_numpy_f32(v3), to_numpy_f32(f3), cu3)
+    H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0])
+    with pytest.raises(ValueError):
+        cache.decode_attention(q.float())
+    cache.close()
+
+
+def test_capacity_bound_refreshes_from_device():
+    """The host's worst-case bound trips long before the pool is full when few pairs are
+    kept; it must then re-read the true lengths instead of refusing."""
+    wl = small_workload("cap", 2, 4, 2, 64, [0, 0], 0.1, window=16, seed=4)
+    wl.ctx_lens = [4000, 3000]
+    stream = TokenStream(wl, device="cuda")
+    cache = spkv.SPKVCache(2, 4, 2, 64, max_context=4100, max_total_kept_tokens=4096,
+                           window=16, tau=0.5)
+    oracle = SPKVOracle(2, 4, 2, 64, window=16, tau=0.5)
+    H.prefill(cache, oracle, stream, wl, 256)               # 14k pairs pushed out, ~1.4k kept
+    for _ in range(50):
+        k, v, f, cu = stream.next_tokens([1, 1])
+        H.feed(cache, oracle, k, v, f, cu)
+    st = H.check_state(cache, oracle, wl)
+    assert st.kept_tokens < 4096
+    q = stream.next_query()
+    H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0])
+    cache.close()
+
+
+def test_reset_reuses_the_arena():
+    wl = small_workload("reset", 2, 8, 2, 64, [500, 300], 0.5, seed=6)
+    stream = TokenStream(wl, device="cuda")
+    cache = H.make_cache(wl)
+    k, v, f, cu = stream.next_tokens(wl.ctx_lens)
+    cache.append(k, v, f, cu)
+    cache.reset()
+    assert cache.stats().total_tokens == 0
+    k, v, f, cu = stream.next_tokens([70, 20])
+    oracle = H.make_oracle(wl)
+    H.feed(cache, oracle, k, v, f, cu)
+    q = stream.next_query()
+    H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0])
+    H.check_state(cache, oracle, wl)
+    cache.close()
+
+
+def test_medium_ragged_batch():
+    """Several pages per head, ragged tails, dense and window-only heads side by side."""
+    keep = np.array([[1.0, 0.0, 0.3, 0.05], [0.2, 1.0, 0.0, 0.5], [0.1, 0.1, 0.9, 0.0]])
+    wl = small_workload("ragged", 3, 16, 4, 128, [9000, 2049, 4500], keep, decode_steps=3, seed=8)
+    H.run_workload(wl, chunk=2048)

@@ -340,8 +340,8 @@ class _WrongGroup(SPKVOracle):               # query head j reads KV head j % H_
 
 
 class _TransposedPV(SPKVOracle):             # weights applied with K instead of V
-    def _decode_pair(self, b, h, q_bh):
-        out, lse = super()._decode_pair(b, h, q_bh)
+    def decode_pair(self, b, h, q_bh):
+        out, lse = super().decode_pair(b, h, q_bh)
         K = self._k(b)[:, h, :].astype(np.float64)
         V = self._v(b)[:, h, :].astype(np.float64)
         avail = self.available(b, h)
