@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""SP-KV decode benchmark on one MI355X.
+
+A step is one pass of the whole hot path over one batch: spkv_append of one new token per
+sequence (gate, ring write, evict + compact) followed by spkv_decode_attention (schedule,
+split-K MFMA decode, log-sum-exp combine).  Inputs are synthetic, seeded and resident in
+HBM before the timed region.  The workload is the Llama-3-8B-shaped layer: batch 16,
+32 query / 8 KV heads, head_dim 128, context 32768, window 128, tau 0.5, per-head keep
+rates U[0.10, 0.33].  Several independent cache instances are rotated so that the working
+set is far larger than the 256 MB Infinity Cache and every step reads its K/V from HBM.
+
+Prints ONE JSON line (see README for the fields).
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2605_14037_amd as spkv  # noqa: E402
+from paper_2605_14037_amd.inputs import (TokenStream, Workload, prefill_chunks,  # noqa: E402
+                                         to_numpy_f32, workload)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def build_cache(wl: Workload, instance: int, chunk: int, tau=None, oracle=None, oracle_seqs=0):
+    """Prefill one cache instance with its own seeded data; optionally mirror the first
+    `oracle_seqs` sequences into an oracle."""
+    tau = wl.tau if tau is None else tau
+    if tau <= 0.0:
+        pool = sum(max(0, c + 4096 - wl.window) for c in wl.ctx_lens) * wl.n_kv_heads
+    else:
+        pool = int(wl.expected_kept_tokens() * 1.08) + wl.batch * wl.n_kv_heads * (chunk + 256)
+    cache = spkv.SPKVCache(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
+                           max_context=max(wl.ctx_lens) + 4096, max_total_kept_tokens=pool,
+                           window=wl.window, tau=tau)
+    stream = TokenStream(wl, device="cuda", layer=instance)
+    for counts in prefill_chunks(wl.ctx_lens, chunk):
+        k, v, f, cu = stream.next_tokens(counts)
+        cache.append(k, v, f, cu)
+        if oracle is not None:
+            n = cu[oracle_seqs]
+            oracle.append(to_numpy_f32(k[:n]), to_numpy_f32(v[:n]), to_numpy_f32(f[:n]),
+                          cu[:oracle_seqs + 1])
+    return cache, stream
+
+
+HOST_ISSUE_S = []      # host time spent issuing each timed region (before the final sync)
+
+
+def timed_steps(caches, steps_in, n_steps, offset, do_append=True, do_decode=True):
+    """n_steps steps, rotating over the cache instances; returns seconds."""
+    R = len(caches)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n_steps):
+        j = offset + i
+        c = caches[j % R]
+        k, v, f, cu, q, out = steps_in[j % len(steps_in)]
+        if do_append:
+            c.append(k, v, f, cu)
+        if do_decode:
+            c.decode_attention(q, out=out)
+    t1 = time.perf_counter()
+    torch.cuda.synchronize()
+    HOST_ISSUE_S.append((t1 - t0) / max(1, n_steps))
+    return time.perf_counter() - t0
+
+
+def read_traffic_summary():
+    """HBM bytes per launch of the split-K kernel from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size), if present."""
+    path = os.path.join(ROOT, "profiles", "decode_split_cfg2_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(wl, oracle, q, seqs, kept_bytes_sample, repeats=3):
+    from oracle.spkv_oracle import SPKVOracle  # noqa: F401  (the oracle is only used here)
+    workers = max(1, min(16, os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16"))))
+    qn = to_numpy_f32(q[:seqs])
+    best = None
+    for _ in range(repeats):
+        t0 = time.perf_counter()
+        oracle.decode(qn, workers=workers)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    return {
+        "value": kept_bytes_sample / best / 1e9, "unit": "GB/s", "cores": workers,
+        "kind": "oracle",
+        "sample": (f"fp64 oracle, one decode step (attention over the dense history under the "
+                   f"explicit mask) for the first {seqs} of {wl.batch} sequences x {wl.n_kv_heads} "
+                   f"KV heads of instance 0, best of {repeats}; GB/s counts the same kept-KV bytes "
+                   f"as the GPU figure for those sequences"),
+        "seconds_per_step_sample": best,
+        "us_per_step_extrapolated": best * wl.batch / seqs * 1e6,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--instances", type=int, default=0, help="cache instances to rotate (0 = auto)")
+    ap.add_argument("--item-target", type=int, default=0)
+    ap.add_argument("--chunk", type=int, default=1024, help="prefill chunk (tokens per sequence)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=4)
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="run only the plain 1 GiB copy kernel 20 times (profiler calibration)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (every sequence and "
+              "KV head is independent; see DESIGN.md for how it would shard). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    spkv.load_library()
+
+    if args.copy_reference:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            spkv.debug_copy(dst, src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 20
+        print(json.dumps({"copy_reference_bytes_read": 1 << 30, "bytes_written": 1 << 30,
+                          "us_per_copy": dt * 1e6, "GBps_read_plus_write": 2 * (1 << 30) / dt / 1e9}))
+        return
+
+    wl = workload(args.workload)
+    exp_bytes = (wl.expected_kept_tokens() + wl.batch * wl.n_kv_heads * wl.window) * 4 * wl.head_dim
+    R = args.instances or max(2, int(np.ceil(2.5e9 / exp_bytes)))
+    cpu_seqs = min(args.cpu_seqs, wl.batch)
+
+    oracle = None
+    if not args.no_cpu:
+        from oracle.spkv_oracle import SPKVOracle
+        oracle = SPKVOracle(cpu_seqs, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
+                            window=wl.window, tau=wl.tau)
+    caches, streams = [], []
+    for r in range(R):
+        c, s = build_cache(wl, r, args.chunk, oracle=oracle if r == 0 else None,
+                           oracle_seqs=cpu_seqs)
+        if args.item_target:
+            c.set_option(spkv.OPT_ITEM_TARGET, args.item_target)
+        caches.append(c)
+        streams.append(s)
+
+    # Per-step inputs, resident before timing (a ring of 64 distinct steps).
+    steps_in = []
+    for j in range(64):
+        k, v, f, cu = streams[j % R].next_tokens([1] * wl.batch)
+        q = streams[j % R].next_query()
+        out = torch.empty_like(q)
+        steps_in.append((k, v, f, caches[0].make_cu(cu), q, out))
+
+    W, K = args.warmup, args.steps
+    timed_steps(caches, steps_in, W, 0)
+    dt = timed_steps(caches, steps_in, K, W)
+    ms_per_step = dt / K * 1e3
+    host_issue_us = HOST_ISSUE_S[-1] * 1e6
+
+    # Same steps again with HIP events around every split-K launch (roofline of the kernel).
+    for c in caches:
+        c.set_option(spkv.OPT_KERNEL_TIMING, 1)
+    dt_ev = timed_steps(caches, steps_in, K, W + K)
+    kern_ms = []
+    for c in caches:
+        kern_ms += c.read_kernel_timing()
+        c.set_option(spkv.OPT_KERNEL_TIMING, 0)
+    dt_dec = timed_steps(caches, steps_in, K, W + 2 * K, do_append=False)
+    dt_app = timed_steps(caches, steps_in, K, W + 3 * K, do_decode=False)
+
+    stats = [c.stats() for c in caches]
+    kept_bytes = float(np.mean([s.kept_kv_bytes for s in stats]))
+    dense_bytes = float(np.mean([s.dense_kv_bytes for s in stats]))
+    density = float(np.mean([s.density_evicted for s in stats]))
+    assert all(s.device_error == 0 for s in stats)
+    kern_avg_ms = float(np.mean(kern_ms))
+    achieved = kept_bytes / (kern_avg_ms * 1e-3) / 1e9
+
+    dense = None
+    if not args.no_dense:
+        for c in caches[2:]:
+            c.close()
+        del caches[2:]
+        torch.cuda.empty_cache()
+        dc, ds = build_cache(wl, 1000, args.chunk, tau=0.0)
+        Kd = max(10, K // 4)
+        timed_steps([dc], steps_in, 5, 0)
+        ddt = timed_steps([dc], steps_in, Kd, 5)
+        dst = dc.stats()
+        dense = {
+            "what": "same library, tau = 0 (every pair kept): dense-cache decode on the same GPU",
+            "us_per_step": ddt / Kd * 1e6,
+            "kv_bytes_per_step": dst.kept_kv_bytes,
+            "GBps": dst.kept_kv_bytes / (ddt / Kd) / 1e9,
+            "speedup_of_spkv": (ddt / Kd) / (dt / K),
+        }
+        dc.close()
+
+    # CPU baseline last (a long host-only phase lets the GPU clocks drop, so it must not
+    # precede a timed region): the oracle mirrors the first sequences of instance 0 up to
+    # the end of prefill; give it one more step of instance 0 and time its decode.
+    cpu = None
+    if oracle is not None:
+        k, v, f, cu, q, out = steps_in[0]
+        n = cu[cpu_seqs]
+        oracle.append(to_numpy_f32(k[:n]), to_numpy_f32(v[:n]), to_numpy_f32(f[:n]),
+                      list(cu[:cpu_seqs + 1]))
+        ost = oracle.stats()
+        cpu = cpu_baseline(wl, oracle, q, cpu_seqs, ost["kept_kv_bytes"])
+        oracle = None
+
+    result = {
+        "metric": "sp-kv decode step (append + decode attention): achieved HBM GB/s on kept-KV bytes",
+        "value": kept_bytes / (dt / K) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step,
+        "us_per_step": ms_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{wl.name}: batch {wl.batch}, {wl.n_q_heads}q/{wl.n_kv_heads}kv heads, "
+                        f"head_dim {wl.head_dim}, ctx {max(wl.ctx_lens)}, window {wl.window}, "
+                        f"tau {wl.tau}, keep U[0.10,0.33] per head",
+            "cache_instances_rotated": R,
+            "kept_kv_bytes_per_step": kept_bytes,
+            "dense_kv_bytes_per_step": dense_bytes,
+            "density_evicted": density,
+            "work_items": int(stats[0].n_work_items),
+        },
+        "host_issue_us_per_step": host_issue_us,
+        "decode_only_us": dt_dec / K * 1e6,
+        "append_only_us": dt_app / K * 1e6,
+        "frac_of_hbm_peak_step": kept_bytes / (dt / K) / 1e9 / HBM_PEAK_GBPS,
+        "dense_cache": dense,
+        "roofline": {
+            "bound": "hbm", "kernel": "spkv_decode_split<128>",
+            "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": read_traffic_summary(),
+            "algorithmic_bytes_per_launch": kept_bytes,
+            "kernel_avg_us": kern_avg_ms * 1e3,
+            "launches_timed": len(kern_ms),
+            "us_per_step_with_events": dt_ev / K * 1e6,
+        },
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

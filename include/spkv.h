@@ -83,7 +83,7 @@ typedef struct spkv_stats {
     int64_t pool_pages_total;
     int64_t arena_bytes;
     int32_t device_error;      /* nonzero if a kernel ever flagged an inconsistency         */
-    int32_t n_work_items;      /* split-K work items of the current schedule                */
+    int32_t n_work_items;      /* split-K work items the next decode call would launch      */
 } spkv_stats_t;
 
 /* Options for spkv_cache_set_option. */
@@ -132,6 +132,8 @@ int spkv_append(spkv_cache_t* cache, const void* k, const void* v, const float* 
  *   lse  device fp32 [batch, n_q_heads] or NULL: log sum_s exp(sm_scale * <q, k_s>)
  *   sm_scale <= 0 selects 1 / sqrt(head_dim)
  * Call after spkv_append of the same step, so that the query's own key is in the window.
+ * The first call after a multi-token append synchronises `stream` once to read the kept
+ * lengths back (they size the split-K grid); decode steps in steady state never wait.
  * Errors: SPKV_E_STATE if some sequence holds no token. */
 int spkv_decode_attention(spkv_cache_t* cache, const void* q, void* out, float* lse,
                           float sm_scale, void* stream);
@@ -163,6 +165,11 @@ int spkv_cache_read_kernel_timing(spkv_cache_t* cache, float* ms, int32_t cap, i
  * (1) or the key (0).  Returns -1 for arguments out of range.  Host-only; lets tests check
  * that the page layout is a bijection and matches the MFMA operand order. */
 int64_t spkv_debug_layout_offset(int32_t head_dim, int32_t is_v, int32_t kidx, int32_t d);
+
+/* Plain device-to-device copy of `bytes` (a multiple of 16; src, dst device, 16-byte
+ * aligned, not overlapping) by a simple grid-stride kernel: a kernel of exactly known HBM
+ * traffic (bytes read + bytes written) against which profiler byte counters are scaled. */
+int spkv_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 /* Static text for an error code. */
 const char* spkv_strerror(int code);

@@ -75,7 +75,7 @@ class SPKVOracle:
     """
 
     def __init__(self, batch, n_q_heads, n_kv_heads, head_dim, window=128,
-                 tau=0.5, sm_scale=None, store_dtype=np.float32):
+                 tau=0.5, sm_scale=None, store_dtype=np.float32, track_kv=True):
         if n_q_heads % n_kv_heads != 0:
             raise ValueError("n_q_heads must be a multiple of n_kv_heads")
         if window < 1:
@@ -86,6 +86,10 @@ class SPKVOracle:
         self.theta = threshold_logit(tau)
         self.scale = (1.0 / math.sqrt(head_dim)) if sm_scale is None else float(sm_scale)
         self.store_dtype = store_dtype
+        # track_kv=False keeps only the utility logits: gate bookkeeping (kept lists,
+        # lengths, density) for every sequence of a large batch without the K/V history;
+        # decode is then unavailable.
+        self.track_kv = bool(track_kv)
         # Full, never-pruned history per sequence, in buffers that grow by
         # doubling; rows [0, _len[b]) are live.
         self._kbuf = [np.zeros((0, n_kv_heads, head_dim), store_dtype) for _ in range(batch)]
@@ -98,13 +102,14 @@ class SPKVOracle:
         """Append tokens.  k, v: [total, H_kv, D]; util_logits: fp32
         [total, H_kv] (pre-sigmoid); cu_seqlens: [B+1] row offsets, sequence b
         owns rows cu[b]:cu[b+1] in order of position."""
-        k = np.asarray(k)
-        v = np.asarray(v)
         f = np.asarray(util_logits)
         if f.dtype != np.float32:
             raise TypeError("utility logits must be float32")
+        if self.track_kv:
+            k = np.asarray(k)
+            v = np.asarray(v)
         cu = [int(x) for x in cu_seqlens]
-        if len(cu) != self.B + 1 or cu[0] != 0 or cu[-1] != k.shape[0]:
+        if len(cu) != self.B + 1 or cu[0] != 0 or cu[-1] != f.shape[0]:
             raise ValueError("bad cu_seqlens")
         for b in range(self.B):
             lo, hi = cu[b], cu[b + 1]
@@ -113,14 +118,16 @@ class SPKVOracle:
             if hi == lo:
                 continue
             old, new = self._len[b], self._len[b] + (hi - lo)
-            if new > self._kbuf[b].shape[0]:
-                cap = max(new, 2 * self._kbuf[b].shape[0])
-                for bufs in (self._kbuf, self._vbuf, self._fbuf):
+            if new > self._fbuf[b].shape[0]:
+                cap = max(new, 2 * self._fbuf[b].shape[0])
+                grow = (self._kbuf, self._vbuf, self._fbuf) if self.track_kv else (self._fbuf,)
+                for bufs in grow:
                     grown = np.zeros((cap,) + bufs[b].shape[1:], bufs[b].dtype)
                     grown[:old] = bufs[b][:old]
                     bufs[b] = grown
-            self._kbuf[b][old:new] = k[lo:hi]
-            self._vbuf[b][old:new] = v[lo:hi]
+            if self.track_kv:
+                self._kbuf[b][old:new] = k[lo:hi]
+                self._vbuf[b][old:new] = v[lo:hi]
             self._fbuf[b][old:new] = f[lo:hi]
             self._len[b] = new
 
@@ -185,6 +192,8 @@ class SPKVOracle:
     def decode_pair(self, b, h, q_bh):
         """One (sequence, KV head): q_bh [G, D] (the group's query heads) ->
         (out [G, D], lse [G]) for the newest position, in fp64."""
+        if not self.track_kv:
+            raise RuntimeError("this oracle instance tracks logits only")
         q_bh = np.asarray(q_bh, dtype=np.float64)
         K = self._k(b)[:, h, :].astype(np.float64)       # [T, D]
         V = self._v(b)[:, h, :].astype(np.float64)

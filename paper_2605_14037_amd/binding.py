@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_reset",
     "spkv_append", "spkv_decode_attention", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
-    "spkv_debug_layout_offset", "spkv_strerror",
+    "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
 
 
@@ -92,6 +92,8 @@ def load_library():
     lib.spkv_cache_read_kernel_timing.argtypes = [vp, P(f32), i32, P(i32)]
     lib.spkv_debug_layout_offset.restype = i64
     lib.spkv_debug_layout_offset.argtypes = [i32, i32, i32, i32]
+    lib.spkv_debug_copy.restype = C.c_int
+    lib.spkv_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.spkv_strerror.restype = C.c_char_p
     lib.spkv_strerror.argtypes = [C.c_int]
     _LIB = lib
@@ -108,6 +110,16 @@ def required_bytes(cfg: SPKVConfig) -> int:
 
 def layout_offset(head_dim, is_v, kidx, d) -> int:
     return int(load_library().spkv_debug_layout_offset(head_dim, int(is_v), kidx, d))
+
+
+def debug_copy(dst: torch.Tensor, src: torch.Tensor):
+    """Plain copy kernel of known traffic (src.nbytes read + written); see spkv_debug_copy."""
+    nbytes = src.numel() * src.element_size()
+    if not (dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()
+            and dst.numel() * dst.element_size() == nbytes):
+        raise ValueError("debug_copy: need contiguous cuda tensors of equal byte size")
+    _check(load_library().spkv_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
+                                          nbytes, _stream()), "spkv_debug_copy")
 
 
 def _check(code, where):
@@ -158,10 +170,14 @@ class SPKVCache:
             pass
 
     # ---- write path
+    def make_cu(self, cu_seqlens):
+        """cu_seqlens as the C array spkv_append takes (build once, reuse every step)."""
+        return (C.c_int32 * (self.cfg.batch + 1))(*[int(x) for x in cu_seqlens])
+
     def append(self, k, v, util_logits, cu_seqlens):
         cfg = self.cfg
-        total = int(cu_seqlens[-1])
-        cu = (C.c_int32 * (cfg.batch + 1))(*[int(x) for x in cu_seqlens])
+        cu = cu_seqlens if isinstance(cu_seqlens, C.Array) else self.make_cu(cu_seqlens)
+        total = cu[cfg.batch]
         if total == 0:
             _check(self.lib.spkv_append(self.handle, None, None, None, cu, _stream()), "spkv_append")
             return

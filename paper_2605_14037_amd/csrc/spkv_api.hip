@@ -13,14 +13,14 @@
 namespace {
 
 constexpr size_t kAlign = 256;
-constexpr int kDefaultItemTarget = 4096;
+constexpr int kDefaultItemTarget = 3072;   // 12 waves per CU on 256 CUs
 constexpr int kMaxTimedLaunches = 8192;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Carve {
     size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, err_flag, page_table, pool,
-        pos_pool, seg_count, bulk_info, n_items, items, item_start, part_acc, part_ml,
+        pos_pool, seg_count, bulk_info, part_acc, part_ml,
         pos_scratch, total;
     int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items;
 };
@@ -52,7 +52,7 @@ bool carve(const spkv_config_t* c, Carve* out) {
     if (n_pages > ((int64_t)1 << 30)) return false;
     k.n_pages = (int)n_pages;
     k.n_seg_cap = (int)((max_evicted + kSegTokens - 1) / kSegTokens) + 1;
-    k.max_items = kMaxItemTarget + k.n_pairs;
+    k.max_items = kMaxSlots + k.n_pairs;
     const size_t page_bytes = (size_t)spkv_page_elems(c->head_dim) * 2;
     size_t off = 0;
     auto take = [&off](size_t bytes) {
@@ -72,9 +72,6 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.pos_pool = take((size_t)k.n_pages * kPageTokens * 4);
     k.seg_count = take((size_t)k.n_pairs * k.n_seg_cap * 4);
     k.bulk_info = take((size_t)k.n_pairs * 16);
-    k.n_items = take(4);
-    k.items = take((size_t)k.max_items * 16);
-    k.item_start = take((size_t)(k.n_pairs + 1) * 4);
     k.part_acc = take((size_t)k.max_items * k.G * c->head_dim * 4);
     k.part_ml = take((size_t)k.max_items * k.G * 2 * 4);
     k.pos_scratch = take((size_t)k.pt_cap * kPageTokens * 4);
@@ -103,7 +100,9 @@ struct spkv_cache {
     std::vector<int32_t> T;       // tokens per sequence (exact: the host sees every append)
     std::vector<int32_t> L_ub;    // per (seq, head): upper bound of the long-term length
     int64_t pages_ub;             // sum of pages_for(L_ub): upper bound of pool pages in use
+    bool bound_is_loose;          // a bulk append grew L_ub by far more than the truth
     int item_target;
+    SpkvSplit split;              // partition used by the last decode call
     bool timing;
     std::vector<hipEvent_t> events;   // pairs (before, after)
     int n_timed;
@@ -123,20 +122,34 @@ int refresh_bound(spkv_cache* c, hipStream_t s, int32_t* kept_len_out) {
         pages += pages_for(len[p]);
     }
     c->pages_ub = pages;
+    c->bound_is_loose = false;
     if (kept_len_out != nullptr) std::memcpy(kept_len_out, len.data(), len.size() * 4);
     return SPKV_OK;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int64_t half_pages_ub(const spkv_cache* c) {
-    int64_t hp = 0;
+// Work partition for one decode call from the host's upper bound of the lengths: items of
+// about (all half-pages / item_target) half-pages, and enough slots per pair for the
+// longest pair.  The kernels apply it to the exact device-side lengths, which never
+// exceed the bound, so every pair fits its slots.
+SpkvSplit choose_split(const spkv_cache* c) {
+    int64_t sum_hp = 0, max_hp = 1;
     const int Hkv = c->cfg.n_kv_heads;
     for (int p = 0; p < c->carve.n_pairs; ++p) {
         const int Tw = std::min(c->T[p / Hkv], c->cfg.window);
-        hp += (c->L_ub[p] + kHalfTokens - 1) / kHalfTokens + (Tw + kHalfTokens - 1) / kHalfTokens;
+        const int64_t hp =
+            (c->L_ub[p] + kHalfTokens - 1) / kHalfTokens + (Tw + kHalfTokens - 1) / kHalfTokens;
+        sum_hp += hp;
+        max_hp = std::max(max_hp, hp);
     }
-    return hp;
+    int64_t per = std::max<int64_t>(1, (sum_hp + c->item_target - 1) / c->item_target);
+    const int64_t slots_cap = c->carve.max_items / c->carve.n_pairs - 1;
+    if ((max_hp + per - 1) / per > slots_cap) per = (max_hp + slots_cap - 1) / slots_cap;
+    SpkvSplit sp;
+    sp.hp_per_item = (int32_t)per;
+    sp.slots = (int32_t)((max_hp + per - 1) / per) | 1;   // odd: see spkv_decode_split
+    return sp;
 }
 
 }  // namespace
@@ -167,7 +180,9 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->T.assign(cfg->batch, 0);
     c->L_ub.assign(k.n_pairs, 0);
     c->pages_ub = 0;
+    c->bound_is_loose = false;
     c->item_target = kDefaultItemTarget;
+    c->split = SpkvSplit{1, 1};
     c->timing = false;
     c->n_timed = 0;
     SpkvView& v = c->view;
@@ -197,9 +212,6 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     v.pos_pool = reinterpret_cast<int32_t*>(a + k.pos_pool);
     v.seg_count = reinterpret_cast<int32_t*>(a + k.seg_count);
     v.bulk_info = reinterpret_cast<int32_t*>(a + k.bulk_info);
-    v.n_items = reinterpret_cast<int32_t*>(a + k.n_items);
-    v.items = reinterpret_cast<int4*>(a + k.items);
-    v.item_start = reinterpret_cast<int32_t*>(a + k.item_start);
     v.part_acc = reinterpret_cast<float*>(a + k.part_acc);
     v.part_ml = reinterpret_cast<float*>(a + k.part_ml);
     v.pos_scratch = reinterpret_cast<int32_t*>(a + k.pos_scratch);
@@ -286,7 +298,7 @@ int spkv_append(spkv_cache_t* c, const void* k, const void* v, const float* util
             L += (int32_t)ev;
         }
     }
-    if (spkv_launch_schedule(c->view, c->item_target, s) != hipSuccess) return SPKV_E_HIP;
+    if (n_max > 1) c->bound_is_loose = true;
     return SPKV_OK;
 }
 
@@ -298,6 +310,10 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
         if (c->T[b] == 0) return SPKV_E_STATE;
     if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (c->bound_is_loose) {   // first decode after a bulk append: one read-back of the lengths
+        const int rc = refresh_bound(c, s, nullptr);
+        if (rc != SPKV_OK) return rc;
+    }
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (c->timing && c->n_timed < kMaxTimedLaunches) {
         if ((size_t)(2 * c->n_timed + 2) > c->events.size()) {
@@ -314,10 +330,9 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
         ev1 = c->events[2 * c->n_timed + 1];
         c->n_timed += 1;
     }
-    const int64_t hp = half_pages_ub(c);
-    const int grid = (int)std::min<int64_t>(hp, c->item_target) + c->carve.n_pairs;
+    c->split = choose_split(c);
     if (spkv_launch_decode(c->view, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
-                           lse, sm_scale, grid, ev0, ev1, s) != hipSuccess)
+                           lse, sm_scale, c->split, ev0, ev1, s) != hipSuccess)
         return SPKV_E_HIP;
     return SPKV_OK;
 }
@@ -329,11 +344,10 @@ int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void*
     std::vector<int32_t> len(n_pairs), gate(n_pairs);
     int rc = refresh_bound(c, s, len.data());
     if (rc != SPKV_OK) return rc;
-    int32_t pool_next = 0, err = 0, n_items = 0;
+    int32_t pool_next = 0, err = 0;
     if (hipMemcpy(gate.data(), c->view.gate_on, (size_t)n_pairs * 4, hipMemcpyDeviceToHost) != hipSuccess ||
         hipMemcpy(&pool_next, c->view.pool_next, 4, hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy(&err, c->view.err_flag, 4, hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy(&n_items, c->view.n_items, 4, hipMemcpyDeviceToHost) != hipSuccess)
+        hipMemcpy(&err, c->view.err_flag, 4, hipMemcpyDeviceToHost) != hipSuccess)
         return SPKV_E_HIP;
     std::memset(st, 0, sizeof(*st));
     for (int b = 0; b < c->cfg.batch; ++b) {
@@ -354,7 +368,14 @@ int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void*
     st->pool_pages_total = c->carve.n_pages;
     st->arena_bytes = (int64_t)c->arena_bytes;
     st->device_error = err;
-    st->n_work_items = n_items;
+    const SpkvSplit sp = choose_split(c);   // the partition the next decode call would use
+    int64_t n_items = 0;
+    for (int p = 0; p < n_pairs; ++p) {
+        const int Tw = std::min(c->T[p / Hkv], w);
+        const int64_t hp = (len[p] + kHalfTokens - 1) / kHalfTokens + (Tw + kHalfTokens - 1) / kHalfTokens;
+        n_items += std::min<int64_t>((hp + sp.hp_per_item - 1) / sp.hp_per_item, sp.slots);
+    }
+    st->n_work_items = (int32_t)n_items;
     if (kept_len != nullptr) std::memcpy(kept_len, len.data(), (size_t)n_pairs * 4);
     return err ? SPKV_E_DEVICE : SPKV_OK;
 }
@@ -418,6 +439,14 @@ int64_t spkv_debug_layout_offset(int32_t head_dim, int32_t is_v, int32_t kidx, i
         d >= head_dim)
         return -1;
     return is_v ? spkv_v_off(head_dim, kidx, d) : spkv_k_off(head_dim, kidx, d);
+}
+
+int spkv_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (dst == nullptr || src == nullptr || (bytes & 15u) != 0 || !aligned16(dst) || !aligned16(src))
+        return SPKV_E_INVAL;
+    return spkv_launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? SPKV_OK
+               : SPKV_E_HIP;
 }
 
 const char* spkv_strerror(int code) {

@@ -8,6 +8,7 @@
 
 constexpr int kSegTokens = 1024;      // bulk append: tokens per compaction segment
 constexpr int kMaxItemTarget = 16384;
+constexpr int kMaxSlots = 32768;      // work-item slots beyond one per (seq, head)
 
 // Device-side view of one cache: plain pointers into the caller's arena.
 struct SpkvView {
@@ -17,7 +18,7 @@ struct SpkvView {
     int32_t pt_cap;         // page-table entries per (seq, head)
     int32_t n_pages;        // pages in the long-term pool
     int32_t n_seg_cap;      // bulk-append segments per (seq, head)
-    int32_t max_items;      // capacity of the work-item table / partials
+    int32_t max_items;      // capacity (work-item slots) of the partial buffers
     float   theta;          // gate threshold on the logit
 
     uint16_t* ring;         // [n_pairs][n_ring_pages] pages (K and V interleaved by half)
@@ -32,9 +33,6 @@ struct SpkvView {
     int32_t*  pos_pool;     // [n_pages][64] position of every long-term entry
     int32_t*  seg_count;    // [n_pairs][n_seg_cap] bulk scratch: kept per segment, then offsets
     int32_t*  bulk_info;    // [n_pairs][4] bulk scratch: T_old, first long-term index of new tokens
-    int32_t*  n_items;      // [1] work items in the current schedule
-    int4*     items;        // [max_items] {pair, first half-page, end half-page, 0}
-    int32_t*  item_start;   // [n_pairs + 1] first item of every pair
     float*    part_acc;     // [max_items][G][D] un-normalised partial outputs
     float*    part_ml;      // [max_items][G][2] running max (log2 domain) and sum
     int32_t*  pos_scratch;  // [pt_cap * 64] gather buffer for kept positions
@@ -46,12 +44,20 @@ struct SpkvCu {
 };
 
 hipError_t spkv_launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const SpkvCu& cu, hipStream_t s);
 hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const SpkvCu& cu, int n_max, hipStream_t s);
-hipError_t spkv_launch_schedule(const SpkvView& v, int item_target, hipStream_t s);
+// Split of every (seq, head) list into work items, chosen by the host per decode call:
+// a pair with n half-pages (32 keys each) is cut evenly into min(ceil(n / hp_per_item),
+// slots) items; item j of pair p owns partial slot p * slots + j.
+struct SpkvSplit {
+    int32_t hp_per_item;
+    int32_t slots;
+};
+
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
-                              float sm_scale, int grid_items, hipEvent_t ev0, hipEvent_t ev1,
+                              float sm_scale, SpkvSplit split, hipEvent_t ev0, hipEvent_t ev1,
                               hipStream_t s);
 hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s);

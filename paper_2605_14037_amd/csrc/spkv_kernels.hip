@@ -3,7 +3,8 @@
 //   write path : spkv_append_step (one token per sequence, fused evict + append),
 //                spkv_bulk_count / spkv_bulk_ring / spkv_bulk_scatter (many tokens:
 //                ballot + mbcnt stream compaction, stable order)
-//   scheduler  : spkv_schedule (split every head's kept list into equal work items)
+//   partition  : pair_split (every head's kept list cut into equal work items, derived
+//                in both decode kernels from the device-side lengths)
 //   read path  : spkv_decode_split (split-K flash decoding on MFMA, one wave per item),
 //                spkv_decode_combine (log-sum-exp merge of the partials)
 //
@@ -21,6 +22,17 @@ typedef __attribute__((ext_vector_type(8))) float f32x8;
 
 // ------------------------------------------------------------------ small helpers
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// 128-bit streaming load of 8 bf16.  K/V tiles are read once per decode step and never
+// again before the whole cache has gone by, so they are loaded non-temporal: the lines
+// bypass L2 / Infinity Cache retention instead of evicting the little that is reused
+// (queries, page tables, partials).  Measured on MI355X: about 12 % more read bandwidth
+// than plain loads for this access pattern.
+__device__ __forceinline__ bf16x8 load_stream_b128(const uint16_t* p) {
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    const u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return __builtin_bit_cast(bf16x8, r);
+}
 
 __device__ __forceinline__ int mbcnt64(unsigned long long mask) {
     return __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
@@ -71,6 +83,24 @@ hipError_t spkv_launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
     size_t blocks = (n16 + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
     spkv_fill_zero<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(static_cast<uint4*>(p), n16);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------- plain copy (reference)
+__global__ __launch_bounds__(256) void spkv_plain_copy(uint4* __restrict__ d,
+                                                       const uint4* __restrict__ s, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+         i += (size_t)gridDim.x * blockDim.x)
+        d[i] = s[i];
+}
+
+hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    spkv_plain_copy<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(
+        static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
     return hipGetLastError();
 }
 
@@ -365,69 +395,28 @@ hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const u
     return hipGetLastError();
 }
 
-// ------------------------------------------------------------------------- scheduler
+// ------------------------------------------------------------------ work partition
 // Work unit: a half-page (32 keys).  Pair p has ceil(L/32) long-term half-pages followed
-// by ceil(min(T, w)/32) ring half-pages.  All pairs are cut into items of about
-// total / item_target half-pages, each pair split evenly, so that the split-K grid is
-// balanced over the kept lengths whatever their spread.
-__device__ __forceinline__ int pair_half_pages(const SpkvView& v, int p) {
-    const int L = v.kept_len[p];
-    const int Tw = min(v.t_pair[p], v.w);
-    return ((L + kHalfTokens - 1) >> 5) + ((Tw + kHalfTokens - 1) >> 5);
-}
+// by ceil(min(T, w)/32) ring half-pages.  The host picks hp_per_item (about total half-
+// pages / target item count, from its upper bound of the lengths) and the slot count per
+// pair; every pair is then cut evenly into ceil(n / hp_per_item) items from its exact
+// device-side lengths, so that the split-K grid is balanced over the kept lengths
+// whatever their spread.  Both decode kernels derive the same partition from (L, T).
+struct PairSplit {
+    int nhp;    // half-pages of the pair
+    int ghp;    // of which long-term
+    int items;  // work items the pair is cut into
+    int L, Tw;
+};
 
-__global__ __launch_bounds__(256) void spkv_schedule(SpkvView v, int item_target) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    __shared__ long long s_red[4];
-    __shared__ int s_w[4];
-    long long local = 0;
-    for (int p = tid; p < v.n_pairs; p += 256) local += pair_half_pages(v, p);
-    for (int o = 32; o > 0; o >>= 1) local += __shfl_xor(local, o);
-    if (lane == 0) s_red[wave] = local;
-    __syncthreads();
-    const long long total = s_red[0] + s_red[1] + s_red[2] + s_red[3];
-    int cb = (int)((total + item_target - 1) / item_target);
-    if (cb < 1) cb = 1;
-
-    int carry = 0;
-    for (int base = 0; base < v.n_pairs; base += 256) {
-        const int p = base + tid;
-        const int nhp = p < v.n_pairs ? pair_half_pages(v, p) : 0;
-        const int it = (nhp + cb - 1) / cb;
-        int incl = it;                                   // inclusive scan inside the wave
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(incl, o);
-            if (lane >= o) incl += t;
-        }
-        __syncthreads();
-        if (lane == 63) s_w[wave] = incl;
-        __syncthreads();
-        int woff = 0, ctot = 0;
-        for (int i = 0; i < 4; ++i) {
-            if (i < wave) woff += s_w[i];
-            ctot += s_w[i];
-        }
-        const int excl = carry + woff + incl - it;
-        if (p < v.n_pairs) {
-            v.item_start[p] = excl;
-            for (int j = 0; j < it; ++j) {
-                if (excl + j >= v.max_items) { *v.err_flag = 2; break; }
-                const int hb = (int)((long long)nhp * j / it);
-                const int he = (int)((long long)nhp * (j + 1) / it);
-                v.items[excl + j] = make_int4(p, hb, he, 0);
-            }
-        }
-        carry += ctot;
-    }
-    if (tid == 0) {
-        v.item_start[v.n_pairs] = carry;
-        *v.n_items = min(carry, v.max_items);
-    }
-}
-
-hipError_t spkv_launch_schedule(const SpkvView& v, int item_target, hipStream_t s) {
-    spkv_schedule<<<dim3(1), dim3(256), 0, s>>>(v, item_target);
-    return hipGetLastError();
+__device__ __forceinline__ PairSplit pair_split(const SpkvView& v, int pair, SpkvSplit sp) {
+    PairSplit r;
+    r.L = v.kept_len[pair];
+    r.Tw = min(v.t_pair[pair], v.w);
+    r.ghp = (r.L + kHalfTokens - 1) >> 5;
+    r.nhp = r.ghp + ((r.Tw + kHalfTokens - 1) >> 5);
+    r.items = min((r.nhp + sp.hp_per_item - 1) / sp.hp_per_item, sp.slots);
+    return r;
 }
 
 // ------------------------------------------------------------------- split-K decode
@@ -437,18 +426,23 @@ hipError_t spkv_launch_schedule(const SpkvView& v, int item_target, hipStream_t 
 //   O[d][head]    += V[key][d] * P[key][head]        D/16 MFMA 16x16x32
 // The G <= 16 query heads of the GQA group are the N = 16 columns of every MFMA, so each
 // K/V tile is read exactly once per group.  Every wave-wide load is 1 KB contiguous.
+// Block id = pair * slots + j with an odd slot count: workgroups go round-robin to the 8
+// XCDs, so the items of every pair -- long or short -- spread evenly over all of them
+// (heads differ in kept length by several times; pinning a head to one XCD would leave
+// the others idle), and the odd stride keeps the per-pair remainders from piling up on
+// the low XCDs.
 template <int D>
 __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
-                                                        float scale_log2e) {
+                                                        float scale_log2e, SpkvSplit sp) {
     constexpr int NS = D / 32;   // head-dim slabs of one K tile
     constexpr int NB = D / 16;   // 16-wide output blocks
-    const int item = blockIdx.x;
-    if (item >= *v.n_items) return;
-    const int4 it = v.items[item];
-    const int pair = it.x, hp0 = it.y, hp1 = it.z;
-    const int L = v.kept_len[pair];
-    const int Tw = min(v.t_pair[pair], v.w);
-    const int ghp = (L + kHalfTokens - 1) >> 5;
+    const int pair = blockIdx.x / sp.slots;
+    const int j = blockIdx.x - pair * sp.slots;
+    const PairSplit ps = pair_split(v, pair, sp);
+    if (j >= ps.items) return;
+    const int hbase = ps.nhp / ps.items, hrem = ps.nhp - hbase * ps.items;
+    const int hp0 = j * hbase + min(j, hrem);
+    const int hp1 = hp0 + hbase + (j < hrem ? 1 : 0);
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int lane = threadIdx.x, kc = lane >> 4, n = lane & 15;
 
@@ -466,84 +460,94 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
 #pragma unroll
     for (int i = 0; i < NB; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float m = SPKV_NEG_INF, l = 0.f;
+    const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
 
-    for (int hp = hp0; hp < hp1; ++hp) {
-        const uint16_t* base;
-        int nvalid;
-        if (hp < ghp) {
-            const int page = v.page_table[(size_t)pair * v.pt_cap + (hp >> 1)];
-            base = pool_page(v, page) + (hp & 1) * (2 * kHalfTokens * D);
-            nvalid = min(kHalfTokens, L - hp * kHalfTokens);
-        } else {
-            const int r = hp - ghp;
-            base = ring_page(v, pair, r >> 1) + (r & 1) * (2 * kHalfTokens * D);
-            nvalid = min(kHalfTokens, Tw - r * kHalfTokens);
-        }
-        const uint16_t* kp = base + lane * 8;
-        const uint16_t* vp = base + kHalfTokens * D + lane * 8;
-        bf16x8 ka[2][NS], va[NB];
+    int hp = hp0;
+    while (hp < hp1) {
+        // Page ids of the next 64 logical pages, one per lane; read back with readlane so
+        // that no half-page waits on a dependent table lookup.
+        const int pbase = hp >> 1;
+        const int my_page = pt[min(pbase + lane, v.pt_cap - 1)];
+        const int hp_end = min(hp1, (pbase + 64) << 1);
+        for (; hp < hp_end; ++hp) {
+            const uint16_t* base;
+            int nvalid;
+            if (hp < ps.ghp) {
+                const int page = __builtin_amdgcn_readlane(my_page, (hp >> 1) - pbase);
+                base = pool_page(v, page) + (hp & 1) * (2 * kHalfTokens * D);
+                nvalid = min(kHalfTokens, ps.L - hp * kHalfTokens);
+            } else {
+                const int r = hp - ps.ghp;
+                base = ring_page(v, pair, r >> 1) + (r & 1) * (2 * kHalfTokens * D);
+                nvalid = min(kHalfTokens, ps.Tw - r * kHalfTokens);
+            }
+            const uint16_t* kp = base + lane * 8;
+            const uint16_t* vp = base + kHalfTokens * D + lane * 8;
+            bf16x8 ka[2][NS], va[NB];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int sl = 0; sl < NS; ++sl)
-                ka[t][sl] = *reinterpret_cast<const bf16x8*>(kp + (t * (D / 8) + sl * 4) * 128);
+                for (int sl = 0; sl < NS; ++sl)
+                    ka[t][sl] = load_stream_b128(kp + (t * (D / 8) + sl * 4) * 128);
 #pragma unroll
-        for (int db = 0; db < NB; ++db)
-            va[db] = *reinterpret_cast<const bf16x8*>(vp + db * 512);
+            for (int db = 0; db < NB; ++db)
+                va[db] = load_stream_b128(vp + db * 512);
 
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int sl = 0; sl < NS; ++sl) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][sl], qb[sl], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][sl], qb[sl], s1, 0, 0, 0);
-        }
-        // Lane (kc, n) now holds, for head n, the keys r = 16 t + 4 kc + i of the half-page.
-        float x[8];
+            for (int sl = 0; sl < NS; ++sl) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][sl], qb[sl], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][sl], qb[sl], s1, 0, 0, 0);
+            }
+            // Lane (kc, n) now holds, for head n, the keys r = 16 t + 4 kc + i of the half-page.
+            float x[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            x[i] = s0[i] * scale_log2e;
-            x[4 + i] = s1[i] * scale_log2e;
-        }
-        if (nvalid < kHalfTokens) {
+            for (int i = 0; i < 4; ++i) {
+                x[i] = s0[i] * scale_log2e;
+                x[4 + i] = s1[i] * scale_log2e;
+            }
+            if (nvalid < kHalfTokens) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int r = (e >> 2) * 16 + kc * 4 + (e & 3);
+                    if (r >= nvalid) x[e] = SPKV_NEG_INF;
+                }
+            }
+            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                             fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            f32x8 p;
+            float psum = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int r = (e >> 2) * 16 + kc * 4 + (e & 3);
-                if (r >= nvalid) x[e] = SPKV_NEG_INF;
+                p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
+                psum += p[e];
             }
-        }
-        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                         fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        f32x8 p;
-        float psum = 0.f;
+            l = l * alpha + psum;
+            if (__ballot(m_new != m) != 0ull) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
-            psum += p[e];
-        }
-        l = l * alpha + psum;
-        if (__ballot(m_new != m) != 0ull) {
+                for (int db = 0; db < NB; ++db) acc[db] *= alpha;
+            }
+            m = m_new;
+            const bf16x8 pb = __builtin_convertvector(p, bf16x8);
 #pragma unroll
-            for (int db = 0; db < NB; ++db) acc[db] *= alpha;
+            for (int db = 0; db < NB; ++db)
+                acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[db], pb, acc[db], 0, 0, 0);
         }
-        m = m_new;
-        const bf16x8 pb = __builtin_convertvector(p, bf16x8);
-#pragma unroll
-        for (int db = 0; db < NB; ++db)
-            acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[db], pb, acc[db], 0, 0, 0);
     }
 
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     if (n < v.G) {
-        float* pa = v.part_acc + ((size_t)item * v.G + n) * D + kc * 4;
+        const size_t slot = (size_t)pair * sp.slots + j;
+        float* pa = v.part_acc + (slot * v.G + n) * D + kc * 4;
 #pragma unroll
         for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[db];
         if (kc == 0) {
-            float* pm = v.part_ml + ((size_t)item * v.G + n) * 2;
+            float* pm = v.part_ml + (slot * v.G + n) * 2;
             pm[0] = m;
             pm[1] = l;
         }
@@ -552,44 +556,73 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
 
 // Merge the partials of one (sequence, query head): with M = max_i m_i,
 //   out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i,  lse = (M + log2(sum)) ln 2.
+// One workgroup of 4 waves per (pair, head): the waves take the items round-robin (their
+// loads are independent, so a handful of load rounds covers the list), each lane owns
+// D/64 output elements, and the four wave sums meet in LDS.
 template <int D>
-__global__ __launch_bounds__(D) void spkv_decode_combine(SpkvView v, uint16_t* __restrict__ out,
-                                                         float* __restrict__ lse) {
+__global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t* __restrict__ out,
+                                                           float* __restrict__ lse, SpkvSplit sp) {
+    constexpr int E = D / 64;
     const int pair = blockIdx.x / v.G, g = blockIdx.x - pair * v.G;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
-    const int d = threadIdx.x;
-    const int i0 = v.item_start[pair], i1 = min(v.item_start[pair + 1], v.max_items);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int items = pair_split(v, pair, sp).items;
+    const size_t slot0 = (size_t)pair * sp.slots;
+    __shared__ float s_m[4];
+    __shared__ float s_den[4];
+    __shared__ float s_acc[4][D];
+
     float M = SPKV_NEG_INF;
-    for (int i = i0; i < i1; ++i) M = fmaxf(M, v.part_ml[((size_t)i * v.G + g) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int i = i0; i < i1; ++i) {
-        const float* pm = v.part_ml + ((size_t)i * v.G + g) * 2;
+    for (int i = tid; i < items; i += 256) M = fmaxf(M, v.part_ml[((slot0 + i) * v.G + g) * 2]);
+    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+    if (lane == 0) s_m[wave] = M;
+    __syncthreads();
+    M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+
+    float num[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) num[e] = 0.f;
+    float den = 0.f;
+#pragma unroll 4
+    for (int i = wave; i < items; i += 4) {
+        const float* pm = v.part_ml + ((slot0 + i) * v.G + g) * 2;
+        const float* pa = v.part_acc + ((slot0 + i) * v.G + g) * D + lane * E;
         const float wgt = __builtin_amdgcn_exp2f(pm[0] - M);
         den += wgt * pm[1];
-        num += wgt * v.part_acc[((size_t)i * v.G + g) * D + d];
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] += wgt * pa[e];
     }
-    const size_t o = ((size_t)b * v.Hq + (size_t)h * v.G + g);
-    const __bf16 r = (__bf16)(num / den);
-    out[o * D + d] = __builtin_bit_cast(uint16_t, r);
-    if (lse != nullptr && d == 0) lse[o] = (M + __builtin_log2f(den)) * 0.6931471805599453f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
+    if (lane == 0) s_den[wave] = den;
+    __syncthreads();
+    if (tid < D) {
+        const float nsum = s_acc[0][tid] + s_acc[1][tid] + s_acc[2][tid] + s_acc[3][tid];
+        const float dsum = s_den[0] + s_den[1] + s_den[2] + s_den[3];
+        const size_t o = ((size_t)b * v.Hq + (size_t)h * v.G + g);
+        const __bf16 r = (__bf16)(nsum / dsum);
+        out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
+        if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
+    }
 }
 
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
-                              float sm_scale, int grid_items, hipEvent_t ev0, hipEvent_t ev1,
+                              float sm_scale, SpkvSplit sp, hipEvent_t ev0, hipEvent_t ev1,
                               hipStream_t s) {
     const float scale_log2e = sm_scale * 1.4426950408889634f;
+    const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
     hipError_t e;
     if (ev0 != nullptr && (e = hipEventRecord(ev0, s)) != hipSuccess) return e;
     if (v.D == 128)
-        spkv_decode_split<128><<<dim3(grid_items), dim3(64), 0, s>>>(v, q, scale_log2e);
+        spkv_decode_split<128><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
     else
-        spkv_decode_split<64><<<dim3(grid_items), dim3(64), 0, s>>>(v, q, scale_log2e);
+        spkv_decode_split<64><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
     if (v.D == 128)
-        spkv_decode_combine<128><<<dim3(v.n_pairs * v.G), dim3(128), 0, s>>>(v, out, lse);
+        spkv_decode_combine<128><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
     else
-        spkv_decode_combine<64><<<dim3(v.n_pairs * v.G), dim3(64), 0, s>>>(v, out, lse);
+        spkv_decode_combine<64><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
     return hipGetLastError();
 }
 
