@@ -104,6 +104,7 @@ struct spkv_cache {
     int item_target;
     SpkvSplit split;              // partition used by the last decode call
     bool timing;
+    bool split_only;
     std::vector<hipEvent_t> events;   // pairs (before, after)
     int n_timed;
 };
@@ -184,6 +185,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->item_target = kDefaultItemTarget;
     c->split = SpkvSplit{1, 1};
     c->timing = false;
+    c->split_only = false;
     c->n_timed = 0;
     SpkvView& v = c->view;
     v.B = cfg->batch;
@@ -332,7 +334,7 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
     }
     c->split = choose_split(c);
     if (spkv_launch_decode(c->view, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
-                           lse, sm_scale, c->split, ev0, ev1, s) != hipSuccess)
+                           lse, sm_scale, c->split, c->split_only, ev0, ev1, s) != hipSuccess)
         return SPKV_E_HIP;
     return SPKV_OK;
 }
@@ -411,6 +413,9 @@ int spkv_cache_set_option(spkv_cache_t* c, int32_t option, int64_t value) {
         case SPKV_OPT_ITEM_TARGET:
             if (value < 1 || value > kMaxItemTarget) return SPKV_E_INVAL;
             c->item_target = (int)value;
+            return SPKV_OK;
+        case SPKV_OPT_SPLIT_ONLY:
+            c->split_only = value != 0;
             return SPKV_OK;
         case SPKV_OPT_KERNEL_TIMING:
             c->timing = value != 0;

@@ -58,6 +58,6 @@ struct SpkvSplit {
 };
 
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
-                              float sm_scale, SpkvSplit split, hipEvent_t ev0, hipEvent_t ev1,
-                              hipStream_t s);
+                              float sm_scale, SpkvSplit split, bool split_only, hipEvent_t ev0,
+                              hipEvent_t ev1, hipStream_t s);
 hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s);

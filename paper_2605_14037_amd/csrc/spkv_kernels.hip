@@ -607,8 +607,8 @@ __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t*
 }
 
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
-                              float sm_scale, SpkvSplit sp, hipEvent_t ev0, hipEvent_t ev1,
-                              hipStream_t s) {
+                              float sm_scale, SpkvSplit sp, bool split_only, hipEvent_t ev0,
+                              hipEvent_t ev1, hipStream_t s) {
     const float scale_log2e = sm_scale * 1.4426950408889634f;
     const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
     hipError_t e;
@@ -619,6 +619,7 @@ hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* ou
         spkv_decode_split<64><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
+    if (split_only) return hipSuccess;
     if (v.D == 128)
         spkv_decode_combine<128><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
     else

@@ -2,7 +2,7 @@
 validates configurations, and its page layout is the MFMA operand order it claims."""
 
 import ctypes as C
-import math
+
 import os
 import re
 
@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 import paper_2605_14037_amd as spkv
-from oracle.spkv_oracle import threshold_logit
+
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
