@@ -78,6 +78,61 @@ def timed_steps(caches, steps_in, n_steps, offset, do_append=True, do_decode=Tru
     return time.perf_counter() - t0
 
 
+def quick_point(wl, chunk, steps, warmup):
+    """Step and split-K kernel time of one workload (rotating cold cache instances)."""
+    exp_bytes = (wl.expected_kept_tokens() + wl.batch * wl.n_kv_heads * wl.window) * 4 * wl.head_dim
+    R = max(2, int(np.ceil(2.5e9 / exp_bytes)))
+    caches, streams = [], []
+    for r in range(R):
+        c, s = build_cache(wl, r, chunk)
+        caches.append(c)
+        streams.append(s)
+    steps_in = []
+    for j in range(32):
+        k, v, f, cu = streams[j % R].next_tokens([1] * wl.batch)
+        q = streams[j % R].next_query()
+        steps_in.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
+    timed_steps(caches, steps_in, warmup, 0)
+    dt = timed_steps(caches, steps_in, steps, warmup)
+    for c in caches:
+        c.set_option(spkv.OPT_SPLIT_ONLY, 1)
+    timed_steps(caches, steps_in, max(warmup, R), 0, do_append=False)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        caches[i % R].decode_attention(steps_in[i % 32][4], out=steps_in[i % 32][5])
+    e1.record()
+    torch.cuda.synchronize()
+    kern_us = e0.elapsed_time(e1) / steps * 1e3
+    stats = [c.stats() for c in caches]
+    kept = float(np.mean([s.kept_kv_bytes for s in stats]))
+    res = {"ctx": max(wl.ctx_lens), "keep": float(wl.keep.mean()), "instances": R,
+           "kept_kv_MB": kept / 1e6, "dense_kv_MB": float(np.mean([s.dense_kv_bytes for s in stats])) / 1e6,
+           "us_per_step": dt / steps * 1e6, "kernel_us": kern_us,
+           "kernel_GBps": kept / kern_us / 1e3, "step_GBps": kept / (dt / steps) / 1e9}
+    for c in caches:
+        c.close()
+    torch.cuda.empty_cache()
+    return res
+
+
+def scaling_sweep(args):
+    """Step time against kept bytes at fixed context, and against context at fixed kept
+    length (batch 16, 32q/8kv heads, head_dim 128, window 128, tau 0.5)."""
+    from paper_2605_14037_amd.inputs import small_workload
+    rows = []
+    for keep in (0.02, 0.05, 0.10, 0.20, 0.33, 0.50, 1.00):
+        wl = small_workload(f"keep{keep}", 16, 32, 8, 128, [32768] * 16, keep, seed=int(keep * 100))
+        rows.append(dict(sweep="keep at ctx 32768", **quick_point(wl, args.chunk, 60, 10)))
+        print(json.dumps(rows[-1]), flush=True)
+    for ctx in (8192, 16384, 32768, 65536, 131072):
+        keep = 3264.0 / (ctx - 128)
+        wl = small_workload(f"ctx{ctx}", 16, 32, 8, 128, [ctx] * 16, keep, seed=ctx)
+        rows.append(dict(sweep="ctx at ~3264 kept pairs per head", **quick_point(wl, args.chunk, 60, 10)))
+        print(json.dumps(rows[-1]), flush=True)
+    return rows
+
+
 def read_traffic_summary():
     """HBM bytes per launch of the split-K kernel from the committed rocprofv3 --pmc
     summary (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size), if present."""
@@ -125,6 +180,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=4)
+    ap.add_argument("--scaling", action="store_true",
+                    help="run the keep-rate and context sweeps instead of the benchmark")
     ap.add_argument("--copy-reference", action="store_true",
                     help="run only the plain 1 GiB copy kernel 20 times (profiler calibration)")
     args = ap.parse_args()
@@ -148,6 +205,10 @@ def main():
         dt = (time.perf_counter() - t0) / 20
         print(json.dumps({"copy_reference_bytes_read": 1 << 30, "bytes_written": 1 << 30,
                           "us_per_copy": dt * 1e6, "GBps_read_plus_write": 2 * (1 << 30) / dt / 1e9}))
+        return
+
+    if args.scaling:
+        scaling_sweep(args)
         return
 
     wl = workload(args.workload)

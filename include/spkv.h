@@ -87,7 +87,8 @@ typedef struct spkv_stats {
 } spkv_stats_t;
 
 /* Options for spkv_cache_set_option. */
-#define SPKV_OPT_ITEM_TARGET    1  /* split-K work items to aim for per decode, 1..16384     */
+#define SPKV_OPT_ITEM_TARGET    1  /* split-K work items to aim for per decode, 1..32768;
+                                      0 (default) = chosen from the cache size              */
 #define SPKV_OPT_KERNEL_TIMING  2  /* 1: bracket every split-K kernel launch with HIP events */
 #define SPKV_OPT_SPLIT_ONLY     3  /* 1: spkv_decode_attention launches the split-K kernel
                                       only (no combine, `out` and `lse` left untouched):

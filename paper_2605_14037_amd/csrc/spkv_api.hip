@@ -2,6 +2,7 @@
 // conservative capacity bound (the "safe budget" idea of the paper's appendix "Inference
 // Kernels": capacity is checked on the host without reading the device until a worst-case
 // bound trips), and kernel launches.  See include/spkv.h for the contract.
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -13,7 +14,9 @@
 namespace {
 
 constexpr size_t kAlign = 256;
-constexpr int kDefaultItemTarget = 3072;   // 12 waves per CU on 256 CUs
+constexpr int kMinItems = 3072;        // 12 one-wave workgroups per CU on 256 CUs
+constexpr int kMaxAutoItems = 8192;
+constexpr int kAutoItemHalfPages = 16; // above kMinItems items, aim at 16 half-pages (256 KB) each
 constexpr int kMaxTimedLaunches = 8192;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -52,7 +55,9 @@ bool carve(const spkv_config_t* c, Carve* out) {
     if (n_pages > ((int64_t)1 << 30)) return false;
     k.n_pages = (int)n_pages;
     k.n_seg_cap = (int)((max_evicted + kSegTokens - 1) / kSegTokens) + 1;
-    k.max_items = kMaxSlots + k.n_pairs;
+    // Work-item slots: 128 per pair leaves room for a pair 40 times longer than the mean at
+    // the default item count; at least enough for the largest item target on one pair.
+    k.max_items = std::max(kMaxItemTarget + k.n_pairs, std::min(k.n_pairs * 128, 1 << 17));
     const size_t page_bytes = (size_t)spkv_page_elems(c->head_dim) * 2;
     size_t off = 0;
     auto take = [&off](size_t bytes) {
@@ -144,7 +149,13 @@ SpkvSplit choose_split(const spkv_cache* c) {
         sum_hp += hp;
         max_hp = std::max(max_hp, hp);
     }
-    int64_t per = std::max<int64_t>(1, (sum_hp + c->item_target - 1) / c->item_target);
+    // Item count: the caller's target, else enough one-wave items to fill the chip once
+    // (kMinItems) and, for large caches, more of them (about 256 KB each) so that the tail
+    // of the launch stays short when the pairs differ widely in length.
+    int64_t target = c->item_target;
+    if (target <= 0)
+        target = std::min<int64_t>(kMaxAutoItems, std::max<int64_t>(kMinItems, sum_hp / kAutoItemHalfPages));
+    int64_t per = std::max<int64_t>(1, (sum_hp + target - 1) / target);
     const int64_t slots_cap = c->carve.max_items / c->carve.n_pairs - 1;
     if ((max_hp + per - 1) / per > slots_cap) per = (max_hp + slots_cap - 1) / slots_cap;
     SpkvSplit sp;
@@ -182,7 +193,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->L_ub.assign(k.n_pairs, 0);
     c->pages_ub = 0;
     c->bound_is_loose = false;
-    c->item_target = kDefaultItemTarget;
+    c->item_target = 0;
     c->split = SpkvSplit{1, 1};
     c->timing = false;
     c->split_only = false;
@@ -411,7 +422,7 @@ int spkv_cache_set_option(spkv_cache_t* c, int32_t option, int64_t value) {
     if (c == nullptr) return SPKV_E_INVAL;
     switch (option) {
         case SPKV_OPT_ITEM_TARGET:
-            if (value < 1 || value > kMaxItemTarget) return SPKV_E_INVAL;
+            if (value < 0 || value > kMaxItemTarget) return SPKV_E_INVAL;
             c->item_target = (int)value;
             return SPKV_OK;
         case SPKV_OPT_SPLIT_ONLY:

@@ -7,8 +7,7 @@
 #include "spkv_layout.h"
 
 constexpr int kSegTokens = 1024;      // bulk append: tokens per compaction segment
-constexpr int kMaxItemTarget = 16384;
-constexpr int kMaxSlots = 32768;      // work-item slots beyond one per (seq, head)
+constexpr int kMaxItemTarget = 32768;
 
 // Device-side view of one cache: plain pointers into the caller's arena.
 struct SpkvView {

@@ -119,56 +119,64 @@ __global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t
     const int row = cu.v[b];
     if (cu.v[b + 1] - row == 0) return;
     const int tid = threadIdx.x;
+    __shared__ int s_page;
+
+    // Round 1: the two counters.  Round 2: everything they address, issued together (the
+    // outgoing row is read before it is known whether it is kept: 2 + 16 bytes per thread).
     const int T = v.t_pair[pair];
+    const int L = v.kept_len[pair];
     const int slot = T % v.w;
     uint16_t* rp = ring_page(v, pair, slot >> 6);
     const int rk = slot & 63;
-    __shared__ int s_page;
+    const bool full = T >= v.w;
+    const int lp = L >> 6, gk = L & 63;
+    const bool have_page = gk != 0 && lp < v.pt_cap;
+    const size_t src = ((size_t)row * v.Hkv + h) * D;
 
-    if (T >= v.w) {
-        const float f_old = v.ring_logit[(size_t)pair * v.w + slot];
-        if (f_old >= v.theta) {                                   // Eq. 2 on the logit
-            const int L = v.kept_len[pair];
-            const int lp = L >> 6, gk = L & 63;
+    const float f_old = full ? v.ring_logit[(size_t)pair * v.w + slot] : 0.f;
+    const int page_entry = have_page ? v.page_table[(size_t)pair * v.pt_cap + lp] : -1;
+    const float f_new = f[(size_t)row * v.Hkv + h];
+    const uint16_t v_new = vv[src + tid];
+    uint4 k_new = {0u, 0u, 0u, 0u}, k_old = {0u, 0u, 0u, 0u};
+    if (tid < D / 8) k_new = *reinterpret_cast<const uint4*>(k + src + tid * 8);
+    uint16_t v_old = 0;
+    if (full) {
+        v_old = rp[spkv_v_off(D, rk, tid)];
+        if (tid < D / 8) k_old = *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
+    }
+
+    if (full && f_old >= v.theta) {                               // Eq. 2 on the logit
+        int page = page_entry;
+        if (!have_page) {                                         // first pair of a new page
             if (tid == 0) {
-                int page;
-                if (lp >= v.pt_cap) {
-                    page = -1;
-                } else if (gk == 0) {
-                    page = atomicAdd(v.pool_next, 1);
-                    if (page >= v.n_pages) page = -1;
-                    else v.page_table[(size_t)pair * v.pt_cap + lp] = page;
-                } else {
-                    page = v.page_table[(size_t)pair * v.pt_cap + lp];
+                int np = -1;
+                if (lp < v.pt_cap) {
+                    np = atomicAdd(v.pool_next, 1);
+                    if (np >= v.n_pages) np = -1;
                 }
-                if (page < 0) *v.err_flag = 1;
-                s_page = page;
+                if (np >= 0) v.page_table[(size_t)pair * v.pt_cap + lp] = np;
+                else *v.err_flag = 1;
+                s_page = np;
             }
             __syncthreads();
-            const int page = s_page;
-            if (page >= 0) {
-                uint16_t* gp = pool_page(v, page);
-                gp[spkv_v_off(D, gk, tid)] = rp[spkv_v_off(D, rk, tid)];
-                if (tid < D / 8)
-                    *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) =
-                        *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
-                if (tid == 0) {
-                    v.pos_pool[(size_t)page * kPageTokens + gk] = T - v.w;
-                    v.kept_len[pair] = L + 1;
-                }
+            page = s_page;
+        }
+        if (page >= 0) {
+            uint16_t* gp = pool_page(v, page);
+            gp[spkv_v_off(D, gk, tid)] = v_old;
+            if (tid < D / 8) *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) = k_old;
+            if (tid == 0) {
+                v.pos_pool[(size_t)page * kPageTokens + gk] = T - v.w;
+                v.kept_len[pair] = L + 1;
             }
         }
     }
-    const size_t src = ((size_t)row * v.Hkv + h) * D;
-    rp[spkv_v_off(D, rk, tid)] = vv[src + tid];
-    if (tid < D / 8)
-        *reinterpret_cast<uint4*>(rp + spkv_k_off(D, rk, tid * 8)) =
-            *reinterpret_cast<const uint4*>(k + src + tid * 8);
+    rp[spkv_v_off(D, rk, tid)] = v_new;
+    if (tid < D / 8) *reinterpret_cast<uint4*>(rp + spkv_k_off(D, rk, tid * 8)) = k_new;
     if (tid == 0) {
-        const float fn = f[(size_t)row * v.Hkv + h];
-        v.ring_logit[(size_t)pair * v.w + slot] = fn;
+        v.ring_logit[(size_t)pair * v.w + slot] = f_new;
         v.t_pair[pair] = T + 1;
-        if (fn >= v.theta) v.gate_on[pair] += 1;
+        if (f_new >= v.theta) v.gate_on[pair] += 1;
     }
 }
 
@@ -556,9 +564,8 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
 
 // Merge the partials of one (sequence, query head): with M = max_i m_i,
 //   out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i,  lse = (M + log2(sum)) ln 2.
-// One workgroup of 4 waves per (pair, head): the waves take the items round-robin (their
-// loads are independent, so a handful of load rounds covers the list), each lane owns
-// D/64 output elements, and the four wave sums meet in LDS.
+// One workgroup of 4 waves per (pair, head): the waves take the items round-robin, each
+// lane owns D/64 output elements, and the four wave results meet in LDS.
 template <int D>
 __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t* __restrict__ out,
                                                            float* __restrict__ lse, SpkvSplit sp) {
@@ -572,33 +579,43 @@ __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t*
     __shared__ float s_den[4];
     __shared__ float s_acc[4][D];
 
-    float M = SPKV_NEG_INF;
-    for (int i = tid; i < items; i += 256) M = fmaxf(M, v.part_ml[((slot0 + i) * v.G + g) * 2]);
-    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-    if (lane == 0) s_m[wave] = M;
-    __syncthreads();
-    M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
-
+    // One pass: every wave folds its items into a running (max, sum, acc) triple; the
+    // loads of successive items do not depend on each other, only the cheap rescaling does.
+    float mw = SPKV_NEG_INF, den = 0.f;
     float num[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) num[e] = 0.f;
-    float den = 0.f;
-#pragma unroll 4
+#pragma unroll 8
     for (int i = wave; i < items; i += 4) {
         const float* pm = v.part_ml + ((slot0 + i) * v.G + g) * 2;
         const float* pa = v.part_acc + ((slot0 + i) * v.G + g) * D + lane * E;
-        const float wgt = __builtin_amdgcn_exp2f(pm[0] - M);
-        den += wgt * pm[1];
+        const float mi = pm[0], li = pm[1];
+        float a[E];
 #pragma unroll
-        for (int e = 0; e < E; ++e) num[e] += wgt * pa[e];
+        for (int e = 0; e < E; ++e) a[e] = pa[e];
+        const float m_new = fmaxf(mw, mi);
+        const float so = __builtin_amdgcn_exp2f(mw - m_new), si = __builtin_amdgcn_exp2f(mi - m_new);
+        den = den * so + li * si;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] = num[e] * so + a[e] * si;
+        mw = m_new;
     }
 #pragma unroll
     for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
-    if (lane == 0) s_den[wave] = den;
+    if (lane == 0) {
+        s_m[wave] = mw;
+        s_den[wave] = den;
+    }
     __syncthreads();
     if (tid < D) {
-        const float nsum = s_acc[0][tid] + s_acc[1][tid] + s_acc[2][tid] + s_acc[3][tid];
-        const float dsum = s_den[0] + s_den[1] + s_den[2] + s_den[3];
+        const float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+        float nsum = 0.f, dsum = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) {
+            const float sc = __builtin_amdgcn_exp2f(s_m[wv] - M);   // 0 for a wave without items
+            nsum += s_acc[wv][tid] * sc;
+            dsum += s_den[wv] * sc;
+        }
         const size_t o = ((size_t)b * v.Hq + (size_t)h * v.G + g);
         const __bf16 r = (__bf16)(nsum / dsum);
         out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
