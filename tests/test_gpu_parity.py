@@ -229,3 +229,41 @@ def test_medium_ragged_batch():
     keep = np.array([[1.0, 0.0, 0.3, 0.05], [0.2, 1.0, 0.0, 0.5], [0.1, 0.1, 0.9, 0.0]])
     wl = small_workload("ragged", 3, 16, 4, 128, [9000, 2049, 4500], keep, decode_steps=3, seed=8)
     H.run_workload(wl, chunk=2048)
+
+
+@pytest.mark.parametrize("trial", range(24))
+def test_random_shapes_and_ragged_appends(trial):
+    """Seeded random shapes; appends of 0..300 tokens per sequence in random order, mixed
+    with single-token steps; state and outputs checked after every call."""
+    rng = np.random.default_rng(1000 + trial)
+    B = int(rng.integers(1, 5))
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    D = int(rng.choice([64, 128]))
+    w = int(rng.choice([1, 2, 7, 31, 32, 33, 64, 100, 128, 129, 200]))
+    tau = float(rng.choice([0.2, 0.5, 0.8]))
+    keep = rng.uniform(0.0, 1.0, size=(B, Hkv))
+    wl = small_workload("rand", B, G * Hkv, Hkv, D, [0] * B, keep, window=w, tau=tau,
+                        seed=5000 + trial)
+    stream = TokenStream(wl, device="cuda")
+    cache = spkv.SPKVCache(B, G * Hkv, Hkv, D, max_context=4000, max_total_kept_tokens=4000 * B * Hkv,
+                           window=w, tau=tau)
+    oracle = H.make_oracle(wl)
+    for call in range(int(rng.integers(4, 9))):
+        kind = rng.integers(0, 3)
+        if kind == 0:
+            counts = [1] * B
+        elif kind == 1:
+            counts = rng.integers(0, 2, size=B).tolist()
+        else:
+            counts = rng.integers(0, 301, size=B).tolist()
+        k, v, f, cu = stream.next_tokens(counts)
+        H.feed(cache, oracle, k, v, f, cu)
+        H.check_state(cache, oracle, wl, label=f"trial {trial} call {call}")
+        if all(oracle.seq_len(b) > 0 for b in range(B)):
+            q = stream.next_query()
+            out, lse = cache.decode_attention(q, want_lse=True)
+            ref_out, ref_lse = oracle.decode(to_numpy_f32(q))
+            H.check_output(out, ref_out, f"trial {trial} call {call}")
+            H.check_lse(lse, ref_lse, f"trial {trial} call {call}")
+    cache.close()
