@@ -76,7 +76,7 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.pool = take((size_t)k.n_pages * page_bytes);
     k.pos_pool = take((size_t)k.n_pages * kPageTokens * 4);
     k.seg_count = take((size_t)k.n_pairs * k.n_seg_cap * 4);
-    k.bulk_info = take((size_t)k.n_pairs * 16);
+    k.bulk_info = take((size_t)k.n_pairs * 32);
     k.part_acc = take((size_t)k.max_items * k.G * c->head_dim * 4);
     k.part_ml = take((size_t)k.max_items * k.G * 2 * 4);
     k.pos_scratch = take((size_t)k.pt_cap * kPageTokens * 4);

@@ -6,7 +6,7 @@
 #include "../../include/spkv.h"
 #include "spkv_layout.h"
 
-constexpr int kSegTokens = 1024;      // bulk append: tokens per compaction segment
+constexpr int kSegTokens = 256;       // bulk append: tokens per compaction segment (one per thread)
 constexpr int kMaxItemTarget = 32768;
 
 // Device-side view of one cache: plain pointers into the caller's arena.
@@ -31,7 +31,7 @@ struct SpkvView {
     uint16_t* pool;         // [n_pages] pages
     int32_t*  pos_pool;     // [n_pages][64] position of every long-term entry
     int32_t*  seg_count;    // [n_pairs][n_seg_cap] bulk scratch: kept per segment, then offsets
-    int32_t*  bulk_info;    // [n_pairs][4] bulk scratch: T_old, first long-term index of new tokens
+    int32_t*  bulk_info;    // [n_pairs][8] bulk scratch, see BulkInfo in spkv_kernels.hip
     float*    part_acc;     // [max_items][G][D] un-normalised partial outputs
     float*    part_ml;      // [max_items][G][2] running max (log2 domain) and sum
     int32_t*  pos_scratch;  // [pt_cap * 64] gather buffer for kept positions

@@ -193,9 +193,41 @@ hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const u
 // For (sequence, head) with n new tokens, T_old stored: positions that leave the window
 // are [max(0, T_old - w), T_old + n - w).  Those below T_old sit in the ring (<= w of
 // them, handled by spkv_bulk_ring); the others are new tokens j in [0, n - w) that enter
-// and leave the window within this call (handled per 1024-token segment).  The last
-// min(n, w) new tokens land in the ring.  Long-term order is ascending position:
-// ring-evicted first, then new tokens, ranks from ballot + mbcnt prefix sums.
+// and leave the window within this call (handled per 256-token segment, one token per
+// thread).  The last min(n, w) new tokens land in the ring.  Long-term order is ascending
+// position: ring-evicted first, then new tokens; ranks come from ballot + mbcnt prefix
+// sums inside a wave, popcounts across the four waves of a segment, and a scan of the
+// per-segment counts across segments.
+//
+// Rows are moved 16 at a time per workgroup: 16 lanes per row, each lane one 16-byte K
+// chunk and the 8 V elements of the same head-dim range (loads coalesced per row; the V
+// elements go out as 2-byte stores at 16-byte stride, which is what the page layout asks).
+
+// Per-pair scratch written by spkv_bulk_ring for spkv_bulk_scatter.
+struct BulkInfo {
+    int32_t T_old;        // tokens held before this call
+    int32_t new_base;     // long-term index of the first kept NEW token (after ring-evicted ones)
+    int32_t ok;           // 0: capacity error, the call writes nothing more for this pair
+    int32_t first_new_lp; // first logical page allocated by this call
+    int32_t base_page;    // pool page of first_new_lp (the call's pages are consecutive)
+    int32_t tail_page;    // pool page of logical page first_new_lp - 1 (partly filled before)
+    int32_t pad[2];
+};
+
+__device__ __forceinline__ int bulk_page_of(const BulkInfo& bi, int gidx) {
+    const int lp = gidx >> 6;
+    return lp < bi.first_new_lp ? bi.tail_page : bi.base_page + (lp - bi.first_new_lp);
+}
+
+// Lane (r = lane / 16, c = lane % 16) moves chunk c of one row into row dk of page dp.
+template <int D>
+__device__ __forceinline__ void store_row_chunk(uint16_t* dp, int dk, int c, uint4 kk, uint4 vv) {
+    *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk, c * 8)) = kk;
+    uint16_t* vd = dp + spkv_v_off(D, dk, c * 8);      // element e of the chunk is 8 e further
+    const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vd[e * 8] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+}
 
 // Stage 1: per (segment, pair) count of new tokens j < n - w that pass the gate.
 __global__ __launch_bounds__(256) void spkv_bulk_count(SpkvView v, const float* __restrict__ f,
@@ -204,25 +236,43 @@ __global__ __launch_bounds__(256) void spkv_bulk_count(SpkvView v, const float* 
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int n = cu.v[b + 1] - cu.v[b];
     const int n_ev = max(0, n - v.w);
-    const int j0 = seg * kSegTokens;
-    if (j0 >= n_ev) return;
-    const int j1 = min(n_ev, j0 + kSegTokens);
+    const int j = seg * kSegTokens + (int)threadIdx.x;
+    if (seg * kSegTokens >= n_ev) return;
     __shared__ int s_wave[4];
-    int cnt = 0;
-    for (int base = j0; base < j1; base += 256) {
-        const int j = base + (int)threadIdx.x;
-        const bool flag = j < j1 && f[((size_t)cu.v[b] + j) * v.Hkv + h] >= v.theta;
-        cnt += __popcll(__ballot(flag));
-    }
+    const bool flag = j < n_ev && f[((size_t)cu.v[b] + j) * v.Hkv + h] >= v.theta;
+    const int cnt = __popcll(__ballot(flag));
     if (lane_id() == 0) s_wave[threadIdx.x >> 6] = cnt;
     __syncthreads();
     if (threadIdx.x == 0)
         v.seg_count[(size_t)pair * v.n_seg_cap + seg] = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
 }
 
-// Stage 2: one workgroup per pair.  Compacts the pairs leaving the ring, turns the
-// segment counts into offsets, allocates every page the call needs with one atomic,
-// and publishes the new lengths.
+// Block-wide exclusive scan of one int per thread (256 threads); returns the exclusive
+// prefix and the block total.  s_w: 4 ints of shared memory.
+__device__ __forceinline__ int block_excl_scan(int x, int* s_w, int& total) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    int incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    __syncthreads();
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    int woff = 0;
+    total = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (i < wave) woff += s_w[i];
+        total += s_w[i];
+    }
+    return woff + incl - x;
+}
+
+// Stage 2: one workgroup per pair.  Counts the pairs leaving the ring that are kept,
+// turns the segment counts into offsets, allocates every page the call needs with one
+// atomic, publishes the new lengths, then moves the kept ring rows.
 template <int D>
 __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
     const int pair = blockIdx.x;
@@ -237,27 +287,36 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
     const int n_ev = max(0, n - v.w);
     const int nseg = (n_ev + kSegTokens - 1) / kSegTokens;
     const float* rl = v.ring_logit + (size_t)pair * v.w;
-    __shared__ int s_wave[4];
-    __shared__ int s_first, s_need, s_base, s_ok;
+    int32_t* sc = v.seg_count + (size_t)pair * v.n_seg_cap;
+    __shared__ int s_w[4];
+    __shared__ BulkInfo s_bi;
+    __shared__ uint16_t s_list[256];
 
+    // (a) how many ring pairs are kept
     int cnt = 0;
     for (int base = 0; base < nr; base += 256) {
         const int idx = base + tid;
         const bool flag = idx < nr && rl[(r0 + idx) % v.w] >= v.theta;
         cnt += __popcll(__ballot(flag));
     }
-    if (lane == 0) s_wave[wave] = cnt;
+    if (lane == 0) s_w[wave] = cnt;
     __syncthreads();
+    const int ring_kept = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+
+    // (b) segment counts -> exclusive offsets (in place)
+    int carry = 0;
+    for (int base = 0; base < nseg; base += 256) {
+        const int i = base + tid;
+        const int c = i < nseg ? sc[i] : 0;
+        int tot;
+        const int ex = block_excl_scan(c, s_w, tot);
+        if (i < nseg) sc[i] = carry + ex;
+        carry += tot;
+    }
+    const int total_new = ring_kept + carry;
+
+    // (c) pages: the call's new pages are consecutive pool pages from one atomicAdd
     if (tid == 0) {
-        const int ring_kept = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
-        int acc = 0;
-        int32_t* sc = v.seg_count + (size_t)pair * v.n_seg_cap;
-        for (int sgi = 0; sgi < nseg; ++sgi) {
-            const int c = sc[sgi];
-            sc[sgi] = acc;
-            acc += c;
-        }
-        const int total_new = ring_kept + acc;
         const int first = (L_old + kPageTokens - 1) / kPageTokens;
         const int last = (L_old + total_new + kPageTokens - 1) / kPageTokens;
         const int need = last - first;
@@ -268,61 +327,61 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
             if (base + need > v.n_pages) ok = 0;
         }
         if (!ok) *v.err_flag = 1;
-        s_first = first;
-        s_need = ok ? need : 0;
-        s_base = base;
-        s_ok = ok;
-        int32_t* bi = v.bulk_info + (size_t)pair * 4;
-        bi[0] = T_old;
-        bi[1] = L_old + ring_kept;
-        bi[2] = ok;
+        s_bi.T_old = T_old;
+        s_bi.new_base = L_old + ring_kept;
+        s_bi.ok = ok;
+        s_bi.first_new_lp = first;
+        s_bi.base_page = base;
+        s_bi.tail_page = first > 0 ? v.page_table[(size_t)pair * v.pt_cap + first - 1] : 0;
+        s_bi.pad[0] = ok ? need : 0;
+        *reinterpret_cast<BulkInfo*>(v.bulk_info + (size_t)pair * 8) = s_bi;
         if (ok) v.kept_len[pair] = L_old + total_new;
+        v.t_pair[pair] = T_new;
     }
     __syncthreads();
-    const int ok = s_ok;
-    for (int i = tid; i < s_need; i += 256)
-        v.page_table[(size_t)pair * v.pt_cap + s_first + i] = s_base + i;
-    __threadfence_block();
-    __syncthreads();
+    const BulkInfo bi = s_bi;
+    for (int i = tid; i < bi.pad[0]; i += 256)
+        v.page_table[(size_t)pair * v.pt_cap + bi.first_new_lp + i] = bi.base_page + i;
+    if (!bi.ok) return;
 
-    int carry = 0;
+    // (d) move the kept ring rows, 256 ring positions at a time
+    int done = 0;
     for (int base = 0; base < nr; base += 256) {
         const int idx = base + tid;
         const bool flag = idx < nr && rl[(r0 + idx) % v.w] >= v.theta;
-        const unsigned long long mask = __ballot(flag);
+        int tot;
+        const int rank = block_excl_scan(flag ? 1 : 0, s_w, tot);
+        if (flag) s_list[rank] = (uint16_t)tid;
         __syncthreads();
-        if (lane == 0) s_wave[wave] = __popcll(mask);
-        __syncthreads();
-        int woff = 0, ctot = 0;
-        for (int i = 0; i < 4; ++i) {
-            if (i < wave) woff += s_wave[i];
-            ctot += s_wave[i];
-        }
-        if (ok) {
-            unsigned long long m = mask;
-            int c = 0;
-            while (m) {
-                const int bit = __ffsll((long long)m) - 1;
-                m &= m - 1;
-                const int s = r0 + base + wave * 64 + bit;
+        const int c = lane & 15;
+        for (int rb = wave * 4; rb < tot; rb += 16) {
+            const int r = rb + (lane >> 4);
+            if (r < tot && c < D / 8) {
+                const int s = r0 + base + s_list[r];
                 const int slot = s % v.w;
-                const int gi = L_old + carry + woff + c;
-                ++c;
-                const int page = v.page_table[(size_t)pair * v.pt_cap + (gi >> 6)];
-                copy_row_paged<D>(ring_page(v, pair, slot >> 6), slot & 63, pool_page(v, page),
-                                  gi & 63, lane);
-                if (lane == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = s;
+                const uint16_t* sp = ring_page(v, pair, slot >> 6);
+                const int sk = slot & 63;
+                const uint4 kk = *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, c * 8));
+                const uint16_t* vs = sp + spkv_v_off(D, sk, c * 8);
+                unsigned w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] = (unsigned)vs[(2 * e) * 8] | ((unsigned)vs[(2 * e + 1) * 8] << 16);
+                const int gi = L_old + done + r;
+                const int page = bulk_page_of(bi, gi);
+                store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, make_uint4(w[0], w[1], w[2], w[3]));
+                if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = s;
             }
         }
-        carry += ctot;
+        done += tot;
+        __syncthreads();
     }
-    if (tid == 0) v.t_pair[pair] = T_new;
 }
 
-// Stage 3: per (segment, pair).  Recomputes the keep flags of the segment's tokens,
-// ranks them (ballot + mbcnt within a wave, popcount prefix across the 16 wave-steps of
-// the segment, segment offset from stage 2) and copies kept rows into the long-term pages;
-// writes the last min(n, w) tokens into the ring.
+// Stage 3: per (256-token segment, pair).  Thread i owns token j0 + i: gate flag, rank
+// (mbcnt inside the wave + the popcounts of the lower waves + the segment offset from
+// stage 2); the kept tokens' indices are compacted into LDS and their rows moved 16 at a
+// time; the last min(n, w) tokens of the call are written into the ring.
 template <int D>
 __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint16_t* __restrict__ k,
                                                          const uint16_t* __restrict__ vv,
@@ -333,54 +392,57 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
     const int n = cu.v[b + 1] - row0;
     const int j0 = seg * kSegTokens;
     if (j0 >= n) return;
-    const int32_t* bi = v.bulk_info + (size_t)pair * 4;
-    if (bi[2] == 0) return;
-    const int T_old = bi[0], Lbase = bi[1];
+    const BulkInfo bi = *reinterpret_cast<const BulkInfo*>(v.bulk_info + (size_t)pair * 8);
+    if (bi.ok == 0) return;
     const int n_ev = max(0, n - v.w);
-    const int seg_off = (j0 < n_ev) ? v.seg_count[(size_t)pair * v.n_seg_cap + seg] : 0;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    __shared__ int s_cnt[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15;
+    __shared__ int s_cnt[4];
+    __shared__ uint16_t s_list[256];
 
-    unsigned long long masks[4];
-    int gate_cnt = 0;
+    const int j = j0 + tid;
+    const bool on = j < n && f[((size_t)row0 + j) * v.Hkv + h] >= v.theta;
+    const unsigned long long on_mask = __ballot(on);
+    if (lane == 0 && on_mask != 0ull) atomicAdd(v.gate_on + pair, __popcll(on_mask));
+    const bool ev = on && j < n_ev;
+    const unsigned long long mask = __ballot(ev);
+    if (lane == 0) s_cnt[wave] = __popcll(mask);
+    __syncthreads();
+    int woff = 0, total = 0;
 #pragma unroll
-    for (int gi = 0; gi < 4; ++gi) {
-        const int g = wave * 4 + gi;
-        const int j = j0 + g * 64 + lane;
-        const bool on = j < n && f[((size_t)row0 + j) * v.Hkv + h] >= v.theta;
-        gate_cnt += __popcll(__ballot(on));
-        masks[gi] = __ballot(on && j < n_ev);
-        if (lane == 0) s_cnt[g] = __popcll(masks[gi]);
+    for (int i = 0; i < 4; ++i) {
+        if (i < wave) woff += s_cnt[i];
+        total += s_cnt[i];
     }
-    if (lane == 0 && gate_cnt) atomicAdd(v.gate_on + pair, gate_cnt);
+    if (ev) s_list[woff + mbcnt64(mask)] = (uint16_t)tid;
     __syncthreads();
 
-    for (int gi = 0; gi < 4; ++gi) {
-        const int g = wave * 4 + gi;
-        const int jg = j0 + g * 64;
-        if (jg >= n) break;
-        int prefix = 0;
-        for (int i = 0; i < g; ++i) prefix += s_cnt[i];
-        unsigned long long m = masks[gi];
-        int c = 0;
-        while (m) {
-            const int bit = __ffsll((long long)m) - 1;
-            m &= m - 1;
-            const int j = jg + bit;
-            const int gidx = Lbase + seg_off + prefix + c;
-            ++c;
-            const int page = v.page_table[(size_t)pair * v.pt_cap + (gidx >> 6)];
-            const size_t src = ((size_t)(row0 + j) * v.Hkv + h) * D;
-            copy_row_dense<D>(k + src, vv + src, pool_page(v, page), gidx & 63, lane);
-            if (lane == 0) v.pos_pool[(size_t)page * kPageTokens + (gidx & 63)] = T_old + j;
+    if (total > 0) {
+        const int g0 = bi.new_base + v.seg_count[(size_t)pair * v.n_seg_cap + seg];
+        for (int rb = wave * 4; rb < total; rb += 16) {
+            const int r = rb + (lane >> 4);
+            if (r < total && c < D / 8) {
+                const int jj = j0 + s_list[r];
+                const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
+                const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
+                const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
+                const int gi = g0 + r;
+                const int page = bulk_page_of(bi, gi);
+                store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, vl);
+                if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = bi.T_old + jj;
+            }
         }
-        const int ja = max(jg, n_ev), jb = min(n, jg + 64);
-        for (int j = ja; j < jb; ++j) {
-            const int slot = (T_old + j) % v.w;
-            const size_t src = ((size_t)(row0 + j) * v.Hkv + h) * D;
-            copy_row_dense<D>(k + src, vv + src, ring_page(v, pair, slot >> 6), slot & 63, lane);
-            if (lane == 0)
-                v.ring_logit[(size_t)pair * v.w + slot] = f[((size_t)row0 + j) * v.Hkv + h];
+    }
+    const int ja = max(j0, n_ev), jb = min(n, j0 + kSegTokens);
+    for (int rb = ja + wave * 4; rb < jb; rb += 16) {
+        const int jj = rb + (lane >> 4);
+        if (jj < jb && c < D / 8) {
+            const int slot = (bi.T_old + jj) % v.w;
+            const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
+            const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
+            const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
+            store_row_chunk<D>(ring_page(v, pair, slot >> 6), slot & 63, c, kk, vl);
+            if (c == 0)
+                v.ring_logit[(size_t)pair * v.w + slot] = f[((size_t)row0 + jj) * v.Hkv + h];
         }
     }
 }
