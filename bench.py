@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """SP-KV decode benchmark on one MI355X.
 
-A step is one pass of the whole hot path over one batch: spkv_append of one new token per
-sequence (gate, ring write, evict + compact) followed by spkv_decode_attention (schedule,
-split-K MFMA decode, log-sum-exp combine).  Inputs are synthetic, seeded and resident in
+A step is one pass of the whole hot path over one batch: the append of one new token per
+sequence (gate, ring write, evict + compact) and the decode attention of that token (work
+partition, split-K MFMA decode, log-sum-exp combine), taken through spkv_decode_step (two
+launches; --two-call times spkv_append + spkv_decode_attention, three launches, instead).  Inputs are synthetic, seeded and resident in
 HBM before the timed region.  The workload is the Llama-3-8B-shaped layer: batch 16,
 32 query / 8 KV heads, head_dim 128, context 32768, window 128, tau 0.5, per-head keep
 rates U[0.10, 0.33].  Several independent cache instances are rotated so that the working
@@ -80,8 +81,9 @@ def build_cache(wl: Workload, instance: int, chunk: int, tau=None, oracle=None, 
 HOST_ISSUE_S = []      # host time spent issuing each timed region (before the final sync)
 
 
-def timed_steps(caches, steps_in, n_steps, offset, do_append=True, do_decode=True):
-    """n_steps steps, rotating over the cache instances; returns seconds."""
+def timed_steps(caches, steps_in, n_steps, offset, do_append=True, do_decode=True, fused=False):
+    """n_steps steps, rotating over the cache instances; returns seconds.  fused: one
+    spkv_decode_step per step instead of spkv_append + spkv_decode_attention."""
     R = len(caches)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -89,6 +91,9 @@ def timed_steps(caches, steps_in, n_steps, offset, do_append=True, do_decode=Tru
         j = offset + i
         c = caches[j % R]
         k, v, f, cu, q, out = steps_in[j % len(steps_in)]
+        if fused:
+            c.decode_step(k, v, f, q, out=out)
+            continue
         if do_append:
             c.append(k, v, f, cu)
         if do_decode:
@@ -113,8 +118,8 @@ def quick_point(wl, chunk, steps, warmup):
         k, v, f, cu = streams[j % R].next_tokens([1] * wl.batch)
         q = streams[j % R].next_query()
         steps_in.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
-    timed_steps(caches, steps_in, warmup, 0)
-    dt = timed_steps(caches, steps_in, steps, warmup)
+    timed_steps(caches, steps_in, warmup, 0, fused=True)
+    dt = timed_steps(caches, steps_in, steps, warmup, fused=True)
     for c in caches:
         c.set_option(spkv.OPT_SPLIT_ONLY, 1)
     timed_steps(caches, steps_in, max(warmup, R), 0, do_append=False)
@@ -152,6 +157,99 @@ def scaling_sweep(args):
         rows.append(dict(sweep="ctx at ~3264 kept pairs per head", **quick_point(wl, args.chunk, 60, 10)))
         print(json.dumps(rows[-1]), flush=True)
     return rows
+
+
+def layered_bench(wl, args):
+    """The 32-layer configuration: one cache per layer; a step runs, for every layer, the
+    stand-in utility predictor (logits = h W_l + b, a [B, 4096] x [4096, H_kv] product done
+    by torch outside the C ABI), spkv_append and spkv_decode_attention.  The layers' caches
+    (10.8 GB of kept K/V) are the cold rotation.  Dense baseline: the same loop over
+    tau = 0 caches of `dense_layers` layers, scaled to all layers (stated in the output)."""
+    Lyr, B, Hkv = wl.n_layers, wl.batch, wl.n_kv_heads
+    caches, streams = [], []
+    for l in range(Lyr):
+        c, s = build_cache(wl, l, args.chunk)
+        caches.append(c)
+        streams.append(s)
+    g = torch.Generator(device="cuda").manual_seed(wl.seed)
+    W = [torch.randn(4096, Hkv, generator=g, device="cuda") / 64.0 for _ in range(Lyr)]
+    bias = torch.full((B, Hkv), float(wl.mu.mean()), device="cuda")
+    ring = []
+    for j in range(4):
+        per_layer = []
+        for l in range(Lyr):
+            k, v, _, cu = streams[l].next_tokens([1] * B)
+            h = torch.randn(B, 4096, generator=g, device="cuda")
+            q = streams[l].next_query()
+            per_layer.append((k, v, h, caches[0].make_cu(cu), q, torch.empty_like(q),
+                              torch.empty(B, Hkv, device="cuda")))
+        ring.append(per_layer)
+
+    def run(cs, n_steps, offset, layers):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n_steps):
+            for l in range(layers):
+                k, v, h, cu, q, out, f = ring[(offset + i) % 4][l]
+                torch.addmm(bias, h, W[l], out=f)
+                cs[l].decode_step(k, v, f, q, out=out)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n_steps
+
+    W_, K_ = max(2, args.warmup // 10), max(5, args.steps // 10)
+    run(caches, W_, 0, Lyr)
+    dt = run(caches, K_, W_, Lyr)
+    for c in caches:
+        c.set_option(spkv.OPT_SPLIT_ONLY, 1)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for l in range(Lyr):
+        caches[l].decode_attention(ring[0][l][4], out=ring[0][l][5])
+    e0.record()
+    for i in range(K_):
+        for l in range(Lyr):
+            caches[l].decode_attention(ring[i % 4][l][4], out=ring[i % 4][l][5])
+    e1.record()
+    torch.cuda.synchronize()
+    kern_us = e0.elapsed_time(e1) / (K_ * Lyr) * 1e3
+    for c in caches:
+        c.set_option(spkv.OPT_SPLIT_ONLY, 0)
+    stats = [c.stats() for c in caches]
+    kept = float(sum(s.kept_kv_bytes for s in stats))
+    dense_bytes = float(sum(s.dense_kv_bytes for s in stats))
+    arena = float(sum(s.arena_bytes for s in stats))
+    dense = None
+    if not args.no_dense:
+        DL = 8
+        dcs = [build_cache(wl, 1000 + l, args.chunk, tau=0.0)[0] for l in range(DL)]
+        run(dcs, 1, 0, DL)
+        ddt = run(dcs, max(3, K_ // 2), 1, DL)
+        dense = {"what": f"same loop over tau = 0 caches of {DL} layers, scaled x{Lyr // DL} to {Lyr} layers",
+                 "us_per_step": ddt * Lyr / DL * 1e6, "kv_bytes_per_step": dense_bytes,
+                 "GBps": dense_bytes / (ddt * Lyr / DL) / 1e9, "speedup_of_spkv": ddt * Lyr / DL / dt}
+        for c in dcs:
+            c.close()
+    result = {
+        "metric": "sp-kv decode step (append + decode attention): achieved HBM GB/s on kept-KV bytes",
+        "value": kept / dt / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": K_, "warmup": W_,
+        "ms_per_step": dt * 1e3, "us_per_step": dt * 1e6, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {Lyr} layers x (batch {B}, {wl.n_q_heads}q/{Hkv}kv heads, "
+                               f"head_dim {wl.head_dim}, ctx {max(wl.ctx_lens)}, window {wl.window}, "
+                               f"tau {wl.tau}), linear 4096->{Hkv} stand-in predictor per layer",
+                   "kept_kv_bytes_per_step": kept, "dense_kv_bytes_per_step": dense_bytes,
+                   "cache_arena_bytes": arena,
+                   "density_evicted": float(np.mean([s.density_evicted for s in stats]))},
+        "frac_of_hbm_peak_step": kept / dt / 1e9 / HBM_PEAK_GBPS,
+        "dense_cache": dense,
+        "roofline": {"bound": "hbm", "kernel": "spkv_decode_split<128>",
+                     "achieved": kept / Lyr / kern_us / 1e3, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": kept / Lyr / kern_us / 1e3 / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": kept / Lyr, "kernel_avg_us": kern_us,
+                     "launches_timed": K_ * Lyr,
+                     "timing": "HIP events around back-to-back launches of the split-K kernel alone"},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(result))
 
 
 def read_traffic_summary():
@@ -198,6 +296,9 @@ def main():
     ap.add_argument("--instances", type=int, default=0, help="cache instances to rotate (0 = auto)")
     ap.add_argument("--item-target", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=1024, help="prefill chunk (tokens per sequence)")
+    ap.add_argument("--two-call", action="store_true",
+                    help="time spkv_append + spkv_decode_attention (3 launches) as the step "
+                         "instead of the fused spkv_decode_step (2 launches)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=4)
@@ -233,6 +334,9 @@ def main():
         return
 
     wl = workload(args.workload)
+    if wl.n_layers > 1:
+        layered_bench(wl, args)
+        return
     exp_bytes = (wl.expected_kept_tokens() + wl.batch * wl.n_kv_heads * wl.window) * 4 * wl.head_dim
     R = args.instances or max(2, int(np.ceil(2.5e9 / exp_bytes)))
     cpu_seqs = min(args.cpu_seqs, wl.batch)
@@ -260,10 +364,14 @@ def main():
         steps_in.append((k, v, f, caches[0].make_cu(cu), q, out))
 
     W, K = args.warmup, args.steps
-    timed_steps(caches, steps_in, W, 0)
-    dt = timed_steps(caches, steps_in, K, W)
+    fused = not args.two_call
+    timed_steps(caches, steps_in, W, 0, fused=fused)
+    dt = timed_steps(caches, steps_in, K, W, fused=fused)
     ms_per_step = dt / K * 1e3
     host_issue_us = HOST_ISSUE_S[-1] * 1e6
+    # the other way of taking the same step, for reference
+    timed_steps(caches, steps_in, max(W, R), 0, fused=not fused)
+    dt_other = timed_steps(caches, steps_in, K, W, fused=not fused)
 
     # Roofline of the dominant kernel: K launches of the split-K kernel alone, back to back
     # on the launch stream (same rotation over the cache instances), between two HIP events.
@@ -305,8 +413,8 @@ def main():
         torch.cuda.empty_cache()
         dc, ds = build_cache(wl, 1000, args.chunk, tau=0.0)
         Kd = max(10, K // 4)
-        timed_steps([dc], steps_in, 5, 0)
-        ddt = timed_steps([dc], steps_in, Kd, 5)
+        timed_steps([dc], steps_in, 5, 0, fused=fused)
+        ddt = timed_steps([dc], steps_in, Kd, 5, fused=fused)
         dst = dc.stats()
         dense = {
             "what": "same library, tau = 0 (every pair kept): dense-cache decode on the same GPU",
@@ -352,6 +460,9 @@ def main():
             "density_evicted": density,
             "work_items": int(stats[0].n_work_items),
         },
+        "step_entry": ("spkv_decode_step (fused append + decode, 2 launches)" if fused else
+                       "spkv_append + spkv_decode_attention (3 launches)"),
+        "us_per_step_other_entry": dt_other / K * 1e6,
         "host_issue_us_per_step": host_issue_us,
         "decode_only_us": dt_dec / K * 1e6,
         "append_only_us": dt_app / K * 1e6,

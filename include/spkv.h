@@ -142,6 +142,22 @@ int spkv_append(spkv_cache_t* cache, const void* k, const void* v, const float* 
 int spkv_decode_attention(spkv_cache_t* cache, const void* q, void* out, float* lse,
                           float sm_scale, void* stream);
 
+/* One whole decode step in two kernel launches instead of three: the same result and the
+ * same cache state as
+ *     spkv_append(cache, k, v, util_logits, {0, 1, .., batch}, stream);
+ *     spkv_decode_attention(cache, q, out, lse, sm_scale, stream);
+ * (appendix "Inference Kernels" for the write, Eq. 3-5 for the read), for the case of exactly
+ * one new token per sequence:
+ *   k, v         device bf16 [batch, n_kv_heads, head_dim]   (the new token's pair)
+ *   util_logits  device fp32 [batch, n_kv_heads]
+ *   q, out, lse, sm_scale as for spkv_decode_attention
+ * The split-K kernel attends to the cache as it stands plus the new pair read from k / v,
+ * leaving out the pair the new token pushes out of the window unless it passes the gate;
+ * the second kernel merges the partials and then performs the append.  Sequences may be
+ * empty before the call.  Errors as for spkv_append (SPKV_E_CAPACITY before any launch). */
+int spkv_decode_step(spkv_cache_t* cache, const void* k, const void* v, const float* util_logits,
+                     const void* q, void* out, float* lse, float sm_scale, void* stream);
+
 /* Gate density and sizes (Eq. 8).  Synchronises `stream`.  kept_len (host int32
  * [batch * n_kv_heads], or NULL) receives the long-term length of every (seq, head). */
 int spkv_cache_stats(spkv_cache_t* cache, spkv_stats_t* stats, int32_t* kept_len, void* stream);

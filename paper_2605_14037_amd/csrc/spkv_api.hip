@@ -23,7 +23,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Carve {
     size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, err_flag, page_table, pool,
-        pos_pool, seg_count, bulk_info, part_acc, part_ml,
+        pos_pool, seg_count, bulk_info, part_acc, part_ml, pair_items,
         pos_scratch, total;
     int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items;
 };
@@ -79,6 +79,7 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.bulk_info = take((size_t)k.n_pairs * 32);
     k.part_acc = take((size_t)k.max_items * k.G * c->head_dim * 4);
     k.part_ml = take((size_t)k.max_items * k.G * 2 * 4);
+    k.pair_items = take((size_t)k.n_pairs * 4);
     k.pos_scratch = take((size_t)k.pt_cap * kPageTokens * 4);
     k.total = off;
     *out = k;
@@ -164,6 +165,52 @@ SpkvSplit choose_split(const spkv_cache* c) {
     return sp;
 }
 
+// Tokens sequence b receives in a call: from cu_seqlens, or one each (cu == nullptr).
+int tokens_for(const int32_t* cu, int b) { return cu == nullptr ? 1 : cu[b + 1] - cu[b]; }
+
+// Capacity check before any launch.  Worst case for the pool: every pair pushed out of
+// the window by this call is kept.  If that does not fit, the true lengths are read back
+// once (synchronises) and the check repeated; SPKV_E_CAPACITY if it still does not fit.
+int reserve_capacity(spkv_cache* c, const int32_t* cu, hipStream_t s) {
+    const int B = c->cfg.batch, Hkv = c->cfg.n_kv_heads, w = c->cfg.window;
+    for (int b = 0; b < B; ++b)
+        if ((int64_t)c->T[b] + tokens_for(cu, b) > c->cfg.max_context) return SPKV_E_CAPACITY;
+    for (int attempt = 0;; ++attempt) {
+        int64_t pages = c->pages_ub;
+        for (int b = 0; b < B; ++b) {
+            const int n = tokens_for(cu, b);
+            const int64_t ev = std::max<int64_t>(0, (int64_t)c->T[b] + n - w) -
+                               std::max<int64_t>(0, (int64_t)c->T[b] - w);
+            if (ev == 0) continue;
+            for (int h = 0; h < Hkv; ++h) {
+                const int64_t L = c->L_ub[b * Hkv + h];
+                pages += pages_for(L + ev) - pages_for(L);
+            }
+        }
+        if (pages <= c->carve.n_pages) return SPKV_OK;
+        if (attempt == 1) return SPKV_E_CAPACITY;
+        const int rc = refresh_bound(c, s, nullptr);
+        if (rc != SPKV_OK) return rc;
+    }
+}
+
+// Host bookkeeping after the launch: exact token counts, upper bounds of the lengths.
+void commit_lengths(spkv_cache* c, const int32_t* cu) {
+    const int B = c->cfg.batch, Hkv = c->cfg.n_kv_heads, w = c->cfg.window;
+    for (int b = 0; b < B; ++b) {
+        const int n = tokens_for(cu, b);
+        const int64_t ev = std::max<int64_t>(0, (int64_t)c->T[b] + n - w) -
+                           std::max<int64_t>(0, (int64_t)c->T[b] - w);
+        c->T[b] += n;
+        if (ev == 0) continue;
+        for (int h = 0; h < Hkv; ++h) {
+            int32_t& L = c->L_ub[b * Hkv + h];
+            c->pages_ub += pages_for(L + ev) - pages_for(L);
+            L += (int32_t)ev;
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -227,6 +274,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     v.bulk_info = reinterpret_cast<int32_t*>(a + k.bulk_info);
     v.part_acc = reinterpret_cast<float*>(a + k.part_acc);
     v.part_ml = reinterpret_cast<float*>(a + k.part_ml);
+    v.pair_items = reinterpret_cast<int32_t*>(a + k.pair_items);
     v.pos_scratch = reinterpret_cast<int32_t*>(a + k.pos_scratch);
     if (spkv_launch_fill_zero(c->arena, c->arena_bytes, static_cast<hipStream_t>(stream)) !=
         hipSuccess) {
@@ -257,38 +305,20 @@ int spkv_cache_reset(spkv_cache_t* c, void* stream) {
 int spkv_append(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
                 const int32_t* cu_seqlens, void* stream) {
     if (c == nullptr || cu_seqlens == nullptr) return SPKV_E_INVAL;
-    const int B = c->cfg.batch, Hkv = c->cfg.n_kv_heads, w = c->cfg.window;
+    const int B = c->cfg.batch;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (cu_seqlens[0] != 0) return SPKV_E_INVAL;
     int n_max = 0;
     for (int b = 0; b < B; ++b) {
         const int64_t n = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
         if (n < 0) return SPKV_E_INVAL;
-        if ((int64_t)c->T[b] + n > c->cfg.max_context) return SPKV_E_CAPACITY;
-        if (n > n_max) n_max = (int)n;
+        if (n > n_max) n_max = (int)std::min<int64_t>(n, INT32_MAX);
     }
     if (n_max == 0) return SPKV_OK;
     if (k == nullptr || v == nullptr || util_logits == nullptr) return SPKV_E_INVAL;
     if (!aligned16(k) || !aligned16(v) || !aligned16(util_logits)) return SPKV_E_INVAL;
-
-    // Worst case for the pool: every pair pushed out of the window by this call is kept.
-    for (int attempt = 0;; ++attempt) {
-        int64_t pages = c->pages_ub;
-        for (int b = 0; b < B; ++b) {
-            const int n = cu_seqlens[b + 1] - cu_seqlens[b];
-            const int64_t ev = std::max<int64_t>(0, (int64_t)c->T[b] + n - w) -
-                               std::max<int64_t>(0, (int64_t)c->T[b] - w);
-            if (ev == 0) continue;
-            for (int h = 0; h < Hkv; ++h) {
-                const int64_t L = c->L_ub[b * Hkv + h];
-                pages += pages_for(L + ev) - pages_for(L);
-            }
-        }
-        if (pages <= c->carve.n_pages) break;
-        if (attempt == 1) return SPKV_E_CAPACITY;
-        const int rc = refresh_bound(c, s, nullptr);
-        if (rc != SPKV_OK) return rc;
-    }
+    const int rc = reserve_capacity(c, cu_seqlens, s);
+    if (rc != SPKV_OK) return rc;
 
     SpkvCu cu;
     std::memcpy(cu.v, cu_seqlens, (size_t)(B + 1) * 4);
@@ -298,20 +328,34 @@ int spkv_append(spkv_cache_t* c, const void* k, const void* v, const float* util
                        ? spkv_launch_append_step(c->view, kk, vv, util_logits, cu, s)
                        : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, s);
     if (e != hipSuccess) return SPKV_E_HIP;
-
-    for (int b = 0; b < B; ++b) {
-        const int n = cu_seqlens[b + 1] - cu_seqlens[b];
-        const int64_t ev = std::max<int64_t>(0, (int64_t)c->T[b] + n - w) -
-                           std::max<int64_t>(0, (int64_t)c->T[b] - w);
-        c->T[b] += n;
-        if (ev == 0) continue;
-        for (int h = 0; h < Hkv; ++h) {
-            int32_t& L = c->L_ub[b * Hkv + h];
-            c->pages_ub += pages_for(L + ev) - pages_for(L);
-            L += (int32_t)ev;
-        }
-    }
+    commit_lengths(c, cu_seqlens);
     if (n_max > 1) c->bound_is_loose = true;
+    return SPKV_OK;
+}
+
+int spkv_decode_step(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
+                     const void* q, void* out, float* lse, float sm_scale, void* stream) {
+    if (c == nullptr || k == nullptr || v == nullptr || util_logits == nullptr || q == nullptr ||
+        out == nullptr)
+        return SPKV_E_INVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(util_logits) || !aligned16(q) ||
+        !aligned16(out) || (lse != nullptr && !aligned16(lse)))
+        return SPKV_E_INVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
+    if (c->bound_is_loose) {
+        const int rc = refresh_bound(c, s, nullptr);
+        if (rc != SPKV_OK) return rc;
+    }
+    const int rc = reserve_capacity(c, nullptr, s);
+    if (rc != SPKV_OK) return rc;
+    c->split = choose_split(c);          // partition of the state BEFORE the append
+    if (spkv_launch_decode_step(c->view, static_cast<const uint16_t*>(k),
+                                static_cast<const uint16_t*>(v), util_logits,
+                                static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out), lse,
+                                sm_scale, c->split, s) != hipSuccess)
+        return SPKV_E_HIP;
+    commit_lengths(c, nullptr);
     return SPKV_OK;
 }
 

@@ -34,6 +34,7 @@ struct SpkvView {
     int32_t*  bulk_info;    // [n_pairs][8] bulk scratch, see BulkInfo in spkv_kernels.hip
     float*    part_acc;     // [max_items][G][D] un-normalised partial outputs
     float*    part_ml;      // [max_items][G][2] running max (log2 domain) and sum
+    int32_t*  pair_items;   // [n_pairs] fused step: item count of every pair, split -> combine
     int32_t*  pos_scratch;  // [pt_cap * 64] gather buffer for kept positions
 };
 
@@ -59,4 +60,7 @@ struct SpkvSplit {
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
                               float sm_scale, SpkvSplit split, bool split_only, hipEvent_t ev0,
                               hipEvent_t ev1, hipStream_t s);
+hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                                   float sm_scale, SpkvSplit split, hipStream_t s);
 hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s);

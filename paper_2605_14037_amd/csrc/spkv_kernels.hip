@@ -7,6 +7,8 @@
 //                in both decode kernels from the device-side lengths)
 //   read path  : spkv_decode_split (split-K flash decoding on MFMA, one wave per item),
 //                spkv_decode_combine (log-sum-exp merge of the partials)
+//   fused step : spkv_decode_split<.., true> + spkv_combine_append (append and decode of
+//                one token per sequence in two launches instead of three)
 //
 // Gate: Eq. 2 of the paper taken on the logit, z = 1[f >= theta].  Availability:
 // Eq. 3-4; the window ring holds exactly the keys with 0 <= t - s < w and the long-term
@@ -45,28 +47,6 @@ __device__ __forceinline__ uint16_t* ring_page(const SpkvView& v, int pair, int 
 
 __device__ __forceinline__ uint16_t* pool_page(const SpkvView& v, int page) {
     return v.pool + (size_t)page * (size_t)spkv_page_elems(v.D);
-}
-
-// One wave copies row `sk` of page `sp` to row `dk` of page `dp` (both in page layout).
-template <int D>
-__device__ __forceinline__ void copy_row_paged(const uint16_t* sp, int sk, uint16_t* dp, int dk,
-                                               int lane) {
-#pragma unroll
-    for (int d = lane; d < D; d += 64) dp[spkv_v_off(D, dk, d)] = sp[spkv_v_off(D, sk, d)];
-    if (lane < D / 8)
-        *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk, lane * 8)) =
-            *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, lane * 8));
-}
-
-// One wave copies a dense (row-major) K row and V row into row `dk` of page `dp`.
-template <int D>
-__device__ __forceinline__ void copy_row_dense(const uint16_t* krow, const uint16_t* vrow,
-                                               uint16_t* dp, int dk, int lane) {
-#pragma unroll
-    for (int d = lane; d < D; d += 64) dp[spkv_v_off(D, dk, d)] = vrow[d];
-    if (lane < D / 8)
-        *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk, lane * 8)) =
-            *reinterpret_cast<const uint4*>(krow + lane * 8);
 }
 
 // ------------------------------------------------------------------------ zero fill
@@ -110,21 +90,15 @@ hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_
 // long-term pages, allocating a page with one atomic when a page boundary is crossed) if
 // its stored logit passes the gate, else drop it.  One workgroup of D threads per
 // (sequence, KV head); thread d moves V element d, threads < D/8 move one 16-byte K chunk.
+// Body shared by spkv_append_step (workgroup of D threads) and spkv_combine_append
+// (256 threads, the first D of them move data).  `row` indexes the new token in k/vv/f;
+// T and L are the pair's counters as read by every thread before any of them is updated.
 template <int D>
-__global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t* __restrict__ k,
-                                                      const uint16_t* __restrict__ vv,
-                                                      const float* __restrict__ f, SpkvCu cu) {
-    const int pair = blockIdx.x;
-    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
-    const int row = cu.v[b];
-    if (cu.v[b + 1] - row == 0) return;
-    const int tid = threadIdx.x;
-    __shared__ int s_page;
-
-    // Round 1: the two counters.  Round 2: everything they address, issued together (the
-    // outgoing row is read before it is known whether it is kept: 2 + 16 bytes per thread).
-    const int T = v.t_pair[pair];
-    const int L = v.kept_len[pair];
+__device__ __forceinline__ void append_one(const SpkvView& v, int pair, int h, int row, int T, int L,
+                                           const uint16_t* __restrict__ k,
+                                           const uint16_t* __restrict__ vv,
+                                           const float* __restrict__ f, int tid, int* s_page) {
+    const bool mover = tid < D, kmover = tid < D / 8;
     const int slot = T % v.w;
     uint16_t* rp = ring_page(v, pair, slot >> 6);
     const int rk = slot & 63;
@@ -133,16 +107,18 @@ __global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t
     const bool have_page = gk != 0 && lp < v.pt_cap;
     const size_t src = ((size_t)row * v.Hkv + h) * D;
 
+    // Everything the counters address, issued together (the outgoing row is read before it
+    // is known whether it is kept: 2 + 16 bytes per thread).
     const float f_old = full ? v.ring_logit[(size_t)pair * v.w + slot] : 0.f;
     const int page_entry = have_page ? v.page_table[(size_t)pair * v.pt_cap + lp] : -1;
     const float f_new = f[(size_t)row * v.Hkv + h];
-    const uint16_t v_new = vv[src + tid];
+    uint16_t v_new = 0, v_old = 0;
     uint4 k_new = {0u, 0u, 0u, 0u}, k_old = {0u, 0u, 0u, 0u};
-    if (tid < D / 8) k_new = *reinterpret_cast<const uint4*>(k + src + tid * 8);
-    uint16_t v_old = 0;
+    if (mover) v_new = vv[src + tid];
+    if (kmover) k_new = *reinterpret_cast<const uint4*>(k + src + tid * 8);
     if (full) {
-        v_old = rp[spkv_v_off(D, rk, tid)];
-        if (tid < D / 8) k_old = *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
+        if (mover) v_old = rp[spkv_v_off(D, rk, tid)];
+        if (kmover) k_old = *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
     }
 
     if (full && f_old >= v.theta) {                               // Eq. 2 on the logit
@@ -156,28 +132,42 @@ __global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t
                 }
                 if (np >= 0) v.page_table[(size_t)pair * v.pt_cap + lp] = np;
                 else *v.err_flag = 1;
-                s_page = np;
+                *s_page = np;
             }
             __syncthreads();
-            page = s_page;
+            page = *s_page;
         }
         if (page >= 0) {
             uint16_t* gp = pool_page(v, page);
-            gp[spkv_v_off(D, gk, tid)] = v_old;
-            if (tid < D / 8) *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) = k_old;
+            if (mover) gp[spkv_v_off(D, gk, tid)] = v_old;
+            if (kmover) *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) = k_old;
             if (tid == 0) {
                 v.pos_pool[(size_t)page * kPageTokens + gk] = T - v.w;
                 v.kept_len[pair] = L + 1;
             }
         }
     }
-    rp[spkv_v_off(D, rk, tid)] = v_new;
-    if (tid < D / 8) *reinterpret_cast<uint4*>(rp + spkv_k_off(D, rk, tid * 8)) = k_new;
+    if (mover) rp[spkv_v_off(D, rk, tid)] = v_new;
+    if (kmover) *reinterpret_cast<uint4*>(rp + spkv_k_off(D, rk, tid * 8)) = k_new;
     if (tid == 0) {
         v.ring_logit[(size_t)pair * v.w + slot] = f_new;
         v.t_pair[pair] = T + 1;
         if (f_new >= v.theta) v.gate_on[pair] += 1;
     }
+}
+
+template <int D>
+__global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t* __restrict__ k,
+                                                      const uint16_t* __restrict__ vv,
+                                                      const float* __restrict__ f, SpkvCu cu) {
+    const int pair = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row = cu.v[b];
+    if (cu.v[b + 1] - row == 0) return;
+    __shared__ int s_page;
+    const int T = v.t_pair[pair];
+    const int L = v.kept_len[pair];
+    append_one<D>(v, pair, h, row, T, L, k, vv, f, threadIdx.x, &s_page);
 }
 
 hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
@@ -476,13 +466,14 @@ struct PairSplit {
     int nhp;    // half-pages of the pair
     int ghp;    // of which long-term
     int items;  // work items the pair is cut into
-    int L, Tw;
+    int L, T, Tw;
 };
 
 __device__ __forceinline__ PairSplit pair_split(const SpkvView& v, int pair, SpkvSplit sp) {
     PairSplit r;
     r.L = v.kept_len[pair];
-    r.Tw = min(v.t_pair[pair], v.w);
+    r.T = v.t_pair[pair];
+    r.Tw = min(r.T, v.w);
     r.ghp = (r.L + kHalfTokens - 1) >> 5;
     r.nhp = r.ghp + ((r.Tw + kHalfTokens - 1) >> 5);
     r.items = min((r.nhp + sp.hp_per_item - 1) / sp.hp_per_item, sp.slots);
@@ -490,18 +481,82 @@ __device__ __forceinline__ PairSplit pair_split(const SpkvView& v, int pair, Spk
 }
 
 // ------------------------------------------------------------------- split-K decode
-// One wavefront per work item.  For each half-page (32 keys) of the item:
+// One half-page (32 keys) of flash decoding on the MFMA operands already in registers:
 //   S[key][head]   = K[key][:] . Q[head][:]          2 x D/32 MFMA 16x16x32 (bf16 -> fp32)
 //   online softmax in the log2 domain (running max m, sum l), weights rounded to bf16
 //   O[d][head]    += V[key][d] * P[key][head]        D/16 MFMA 16x16x32
-// The G <= 16 query heads of the GQA group are the N = 16 columns of every MFMA, so each
-// K/V tile is read exactly once per group.  Every wave-wide load is 1 KB contiguous.
+// Keys r >= nvalid and the key r == masked_r (if >= 0) are excluded.
+template <int D>
+__device__ __forceinline__ void attend_half_page(const bf16x8 (&ka)[2][D / 32],
+                                                 const bf16x8 (&va)[D / 16],
+                                                 const bf16x8 (&qb)[D / 32], int nvalid,
+                                                 int masked_r, int kc, float scale_log2e,
+                                                 f32x4 (&acc)[D / 16], float& m, float& l) {
+    constexpr int NS = D / 32, NB = D / 16;
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int sl = 0; sl < NS; ++sl) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][sl], qb[sl], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][sl], qb[sl], s1, 0, 0, 0);
+    }
+    // Lane (kc, n) now holds, for head n, the keys r = 16 t + 4 kc + i of the half-page.
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[i] = s0[i] * scale_log2e;
+        x[4 + i] = s1[i] * scale_log2e;
+    }
+    if (nvalid < kHalfTokens || masked_r >= 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int r = (e >> 2) * 16 + kc * 4 + (e & 3);
+            if (r >= nvalid || r == masked_r) x[e] = SPKV_NEG_INF;
+        }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);
+    // m_new is -inf only while every key seen so far was excluded; a finite reference then
+    // keeps exp2(-inf - ref) = 0 instead of exp2(-inf + inf) = NaN.
+    const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
+    f32x8 p;
+    float psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(x[e] - m_ref);
+        psum += p[e];
+    }
+    l = l * alpha + psum;
+    if (__ballot(m_new != m) != 0ull) {
+#pragma unroll
+        for (int db = 0; db < NB; ++db) acc[db] *= alpha;
+    }
+    m = m_new;
+    const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[db], pb, acc[db], 0, 0, 0);
+}
+
+// One wavefront per work item.  The G <= 16 query heads of the GQA group are the N = 16
+// columns of every MFMA, so each K/V tile is read exactly once per group.  Every wave-wide
+// load is 1 KB contiguous.
 // Block id = pair * slots + j with an odd slot count: workgroups go round-robin to the 8
 // XCDs, so the items of every pair -- long or short -- spread evenly over all of them
 // (heads differ in kept length by several times; pinning a head to one XCD would leave
 // the others idle), and the odd stride keeps the per-pair remainders from piling up on
 // the low XCDs.
-template <int D>
+//
+// FUSED = false: the cache already holds the newest token (spkv_append ran before).
+// FUSED = true (spkv_decode_step): the cache is in the state before the append of the
+// newest token.  The kernel then excludes the ring slot that token will overwrite unless
+// the pair in it passes the gate (it is the pair leaving the window: kept -> it stays
+// attended, as the next long-term entry; dropped -> it is gone), and publishes every
+// pair's item count for spkv_combine_append, which adds the new token's own term.
+template <int D, bool FUSED>
 __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
                                                         float scale_log2e, SpkvSplit sp) {
     constexpr int NS = D / 32;   // head-dim slabs of one K tile
@@ -509,6 +564,7 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
     const int pair = blockIdx.x / sp.slots;
     const int j = blockIdx.x - pair * sp.slots;
     const PairSplit ps = pair_split(v, pair, sp);
+    if (FUSED && j == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.items;
     if (j >= ps.items) return;
     const int hbase = ps.nhp / ps.items, hrem = ps.nhp - hbase * ps.items;
     const int hp0 = j * hbase + min(j, hrem);
@@ -531,6 +587,17 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
     for (int i = 0; i < NB; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float m = SPKV_NEG_INF, l = 0.f;
     const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+
+    // Fused step: which ring key (if any) must be left out.  Only items that reach into
+    // the ring look (most do not), and only after their query loads are under way.
+    int drop_hp = -1, drop_r = -1;
+    if (FUSED && hp1 > ps.ghp && ps.T >= v.w) {
+        const int slot = ps.T % v.w;
+        if (!(v.ring_logit[(size_t)pair * v.w + slot] >= v.theta)) {
+            drop_hp = ps.ghp + (slot >> 5);
+            drop_r = slot & 31;
+        }
+    }
 
     int hp = hp0;
     while (hp < hp1) {
@@ -560,52 +627,9 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
                 for (int sl = 0; sl < NS; ++sl)
                     ka[t][sl] = load_stream_b128(kp + (t * (D / 8) + sl * 4) * 128);
 #pragma unroll
-            for (int db = 0; db < NB; ++db)
-                va[db] = load_stream_b128(vp + db * 512);
-
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int sl = 0; sl < NS; ++sl) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][sl], qb[sl], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][sl], qb[sl], s1, 0, 0, 0);
-            }
-            // Lane (kc, n) now holds, for head n, the keys r = 16 t + 4 kc + i of the half-page.
-            float x[8];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                x[i] = s0[i] * scale_log2e;
-                x[4 + i] = s1[i] * scale_log2e;
-            }
-            if (nvalid < kHalfTokens) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int r = (e >> 2) * 16 + kc * 4 + (e & 3);
-                    if (r >= nvalid) x[e] = SPKV_NEG_INF;
-                }
-            }
-            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                             fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-            f32x8 p;
-            float psum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
-                psum += p[e];
-            }
-            l = l * alpha + psum;
-            if (__ballot(m_new != m) != 0ull) {
-#pragma unroll
-                for (int db = 0; db < NB; ++db) acc[db] *= alpha;
-            }
-            m = m_new;
-            const bf16x8 pb = __builtin_convertvector(p, bf16x8);
-#pragma unroll
-            for (int db = 0; db < NB; ++db)
-                acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[db], pb, acc[db], 0, 0, 0);
+            for (int db = 0; db < NB; ++db) va[db] = load_stream_b128(vp + db * 512);
+            attend_half_page<D>(ka, va, qb, nvalid, (FUSED && hp == drop_hp) ? drop_r : -1, kc,
+                                scale_log2e, acc, m, l);
         }
     }
 
@@ -624,7 +648,38 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
     }
 }
 
-// Merge the partials of one (sequence, query head): with M = max_i m_i,
+// One wave folds the partials of one (pair, head) into a running (max, sum, acc) triple:
+// with M the running max,  acc = sum_i 2^(m_i - M) acc_i,  den = sum_i 2^(m_i - M) l_i.
+// The loads of successive items are independent; only the cheap rescaling is chained.
+// Lane owns E = D / 64 output elements.
+template <int D>
+__device__ __forceinline__ void fold_items(const SpkvView& v, size_t slot0, int g, int first,
+                                           int stride, int items, int lane, float& mw, float& den,
+                                           float (&num)[D / 64]) {
+    constexpr int E = D / 64;
+    mw = SPKV_NEG_INF;
+    den = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) num[e] = 0.f;
+#pragma unroll 8
+    for (int i = first; i < items; i += stride) {
+        const float* pm = v.part_ml + ((slot0 + i) * v.G + g) * 2;
+        const float* pa = v.part_acc + ((slot0 + i) * v.G + g) * D + lane * E;
+        const float mi = pm[0], li = pm[1];
+        float a[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) a[e] = pa[e];
+        const float m_new = fmaxf(mw, mi);
+        const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;   // items with no key: weight 0
+        const float so = __builtin_amdgcn_exp2f(mw - m_ref), si = __builtin_amdgcn_exp2f(mi - m_ref);
+        den = den * so + li * si;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] = num[e] * so + a[e] * si;
+        mw = m_new;
+    }
+}
+
+// Merge the partials of one (sequence, query head):
 //   out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i,  lse = (M + log2(sum)) ln 2.
 // One workgroup of 4 waves per (pair, head): the waves take the items round-robin, each
 // lane owns D/64 output elements, and the four wave results meet in LDS.
@@ -641,27 +696,8 @@ __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t*
     __shared__ float s_den[4];
     __shared__ float s_acc[4][D];
 
-    // One pass: every wave folds its items into a running (max, sum, acc) triple; the
-    // loads of successive items do not depend on each other, only the cheap rescaling does.
-    float mw = SPKV_NEG_INF, den = 0.f;
-    float num[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) num[e] = 0.f;
-#pragma unroll 8
-    for (int i = wave; i < items; i += 4) {
-        const float* pm = v.part_ml + ((slot0 + i) * v.G + g) * 2;
-        const float* pa = v.part_acc + ((slot0 + i) * v.G + g) * D + lane * E;
-        const float mi = pm[0], li = pm[1];
-        float a[E];
-#pragma unroll
-        for (int e = 0; e < E; ++e) a[e] = pa[e];
-        const float m_new = fmaxf(mw, mi);
-        const float so = __builtin_amdgcn_exp2f(mw - m_new), si = __builtin_amdgcn_exp2f(mi - m_new);
-        den = den * so + li * si;
-#pragma unroll
-        for (int e = 0; e < E; ++e) num[e] = num[e] * so + a[e] * si;
-        mw = m_new;
-    }
+    float mw, den, num[E];
+    fold_items<D>(v, slot0, g, wave, 4, items, lane, mw, den, num);
 #pragma unroll
     for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
     if (lane == 0) {
@@ -685,6 +721,77 @@ __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t*
     }
 }
 
+// Second launch of the fused step: one workgroup per (sequence, query head) merges the
+// partials as spkv_decode_combine does, plus one more term for the new token itself, taken
+// straight from the caller's k_new / v_new (score q . k_new in fp32, weight sum 1, value
+// v_new); the workgroup of the group's first head then performs the append of the new
+// token exactly as spkv_append_step does.  The item
+// count of the pair comes from pair_items (written by the split kernel), not from the
+// counters, so the other heads' workgroups never read what the append is changing.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t* __restrict__ out,
+                                                           float* __restrict__ lse, SpkvSplit sp,
+                                                           const uint16_t* __restrict__ k_new,
+                                                           const uint16_t* __restrict__ v_new,
+                                                           const float* __restrict__ f_new,
+                                                           const uint16_t* __restrict__ q,
+                                                           float scale_log2e) {
+    constexpr int E = D / 64;
+    const int pair = blockIdx.x / v.G, g = blockIdx.x - pair * v.G;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int items = v.pair_items[pair];
+    const size_t kv_row = ((size_t)b * v.Hkv + h) * D;
+    const size_t q_row = ((size_t)b * v.Hq + (size_t)h * v.G + g) * D;
+    // score of the new token for this head (every wave computes it; 6 shuffles)
+    float dot = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const unsigned qe = q[q_row + lane * E + e], ke = k_new[kv_row + lane * E + e];
+        dot += __builtin_bit_cast(float, qe << 16) * __builtin_bit_cast(float, ke << 16);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+    const float m_tok = dot * scale_log2e;
+    const size_t slot0 = (size_t)pair * sp.slots;
+    __shared__ float s_m[4];
+    __shared__ float s_den[4];
+    __shared__ float s_acc[4][D];
+    __shared__ int s_page;
+    int T = 0, L = 0;
+    if (g == 0) {
+        T = v.t_pair[pair];
+        L = v.kept_len[pair];
+    }
+
+    float mw, den, num[E];
+    fold_items<D>(v, slot0, g, wave, 4, items, lane, mw, den, num);
+#pragma unroll
+    for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
+    if (lane == 0) {
+        s_m[wave] = mw;
+        s_den[wave] = den;
+    }
+    __syncthreads();
+    if (tid < D) {
+        const float M = fmaxf(fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3])), m_tok);
+        const float w_tok = __builtin_amdgcn_exp2f(m_tok - M);
+        const unsigned ve = v_new[kv_row + tid];
+        float nsum = __builtin_bit_cast(float, ve << 16) * w_tok, dsum = w_tok;
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) {
+            const float sc = __builtin_amdgcn_exp2f(s_m[wv] - M);
+            nsum += s_acc[wv][tid] * sc;
+            dsum += s_den[wv] * sc;
+        }
+        const size_t o = ((size_t)b * v.Hq + (size_t)h * v.G + g);
+        const __bf16 r = (__bf16)(nsum / dsum);
+        out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
+        if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
+    }
+    if (g == 0) append_one<D>(v, pair, h, b, T, L, k_new, v_new, f_new, tid, &s_page);
+}
+
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
                               float sm_scale, SpkvSplit sp, bool split_only, hipEvent_t ev0,
                               hipEvent_t ev1, hipStream_t s) {
@@ -693,9 +800,9 @@ hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* ou
     hipError_t e;
     if (ev0 != nullptr && (e = hipEventRecord(ev0, s)) != hipSuccess) return e;
     if (v.D == 128)
-        spkv_decode_split<128><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+        spkv_decode_split<128, false><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
     else
-        spkv_decode_split<64><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+        spkv_decode_split<64, false><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
     if (split_only) return hipSuccess;
@@ -703,6 +810,21 @@ hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* ou
         spkv_decode_combine<128><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
     else
         spkv_decode_combine<64><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
+    return hipGetLastError();
+}
+
+hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                                   float sm_scale, SpkvSplit sp, hipStream_t s) {
+    const float scale_log2e = sm_scale * 1.4426950408889634f;
+    const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
+    if (v.D == 128) {
+        spkv_decode_split<128, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+        spkv_combine_append<128><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
+    } else {
+        spkv_decode_split<64, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+        spkv_combine_append<64><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
+    }
     return hipGetLastError();
 }
 

@@ -83,8 +83,9 @@ def prefill(cache, oracle, stream, wl, chunk):
 
 
 def run_workload(wl, chunk=4096, q_gain=1.0, check_every=1, pool_tokens=None, item_target=None,
-                 state_pairs=None):
-    """Prefill, then wl.decode_steps steps of append + decode, checking against the oracle."""
+                 state_pairs=None, fused=False):
+    """Prefill, then wl.decode_steps steps of append + decode, checking against the oracle.
+    fused: use the two-launch spkv_decode_step instead of spkv_append + spkv_decode_attention."""
     stream = TokenStream(wl, device="cuda", q_gain=q_gain)
     cache = make_cache(wl, pool_tokens)
     if item_target is not None:
@@ -95,9 +96,13 @@ def run_workload(wl, chunk=4096, q_gain=1.0, check_every=1, pool_tokens=None, it
     metrics = []
     for step in range(wl.decode_steps):
         k, v, f, cu = stream.next_tokens([1] * wl.batch)
-        feed(cache, oracle, k, v, f, cu)
         q = stream.next_query()
-        out, lse = cache.decode_attention(q, want_lse=True)
+        if fused:
+            out, lse = cache.decode_step(k, v, f, q, want_lse=True)
+            oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        else:
+            feed(cache, oracle, k, v, f, cu)
+            out, lse = cache.decode_attention(q, want_lse=True)
         if step % check_every == 0 or step == wl.decode_steps - 1:
             ref_out, ref_lse = oracle.decode(to_numpy_f32(q))
             metrics.append(check_output(out, ref_out, f"step {step}"))

@@ -267,3 +267,74 @@ def test_random_shapes_and_ragged_appends(trial):
             H.check_output(out, ref_out, f"trial {trial} call {call}")
             H.check_lse(lse, ref_lse, f"trial {trial} call {call}")
     cache.close()
+
+
+# ------------------------------------------------------------ fused step (two launches)
+def test_fused_step_cfg1_every_step():
+    m = H.run_workload(workload("cfg1"), chunk=512, fused=True)
+    assert len(m) == 64
+
+
+@pytest.mark.parametrize("ctx,w", [(0, 128), (0, 1), (0, 3), (1, 128), (127, 128), (128, 128),
+                                   (129, 128), (31, 32), (64, 33), (300, 1), (300, 2), (700, 100),
+                                   (1000, 512)])
+def test_fused_step_window_edges(ctx, w):
+    """From an empty cache, across the window filling up, and with tiny windows where the
+    pair leaving the window is the only ring key."""
+    wl = small_workload("fedge", 2, 8, 2, 64, [ctx, ctx // 2], [[0.5, 0.2]], window=w,
+                        decode_steps=max(6, 2 * w + 3 if w < 40 else 6), seed=ctx * 1000 + w + 7)
+    H.run_workload(wl, chunk=4096, fused=True)
+
+
+@pytest.mark.parametrize("D,Hq,Hkv", [(64, 2, 2), (128, 32, 8), (128, 16, 1), (64, 24, 3)])
+def test_fused_step_head_shapes(D, Hq, Hkv):
+    wl = small_workload("fheads", 3, Hq, Hkv, D, [900, 130, 417], 0.3, decode_steps=4,
+                        seed=D + Hq + Hkv + 1)
+    H.run_workload(wl, chunk=512, fused=True)
+
+
+def test_fused_and_two_call_steps_build_the_same_cache():
+    """Alternating the fused entry point with append + decode_attention leaves the same
+    kept positions, lengths and statistics as the two-call path alone."""
+    wl = small_workload("fmix", 2, 8, 2, 128, [200, 90], 0.5, window=64, seed=12)
+    stream = TokenStream(wl, device="cuda")
+    a, bcache = H.make_cache(wl, extra_context=300), H.make_cache(wl, extra_context=300)
+    oracle = H.make_oracle(wl)
+    k, v, f, cu = stream.next_tokens(wl.ctx_lens)
+    a.append(k, v, f, cu)
+    bcache.append(k, v, f, cu)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    for step in range(200):
+        k, v, f, cu = stream.next_tokens([1, 1])
+        q = stream.next_query()
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        a.append(k, v, f, cu)
+        out_a = a.decode_attention(q)
+        if step % 3 == 0:
+            bcache.append(k, v, f, cu)
+            out_b = bcache.decode_attention(q)
+        else:
+            out_b = bcache.decode_step(k, v, f, q)
+        assert (out_a.float() - out_b.float()).abs().max().item() <= 2e-2
+        if step % 25 == 0 or step == 199:
+            H.check_state(a, oracle, wl, label=f"two-call step {step}")
+            H.check_state(bcache, oracle, wl, label=f"mixed step {step}")
+            H.check_output(out_b, oracle.decode(to_numpy_f32(q))[0], f"mixed step {step}")
+    a.close()
+    bcache.close()
+
+
+def test_fused_step_capacity_error_leaves_state():
+    cache = spkv.SPKVCache(1, 2, 1, 64, max_context=20, max_total_kept_tokens=64, window=4, tau=0.0)
+    wl = small_workload("fcap", 1, 2, 1, 64, [0], 1.0, window=4, seed=2)
+    stream = TokenStream(wl, device="cuda")
+    for _ in range(20):
+        k, v, f, _ = stream.next_tokens([1])
+        cache.decode_step(k, v, f, stream.next_query())
+    k, v, f, _ = stream.next_tokens([1])
+    with pytest.raises(spkv.SPKVError) as e:
+        cache.decode_step(k, v, f, stream.next_query())
+    assert e.value.code == -3
+    st = cache.stats()
+    assert st.total_tokens == 20 and st.kept_tokens == 16
+    cache.close()
