@@ -14,7 +14,9 @@
 namespace {
 
 constexpr size_t kAlign = 256;
-constexpr int kMinItems = 3072;        // 12 one-wave workgroups per CU on 256 CUs
+constexpr int kMinItems = 2944;        // 11.5 one-wave workgroups per CU on 256 CUs: the split-K
+                                       // kernel fits 12 per CU (3 per SIMD); measured: up to 2875
+                                       // items run in one round, 3045 and more fall into a second
 constexpr int kMaxAutoItems = 8192;
 constexpr int kAutoItemHalfPages = 16; // above kMinItems items, aim at 16 half-pages (256 KB) each
 constexpr int kMaxTimedLaunches = 8192;
@@ -141,23 +143,31 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // longest pair.  The kernels apply it to the exact device-side lengths, which never
 // exceed the bound, so every pair fits its slots.
 SpkvSplit choose_split(const spkv_cache* c) {
+    const int n_pairs = c->carve.n_pairs, Hkv = c->cfg.n_kv_heads;
+    std::vector<int64_t> hp(n_pairs);
     int64_t sum_hp = 0, max_hp = 1;
-    const int Hkv = c->cfg.n_kv_heads;
-    for (int p = 0; p < c->carve.n_pairs; ++p) {
+    for (int p = 0; p < n_pairs; ++p) {
         const int Tw = std::min(c->T[p / Hkv], c->cfg.window);
-        const int64_t hp =
-            (c->L_ub[p] + kHalfTokens - 1) / kHalfTokens + (Tw + kHalfTokens - 1) / kHalfTokens;
-        sum_hp += hp;
-        max_hp = std::max(max_hp, hp);
+        hp[p] = (c->L_ub[p] + kHalfTokens - 1) / kHalfTokens + (Tw + kHalfTokens - 1) / kHalfTokens;
+        sum_hp += hp[p];
+        max_hp = std::max(max_hp, hp[p]);
     }
-    // Item count: the caller's target, else enough one-wave items to fill the chip once
+    // Item count: the caller's target, else just under one resident wave per slot
     // (kMinItems) and, for large caches, more of them (about 256 KB each) so that the tail
     // of the launch stays short when the pairs differ widely in length.
     int64_t target = c->item_target;
     if (target <= 0)
         target = std::min<int64_t>(kMaxAutoItems, std::max<int64_t>(kMinItems, sum_hp / kAutoItemHalfPages));
     int64_t per = std::max<int64_t>(1, (sum_hp + target - 1) / target);
-    const int64_t slots_cap = c->carve.max_items / c->carve.n_pairs - 1;
+    // Every pair rounds its item count up; keep the total within the target, because one
+    // item more than the chip holds at once costs a whole second round of the longest items.
+    for (int guard = 0; guard < 64; ++guard) {
+        int64_t items = 0;
+        for (int p = 0; p < n_pairs; ++p) items += (hp[p] + per - 1) / per;
+        if (items <= target || items <= n_pairs) break;
+        per += std::max<int64_t>(1, per / 16);
+    }
+    const int64_t slots_cap = c->carve.max_items / n_pairs - 1;
     if ((max_hp + per - 1) / per > slots_cap) per = (max_hp + slots_cap - 1) / slots_cap;
     SpkvSplit sp;
     sp.hp_per_item = (int32_t)per;
