@@ -90,14 +90,53 @@ hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_
 // long-term pages, allocating a page with one atomic when a page boundary is crossed) if
 // its stored logit passes the gate, else drop it.  One workgroup of D threads per
 // (sequence, KV head); thread d moves V element d, threads < D/8 move one 16-byte K chunk.
-// Body shared by spkv_append_step (workgroup of D threads) and spkv_combine_append
-// (256 threads, the first D of them move data).  `row` indexes the new token in k/vv/f;
-// T and L are the pair's counters as read by every thread before any of them is updated.
+// Append of one token to one (sequence, head), shared by spkv_append_step (workgroup of D
+// threads) and spkv_combine_append (256 threads, the first D of them move data), in two
+// halves so that a caller can put other work between the loads and the stores.
+// `row` indexes the new token in k/vv/f; T and L are the pair's counters as read by every
+// thread before any of them is updated.
 template <int D>
-__device__ __forceinline__ void append_one(const SpkvView& v, int pair, int h, int row, int T, int L,
-                                           const uint16_t* __restrict__ k,
-                                           const uint16_t* __restrict__ vv,
-                                           const float* __restrict__ f, int tid, int* s_page) {
+struct AppendRegs {
+    float f_old, f_new;
+    int page_entry;
+    uint16_t v_new, v_old;
+    uint4 k_new, k_old;
+};
+
+// Everything the counters address, issued together (the outgoing row is read before it is
+// known whether it is kept: 2 + 16 bytes per thread).
+template <int D>
+__device__ __forceinline__ AppendRegs<D> append_load(const SpkvView& v, int pair, int h, int row,
+                                                     int T, int L, const uint16_t* __restrict__ k,
+                                                     const uint16_t* __restrict__ vv,
+                                                     const float* __restrict__ f, int tid) {
+    AppendRegs<D> r;
+    const bool mover = tid < D, kmover = tid < D / 8;
+    const int slot = T % v.w;
+    const uint16_t* rp = ring_page(v, pair, slot >> 6);
+    const int rk = slot & 63;
+    const bool full = T >= v.w;
+    const int lp = L >> 6, gk = L & 63;
+    const size_t src = ((size_t)row * v.Hkv + h) * D;
+    r.f_old = full ? v.ring_logit[(size_t)pair * v.w + slot] : 0.f;
+    r.page_entry = (gk != 0 && lp < v.pt_cap) ? v.page_table[(size_t)pair * v.pt_cap + lp] : -1;
+    r.f_new = f[(size_t)row * v.Hkv + h];
+    r.v_new = 0;
+    r.v_old = 0;
+    r.k_new = make_uint4(0u, 0u, 0u, 0u);
+    r.k_old = make_uint4(0u, 0u, 0u, 0u);
+    if (mover) r.v_new = vv[src + tid];
+    if (kmover) r.k_new = *reinterpret_cast<const uint4*>(k + src + tid * 8);
+    if (full) {
+        if (mover) r.v_old = rp[spkv_v_off(D, rk, tid)];
+        if (kmover) r.k_old = *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
+    }
+    return r;
+}
+
+template <int D>
+__device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T, int L,
+                                             const AppendRegs<D>& r, int tid, int* s_page) {
     const bool mover = tid < D, kmover = tid < D / 8;
     const int slot = T % v.w;
     uint16_t* rp = ring_page(v, pair, slot >> 6);
@@ -105,24 +144,8 @@ __device__ __forceinline__ void append_one(const SpkvView& v, int pair, int h, i
     const bool full = T >= v.w;
     const int lp = L >> 6, gk = L & 63;
     const bool have_page = gk != 0 && lp < v.pt_cap;
-    const size_t src = ((size_t)row * v.Hkv + h) * D;
-
-    // Everything the counters address, issued together (the outgoing row is read before it
-    // is known whether it is kept: 2 + 16 bytes per thread).
-    const float f_old = full ? v.ring_logit[(size_t)pair * v.w + slot] : 0.f;
-    const int page_entry = have_page ? v.page_table[(size_t)pair * v.pt_cap + lp] : -1;
-    const float f_new = f[(size_t)row * v.Hkv + h];
-    uint16_t v_new = 0, v_old = 0;
-    uint4 k_new = {0u, 0u, 0u, 0u}, k_old = {0u, 0u, 0u, 0u};
-    if (mover) v_new = vv[src + tid];
-    if (kmover) k_new = *reinterpret_cast<const uint4*>(k + src + tid * 8);
-    if (full) {
-        if (mover) v_old = rp[spkv_v_off(D, rk, tid)];
-        if (kmover) k_old = *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
-    }
-
-    if (full && f_old >= v.theta) {                               // Eq. 2 on the logit
-        int page = page_entry;
+    if (full && r.f_old >= v.theta) {                             // Eq. 2 on the logit
+        int page = r.page_entry;
         if (!have_page) {                                         // first pair of a new page
             if (tid == 0) {
                 int np = -1;
@@ -139,20 +162,20 @@ __device__ __forceinline__ void append_one(const SpkvView& v, int pair, int h, i
         }
         if (page >= 0) {
             uint16_t* gp = pool_page(v, page);
-            if (mover) gp[spkv_v_off(D, gk, tid)] = v_old;
-            if (kmover) *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) = k_old;
+            if (mover) gp[spkv_v_off(D, gk, tid)] = r.v_old;
+            if (kmover) *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) = r.k_old;
             if (tid == 0) {
                 v.pos_pool[(size_t)page * kPageTokens + gk] = T - v.w;
                 v.kept_len[pair] = L + 1;
             }
         }
     }
-    if (mover) rp[spkv_v_off(D, rk, tid)] = v_new;
-    if (kmover) *reinterpret_cast<uint4*>(rp + spkv_k_off(D, rk, tid * 8)) = k_new;
+    if (mover) rp[spkv_v_off(D, rk, tid)] = r.v_new;
+    if (kmover) *reinterpret_cast<uint4*>(rp + spkv_k_off(D, rk, tid * 8)) = r.k_new;
     if (tid == 0) {
-        v.ring_logit[(size_t)pair * v.w + slot] = f_new;
+        v.ring_logit[(size_t)pair * v.w + slot] = r.f_new;
         v.t_pair[pair] = T + 1;
-        if (f_new >= v.theta) v.gate_on[pair] += 1;
+        if (r.f_new >= v.theta) v.gate_on[pair] += 1;
     }
 }
 
@@ -167,7 +190,8 @@ __global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t
     __shared__ int s_page;
     const int T = v.t_pair[pair];
     const int L = v.kept_len[pair];
-    append_one<D>(v, pair, h, row, T, L, k, vv, f, threadIdx.x, &s_page);
+    const AppendRegs<D> r = append_load<D>(v, pair, h, row, T, L, k, vv, f, threadIdx.x);
+    append_store<D>(v, pair, T, L, r, threadIdx.x, &s_page);
 }
 
 hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
@@ -758,10 +782,13 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
     __shared__ float s_den[4];
     __shared__ float s_acc[4][D];
     __shared__ int s_page;
+    // The append's loads are issued before the merge and consumed after it.
     int T = 0, L = 0;
+    AppendRegs<D> ar;
     if (g == 0) {
         T = v.t_pair[pair];
         L = v.kept_len[pair];
+        ar = append_load<D>(v, pair, h, b, T, L, k_new, v_new, f_new, tid);
     }
 
     float mw, den, num[E];
@@ -789,7 +816,7 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
         out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
         if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
     }
-    if (g == 0) append_one<D>(v, pair, h, b, T, L, k_new, v_new, f_new, tid, &s_page);
+    if (g == 0) append_store<D>(v, pair, T, L, ar, tid, &s_page);
 }
 
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
