@@ -14,9 +14,7 @@
 namespace {
 
 constexpr size_t kAlign = 256;
-constexpr int kMinItems = 2944;        // 11.5 one-wave workgroups per CU on 256 CUs: the split-K
-                                       // kernel fits 12 per CU (3 per SIMD); measured: up to 2875
-                                       // items run in one round, 3045 and more fall into a second
+constexpr int kFallbackItems = 2944;   // 11.5 one-wave workgroups per CU on 256 CUs (MI355X, 12 fit)
 constexpr int kMaxAutoItems = 8192;
 constexpr int kAutoItemHalfPages = 16; // above kMinItems items, aim at 16 half-pages (256 KB) each
 constexpr int kMaxTimedLaunches = 8192;
@@ -110,6 +108,7 @@ struct spkv_cache {
     int64_t pages_ub;             // sum of pages_for(L_ub): upper bound of pool pages in use
     bool bound_is_loose;          // a bulk append grew L_ub by far more than the truth
     int item_target;
+    int one_round_items;          // items the chip runs in one resident round, with a margin
     SpkvSplit split;              // partition used by the last decode call
     bool timing;
     bool split_only;
@@ -157,7 +156,7 @@ SpkvSplit choose_split(const spkv_cache* c) {
     // of the launch stays short when the pairs differ widely in length.
     int64_t target = c->item_target;
     if (target <= 0)
-        target = std::min<int64_t>(kMaxAutoItems, std::max<int64_t>(kMinItems, sum_hp / kAutoItemHalfPages));
+        target = std::min<int64_t>(kMaxAutoItems, std::max<int64_t>(c->one_round_items, sum_hp / kAutoItemHalfPages));
     int64_t per = std::max<int64_t>(1, (sum_hp + target - 1) / target);
     // Every pair rounds its item count up; keep the total within the target, because one
     // item more than the chip holds at once costs a whole second round of the longest items.
@@ -251,6 +250,12 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->pages_ub = 0;
     c->bound_is_loose = false;
     c->item_target = 0;
+    {
+        // Measured on MI355X: up to 94 % of the resident slots run in one round; at 99 % some
+        // compute units already queue a second item and the launch takes 15-20 % longer.
+        const int resident = spkv_split_resident_items(cfg->head_dim);
+        c->one_round_items = resident > 0 ? resident - resident / 24 : kFallbackItems;
+    }
     c->split = SpkvSplit{1, 1};
     c->timing = false;
     c->split_only = false;
