@@ -338,3 +338,14 @@ def test_fused_step_capacity_error_leaves_state():
     st = cache.stats()
     assert st.total_tokens == 20 and st.kept_tokens == 16
     cache.close()
+
+
+def test_largest_batch():
+    """SPKV_MAX_BATCH sequences (cu_seqlens fills the kernel-argument block), 8 KV heads:
+    4096 (sequence, head) pairs, ragged lengths around the window."""
+    B = 512
+    rng = np.random.default_rng(99)
+    lens = rng.integers(1, 200, size=B).tolist()
+    wl = small_workload("bigbatch", B, 8, 8, 64, lens, 0.4, window=64, decode_steps=2, seed=17)
+    H.run_workload(wl, chunk=4096, state_pairs=[(0, 0), (511, 7), (255, 3)])
+    H.run_workload(wl, chunk=4096, state_pairs=[(1, 1), (510, 6)], fused=True)
