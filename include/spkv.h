@@ -158,6 +158,16 @@ int spkv_decode_attention(spkv_cache_t* cache, const void* q, void* out, float* 
 int spkv_decode_step(spkv_cache_t* cache, const void* k, const void* v, const float* util_logits,
                      const void* q, void* out, float* lse, float sm_scale, void* stream);
 
+/* Forget sequence b (for example when its request has finished): its window and long-term
+ * entries are dropped, its pages return to the pool for reuse by any sequence, and slot b
+ * holds an empty sequence that can be appended to again.  (The paper's cache manager grows
+ * and shares one page pool across requests, appendix "Inference Kernels"; giving pages
+ * back is the counterpart a serving loop needs.)  Synchronises `stream` once to read the
+ * exact lengths, then enqueues the release.  A recycled page keeps its old bytes beyond the
+ * new owner's length; they are masked in attention, which is exact as long as the old
+ * values were finite. */
+int spkv_cache_release_sequence(spkv_cache_t* cache, int32_t b, void* stream);
+
 /* Gate density and sizes (Eq. 8).  Synchronises `stream`.  kept_len (host int32
  * [batch * n_kv_heads], or NULL) receives the long-term length of every (seq, head). */
 int spkv_cache_stats(spkv_cache_t* cache, spkv_stats_t* stats, int32_t* kept_len, void* stream);

@@ -131,6 +131,13 @@ class SPKVOracle:
             self._fbuf[b][old:new] = f[lo:hi]
             self._len[b] = new
 
+    def release_sequence(self, b):
+        """Forget sequence b: slot b holds an empty sequence again."""
+        self._kbuf[b] = np.zeros((0, self.Hkv, self.D), self.store_dtype)
+        self._vbuf[b] = np.zeros((0, self.Hkv, self.D), self.store_dtype)
+        self._fbuf[b] = np.zeros((0, self.Hkv), np.float32)
+        self._len[b] = 0
+
     # ------------------------------------------------------------- bookkeeping
     def seq_len(self, b):
         return self._len[b]

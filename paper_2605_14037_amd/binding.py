@@ -20,7 +20,7 @@ MAX_BATCH, PAGE_TOKENS = 512, 64
 
 EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_reset",
-    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_cache_stats", "spkv_cache_kept_positions",
+    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_cache_release_sequence", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
     "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
@@ -82,6 +82,8 @@ def load_library():
     lib.spkv_decode_attention.argtypes = [vp, vp, vp, vp, f32, vp]
     lib.spkv_decode_step.restype = C.c_int
     lib.spkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, vp]
+    lib.spkv_cache_release_sequence.restype = C.c_int
+    lib.spkv_cache_release_sequence.argtypes = [vp, i32, vp]
     lib.spkv_cache_stats.restype = C.c_int
     lib.spkv_cache_stats.argtypes = [vp, P(SPKVStats), P(i32), vp]
     lib.spkv_cache_kept_positions.restype = C.c_int
@@ -225,6 +227,10 @@ class SPKVCache:
     # ---- bookkeeping
     def reset(self):
         _check(self.lib.spkv_cache_reset(self.handle, _stream()), "spkv_cache_reset")
+
+    def release_sequence(self, b):
+        _check(self.lib.spkv_cache_release_sequence(self.handle, int(b), _stream()),
+               "spkv_cache_release_sequence")
 
     def stats(self, with_kept_len=False):
         st = SPKVStats()

@@ -22,7 +22,8 @@ constexpr int kMaxTimedLaunches = 8192;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Carve {
-    size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, err_flag, page_table, pool,
+    size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, free_top, free_pages, err_flag,
+        page_table, pool,
         pos_pool, seg_count, bulk_info, part_acc, part_ml, pair_items,
         pos_scratch, total;
     int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items;
@@ -71,6 +72,8 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.kept_len = take((size_t)k.n_pairs * 4);
     k.gate_on = take((size_t)k.n_pairs * 4);
     k.pool_next = take(4);
+    k.free_top = take(4);
+    k.free_pages = take((size_t)k.n_pages * 4);
     k.err_flag = take(4);
     k.page_table = take((size_t)k.n_pairs * k.pt_cap * 4);
     k.pool = take((size_t)k.n_pages * page_bytes);
@@ -281,6 +284,8 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     v.kept_len = reinterpret_cast<int32_t*>(a + k.kept_len);
     v.gate_on = reinterpret_cast<int32_t*>(a + k.gate_on);
     v.pool_next = reinterpret_cast<int32_t*>(a + k.pool_next);
+    v.free_top = reinterpret_cast<int32_t*>(a + k.free_top);
+    v.free_pages = reinterpret_cast<int32_t*>(a + k.free_pages);
     v.err_flag = reinterpret_cast<int32_t*>(a + k.err_flag);
     v.page_table = reinterpret_cast<int32_t*>(a + k.page_table);
     v.pool = reinterpret_cast<uint16_t*>(a + k.pool);
@@ -416,9 +421,10 @@ int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void*
     std::vector<int32_t> len(n_pairs), gate(n_pairs);
     int rc = refresh_bound(c, s, len.data());
     if (rc != SPKV_OK) return rc;
-    int32_t pool_next = 0, err = 0;
+    int32_t pool_next = 0, free_top = 0, err = 0;
     if (hipMemcpy(gate.data(), c->view.gate_on, (size_t)n_pairs * 4, hipMemcpyDeviceToHost) != hipSuccess ||
         hipMemcpy(&pool_next, c->view.pool_next, 4, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(&free_top, c->view.free_top, 4, hipMemcpyDeviceToHost) != hipSuccess ||
         hipMemcpy(&err, c->view.err_flag, 4, hipMemcpyDeviceToHost) != hipSuccess)
         return SPKV_E_HIP;
     std::memset(st, 0, sizeof(*st));
@@ -436,7 +442,7 @@ int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void*
     const int64_t row_bytes = (int64_t)2 * c->cfg.head_dim * 2;
     st->kept_kv_bytes = (st->kept_tokens + st->window_tokens) * row_bytes;
     st->dense_kv_bytes = st->total_tokens * Hkv * row_bytes;
-    st->pool_pages_used = pool_next;
+    st->pool_pages_used = (int64_t)pool_next - free_top;
     st->pool_pages_total = c->carve.n_pages;
     st->arena_bytes = (int64_t)c->arena_bytes;
     st->device_error = err;
@@ -450,6 +456,24 @@ int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void*
     st->n_work_items = (int32_t)n_items;
     if (kept_len != nullptr) std::memcpy(kept_len, len.data(), (size_t)n_pairs * 4);
     return err ? SPKV_E_DEVICE : SPKV_OK;
+}
+
+int spkv_cache_release_sequence(spkv_cache_t* c, int32_t b, void* stream) {
+    if (c == nullptr || b < 0 || b >= c->cfg.batch) return SPKV_E_INVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // Exact lengths first (synchronises): the host's page bound must drop by exactly what
+    // the sequence gives back.
+    const int rc = refresh_bound(c, s, nullptr);
+    if (rc != SPKV_OK) return rc;
+    if (spkv_launch_release_sequence(c->view, b, s) != hipSuccess) return SPKV_E_HIP;
+    const int Hkv = c->cfg.n_kv_heads;
+    for (int h = 0; h < Hkv; ++h) {
+        int32_t& L = c->L_ub[b * Hkv + h];
+        c->pages_ub -= pages_for(L);
+        L = 0;
+    }
+    c->T[b] = 0;
+    return SPKV_OK;
 }
 
 int spkv_cache_kept_positions(spkv_cache_t* c, int32_t b, int32_t h, int32_t* pos, int32_t cap,

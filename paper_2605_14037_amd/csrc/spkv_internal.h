@@ -25,7 +25,9 @@ struct SpkvView {
     int32_t*  t_pair;       // [n_pairs] tokens appended so far (same for all heads of a seq)
     int32_t*  kept_len;     // [n_pairs] long-term length L
     int32_t*  gate_on;      // [n_pairs] count of appended tokens with gate on
-    int32_t*  pool_next;    // [1] next free pool page
+    int32_t*  pool_next;    // [1] next never-used pool page (bump allocator)
+    int32_t*  free_top;     // [1] entries on the stack of recycled pages
+    int32_t*  free_pages;   // [n_pages] stack of pages given back by released sequences
     int32_t*  err_flag;     // [1] set by kernels on an impossible state
     int32_t*  page_table;   // [n_pairs][pt_cap] logical page -> pool page
     uint16_t* pool;         // [n_pages] pages
@@ -66,4 +68,5 @@ hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const u
 // One-wave workgroups of the split-K kernel the current device holds at once (occupancy x
 // compute units); 0 if the runtime cannot tell.
 int spkv_split_resident_items(int head_dim);
+hipError_t spkv_launch_release_sequence(const SpkvView& v, int b, hipStream_t s);
 hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s);

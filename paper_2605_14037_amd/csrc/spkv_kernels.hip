@@ -49,6 +49,18 @@ __device__ __forceinline__ uint16_t* pool_page(const SpkvView& v, int page) {
     return v.pool + (size_t)page * (size_t)spkv_page_elems(v.D);
 }
 
+// One pool page for the caller: a recycled one if the stack of released pages has any,
+// else the next never-used one; -1 if the pool is exhausted.  Pushes onto the stack happen
+// only in spkv_release_sequence, never in the same launch as pops, and a failed pop puts
+// its decrement back, so the counter is exact between launches.
+__device__ __forceinline__ int alloc_page(const SpkvView& v) {
+    const int idx = atomicSub(v.free_top, 1) - 1;
+    if (idx >= 0) return v.free_pages[idx];
+    atomicAdd(v.free_top, 1);
+    const int page = atomicAdd(v.pool_next, 1);
+    return page < v.n_pages ? page : -1;
+}
+
 // ------------------------------------------------------------------------ zero fill
 __global__ __launch_bounds__(256) void spkv_fill_zero(uint4* p, size_t n16) {
     const uint4 z = {0u, 0u, 0u, 0u};
@@ -148,11 +160,7 @@ __device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T,
         int page = r.page_entry;
         if (!have_page) {                                         // first pair of a new page
             if (tid == 0) {
-                int np = -1;
-                if (lp < v.pt_cap) {
-                    np = atomicAdd(v.pool_next, 1);
-                    if (np >= v.n_pages) np = -1;
-                }
+                const int np = lp < v.pt_cap ? alloc_page(v) : -1;
                 if (np >= 0) v.page_table[(size_t)pair * v.pt_cap + lp] = np;
                 else *v.err_flag = 1;
                 *s_page = np;
@@ -222,16 +230,8 @@ struct BulkInfo {
     int32_t T_old;        // tokens held before this call
     int32_t new_base;     // long-term index of the first kept NEW token (after ring-evicted ones)
     int32_t ok;           // 0: capacity error, the call writes nothing more for this pair
-    int32_t first_new_lp; // first logical page allocated by this call
-    int32_t base_page;    // pool page of first_new_lp (the call's pages are consecutive)
-    int32_t tail_page;    // pool page of logical page first_new_lp - 1 (partly filled before)
-    int32_t pad[2];
+    int32_t pad[5];
 };
-
-__device__ __forceinline__ int bulk_page_of(const BulkInfo& bi, int gidx) {
-    const int lp = gidx >> 6;
-    return lp < bi.first_new_lp ? bi.tail_page : bi.base_page + (lp - bi.first_new_lp);
-}
 
 // Lane (r = lane / 16, c = lane % 16) moves chunk c of one row into row dk of page dp.
 template <int D>
@@ -286,7 +286,7 @@ __device__ __forceinline__ int block_excl_scan(int x, int* s_w, int& total) {
 
 // Stage 2: one workgroup per pair.  Counts the pairs leaving the ring that are kept,
 // turns the segment counts into offsets, allocates every page the call needs with one
-// atomic, publishes the new lengths, then moves the kept ring rows.
+// allocation per page, publishes the new lengths, then moves the kept ring rows.
 template <int D>
 __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
     const int pair = blockIdx.x;
@@ -329,34 +329,31 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
     }
     const int total_new = ring_kept + carry;
 
-    // (c) pages: the call's new pages are consecutive pool pages from one atomicAdd
+    // (c) pages: one allocation per new logical page, in parallel; the table entries are
+    //     visible to the whole workgroup after the barrier and to stage 3 after the launch
+    const int first = (L_old + kPageTokens - 1) / kPageTokens;
+    const int last = (L_old + total_new + kPageTokens - 1) / kPageTokens;
+    const int need = last <= v.pt_cap ? last - first : 0;
+    int bad = last > v.pt_cap ? 1 : 0;
+    for (int i = tid; i < need; i += 256) {
+        const int page = alloc_page(v);
+        if (page < 0) bad = 1;
+        else v.page_table[(size_t)pair * v.pt_cap + first + i] = page;
+    }
+    const int any_bad = __syncthreads_or(bad);
     if (tid == 0) {
-        const int first = (L_old + kPageTokens - 1) / kPageTokens;
-        const int last = (L_old + total_new + kPageTokens - 1) / kPageTokens;
-        const int need = last - first;
-        int base = 0, ok = 1;
-        if (last > v.pt_cap) ok = 0;
-        if (ok && need > 0) {
-            base = atomicAdd(v.pool_next, need);
-            if (base + need > v.n_pages) ok = 0;
-        }
-        if (!ok) *v.err_flag = 1;
+        if (any_bad) *v.err_flag = 1;
         s_bi.T_old = T_old;
         s_bi.new_base = L_old + ring_kept;
-        s_bi.ok = ok;
-        s_bi.first_new_lp = first;
-        s_bi.base_page = base;
-        s_bi.tail_page = first > 0 ? v.page_table[(size_t)pair * v.pt_cap + first - 1] : 0;
-        s_bi.pad[0] = ok ? need : 0;
+        s_bi.ok = any_bad ? 0 : 1;
         *reinterpret_cast<BulkInfo*>(v.bulk_info + (size_t)pair * 8) = s_bi;
-        if (ok) v.kept_len[pair] = L_old + total_new;
+        if (!any_bad) v.kept_len[pair] = L_old + total_new;
         v.t_pair[pair] = T_new;
     }
+    __threadfence_block();
     __syncthreads();
-    const BulkInfo bi = s_bi;
-    for (int i = tid; i < bi.pad[0]; i += 256)
-        v.page_table[(size_t)pair * v.pt_cap + bi.first_new_lp + i] = bi.base_page + i;
-    if (!bi.ok) return;
+    if (any_bad) return;
+    const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
 
     // (d) move the kept ring rows, 256 ring positions at a time
     int done = 0;
@@ -382,7 +379,7 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
                 for (int e = 0; e < 4; ++e)
                     w[e] = (unsigned)vs[(2 * e) * 8] | ((unsigned)vs[(2 * e + 1) * 8] << 16);
                 const int gi = L_old + done + r;
-                const int page = bulk_page_of(bi, gi);
+                const int page = pt[gi >> 6];
                 store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, make_uint4(w[0], w[1], w[2], w[3]));
                 if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = s;
             }
@@ -440,7 +437,7 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
                 const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
                 const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
                 const int gi = g0 + r;
-                const int page = bulk_page_of(bi, gi);
+                const int page = v.page_table[(size_t)pair * v.pt_cap + (gi >> 6)];
                 store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, vl);
                 if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = bi.T_old + jj;
             }
@@ -866,6 +863,30 @@ hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const u
         spkv_decode_split<64, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
         spkv_combine_append<64><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
     }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- release a sequence
+// One workgroup per KV head of the sequence: its pages go onto the stack of recycled pages
+// and its counters back to zero (the ring needs no clearing: with T = 0 no slot is valid).
+__global__ __launch_bounds__(256) void spkv_release_sequence(SpkvView v, int b) {
+    const int pair = b * v.Hkv + blockIdx.x;
+    const int tid = threadIdx.x;
+    const int np = (v.kept_len[pair] + kPageTokens - 1) / kPageTokens;
+    __shared__ int s_base;
+    if (tid == 0) s_base = np > 0 ? atomicAdd(v.free_top, np) : 0;
+    __syncthreads();
+    for (int i = tid; i < np; i += 256)
+        v.free_pages[s_base + i] = v.page_table[(size_t)pair * v.pt_cap + i];
+    if (tid == 0) {
+        v.kept_len[pair] = 0;
+        v.t_pair[pair] = 0;
+        v.gate_on[pair] = 0;
+    }
+}
+
+hipError_t spkv_launch_release_sequence(const SpkvView& v, int b, hipStream_t s) {
+    spkv_release_sequence<<<dim3(v.Hkv), dim3(256), 0, s>>>(v, b);
     return hipGetLastError();
 }
 

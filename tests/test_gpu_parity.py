@@ -349,3 +349,60 @@ def test_largest_batch():
     wl = small_workload("bigbatch", B, 8, 8, 64, lens, 0.4, window=64, decode_steps=2, seed=17)
     H.run_workload(wl, chunk=4096, state_pairs=[(0, 0), (511, 7), (255, 3)])
     H.run_workload(wl, chunk=4096, state_pairs=[(1, 1), (510, 6)], fused=True)
+
+
+def test_release_and_reuse_sequences():
+    """Continuous batching: sequences finish, their slots are released and refilled; pages
+    are recycled (the pool would overflow without it) and every state check stays exact."""
+    B, Hq, Hkv, D, w = 3, 8, 2, 128, 32
+    wl = small_workload("release", B, Hq, Hkv, D, [0] * B, [[0.9, 0.4]] * B, window=w, seed=33)
+    stream = TokenStream(wl, device="cuda")
+    # room for about two and a half full sequences of 1500 tokens at these keep rates
+    cache = spkv.SPKVCache(B, Hq, Hkv, D, max_context=1600, max_total_kept_tokens=5200,
+                           window=w, tau=0.5)
+    oracle = H.make_oracle(wl)
+    rng = np.random.default_rng(5)
+
+    def pages_in_use(kept):
+        return sum((L + 63) // 64 for row in kept for L in row)
+
+    def step(fused):
+        k, v, f, cu = stream.next_tokens([1] * B)
+        q = stream.next_query()
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        if fused:
+            out = cache.decode_step(k, v, f, q)
+        else:
+            cache.append(k, v, f, cu)
+            out = cache.decode_attention(q)
+        H.check_output(out, oracle.decode(to_numpy_f32(q))[0])
+
+    # fill all three, then release / refill one at a time, eleven times
+    for b in range(B):
+        counts = [0] * B
+        counts[b] = int(rng.integers(600, 1500))
+        H.feed(cache, oracle, *stream.next_tokens(counts))
+    total_pages_ever = 0
+    for cycle in range(11):
+        step(fused=cycle % 2 == 0)
+        b = cycle % B
+        cache.release_sequence(b)
+        oracle.release_sequence(b)
+        st, kept = cache.stats(with_kept_len=True)
+        assert kept[b] == [0] * Hkv and st.pool_pages_used == pages_in_use(kept)
+        counts = [0] * B
+        counts[b] = int(rng.integers(1, 1500))
+        for piece in (counts[b] // 3, counts[b] - counts[b] // 3):      # two ragged bulk calls
+            c2 = [0] * B
+            c2[b] = piece
+            if piece:
+                H.feed(cache, oracle, *stream.next_tokens(c2))
+        st = H.check_state(cache, oracle, wl, label=f"cycle {cycle}")
+        _, kept = cache.stats(with_kept_len=True)
+        assert st.pool_pages_used == pages_in_use(kept)
+        total_pages_ever += sum((L + 63) // 64 for L in kept[b])
+        step(fused=cycle % 2 == 1)
+    assert total_pages_ever > st.pool_pages_total        # only recycling made this fit
+    with pytest.raises(spkv.SPKVError):
+        cache.release_sequence(B)
+    cache.close()
