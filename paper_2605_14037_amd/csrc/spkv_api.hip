@@ -24,7 +24,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Carve {
     size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, free_top, free_pages, err_flag,
         page_table, pool,
-        pos_pool, seg_count, bulk_info, part_acc, part_ml, pair_items,
+        pos_pool, seg_count, seg_on, bulk_info, part_acc, part_ml, pair_items,
         pos_scratch, total;
     int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items;
 };
@@ -55,7 +55,7 @@ bool carve(const spkv_config_t* c, Carve* out) {
     const int64_t n_pages = (c->max_total_kept_tokens + kPageTokens - 1) / kPageTokens + k.n_pairs;
     if (n_pages > ((int64_t)1 << 30)) return false;
     k.n_pages = (int)n_pages;
-    k.n_seg_cap = (int)((max_evicted + kSegTokens - 1) / kSegTokens) + 1;
+    k.n_seg_cap = (int)(((int64_t)c->max_context + kSegTokens - 1) / kSegTokens) + 1;
     // Work-item slots: 128 per pair leaves room for a pair 40 times longer than the mean at
     // the default item count; at least enough for the largest item target on one pair.
     k.max_items = std::max(kMaxItemTarget + k.n_pairs, std::min(k.n_pairs * 128, 1 << 17));
@@ -79,6 +79,7 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.pool = take((size_t)k.n_pages * page_bytes);
     k.pos_pool = take((size_t)k.n_pages * kPageTokens * 4);
     k.seg_count = take((size_t)k.n_pairs * k.n_seg_cap * 4);
+    k.seg_on = take((size_t)k.n_pairs * k.n_seg_cap * 4);
     k.bulk_info = take((size_t)k.n_pairs * 32);
     k.part_acc = take((size_t)k.max_items * k.G * c->head_dim * 4);
     k.part_ml = take((size_t)k.max_items * k.G * 2 * 4);
@@ -291,6 +292,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     v.pool = reinterpret_cast<uint16_t*>(a + k.pool);
     v.pos_pool = reinterpret_cast<int32_t*>(a + k.pos_pool);
     v.seg_count = reinterpret_cast<int32_t*>(a + k.seg_count);
+    v.seg_on = reinterpret_cast<int32_t*>(a + k.seg_on);
     v.bulk_info = reinterpret_cast<int32_t*>(a + k.bulk_info);
     v.part_acc = reinterpret_cast<float*>(a + k.part_acc);
     v.part_ml = reinterpret_cast<float*>(a + k.part_ml);

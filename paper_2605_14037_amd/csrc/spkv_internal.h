@@ -33,6 +33,7 @@ struct SpkvView {
     uint16_t* pool;         // [n_pages] pages
     int32_t*  pos_pool;     // [n_pages][64] position of every long-term entry
     int32_t*  seg_count;    // [n_pairs][n_seg_cap] bulk scratch: kept per segment, then offsets
+    int32_t*  seg_on;       // [n_pairs][n_seg_cap] bulk scratch: gate-on tokens per segment
     int32_t*  bulk_info;    // [n_pairs][8] bulk scratch, see BulkInfo in spkv_kernels.hip
     float*    part_acc;     // [max_items][G][D] un-normalised partial outputs
     float*    part_ml;      // [max_items][G][2] running max (log2 domain) and sum

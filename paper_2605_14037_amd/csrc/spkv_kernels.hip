@@ -243,7 +243,8 @@ __device__ __forceinline__ void store_row_chunk(uint16_t* dp, int dk, int c, uin
     for (int e = 0; e < 8; ++e) vd[e * 8] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
 }
 
-// Stage 1: per (segment, pair) count of new tokens j < n - w that pass the gate.
+// Stage 1: per (segment, pair): how many of the segment's new tokens pass the gate, and how
+// many of those also leave the window within this call (j < n - w).
 __global__ __launch_bounds__(256) void spkv_bulk_count(SpkvView v, const float* __restrict__ f,
                                                        SpkvCu cu) {
     const int pair = blockIdx.y, seg = blockIdx.x;
@@ -251,14 +252,20 @@ __global__ __launch_bounds__(256) void spkv_bulk_count(SpkvView v, const float* 
     const int n = cu.v[b + 1] - cu.v[b];
     const int n_ev = max(0, n - v.w);
     const int j = seg * kSegTokens + (int)threadIdx.x;
-    if (seg * kSegTokens >= n_ev) return;
-    __shared__ int s_wave[4];
-    const bool flag = j < n_ev && f[((size_t)cu.v[b] + j) * v.Hkv + h] >= v.theta;
-    const int cnt = __popcll(__ballot(flag));
-    if (lane_id() == 0) s_wave[threadIdx.x >> 6] = cnt;
+    if (seg * kSegTokens >= n) return;
+    __shared__ int s_ev[4], s_on[4];
+    const bool on = j < n && f[((size_t)cu.v[b] + j) * v.Hkv + h] >= v.theta;
+    const int c_on = __popcll(__ballot(on));
+    const int c_ev = __popcll(__ballot(on && j < n_ev));
+    if (lane_id() == 0) {
+        s_on[threadIdx.x >> 6] = c_on;
+        s_ev[threadIdx.x >> 6] = c_ev;
+    }
     __syncthreads();
-    if (threadIdx.x == 0)
-        v.seg_count[(size_t)pair * v.n_seg_cap + seg] = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+    if (threadIdx.x == 0) {
+        v.seg_count[(size_t)pair * v.n_seg_cap + seg] = s_ev[0] + s_ev[1] + s_ev[2] + s_ev[3];
+        v.seg_on[(size_t)pair * v.n_seg_cap + seg] = s_on[0] + s_on[1] + s_on[2] + s_on[3];
+    }
 }
 
 // Block-wide exclusive scan of one int per thread (256 threads); returns the exclusive
@@ -329,6 +336,20 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
     }
     const int total_new = ring_kept + carry;
 
+    // gate-on count of the call (Eq. 8 numerator), summed here so that no kernel needs
+    // same-address atomics
+    {
+        const int nseg_all = (n + kSegTokens - 1) / kSegTokens;
+        const int32_t* so = v.seg_on + (size_t)pair * v.n_seg_cap;
+        int on = 0;
+        for (int i = tid; i < nseg_all; i += 256) on += so[i];
+        for (int o = 32; o > 0; o >>= 1) on += __shfl_xor(on, o);
+        __syncthreads();
+        if (lane == 0) s_w[wave] = on;
+        __syncthreads();
+        if (tid == 0) v.gate_on[pair] += s_w[0] + s_w[1] + s_w[2] + s_w[3];
+    }
+
     // (c) pages: one allocation per new logical page, in parallel; the table entries are
     //     visible to the whole workgroup after the barrier and to stage 3 after the launch
     const int first = (L_old + kPageTokens - 1) / kPageTokens;
@@ -391,8 +412,9 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
 
 // Stage 3: per (256-token segment, pair).  Thread i owns token j0 + i: gate flag, rank
 // (mbcnt inside the wave + the popcounts of the lower waves + the segment offset from
-// stage 2); the kept tokens' indices are compacted into LDS and their rows moved 16 at a
-// time; the last min(n, w) tokens of the call are written into the ring.
+// stage 2); the kept tokens' indices are compacted into LDS and their rows moved in groups
+// of eight consecutive destination rows (whole 16-byte V units, transposed through LDS),
+// stragglers row by row; the last min(n, w) tokens of the call are written into the ring.
 template <int D>
 __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint16_t* __restrict__ k,
                                                          const uint16_t* __restrict__ vv,
@@ -409,11 +431,10 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15;
     __shared__ int s_cnt[4];
     __shared__ uint16_t s_list[256];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[4][8][D];
 
     const int j = j0 + tid;
     const bool on = j < n && f[((size_t)row0 + j) * v.Hkv + h] >= v.theta;
-    const unsigned long long on_mask = __ballot(on);
-    if (lane == 0 && on_mask != 0ull) atomicAdd(v.gate_on + pair, __popcll(on_mask));
     const bool ev = on && j < n_ev;
     const unsigned long long mask = __ballot(ev);
     if (lane == 0) s_cnt[wave] = __popcll(mask);
@@ -429,15 +450,66 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
 
     if (total > 0) {
         const int g0 = bi.new_base + v.seg_count[(size_t)pair * v.n_seg_cap + seg];
-        for (int rb = wave * 4; rb < total; rb += 16) {
-            const int r = rb + (lane >> 4);
-            if (r < total && c < D / 8) {
+        const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+        const int gend = g0 + total;
+        const int ga = min(gend, (g0 + 7) & ~7);   // destination indices [ga, gb) are whole
+        const int gb = max(ga, gend & ~7);         // groups of 8 aligned to 8: whole V units
+
+        // Whole groups, one wave each: K chunks go straight out; the eight V rows meet in
+        // LDS and leave as 16-byte units (eight keys of one head-dim element).
+        for (int G8 = ga + wave * 8; G8 < gb; G8 += 32) {
+            const int page = pt[G8 >> 6];
+            uint16_t* dp = pool_page(v, page);
+            const int dk0 = G8 & 63;
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const int row = pass * 4 + (lane >> 4);
+                if (c < D / 8) {
+                    const int jj = j0 + s_list[G8 - g0 + row];
+                    const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
+                    const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
+                    const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
+                    *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk0 + row, c * 8)) = kk;
+                    *reinterpret_cast<uint4*>(&s_v[wave][row][c * 8]) = vl;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane < D / 2) {
+                unsigned dw[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    dw[r] = *reinterpret_cast<const unsigned*>(&s_v[wave][r][2 * lane]);
+                uint4 lo, hi;
+                lo.x = (dw[0] & 0xffffu) | (dw[1] << 16);
+                lo.y = (dw[2] & 0xffffu) | (dw[3] << 16);
+                lo.z = (dw[4] & 0xffffu) | (dw[5] << 16);
+                lo.w = (dw[6] & 0xffffu) | (dw[7] << 16);
+                hi.x = (dw[0] >> 16) | (dw[1] & 0xffff0000u);
+                hi.y = (dw[2] >> 16) | (dw[3] & 0xffff0000u);
+                hi.z = (dw[4] >> 16) | (dw[5] & 0xffff0000u);
+                hi.w = (dw[6] >> 16) | (dw[7] & 0xffff0000u);
+                uint16_t* vd = dp + spkv_v_off(D, dk0, 2 * lane);   // unit of d = 2 lane; d + 1 follows
+                *reinterpret_cast<uint4*>(vd) = lo;
+                *reinterpret_cast<uint4*>(vd + 8) = hi;
+            }
+            if (lane < 8)
+                v.pos_pool[(size_t)page * kPageTokens + dk0 + lane] =
+                    bi.T_old + j0 + s_list[G8 - g0 + lane];
+            __builtin_amdgcn_wave_barrier();
+        }
+        // The rows before the first and after the last whole group, one row per 16 lanes,
+        // V elements as 2-byte stores.
+        const int n_head = ga - g0, n_tail = gend - gb;
+        for (int rb = wave * 4; rb < n_head + n_tail; rb += 16) {
+            const int x = rb + (lane >> 4);
+            if (x < n_head + n_tail && c < D / 8) {
+                const int r = x < n_head ? x : (gb - g0) + (x - n_head);
                 const int jj = j0 + s_list[r];
                 const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
                 const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
                 const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
                 const int gi = g0 + r;
-                const int page = v.page_table[(size_t)pair * v.pt_cap + (gi >> 6)];
+                const int page = pt[gi >> 6];
                 store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, vl);
                 if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = bi.T_old + jj;
             }
@@ -460,12 +532,8 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
 
 hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const SpkvCu& cu, int n_max, hipStream_t s) {
-    const int n_ev_max = n_max - v.w;
-    if (n_ev_max > 0) {
-        const int segs = (n_ev_max + kSegTokens - 1) / kSegTokens;
-        spkv_bulk_count<<<dim3(segs, v.n_pairs), dim3(256), 0, s>>>(v, f, cu);
-    }
     const int segs_all = (n_max + kSegTokens - 1) / kSegTokens;
+    spkv_bulk_count<<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, f, cu);
     if (v.D == 128) {
         spkv_bulk_ring<128><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu);
         spkv_bulk_scatter<128><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu);
@@ -520,7 +588,7 @@ __device__ __forceinline__ void attend_half_page(const bf16x8 (&ka)[2][D / 32],
         s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][sl], qb[sl], s0, 0, 0, 0);
         s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][sl], qb[sl], s1, 0, 0, 0);
     }
-    // Lane (kc, n) now holds, for head n, the keys r = 16 t + 4 kc + i of the half-page.
+    // Lane (kc, n) now holds, for head n, the keys r = 8 kc + 4 t + i of the half-page.
     float x[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -530,7 +598,7 @@ __device__ __forceinline__ void attend_half_page(const bf16x8 (&ka)[2][D / 32],
     if (nvalid < kHalfTokens || masked_r >= 0) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int r = (e >> 2) * 16 + kc * 4 + (e & 3);
+            const int r = kc * 8 + e;
             if (r >= nvalid || r == masked_r) x[e] = SPKV_NEG_INF;
         }
     }

@@ -7,19 +7,24 @@
 // one 128-bit load per lane (lane l reads bytes [16 l, 16 l + 16)) already IS an operand
 // of v_mfma_f32_16x16x32_bf16, with no shuffle and no LDS staging:
 //
-//   K block = [t : 2][chunk : D/8][kk : 16][8 bf16]
-//     key r = 16 t + kk of the half-page, head-dim elements d = 8 chunk .. 8 chunk + 7.
-//     The 1 KB tile (t, slab) = chunks 4 slab .. 4 slab + 3 gives lane (kc = l / 16,
-//     kk = l % 16) the 8 elements d = 32 slab + 8 kc + e of key kk: the A operand
-//     (rows = keys, contraction over d) of  S[key][head] += K[key][d] * Q[head][d].
+//   Key order.  Key r (0..31) of a half-page is written r = 8 kc + 4 t + i with kc in 0..3,
+//   t in 0..1, i in 0..3: K tile t holds, as its row m = 4 kc + i, the key 8 kc + 4 t + i.
+//
+//   K block = [t : 2][chunk : D/8][m : 16][8 bf16]
+//     row m of tile t, head-dim elements d = 8 chunk .. 8 chunk + 7.  The 1 KB tile
+//     (t, slab) = chunks 4 slab .. 4 slab + 3 gives lane (kc' = l / 16, m = l % 16) the
+//     8 elements d = 32 slab + 8 kc' + e of row m: the A operand (rows = keys,
+//     contraction over d) of  S[key][head] += K[key][d] * Q[head][d].
 //
 //   V block = [db : D/16][kc : 4][dr : 16][8 bf16],  element e = 4 t + i
-//     holds V[key r = 16 t + 4 kc + i][d = 16 db + dr].  The 1 KB tile db gives lane
-//     (kc, dr) eight keys of one output dimension: the A operand (rows = d, contraction
-//     over keys) of  O[d][head] += V[key][d] * P[key][head].  The key order inside the
-//     lane group kc is exactly the order in which the S accumulator of the two K tiles
-//     leaves lane (kc, head) -- rows 4 kc + i of tile t -- so the softmax weights go
-//     from the first MFMA to the second without crossing lanes.
+//     holds V[key r = 8 kc + e][d = 16 db + dr]: eight CONSECUTIVE keys of one output
+//     dimension.  The 1 KB tile db gives lane (kc, dr) those eight keys: the A operand
+//     (rows = d, contraction over keys) of  O[d][head] += V[key][d] * P[key][head].  The key
+//     order inside lane group kc is exactly the order in which the S accumulators of the
+//     two K tiles leave lane (kc, head) -- rows 4 kc + i of tile t -- so the softmax
+//     weights go from the first MFMA to the second without crossing lanes; and because a
+//     16-byte V unit is eight consecutive keys, eight rows appended together fill whole
+//     units (the bulk write path assembles them in LDS).
 //
 // The window ring uses the same page layout (slot s mod w -> page slot / 64, index
 // slot % 64), so the decode kernel reads ring and long-term pages with the same code.
@@ -40,13 +45,14 @@ SPKV_HD int spkv_page_elems(int D) { return 2 * kPageTokens * D; }
 
 // Element offset, from the start of the page, of K[kidx][d].
 SPKV_HD int spkv_k_off(int D, int kidx, int d) {
-    const int half = kidx >> 5, t = (kidx >> 4) & 1, kk = kidx & 15;
-    return half * (2 * kHalfTokens * D) + (((t * (D >> 3) + (d >> 3)) << 4) + kk) * 8 + (d & 7);
+    const int half = kidx >> 5, kc = (kidx >> 3) & 3, t = (kidx >> 2) & 1, i = kidx & 3;
+    const int m = 4 * kc + i;
+    return half * (2 * kHalfTokens * D) + (((t * (D >> 3) + (d >> 3)) << 4) + m) * 8 + (d & 7);
 }
 
 // Element offset, from the start of the page, of V[kidx][d].
 SPKV_HD int spkv_v_off(int D, int kidx, int d) {
-    const int half = kidx >> 5, t = (kidx >> 4) & 1, kc = (kidx >> 2) & 3, i = kidx & 3;
+    const int half = kidx >> 5, kc = (kidx >> 3) & 3;
     return half * (2 * kHalfTokens * D) + kHalfTokens * D +
-           (((((d >> 4) << 2) + kc) << 4) + (d & 15)) * 8 + t * 4 + i;
+           (((((d >> 4) << 2) + kc) << 4) + (d & 15)) * 8 + (kidx & 7);
 }

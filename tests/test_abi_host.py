@@ -84,22 +84,23 @@ def test_page_layout_is_a_bijection_in_mfma_operand_order(D):
         vs = voff[half * 32:(half + 1) * 32]
         assert ks.min() == lo and ks.max() == lo + 32 * D - 1     # K block, then V block
         assert vs.min() == lo + 32 * D and vs.max() == lo + 64 * D - 1
-        # K tile (t, slab): lane (kc, kk) holds d = 32 slab + 8 kc + e of key 16 t + kk at
-        # byte 16 * lane of a 1 KB tile.
+        # K tile (t, slab): lane (kc', m) holds d = 32 slab + 8 kc' + e of the tile's row m,
+        # which is key 8 (m // 4) + 4 t + m % 4, at byte 16 * lane of a 1 KB tile.
         for t in range(2):
             for slab in range(D // 32):
                 tile = lo + (t * (D // 8) + slab * 4) * 128
                 for lane in range(64):
-                    kc, kk = lane // 16, lane % 16
+                    kcp, m = lane // 16, lane % 16
+                    key = 8 * (m // 4) + 4 * t + m % 4
                     for e in range(8):
-                        assert koff[half * 32 + 16 * t + kk, 32 * slab + 8 * kc + e] == tile + lane * 8 + e
-        # V tile db: lane (kc, dr) holds keys 16 t + 4 kc + i (element 4 t + i) of d = 16 db + dr.
+                        assert koff[half * 32 + key, 32 * slab + 8 * kcp + e] == tile + lane * 8 + e
+        # V tile db: lane (kc, dr) holds the eight consecutive keys 8 kc + e of d = 16 db + dr,
+        # and e = 4 t + i is the key that leaves row 4 kc + i of K tile t.
         for db in range(D // 16):
             tile = lo + 32 * D + db * 512
             for lane in range(64):
                 kc, dr = lane // 16, lane % 16
-                for t in range(2):
-                    for i in range(4):
-                        assert voff[half * 32 + 16 * t + 4 * kc + i, 16 * db + dr] == tile + lane * 8 + 4 * t + i
+                for e in range(8):
+                    assert voff[half * 32 + 8 * kc + e, 16 * db + dr] == tile + lane * 8 + e
     assert spkv.layout_offset(D, 0, 64, 0) == -1 and spkv.layout_offset(D, 1, 0, D) == -1
     assert spkv.layout_offset(96, 0, 0, 0) == -1
