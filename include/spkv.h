@@ -168,6 +168,20 @@ int spkv_decode_step(spkv_cache_t* cache, const void* k, const void* v, const fl
  * values were finite. */
 int spkv_cache_release_sequence(spkv_cache_t* cache, int32_t b, void* stream);
 
+/* Utility predictor (Eq. 1; the listing's UtilityPredictor: Linear(d_model, d_hidden), SiLU,
+ * Linear(d_hidden, n_kv_heads)), pre-sigmoid, for n_tokens tokens:
+ *   logits[t, h] = b2[h] + sum_j w2[h, j] * silu(b1[j] + sum_k w1[j, k] * hidden[t, k])
+ *   hidden  device bf16 [n_tokens, d_model]          w1  device bf16 [d_hidden, d_model]
+ *   b1      device fp32 [d_hidden] or NULL           w2  device bf16 [n_kv_heads, d_hidden]
+ *   b2      device fp32 [n_kv_heads] or NULL         logits  device fp32 [n_tokens, n_kv_heads]
+ *   workspace  device fp32 [n_tokens * d_hidden] (hidden activations; caller-owned scratch)
+ * (weights in the row-major [out, in] layout of a linear layer).  d_model must be a multiple
+ * of 128, d_hidden of 16.  Products of bf16 values accumulate in fp32.  Stateless: no cache
+ * involved; the output is what spkv_append / spkv_decode_step take as util_logits. */
+int spkv_utility_logits(const void* hidden, const void* w1, const float* b1, const void* w2,
+                        const float* b2, float* logits, float* workspace, int32_t n_tokens,
+                        int32_t d_model, int32_t d_hidden, int32_t n_kv_heads, void* stream);
+
 /* Gate density and sizes (Eq. 8).  Synchronises `stream`.  kept_len (host int32
  * [batch * n_kv_heads], or NULL) receives the long-term length of every (seq, head). */
 int spkv_cache_stats(spkv_cache_t* cache, spkv_stats_t* stats, int32_t* kept_len, void* stream);

@@ -66,6 +66,21 @@ def threshold_logit(tau: float) -> np.float32:
     return np.float32(math.log(t / (1.0 - t)))
 
 
+def utility_logits(hidden, w1, b1, w2, b2):
+    """Pre-sigmoid output of the utility predictor (Eq. 1; listing appendix: Linear, SiLU,
+    Linear), in fp64: f[t, h] = b2[h] + sum_j w2[h, j] silu(b1[j] + sum_k w1[j, k] x[t, k]),
+    silu(a) = a sigmoid(a).  Weights are [out, in]; biases may be None."""
+    x = np.asarray(hidden, np.float64)
+    a = x @ np.asarray(w1, np.float64).T
+    if b1 is not None:
+        a = a + np.asarray(b1, np.float64)
+    a = a / (1.0 + np.exp(-a))
+    f = a @ np.asarray(w2, np.float64).T
+    if b2 is not None:
+        f = f + np.asarray(b2, np.float64)
+    return f
+
+
 class SPKVOracle:
     """Dense-history SP-KV decode attention, one instance per attention layer.
 

@@ -20,7 +20,7 @@ MAX_BATCH, PAGE_TOKENS = 512, 64
 
 EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_reset",
-    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_cache_release_sequence", "spkv_cache_stats", "spkv_cache_kept_positions",
+    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
     "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
@@ -84,6 +84,8 @@ def load_library():
     lib.spkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, vp]
     lib.spkv_cache_release_sequence.restype = C.c_int
     lib.spkv_cache_release_sequence.argtypes = [vp, i32, vp]
+    lib.spkv_utility_logits.restype = C.c_int
+    lib.spkv_utility_logits.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
     lib.spkv_cache_stats.restype = C.c_int
     lib.spkv_cache_stats.argtypes = [vp, P(SPKVStats), P(i32), vp]
     lib.spkv_cache_kept_positions.restype = C.c_int
@@ -124,6 +126,26 @@ def debug_copy(dst: torch.Tensor, src: torch.Tensor):
         raise ValueError("debug_copy: need contiguous cuda tensors of equal byte size")
     _check(load_library().spkv_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
                                           nbytes, _stream()), "spkv_debug_copy")
+
+
+def utility_logits(hidden, w1, b1, w2, b2, out=None, workspace=None):
+    """Pre-sigmoid utility logits of the two-layer predictor (spkv_utility_logits)."""
+    n, d_model = hidden.shape
+    d_hidden, n_heads = w1.shape[0], w2.shape[0]
+    hp = _dev_ptr(hidden, torch.bfloat16, (n, d_model), "hidden")
+    w1p = _dev_ptr(w1, torch.bfloat16, (d_hidden, d_model), "w1")
+    w2p = _dev_ptr(w2, torch.bfloat16, (n_heads, d_hidden), "w2")
+    b1p = _dev_ptr(b1, torch.float32, (d_hidden,), "b1") if b1 is not None else None
+    b2p = _dev_ptr(b2, torch.float32, (n_heads,), "b2") if b2 is not None else None
+    if out is None:
+        out = torch.empty(n, n_heads, dtype=torch.float32, device=hidden.device)
+    if workspace is None:
+        workspace = torch.empty(max(1, n * d_hidden), dtype=torch.float32, device=hidden.device)
+    op = _dev_ptr(out, torch.float32, (n, n_heads), "logits")
+    _check(load_library().spkv_utility_logits(hp, w1p, b1p, w2p, b2p, op,
+                                              C.c_void_p(workspace.data_ptr()), n, d_model,
+                                              d_hidden, n_heads, _stream()), "spkv_utility_logits")
+    return out
 
 
 def _check(code, where):

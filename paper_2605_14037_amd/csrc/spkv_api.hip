@@ -542,6 +542,29 @@ int64_t spkv_debug_layout_offset(int32_t head_dim, int32_t is_v, int32_t kidx, i
     return is_v ? spkv_v_off(head_dim, kidx, d) : spkv_k_off(head_dim, kidx, d);
 }
 
+int spkv_utility_logits(const void* hidden, const void* w1, const float* b1, const void* w2,
+                        const float* b2, float* logits, float* workspace, int32_t n_tokens,
+                        int32_t d_model, int32_t d_hidden, int32_t n_kv_heads, void* stream) {
+    if (hidden == nullptr || w1 == nullptr || w2 == nullptr || logits == nullptr ||
+        workspace == nullptr)
+        return SPKV_E_INVAL;
+    if (n_tokens < 0 || n_tokens > (1 << 24) || d_model < 128 || d_model % 128 != 0 ||
+        d_hidden < 16 || d_hidden % 16 != 0 || d_hidden > (1 << 16) || n_kv_heads < 1 ||
+        n_kv_heads > 1024)
+        return SPKV_E_INVAL;
+    if (!aligned16(hidden) || !aligned16(w1) || !aligned16(w2) || !aligned16(logits) ||
+        !aligned16(workspace))
+        return SPKV_E_INVAL;
+    if (n_tokens == 0) return SPKV_OK;
+    return spkv_launch_predictor(static_cast<const uint16_t*>(hidden),
+                                 static_cast<const uint16_t*>(w1), b1,
+                                 static_cast<const uint16_t*>(w2), b2, logits, workspace, n_tokens,
+                                 d_model, d_hidden, n_kv_heads,
+                                 static_cast<hipStream_t>(stream)) == hipSuccess
+               ? SPKV_OK
+               : SPKV_E_HIP;
+}
+
 int spkv_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
     if (dst == nullptr || src == nullptr || (bytes & 15u) != 0 || !aligned16(dst) || !aligned16(src))
         return SPKV_E_INVAL;

@@ -69,5 +69,9 @@ hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const u
 // One-wave workgroups of the split-K kernel the current device holds at once (occupancy x
 // compute units); 0 if the runtime cannot tell.
 int spkv_split_resident_items(int head_dim);
+hipError_t spkv_launch_predictor(const uint16_t* x, const uint16_t* w1, const float* b1,
+                                 const uint16_t* w2, const float* b2, float* logits, float* act,
+                                 int n_tokens, int d_model, int d_hidden, int n_kv_heads,
+                                 hipStream_t s);
 hipError_t spkv_launch_release_sequence(const SpkvView& v, int b, hipStream_t s);
 hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s);

@@ -406,3 +406,37 @@ def test_release_and_reuse_sequences():
     with pytest.raises(spkv.SPKVError):
         cache.release_sequence(B)
     cache.close()
+
+
+@pytest.mark.parametrize("n,dm,dh,Hk", [(16, 4096, 256, 8), (1, 128, 16, 1), (37, 1024, 48, 3),
+                                        (64, 4096, 512, 8), (300, 512, 64, 2)])
+def test_utility_predictor(n, dm, dh, Hk):
+    """The fused two-layer predictor against the fp64 oracle; and fed into the cache, the
+    logits it produces gate exactly like the same fp32 values in the oracle."""
+    from oracle.spkv_oracle import utility_logits as oracle_logits
+    g = torch.Generator(device="cuda").manual_seed(n + dm + dh)
+    x = torch.randn(n, dm, generator=g, device="cuda").to(torch.bfloat16)
+    w1 = (torch.randn(dh, dm, generator=g, device="cuda") / dm ** 0.5).to(torch.bfloat16)
+    b1 = torch.randn(dh, generator=g, device="cuda")
+    w2 = (torch.randn(Hk, dh, generator=g, device="cuda") / dh ** 0.5).to(torch.bfloat16)
+    b2 = torch.randn(Hk, generator=g, device="cuda")
+    got = spkv.utility_logits(x, w1, b1, w2, b2)
+    ref = oracle_logits(to_numpy_f32(x), to_numpy_f32(w1), to_numpy_f32(b1), to_numpy_f32(w2),
+                        to_numpy_f32(b2))
+    err = np.abs(got.cpu().numpy().astype(np.float64) - ref)
+    assert err.max() <= 1e-4 + 1e-4 * np.abs(ref).max(), err.max()       # fp32 accumulation
+    got_nb = spkv.utility_logits(x, w1, None, w2, None)
+    ref_nb = oracle_logits(to_numpy_f32(x), to_numpy_f32(w1), None, to_numpy_f32(w2), None)
+    assert np.abs(got_nb.cpu().numpy() - ref_nb).max() <= 1e-4 + 1e-4 * np.abs(ref_nb).max()
+    if n == 16:      # one decode step driven by the predictor's logits
+        wl = small_workload("pred", n, 32, Hk, 128, [200] * n, 0.5, window=64, seed=5)
+        stream = TokenStream(wl, device="cuda")
+        cache, oracle = H.make_cache(wl, extra_context=8), H.make_oracle(wl)
+        H.prefill(cache, oracle, stream, wl, 4096)
+        k, v, _, cu = stream.next_tokens([1] * n)
+        q = stream.next_query()
+        out = cache.decode_step(k, v, got, q)
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(got), cu)
+        H.check_output(out, oracle.decode(to_numpy_f32(q))[0])
+        H.check_state(cache, oracle, wl)
+        cache.close()

@@ -370,3 +370,30 @@ def test_planted_mistake_is_caught(mutant):
         except AssertionError:
             caught.append(pin.__name__)
     assert caught, f"no pin catches {mutant.__name__}"
+
+
+# ------------------------------------------------------- utility predictor (Eq. 1)
+def test_utility_logits_against_torch_modules_and_closed_forms():
+    """The oracle's predictor against torch's own Linear / SiLU in fp64 (a library routine),
+    and against cases whose value is known: zero first layer -> b2 + W2 silu(b1);
+    a one-hot path through the network."""
+    from oracle.spkv_oracle import utility_logits
+    rng = np.random.default_rng(3)
+    n, dm, dh, H = 5, 12, 7, 3
+    x, w1, b1 = rng.standard_normal((n, dm)), rng.standard_normal((dh, dm)), rng.standard_normal(dh)
+    w2, b2 = rng.standard_normal((H, dh)), rng.standard_normal(H)
+    net = torch.nn.Sequential(torch.nn.Linear(dm, dh), torch.nn.SiLU(), torch.nn.Linear(dh, H)).double()
+    with torch.no_grad():
+        net[0].weight.copy_(torch.from_numpy(w1)); net[0].bias.copy_(torch.from_numpy(b1))
+        net[2].weight.copy_(torch.from_numpy(w2)); net[2].bias.copy_(torch.from_numpy(b2))
+        ref = net(torch.from_numpy(x)).numpy()
+    np.testing.assert_allclose(utility_logits(x, w1, b1, w2, b2), ref, rtol=1e-12, atol=1e-12)
+    silu = lambda a: a / (1.0 + np.exp(-a))
+    got = utility_logits(x, np.zeros_like(w1), b1, w2, b2)
+    np.testing.assert_allclose(got, np.tile(b2 + w2 @ silu(b1), (n, 1)), rtol=1e-12)
+    # one-hot: x = e_0 scaled by 2, w1 = e_1 e_0^T, w2 = 3 e_2 e_1^T -> logit[2] = 3 silu(2)
+    x1 = np.zeros((1, dm)); x1[0, 0] = 2.0
+    w1h = np.zeros((dh, dm)); w1h[1, 0] = 1.0
+    w2h = np.zeros((H, dh)); w2h[2, 1] = 3.0
+    got = utility_logits(x1, w1h, None, w2h, None)
+    assert abs(got[0, 2] - 3.0 * 2.0 / (1.0 + math.exp(-2.0))) < 1e-14 and got[0, 0] == 0 and got[0, 1] == 0
