@@ -398,6 +398,31 @@ def main():
     dt_dec = timed_steps(caches, steps_in, K, W + 2 * K, do_append=False)
     dt_app = timed_steps(caches, steps_in, K, W + 3 * K, do_decode=False)
 
+    # Multi-token steps (spkv_decode_chunk): 4 and 16 new tokens per sequence per call.
+    chunk_legs = {}
+    for n_tok in (4, 16):
+        if n_tok * (wl.n_q_heads // wl.n_kv_heads) > 64:
+            continue
+        ins = []
+        for j in range(2 * R):
+            k, v, f, cu = streams[j % R].next_tokens([n_tok] * wl.batch)
+            q = streams[j % R].next_query(rows=n_tok * wl.batch)
+            ins.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
+        for j in range(R):
+            k, v, f, cu, q, o = ins[j]
+            caches[j % R].decode_chunk(k, v, f, q, cu, out=o)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        Kc = max(R, K // 8)
+        for j in range(Kc):
+            k, v, f, cu, q, o = ins[j % len(ins)]
+            caches[j % R].decode_chunk(k, v, f, q, cu, out=o)
+        torch.cuda.synchronize()
+        dtc = (time.perf_counter() - t0) / Kc
+        chunk_legs[f"{n_tok}_tokens_per_sequence"] = {
+            "us_per_call": dtc * 1e6, "us_per_token_position": dtc * 1e6 / n_tok,
+            "calls_timed": Kc}
+
     stats = [c.stats() for c in caches]
     kept_bytes = float(np.mean([s.kept_kv_bytes for s in stats]))
     dense_bytes = float(np.mean([s.dense_kv_bytes for s in stats]))
@@ -469,6 +494,7 @@ def main():
         "frac_of_hbm_peak_step": kept_bytes / (dt / K) / 1e9 / HBM_PEAK_GBPS,
         "dense_cache": dense,
         "prefill_append": dict(PREFILL_TIMING),
+        "decode_chunk": chunk_legs,
         "roofline": {
             "bound": "hbm", "kernel": "spkv_decode_split<128>",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -54,6 +54,7 @@ extern "C" {
 
 #define SPKV_MAX_BATCH     512 /* sequences per cache                                       */
 #define SPKV_PAGE_TOKENS   64  /* key/value pairs per long-term page                        */
+#define SPKV_MAX_CHUNK_TOKENS 16 /* new tokens per sequence in one spkv_decode_chunk call   */
 
 typedef struct spkv_cache spkv_cache_t;   /* opaque host object */
 
@@ -157,6 +158,23 @@ int spkv_decode_attention(spkv_cache_t* cache, const void* q, void* out, float* 
  * empty before the call.  Errors as for spkv_append (SPKV_E_CAPACITY before any launch). */
 int spkv_decode_step(spkv_cache_t* cache, const void* k, const void* v, const float* util_logits,
                      const void* q, void* out, float* lse, float sm_scale, void* stream);
+
+/* Multi-token step: every sequence b receives n_b = cu_seqlens[b+1] - cu_seqlens[b] new
+ * tokens (0 <= n_b <= SPKV_MAX_CHUNK_TOKENS, n_b <= window, n_b * group size <= 64) and gets
+ * the attention output of each of them, computed as if the tokens had been appended and
+ * decoded one at a time: token i of the chunk (position T_b + i) attends to the positions
+ * s <= T_b + i that are inside its window or pass the gate (Eq. 3-5; the rows T_b .. of the
+ * masked attention of the listing appendix).  Uses: verification of speculative tokens,
+ * prompt feed in 16-token chunks (the chunk size of the paper's chunked-prefill protocol).
+ *   k, v         device bf16 [total, n_kv_heads, head_dim]    util_logits device fp32 [total, n_kv_heads]
+ *   q, out       device bf16 [total, n_q_heads, head_dim]     lse device fp32 [total, n_q_heads] or NULL
+ *   cu_seqlens   host int32 [batch + 1]
+ * Afterwards the cache holds the chunk exactly as after spkv_append of the same tokens.
+ * One pass over the cache serves all tokens of a chunk (each K/V tile is read once per
+ * (sequence, KV head)).  Errors as for spkv_append; SPKV_E_INVAL if a chunk is too long. */
+int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const float* util_logits,
+                      const void* q, const int32_t* cu_seqlens, void* out, float* lse,
+                      float sm_scale, void* stream);
 
 /* Forget sequence b (for example when its request has finished): its window and long-term
  * entries are dropped, its pages return to the pool for reuse by any sequence, and slot b

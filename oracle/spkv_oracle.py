@@ -192,6 +192,12 @@ class SPKVOracle:
         in_window = (t - s) < self.w          # s <= t holds for every stored s
         return in_window | self.gate(b, h)
 
+    def available_at(self, b, h, t):
+        """Availability of positions 0..t to the query at position t (Eq. 3-4), for any
+        stored position t: s <= t and (t - s < w or z_s)."""
+        s = np.arange(t + 1)
+        return ((t - s) < self.w) | self.gate(b, h)[:t + 1]
+
     def stats(self):
         """Eq. 8 in both readings, plus byte counts at 2 bytes per element."""
         tot_T = sum(self.seq_len(b) for b in range(self.B))
@@ -227,6 +233,39 @@ class SPKVOracle:
         denom = e.sum(axis=0)                            # pass 2
         out = (e.T @ V) / denom[:, None]
         lse = m + np.log(denom)
+        return out, lse
+
+    def decode_chunk(self, q, counts):
+        """Outputs for the newest counts[b] positions of every sequence, each attending as if
+        it had been decoded right after its own append (causal inside the chunk): the rows
+        T - n .. T - 1 of the masked attention of the listing appendix.  q: [sum(counts),
+        H_q, D] packed by sequence in position order.  Returns (out, lse) in fp64."""
+        q = np.asarray(q).astype(np.float64)
+        total = int(sum(counts))
+        if q.shape != (total, self.Hq, self.D):
+            raise ValueError("q must be [sum(counts), H_q, D]")
+        out = np.zeros((total, self.Hq, self.D), np.float64)
+        lse = np.zeros((total, self.Hq), np.float64)
+        row = 0
+        for b in range(self.B):
+            T, n = self.seq_len(b), int(counts[b])
+            if n > T:
+                raise ValueError("chunk longer than the sequence")
+            for i in range(n):
+                t = T - n + i
+                for h in range(self.Hkv):
+                    K = self._k(b)[:t + 1, h, :].astype(np.float64)
+                    V = self._v(b)[:t + 1, h, :].astype(np.float64)
+                    avail = self.available_at(b, h, t)
+                    g0 = h * self.G
+                    x = self.scale * (K @ q[row, g0:g0 + self.G, :].T)
+                    x[~avail, :] = -np.inf
+                    m = x.max(axis=0)
+                    e = np.exp(x - m)
+                    den = e.sum(axis=0)
+                    out[row, g0:g0 + self.G, :] = (e.T @ V) / den[:, None]
+                    lse[row, g0:g0 + self.G] = m + np.log(den)
+                row += 1
         return out, lse
 
     def decode(self, q, workers=1):

@@ -20,7 +20,7 @@ MAX_BATCH, PAGE_TOKENS = 512, 64
 
 EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_reset",
-    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
+    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
     "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
@@ -82,6 +82,8 @@ def load_library():
     lib.spkv_decode_attention.argtypes = [vp, vp, vp, vp, f32, vp]
     lib.spkv_decode_step.restype = C.c_int
     lib.spkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, vp]
+    lib.spkv_decode_chunk.restype = C.c_int
+    lib.spkv_decode_chunk.argtypes = [vp, vp, vp, vp, vp, P(i32), vp, vp, f32, vp]
     lib.spkv_cache_release_sequence.restype = C.c_int
     lib.spkv_cache_release_sequence.argtypes = [vp, i32, vp]
     lib.spkv_utility_logits.restype = C.c_int
@@ -244,6 +246,33 @@ class SPKVCache:
         lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
         _check(self.lib.spkv_decode_step(self.handle, kp, vp, fp, qp, op, lp, float(sm_scale),
                                          _stream()), "spkv_decode_step")
+        return (out, lse) if lse is not None else out
+
+    def decode_chunk(self, k, v, util_logits, q, cu_seqlens, out=None, lse=None, sm_scale=0.0,
+                     want_lse=False):
+        """Append up to 16 tokens per sequence and return each one's attention output
+        (spkv_decode_chunk)."""
+        cfg = self.cfg
+        cu = cu_seqlens if isinstance(cu_seqlens, C.Array) else self.make_cu(cu_seqlens)
+        total = cu[cfg.batch]
+        if total == 0:
+            _check(self.lib.spkv_decode_chunk(self.handle, None, None, None, None, cu, None, None,
+                                              float(sm_scale), _stream()), "spkv_decode_chunk")
+            return None
+        kv_shape = (total, cfg.n_kv_heads, cfg.head_dim)
+        shape = (total, cfg.n_q_heads, cfg.head_dim)
+        kp = _dev_ptr(k, torch.bfloat16, kv_shape, "k")
+        vp = _dev_ptr(v, torch.bfloat16, kv_shape, "v")
+        fp = _dev_ptr(util_logits, torch.float32, kv_shape[:2], "util_logits")
+        qp = _dev_ptr(q, torch.bfloat16, shape, "q")
+        if out is None:
+            out = torch.empty(shape, dtype=torch.bfloat16, device=q.device)
+        op = _dev_ptr(out, torch.bfloat16, shape, "out")
+        if lse is None and want_lse:
+            lse = torch.empty(shape[:2], dtype=torch.float32, device=q.device)
+        lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
+        _check(self.lib.spkv_decode_chunk(self.handle, kp, vp, fp, qp, cu, op, lp, float(sm_scale),
+                                          _stream()), "spkv_decode_chunk")
         return (out, lse) if lse is not None else out
 
     # ---- bookkeeping

@@ -113,6 +113,7 @@ struct spkv_cache {
     bool bound_is_loose;          // a bulk append grew L_ub by far more than the truth
     int item_target;
     int one_round_items;          // items the chip runs in one resident round, with a margin
+    int chunk_round_items[3];     // the same for the chunk kernel with 1, 2, 4 column groups
     SpkvSplit split;              // partition used by the last decode call
     bool timing;
     bool split_only;
@@ -145,7 +146,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // about (all half-pages / item_target) half-pages, and enough slots per pair for the
 // longest pair.  The kernels apply it to the exact device-side lengths, which never
 // exceed the bound, so every pair fits its slots.
-SpkvSplit choose_split(const spkv_cache* c) {
+SpkvSplit choose_split(const spkv_cache* c, int one_round_items, int64_t slots_total_cap) {
     const int n_pairs = c->carve.n_pairs, Hkv = c->cfg.n_kv_heads;
     std::vector<int64_t> hp(n_pairs);
     int64_t sum_hp = 0, max_hp = 1;
@@ -160,7 +161,8 @@ SpkvSplit choose_split(const spkv_cache* c) {
     // of the launch stays short when the pairs differ widely in length.
     int64_t target = c->item_target;
     if (target <= 0)
-        target = std::min<int64_t>(kMaxAutoItems, std::max<int64_t>(c->one_round_items, sum_hp / kAutoItemHalfPages));
+        target = std::min<int64_t>(kMaxAutoItems, std::max<int64_t>(one_round_items, sum_hp / kAutoItemHalfPages));
+    target = std::max<int64_t>(1, std::min<int64_t>(target, slots_total_cap - n_pairs));
     int64_t per = std::max<int64_t>(1, (sum_hp + target - 1) / target);
     // Every pair rounds its item count up; keep the total within the target, because one
     // item more than the chip holds at once costs a whole second round of the longest items.
@@ -170,12 +172,16 @@ SpkvSplit choose_split(const spkv_cache* c) {
         if (items <= target || items <= n_pairs) break;
         per += std::max<int64_t>(1, per / 16);
     }
-    const int64_t slots_cap = c->carve.max_items / n_pairs - 1;
+    const int64_t slots_cap = std::max<int64_t>(1, slots_total_cap / n_pairs - 1);
     if ((max_hp + per - 1) / per > slots_cap) per = (max_hp + slots_cap - 1) / slots_cap;
     SpkvSplit sp;
     sp.hp_per_item = (int32_t)per;
     sp.slots = (int32_t)((max_hp + per - 1) / per) | 1;   // odd: see spkv_decode_split
     return sp;
+}
+
+SpkvSplit choose_split(const spkv_cache* c) {
+    return choose_split(c, c->one_round_items, c->carve.max_items);
 }
 
 // Tokens sequence b receives in a call: from cu_seqlens, or one each (cu == nullptr).
@@ -259,6 +265,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
         // compute units already queue a second item and the launch takes 15-20 % longer.
         const int resident = spkv_split_resident_items(cfg->head_dim);
         c->one_round_items = resident > 0 ? resident - resident / 24 : kFallbackItems;
+        c->chunk_round_items[0] = c->chunk_round_items[1] = c->chunk_round_items[2] = 0;
     }
     c->split = SpkvSplit{1, 1};
     c->timing = false;
@@ -413,6 +420,61 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
     if (spkv_launch_decode(c->view, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
                            lse, sm_scale, c->split, c->split_only, ev0, ev1, s) != hipSuccess)
         return SPKV_E_HIP;
+    return SPKV_OK;
+}
+
+int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
+                      const void* q, const int32_t* cu_seqlens, void* out, float* lse,
+                      float sm_scale, void* stream) {
+    if (c == nullptr || cu_seqlens == nullptr) return SPKV_E_INVAL;
+    const int B = c->cfg.batch, G = c->carve.G;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (cu_seqlens[0] != 0) return SPKV_E_INVAL;
+    int n_max = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t n = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+        if (n < 0 || n > SPKV_MAX_CHUNK_TOKENS || n > c->cfg.window || n * G > 64) return SPKV_E_INVAL;
+        n_max = std::max(n_max, (int)n);
+    }
+    if (n_max == 0) return SPKV_OK;
+    if (k == nullptr || v == nullptr || util_logits == nullptr || q == nullptr || out == nullptr)
+        return SPKV_E_INVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(util_logits) || !aligned16(q) ||
+        !aligned16(out) || (lse != nullptr && !aligned16(lse)))
+        return SPKV_E_INVAL;
+    if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
+    if (c->bound_is_loose) {
+        const int rc = refresh_bound(c, s, nullptr);
+        if (rc != SPKV_OK) return rc;
+    }
+    const int rc = reserve_capacity(c, cu_seqlens, s);
+    if (rc != SPKV_OK) return rc;
+
+    const int cols = n_max * G;
+    const int groups = cols <= 16 ? 1 : (cols <= 32 ? 2 : 4);
+    const int gi = groups == 1 ? 0 : (groups == 2 ? 1 : 2);
+    if (c->chunk_round_items[gi] == 0) {
+        const int resident = spkv_chunk_resident_items(c->cfg.head_dim, groups);
+        c->chunk_round_items[gi] = resident > 0 ? resident - resident / 24 : 960;
+    }
+    // every slot holds groups * 16 columns of partials instead of G
+    const int64_t slot_cap = (int64_t)c->carve.max_items * G / (groups * 16);
+    c->split = choose_split(c, c->chunk_round_items[gi], slot_cap);
+
+    SpkvCu cu;
+    std::memcpy(cu.v, cu_seqlens, (size_t)(B + 1) * 4);
+    const uint16_t* kk = static_cast<const uint16_t*>(k);
+    const uint16_t* vv = static_cast<const uint16_t*>(v);
+    if (spkv_launch_decode_chunk(c->view, kk, vv, static_cast<const uint16_t*>(q),
+                                 static_cast<uint16_t*>(out), lse, sm_scale, c->split, cu, groups,
+                                 s) != hipSuccess)
+        return SPKV_E_HIP;
+    const hipError_t e = (n_max == 1)
+                             ? spkv_launch_append_step(c->view, kk, vv, util_logits, cu, s)
+                             : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, s);
+    if (e != hipSuccess) return SPKV_E_HIP;
+    commit_lengths(c, cu_seqlens);
+    if (n_max > 1) c->bound_is_loose = true;
     return SPKV_OK;
 }
 

@@ -66,6 +66,10 @@ hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* ou
 hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const uint16_t* q, uint16_t* out, float* lse,
                                    float sm_scale, SpkvSplit split, hipStream_t s);
+hipError_t spkv_launch_decode_chunk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                    const uint16_t* q, uint16_t* out, float* lse, float sm_scale,
+                                    SpkvSplit split, const SpkvCu& cu, int col_groups, hipStream_t s);
+int spkv_chunk_resident_items(int head_dim, int col_groups);
 // One-wave workgroups of the split-K kernel the current device holds at once (occupancy x
 // compute units); 0 if the runtime cannot tell.
 int spkv_split_resident_items(int head_dim);

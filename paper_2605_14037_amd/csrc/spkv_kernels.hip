@@ -574,12 +574,13 @@ __device__ __forceinline__ PairSplit pair_split(const SpkvView& v, int pair, Spk
 //   S[key][head]   = K[key][:] . Q[head][:]          2 x D/32 MFMA 16x16x32 (bf16 -> fp32)
 //   online softmax in the log2 domain (running max m, sum l), weights rounded to bf16
 //   O[d][head]    += V[key][d] * P[key][head]        D/16 MFMA 16x16x32
-// Keys r >= nvalid and the key r == masked_r (if >= 0) are excluded.
+// Bit e of `kill` excludes this lane's key r = 8 kc + e (for the column this lane holds);
+// `any_kill` is the wave-uniform "some lane has a bit set".
 template <int D>
 __device__ __forceinline__ void attend_half_page(const bf16x8 (&ka)[2][D / 32],
                                                  const bf16x8 (&va)[D / 16],
-                                                 const bf16x8 (&qb)[D / 32], int nvalid,
-                                                 int masked_r, int kc, float scale_log2e,
+                                                 const bf16x8 (&qb)[D / 32], unsigned kill,
+                                                 bool any_kill, float scale_log2e,
                                                  f32x4 (&acc)[D / 16], float& m, float& l) {
     constexpr int NS = D / 32, NB = D / 16;
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -595,12 +596,10 @@ __device__ __forceinline__ void attend_half_page(const bf16x8 (&ka)[2][D / 32],
         x[i] = s0[i] * scale_log2e;
         x[4 + i] = s1[i] * scale_log2e;
     }
-    if (nvalid < kHalfTokens || masked_r >= 0) {
+    if (any_kill) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int r = kc * 8 + e;
-            if (r >= nvalid || r == masked_r) x[e] = SPKV_NEG_INF;
-        }
+        for (int e = 0; e < 8; ++e)
+            if ((kill >> e) & 1u) x[e] = SPKV_NEG_INF;
     }
     float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
                      fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
@@ -719,8 +718,16 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
             for (int db = 0; db < NB; ++db) va[db] = load_stream_b128(vp + db * 512);
             // (Forcing all 16 loads ahead of the first MFMA with a scheduling barrier was
             // measured 2 % slower than the compiler's interleaving of loads and MFMAs.)
-            attend_half_page<D>(ka, va, qb, nvalid, (FUSED && hp == drop_hp) ? drop_r : -1, kc,
-                                scale_log2e, acc, m, l);
+            // keys past the valid length, and (fused step) the pair leaving the window
+            const int masked_r = (FUSED && hp == drop_hp) ? drop_r : -1;
+            const bool any_kill = nvalid < kHalfTokens || masked_r >= 0;
+            unsigned kill = 0u;
+            if (any_kill) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (kc * 8 + e >= nvalid || kc * 8 + e == masked_r) kill |= 1u << e;
+            }
+            attend_half_page<D>(ka, va, qb, kill, any_kill, scale_log2e, acc, m, l);
         }
     }
 
@@ -884,6 +891,274 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
         if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
     }
     if (g == 0) append_store<D>(v, pair, T, L, ar, tid, &s_page);
+}
+
+// ------------------------------------------------------- multi-token step (chunk)
+// Up to 16 new tokens per sequence attend in one pass (speculative-decoding verification,
+// prompt feed in 16-token chunks): the MFMA columns are (token i, head g) pairs, col =
+// i G + g, in NQ groups of 16, so every K/V tile is still read once per (sequence, KV head).
+// The cache is in the state before the chunk's append.  Long-term keys are available to
+// every token of the chunk (they are at least w + 1 positions behind).  A ring key of age
+// a (0 = oldest, position T - w) is inside the window of chunk token i iff a > i (the window
+// indicator 0 <= t - s < w with t = T + i); otherwise it counts only if its logit passes the
+// gate (Eq. 3-4).  The chunk's own keys (causal, always inside the window because the
+// chunk is not longer than the window) are added by spkv_chunk_combine.
+template <int D, int NQ>
+__global__ __launch_bounds__(64) void spkv_chunk_split(SpkvView v, const uint16_t* __restrict__ q,
+                                                       float scale_log2e, SpkvSplit sp, SpkvCu cu) {
+    constexpr int NS = D / 32, NB = D / 16;
+    const int pair = blockIdx.x / sp.slots;
+    const int j = blockIdx.x - pair * sp.slots;
+    const PairSplit ps = pair_split(v, pair, sp);
+    if (j == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.items;
+    if (j >= ps.items) return;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
+    if (n_tok == 0) return;
+    const int cols = n_tok * v.G;
+    const int hbase = ps.nhp / ps.items, hrem = ps.nhp - hbase * ps.items;
+    const int hp0 = j * hbase + min(j, hrem);
+    const int hp1 = hp0 + hbase + (j < hrem ? 1 : 0);
+    const int lane = threadIdx.x, kc = lane >> 4, n = lane & 15;
+
+    bf16x8 qb[NQ][NS];
+    int tok_of_col[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        const int col = c * 16 + n;
+        const int i = col / v.G, g = col - i * v.G;
+        tok_of_col[c] = i;
+        const uint16_t* qrow = q + ((size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g) * D + kc * 8;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            uint4 raw = {0u, 0u, 0u, 0u};
+            if (col < cols) raw = *reinterpret_cast<const uint4*>(qrow + sl * 32);
+            qb[c][sl] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    f32x4 acc[NQ][NB];
+    float m[NQ], l[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        m[c] = SPKV_NEG_INF;
+        l[c] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) acc[c][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+    const float* rl = v.ring_logit + (size_t)pair * v.w;
+    const int t_mod = ps.T % v.w;
+
+    int hp = hp0;
+    while (hp < hp1) {
+        const int pbase = hp >> 1;
+        const int my_page = pt[min(pbase + lane, v.pt_cap - 1)];
+        const int hp_end = min(hp1, (pbase + 64) << 1);
+        for (; hp < hp_end; ++hp) {
+            const uint16_t* base;
+            int nvalid;
+            const bool ring = hp >= ps.ghp;
+            if (!ring) {
+                const int page = __builtin_amdgcn_readlane(my_page, (hp >> 1) - pbase);
+                base = pool_page(v, page) + (hp & 1) * (2 * kHalfTokens * D);
+                nvalid = min(kHalfTokens, ps.L - hp * kHalfTokens);
+            } else {
+                const int r = hp - ps.ghp;
+                base = ring_page(v, pair, r >> 1) + (r & 1) * (2 * kHalfTokens * D);
+                nvalid = min(kHalfTokens, ps.Tw - r * kHalfTokens);
+            }
+            const uint16_t* kp = base + lane * 8;
+            const uint16_t* vp = base + kHalfTokens * D + lane * 8;
+            bf16x8 ka[2][NS], va[NB];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl)
+                    ka[t][sl] = load_stream_b128(kp + (t * (D / 8) + sl * 4) * 128);
+#pragma unroll
+            for (int db = 0; db < NB; ++db) va[db] = load_stream_b128(vp + db * 512);
+
+            // keys past the valid length (same for every column)
+            unsigned kill_len = 0u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (kc * 8 + e >= nvalid) kill_len |= 1u << e;
+            // ring keys: age and gate of this lane's eight keys
+            int age[8];
+            unsigned gate_ok = 0u;
+            if (ring) {
+                const int x0 = (hp - ps.ghp) * kHalfTokens + kc * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int x = x0 + e;
+                    age[e] = ps.T >= v.w ? (x - t_mod + v.w) % v.w : x + v.w - ps.T;
+                    if (kc * 8 + e < nvalid && rl[x] >= v.theta) gate_ok |= 1u << e;
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < NQ; ++c) {
+                unsigned kill = kill_len;
+                if (ring) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (!(age[e] > tok_of_col[c] || ((gate_ok >> e) & 1u))) kill |= 1u << e;
+                }
+                attend_half_page<D>(ka, va, qb[c], kill, ring || nvalid < kHalfTokens, scale_log2e,
+                                    acc[c], m[c], l[c]);
+            }
+        }
+    }
+
+    const size_t slot = (size_t)pair * sp.slots + j;
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        float lc = l[c];
+        lc += __shfl_xor(lc, 16);
+        lc += __shfl_xor(lc, 32);
+        const int col = c * 16 + n;
+        if (col < cols) {
+            float* pa = v.part_acc + ((slot * (NQ * 16) + col) * D) + kc * 4;
+#pragma unroll
+            for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[c][db];
+            if (kc == 0) {
+                float* pm = v.part_ml + (slot * (NQ * 16) + col) * 2;
+                pm[0] = m[c];
+                pm[1] = lc;
+            }
+        }
+    }
+}
+
+// Merge for one (pair, column = token i, head g): the split-K partials plus one term per
+// chunk token j <= i taken from the caller's k / v rows (score q_i . k_j in fp32, sum 1,
+// value v_j); bf16 output row cu[b] + i.  The waves share the partials and the chunk
+// tokens round-robin and meet in LDS, as in spkv_decode_combine.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_chunk_combine(SpkvView v, const uint16_t* __restrict__ q,
+                                                          const uint16_t* __restrict__ k_new,
+                                                          const uint16_t* __restrict__ v_new,
+                                                          uint16_t* __restrict__ out,
+                                                          float* __restrict__ lse, float scale_log2e,
+                                                          SpkvSplit sp, SpkvCu cu, int cstride) {
+    constexpr int E = D / 64;
+    const int pair = blockIdx.x / cstride, col = blockIdx.x - pair * cstride;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
+    if (col >= n_tok * v.G) return;
+    const int i = col / v.G, g = col - i * v.G;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int items = v.pair_items[pair];
+    const size_t slot0 = (size_t)pair * sp.slots;
+    __shared__ float s_m[4];
+    __shared__ float s_den[4];
+    __shared__ float s_acc[4][D];
+
+    float mw = SPKV_NEG_INF, den = 0.f, num[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) num[e] = 0.f;
+#pragma unroll 8
+    for (int it = wave; it < items; it += 4) {
+        const size_t idx = (slot0 + it) * cstride + col;
+        const float mi = v.part_ml[idx * 2], li = v.part_ml[idx * 2 + 1];
+        float a[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) a[e] = v.part_acc[idx * D + lane * E + e];
+        const float m_new = fmaxf(mw, mi);
+        const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;
+        const float so = __builtin_amdgcn_exp2f(mw - m_ref), si = __builtin_amdgcn_exp2f(mi - m_ref);
+        den = den * so + li * si;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] = num[e] * so + a[e] * si;
+        mw = m_new;
+    }
+    // the chunk's own tokens 0..i
+    const size_t q_row = ((size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g) * D;
+    float qf[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+        qf[e] = __builtin_bit_cast(float, (unsigned)q[q_row + lane * E + e] << 16);
+    for (int jt = wave; jt <= i; jt += 4) {
+        const size_t kv_row = ((size_t)(row0 + jt) * v.Hkv + h) * D;
+        float dot = 0.f, vj[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            dot += qf[e] * __builtin_bit_cast(float, (unsigned)k_new[kv_row + lane * E + e] << 16);
+            vj[e] = __builtin_bit_cast(float, (unsigned)v_new[kv_row + lane * E + e] << 16);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+        const float mi = dot * scale_log2e;
+        const float m_new = fmaxf(mw, mi);
+        const float so = __builtin_amdgcn_exp2f(mw - m_new), si = __builtin_amdgcn_exp2f(mi - m_new);
+        den = den * so + si;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] = num[e] * so + vj[e] * si;
+        mw = m_new;
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
+    if (lane == 0) {
+        s_m[wave] = mw;
+        s_den[wave] = den;
+    }
+    __syncthreads();
+    if (tid < D) {
+        const float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));   // wave 0 has token 0
+        float nsum = 0.f, dsum = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) {
+            const float sc = __builtin_amdgcn_exp2f(s_m[wv] - M);
+            nsum += s_acc[wv][tid] * sc;
+            dsum += s_den[wv] * sc;
+        }
+        const size_t o = (size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g;
+        const __bf16 r = (__bf16)(nsum / dsum);
+        out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
+        if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
+    }
+}
+
+template <int D, int NQ>
+static hipError_t launch_chunk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                               const uint16_t* q, uint16_t* out, float* lse, float scale_log2e,
+                               SpkvSplit sp, const SpkvCu& cu, hipStream_t s) {
+    const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
+    spkv_chunk_split<D, NQ><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp, cu);
+    spkv_chunk_combine<D><<<dim3(v.n_pairs * NQ * 16), dim3(256), 0, s>>>(
+        v, q, k, vv, out, lse, scale_log2e, sp, cu, NQ * 16);
+    return hipGetLastError();
+}
+
+hipError_t spkv_launch_decode_chunk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                    const uint16_t* q, uint16_t* out, float* lse, float sm_scale,
+                                    SpkvSplit sp, const SpkvCu& cu, int col_groups, hipStream_t s) {
+    const float sl = sm_scale * 1.4426950408889634f;
+    if (v.D == 128) {
+        if (col_groups <= 1) return launch_chunk<128, 1>(v, k, vv, q, out, lse, sl, sp, cu, s);
+        if (col_groups == 2) return launch_chunk<128, 2>(v, k, vv, q, out, lse, sl, sp, cu, s);
+        return launch_chunk<128, 4>(v, k, vv, q, out, lse, sl, sp, cu, s);
+    }
+    if (col_groups <= 1) return launch_chunk<64, 1>(v, k, vv, q, out, lse, sl, sp, cu, s);
+    if (col_groups == 2) return launch_chunk<64, 2>(v, k, vv, q, out, lse, sl, sp, cu, s);
+    return launch_chunk<64, 4>(v, k, vv, q, out, lse, sl, sp, cu, s);
+}
+
+int spkv_chunk_resident_items(int head_dim, int col_groups) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    hipError_t e;
+    if (head_dim == 128) {
+        if (col_groups <= 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<128, 1>, 64, 0);
+        else if (col_groups == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<128, 2>, 64, 0);
+        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<128, 4>, 64, 0);
+    } else {
+        if (col_groups <= 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<64, 1>, 64, 0);
+        else if (col_groups == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<64, 2>, 64, 0);
+        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<64, 4>, 64, 0);
+    }
+    if (e != hipSuccess || per_cu <= 0 || cus <= 0) return 0;
+    return per_cu * cus;
 }
 
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,

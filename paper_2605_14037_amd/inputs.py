@@ -143,9 +143,11 @@ class TokenStream:
         logits = self._randn(total, wl.n_kv_heads) + self.mu[seq_of_row]
         return k, v, logits.contiguous(), cu
 
-    def next_query(self):
+    def next_query(self, rows=None):
+        """q bf16 [rows, H_q, D]; rows defaults to one per sequence."""
         wl = self.wl
-        q = self._randn(wl.batch, wl.n_q_heads, wl.head_dim) * self.q_gain
+        rows = wl.batch if rows is None else int(rows)
+        q = self._randn(rows, wl.n_q_heads, wl.head_dim) * self.q_gain
         return q.to(torch.bfloat16)
 
 

@@ -440,3 +440,61 @@ def test_utility_predictor(n, dm, dh, Hk):
         H.check_output(out, oracle.decode(to_numpy_f32(q))[0])
         H.check_state(cache, oracle, wl)
         cache.close()
+
+
+# ---------------------------------------------------- multi-token step (chunks <= 16)
+def _run_chunks(wl, chunk_counts, chunk_prefill=4096, q_gain=1.0):
+    stream = TokenStream(wl, device="cuda", q_gain=q_gain)
+    cache = H.make_cache(wl, extra_context=sum(max(c) for c in chunk_counts) + 8)
+    oracle = H.make_oracle(wl)
+    H.prefill(cache, oracle, stream, wl, chunk_prefill)
+    for counts in chunk_counts:
+        k, v, f, cu = stream.next_tokens(counts)
+        q = stream.next_query(rows=sum(counts))
+        res = cache.decode_chunk(k, v, f, q, cu, want_lse=True)
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        if sum(counts):
+            out, lse = res
+            ref_out, ref_lse = oracle.decode_chunk(to_numpy_f32(q), counts)
+            H.check_output(out, ref_out, f"chunk {counts}")
+            H.check_lse(lse, ref_lse, f"chunk {counts}")
+        H.check_state(cache, oracle, wl, label=f"chunk {counts}")
+    cache.close()
+
+
+@pytest.mark.parametrize("ctx,w", [(0, 128), (0, 16), (5, 128), (120, 128), (128, 128), (129, 128),
+                                   (300, 16), (300, 17), (700, 100), (1000, 512), (64, 33)])
+def test_chunk_window_edges(ctx, w):
+    wl = small_workload("cedge", 2, 8, 2, 64, [ctx, ctx // 2], [[0.5, 0.2]], window=w,
+                        seed=ctx * 100 + w + 3)
+    n = min(16, w)
+    _run_chunks(wl, [[n, n], [1, n], [n, 0], [3, 7 if w >= 7 else 1], [n, n], [0, 0], [n, 1], [n, n]])
+
+
+@pytest.mark.parametrize("D,Hq,Hkv,n", [(128, 32, 8, 16), (128, 32, 8, 4), (128, 32, 8, 7),
+                                        (64, 8, 8, 16), (64, 4, 2, 16), (128, 16, 2, 8),
+                                        (128, 16, 1, 4), (64, 6, 2, 16)])
+def test_chunk_head_shapes(D, Hq, Hkv, n):
+    """Group sizes 1, 2, 3, 4, 8, 16: one, two or four MFMA column groups."""
+    wl = small_workload("cheads", 3, Hq, Hkv, D, [900, 130, 2500], 0.3, seed=D + Hq + n)
+    _run_chunks(wl, [[n, n, n], [n, 1, n // 2], [n, n, n]])
+
+
+def test_chunk_equals_single_steps_state_and_peaked_scores():
+    wl = small_workload("cpeak", 2, 8, 2, 128, [3000, 1000], 0.25, seed=19)
+    _run_chunks(wl, [[16, 16], [16, 9], [2, 16]], q_gain=4.0)
+
+
+def test_chunk_rejects_long_chunks():
+    cache = spkv.SPKVCache(1, 32, 2, 64, 256, 256, window=8)      # group size 16
+    wl = small_workload("cbad", 1, 32, 2, 64, [0], 0.5, window=8, seed=1)
+    stream = TokenStream(wl, device="cuda")
+    for n in (17, 9, 5):          # > 16 tokens; > window; 5 * 16 > 64 columns
+        k, v, f, cu = stream.next_tokens([n])
+        with pytest.raises(spkv.SPKVError) as e:
+            cache.decode_chunk(k, v, f, stream.next_query(rows=n), cu)
+        assert e.value.code == -1
+    k, v, f, cu = stream.next_tokens([4])
+    cache.decode_chunk(k, v, f, stream.next_query(rows=4), cu)
+    assert cache.stats().total_tokens == 4
+    cache.close()

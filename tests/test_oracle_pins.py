@@ -397,3 +397,60 @@ def test_utility_logits_against_torch_modules_and_closed_forms():
     w2h = np.zeros((H, dh)); w2h[2, 1] = 3.0
     got = utility_logits(x1, w1h, None, w2h, None)
     assert abs(got[0, 2] - 3.0 * 2.0 / (1.0 + math.exp(-2.0))) < 1e-14 and got[0, 0] == 0 and got[0, 1] == 0
+
+
+# ------------------------------------------------ multi-token step (chunk of queries)
+def _sdpa_rows(q_rows, k, v, gate, w, scale, Hq, Hkv, first_row):
+    """Rows first_row.. of the full masked attention of one sequence by torch's fp64 SDPA
+    (mask as in the paper's listing: window -> 0, causal non-window -> gate, future -> -inf)."""
+    T, D = k.shape[0], k.shape[2]
+    G = Hq // Hkv
+    kt = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    vt = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+    qt = torch.zeros(1, Hq, T, D, dtype=torch.float64)
+    qt[0, :, first_row:, :] = torch.from_numpy(q_rows).permute(1, 0, 2)
+    qi = torch.arange(T)[:, None]
+    ki = torch.arange(T)[None, :]
+    causal = ki <= qi
+    in_window = causal & ((qi - ki) < w)
+    gt = torch.from_numpy(gate).T.repeat_interleave(G, dim=0)
+    mask = (in_window[None] | (causal[None] & gt[:, None, :]))[None]
+    o = F.scaled_dot_product_attention(qt, kt, vt, attn_mask=mask, scale=scale)
+    return o[0, :, first_row:, :].permute(1, 0, 2).numpy()
+
+
+def test_decode_chunk_matches_sdpa_rows_and_single_steps():
+    rng = np.random.default_rng(29)
+    B, Hq, Hkv, D, w, tau = 2, 4, 2, 8, 5, 0.5
+    lens, counts = [23, 9], [7, 9]                 # second sequence: the chunk is the whole sequence
+    q_all, k, v, f, cu = _random_problem(rng, B, Hq, Hkv, D, lens, mu=-0.3)
+    o = _build(SPKVOracle, B, Hq, Hkv, D, w, tau, k, v, f, cu)
+    q = rng.standard_normal((sum(counts), Hq, D))
+    out, lse = o.decode_chunk(q, counts)
+    row = 0
+    for b in range(B):
+        sl = slice(cu[b], cu[b + 1])
+        sig = 1.0 / (1.0 + np.exp(-f[sl].astype(np.float64)))
+        ref = _sdpa_rows(q[row:row + counts[b]], k[sl], v[sl], sig >= tau, w, 1.0 / math.sqrt(D),
+                         Hq, Hkv, lens[b] - counts[b])
+        np.testing.assert_allclose(out[row:row + counts[b]], ref, rtol=1e-10, atol=1e-12)
+        row += counts[b]
+    # the same outputs from one-token-at-a-time appends and decodes
+    inc = SPKVOracle(B, Hq, Hkv, D, window=w, tau=tau, store_dtype=np.float64)
+    pre = [lens[b] - counts[b] for b in range(B)]
+    rows = [r for b in range(B) for r in range(cu[b], cu[b] + pre[b])]
+    inc.append(k[rows], v[rows], f[rows], [0, pre[0], pre[0] + pre[1]])
+    qoff = [0, counts[0]]
+    for i in range(max(counts)):
+        act = [b for b in range(B) if i < counts[b]]
+        rows = [cu[b] + pre[b] + i for b in act]
+        c = [0] + list(np.cumsum([1 if b in act else 0 for b in range(B)]))
+        inc.append(k[rows], v[rows], f[rows], c)
+        qq = np.zeros((B, Hq, D))
+        for b in act:
+            qq[b] = q[qoff[b] + i]
+        if all(inc.seq_len(b) > 0 for b in range(B)):
+            o1, l1 = inc.decode(qq)
+            for b in act:
+                np.testing.assert_allclose(o1[b], out[qoff[b] + i], rtol=1e-12, atol=1e-13)
+                np.testing.assert_allclose(l1[b], lse[qoff[b] + i], rtol=1e-12, atol=1e-13)
