@@ -14,8 +14,26 @@ SOURCES = ["spkv_api.hip", "spkv_kernels.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage",
 ]
+
+# Waves per SIMD the decode kernels are expected to reach (registers decide it, and the
+# register count depends on how the compiler schedules loads against MFMAs): the library
+# adapts its work-item count to whatever the runtime reports, but a drop costs bandwidth.
+EXPECTED_OCCUPANCY = {"spkv_decode_splitILi128ELb0": 3, "spkv_decode_splitILi128ELb1": 3}
+
+
+def _check_occupancy(remarks: str) -> list:
+    import re
+    warnings = []
+    blocks = re.split(r"remark: Function Name: ", remarks)
+    for blk in blocks[1:]:
+        name = blk.split()[0]
+        m = re.search(r"Occupancy \[waves/SIMD\]: (\d+)", blk)
+        for key, want in EXPECTED_OCCUPANCY.items():
+            if key in name and m and int(m.group(1)) < want:
+                warnings.append(f"{name}: occupancy {m.group(1)} waves/SIMD, expected {want}")
+    return warnings
 
 
 def build(verbose: bool = False) -> str:
@@ -25,9 +43,12 @@ def build(verbose: bool = False) -> str:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    lines = [l for l in res.stderr.splitlines() if noise not in l]
+    err = "\n".join(l for l in lines if "remark:" not in l and "-Rpass-analysis" not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
+    for w in _check_occupancy(res.stderr):
+        print("WARNING:", w, flush=True)
     if verbose and err.strip():
         print(err)
     return LIB

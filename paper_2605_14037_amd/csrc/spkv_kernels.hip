@@ -706,6 +706,15 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
                 base = ring_page(v, pair, r >> 1) + (r & 1) * (2 * kHalfTokens * D);
                 nvalid = min(kHalfTokens, ps.Tw - r * kHalfTokens);
             }
+            // keys past the valid length, and (fused step) the pair leaving the window
+            const int masked_r = (FUSED && hp == drop_hp) ? drop_r : -1;
+            const bool any_kill = nvalid < kHalfTokens || masked_r >= 0;
+            unsigned kill = 0u;
+            if (any_kill) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (kc * 8 + e >= nvalid || kc * 8 + e == masked_r) kill |= 1u << e;
+            }
             const uint16_t* kp = base + lane * 8;
             const uint16_t* vp = base + kHalfTokens * D + lane * 8;
             bf16x8 ka[2][NS], va[NB];
@@ -718,15 +727,6 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
             for (int db = 0; db < NB; ++db) va[db] = load_stream_b128(vp + db * 512);
             // (Forcing all 16 loads ahead of the first MFMA with a scheduling barrier was
             // measured 2 % slower than the compiler's interleaving of loads and MFMAs.)
-            // keys past the valid length, and (fused step) the pair leaving the window
-            const int masked_r = (FUSED && hp == drop_hp) ? drop_r : -1;
-            const bool any_kill = nvalid < kHalfTokens || masked_r >= 0;
-            unsigned kill = 0u;
-            if (any_kill) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (kc * 8 + e >= nvalid || kc * 8 + e == masked_r) kill |= 1u << e;
-            }
             attend_half_page<D>(ka, va, qb, kill, any_kill, scale_log2e, acc, m, l);
         }
     }
@@ -967,17 +967,6 @@ __global__ __launch_bounds__(64) void spkv_chunk_split(SpkvView v, const uint16_
                 base = ring_page(v, pair, r >> 1) + (r & 1) * (2 * kHalfTokens * D);
                 nvalid = min(kHalfTokens, ps.Tw - r * kHalfTokens);
             }
-            const uint16_t* kp = base + lane * 8;
-            const uint16_t* vp = base + kHalfTokens * D + lane * 8;
-            bf16x8 ka[2][NS], va[NB];
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int sl = 0; sl < NS; ++sl)
-                    ka[t][sl] = load_stream_b128(kp + (t * (D / 8) + sl * 4) * 128);
-#pragma unroll
-            for (int db = 0; db < NB; ++db) va[db] = load_stream_b128(vp + db * 512);
-
             // keys past the valid length (same for every column)
             unsigned kill_len = 0u;
 #pragma unroll
@@ -995,6 +984,17 @@ __global__ __launch_bounds__(64) void spkv_chunk_split(SpkvView v, const uint16_
                     if (kc * 8 + e < nvalid && rl[x] >= v.theta) gate_ok |= 1u << e;
                 }
             }
+            const uint16_t* kp = base + lane * 8;
+            const uint16_t* vp = base + kHalfTokens * D + lane * 8;
+            bf16x8 ka[2][NS], va[NB];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl)
+                    ka[t][sl] = load_stream_b128(kp + (t * (D / 8) + sl * 4) * 128);
+#pragma unroll
+            for (int db = 0; db < NB; ++db) va[db] = load_stream_b128(vp + db * 512);
+
 #pragma unroll
             for (int c = 0; c < NQ; ++c) {
                 unsigned kill = kill_len;
