@@ -176,6 +176,29 @@ int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const f
                       const void* q, const int32_t* cu_seqlens, void* out, float* lse,
                       float sm_scale, void* stream);
 
+/* Prefill attention: the multi-token step without a length limit.  Every sequence b
+ * receives n_b >= 0 new tokens and gets the attention output of each, token i (position
+ * T_b + i) attending to the positions s <= T_b + i inside its window or passing the gate
+ * (Eq. 3-5; causal inside the chunk), and the cache afterwards holds the chunk exactly as
+ * after spkv_append.  With this call a prompt both fills the cache and gets its own
+ * attention, in chunks of any size (the chunked-prefill protocol of the evaluation section;
+ * gated-off keys outside the window are never read, the block skipping of Sec. 2.2 at the
+ * granularity of single keys).
+ *   k, v, util_logits, q, cu_seqlens, out, lse, sm_scale   as for spkv_decode_chunk
+ *   workspace     device memory, 256-byte aligned, at least
+ *                 spkv_prefill_workspace_bytes(cache, max_b n_b, sum_b n_b) bytes; contents
+ *                 need not survive between calls; caller-owned
+ * Work is cut per (sequence, KV head) into blocks of 64 / group-size consecutive tokens, one
+ * wavefront each; for chunks of at most SPKV_MAX_CHUNK_TOKENS tokens on a long cache
+ * spkv_decode_chunk (split over the list) is the faster call.
+ * Errors as for spkv_append; SPKV_E_INVAL if the workspace is too small. */
+size_t spkv_prefill_workspace_bytes(const spkv_cache_t* cache, int32_t max_tokens_per_sequence,
+                                    int64_t max_total_tokens);
+int spkv_prefill_attention(spkv_cache_t* cache, const void* k, const void* v,
+                           const float* util_logits, const void* q, const int32_t* cu_seqlens,
+                           void* out, float* lse, float sm_scale, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
 /* Forget sequence b (for example when its request has finished): its window and long-term
  * entries are dropped, its pages return to the pool for reuse by any sequence, and slot b
  * holds an empty sequence that can be appended to again.  (The paper's cache manager grows

@@ -235,11 +235,12 @@ class SPKVOracle:
         lse = m + np.log(denom)
         return out, lse
 
-    def decode_chunk(self, q, counts):
+    def decode_chunk(self, q, counts, rows=None):
         """Outputs for the newest counts[b] positions of every sequence, each attending as if
         it had been decoded right after its own append (causal inside the chunk): the rows
         T - n .. T - 1 of the masked attention of the listing appendix.  q: [sum(counts),
-        H_q, D] packed by sequence in position order.  Returns (out, lse) in fp64."""
+        H_q, D] packed by sequence in position order.  Returns (out, lse) in fp64.  rows: if
+        given, only these packed rows are computed (the others stay zero)."""
         q = np.asarray(q).astype(np.float64)
         total = int(sum(counts))
         if q.shape != (total, self.Hq, self.D):
@@ -253,6 +254,9 @@ class SPKVOracle:
                 raise ValueError("chunk longer than the sequence")
             for i in range(n):
                 t = T - n + i
+                if rows is not None and row not in rows:
+                    row += 1
+                    continue
                 for h in range(self.Hkv):
                     K = self._k(b)[:t + 1, h, :].astype(np.float64)
                     V = self._v(b)[:t + 1, h, :].astype(np.float64)

@@ -20,7 +20,8 @@ MAX_BATCH, PAGE_TOKENS = 512, 64
 
 EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_reset",
-    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
+    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk",
+    "spkv_prefill_workspace_bytes", "spkv_prefill_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
     "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
@@ -84,6 +85,10 @@ def load_library():
     lib.spkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, vp]
     lib.spkv_decode_chunk.restype = C.c_int
     lib.spkv_decode_chunk.argtypes = [vp, vp, vp, vp, vp, P(i32), vp, vp, f32, vp]
+    lib.spkv_prefill_workspace_bytes.restype = C.c_size_t
+    lib.spkv_prefill_workspace_bytes.argtypes = [vp, i32, i64]
+    lib.spkv_prefill_attention.restype = C.c_int
+    lib.spkv_prefill_attention.argtypes = [vp, vp, vp, vp, vp, P(i32), vp, vp, f32, vp, C.c_size_t, vp]
     lib.spkv_cache_release_sequence.restype = C.c_int
     lib.spkv_cache_release_sequence.argtypes = [vp, i32, vp]
     lib.spkv_utility_logits.restype = C.c_int
@@ -273,6 +278,47 @@ class SPKVCache:
         lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
         _check(self.lib.spkv_decode_chunk(self.handle, kp, vp, fp, qp, cu, op, lp, float(sm_scale),
                                           _stream()), "spkv_decode_chunk")
+        return (out, lse) if lse is not None else out
+
+    def prefill_workspace_bytes(self, max_tokens_per_sequence, max_total_tokens):
+        return int(self.lib.spkv_prefill_workspace_bytes(self.handle, int(max_tokens_per_sequence),
+                                                         int(max_total_tokens)))
+
+    def prefill_attention(self, k, v, util_logits, q, cu_seqlens, workspace=None, out=None,
+                          lse=None, sm_scale=0.0, want_lse=False):
+        """Append any number of tokens per sequence and return each one's attention output
+        (spkv_prefill_attention).  workspace: uint8 device tensor of at least
+        prefill_workspace_bytes(max n_b, sum n_b) bytes; allocated here if None."""
+        cfg = self.cfg
+        cu = cu_seqlens if isinstance(cu_seqlens, C.Array) else self.make_cu(cu_seqlens)
+        total = cu[cfg.batch]
+        if total == 0:
+            _check(self.lib.spkv_prefill_attention(self.handle, None, None, None, None, cu, None,
+                                                   None, float(sm_scale), None, 0, _stream()),
+                   "spkv_prefill_attention")
+            return None
+        kv_shape = (total, cfg.n_kv_heads, cfg.head_dim)
+        shape = (total, cfg.n_q_heads, cfg.head_dim)
+        kp = _dev_ptr(k, torch.bfloat16, kv_shape, "k")
+        vp = _dev_ptr(v, torch.bfloat16, kv_shape, "v")
+        fp = _dev_ptr(util_logits, torch.float32, kv_shape[:2], "util_logits")
+        qp = _dev_ptr(q, torch.bfloat16, shape, "q")
+        if workspace is None:
+            n_max = max(cu[b + 1] - cu[b] for b in range(cfg.batch))
+            workspace = torch.empty(self.prefill_workspace_bytes(n_max, total), dtype=torch.uint8,
+                                    device=q.device)
+        if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous uint8 device tensor")
+        if out is None:
+            out = torch.empty(shape, dtype=torch.bfloat16, device=q.device)
+        op = _dev_ptr(out, torch.bfloat16, shape, "out")
+        if lse is None and want_lse:
+            lse = torch.empty(shape[:2], dtype=torch.float32, device=q.device)
+        lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
+        _check(self.lib.spkv_prefill_attention(self.handle, kp, vp, fp, qp, cu, op, lp,
+                                               float(sm_scale), workspace.data_ptr(),
+                                               workspace.numel(), _stream()),
+               "spkv_prefill_attention")
         return (out, lse) if lse is not None else out
 
     # ---- bookkeeping

@@ -355,7 +355,7 @@ int spkv_append(spkv_cache_t* c, const void* k, const void* v, const float* util
     const uint16_t* vv = static_cast<const uint16_t*>(v);
     hipError_t e = (n_max == 1)
                        ? spkv_launch_append_step(c->view, kk, vv, util_logits, cu, s)
-                       : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, s);
+                       : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, nullptr, s);
     if (e != hipSuccess) return SPKV_E_HIP;
     commit_lengths(c, cu_seqlens);
     if (n_max > 1) c->bound_is_loose = true;
@@ -471,10 +471,61 @@ int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float
         return SPKV_E_HIP;
     const hipError_t e = (n_max == 1)
                              ? spkv_launch_append_step(c->view, kk, vv, util_logits, cu, s)
-                             : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, s);
+                             : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, nullptr, s);
     if (e != hipSuccess) return SPKV_E_HIP;
     commit_lengths(c, cu_seqlens);
     if (n_max > 1) c->bound_is_loose = true;
+    return SPKV_OK;
+}
+
+size_t spkv_prefill_workspace_bytes(const spkv_cache_t* c, int32_t max_tokens_per_sequence,
+                                    int64_t max_total_tokens) {
+    if (c == nullptr || max_tokens_per_sequence <= 0 || max_total_tokens <= 0) return 0;
+    const size_t prefix = align_up((size_t)max_total_tokens * c->cfg.n_kv_heads * 4);
+    const size_t shp = ((size_t)c->cfg.window + max_tokens_per_sequence + kHalfTokens - 1) / kHalfTokens;
+    const size_t half_bytes = (size_t)2 * kHalfTokens * c->cfg.head_dim * 2;
+    return prefix + (size_t)c->carve.n_pairs * shp * half_bytes;
+}
+
+int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
+                           const void* q, const int32_t* cu_seqlens, void* out, float* lse,
+                           float sm_scale, void* workspace, size_t workspace_bytes, void* stream) {
+    if (c == nullptr || cu_seqlens == nullptr) return SPKV_E_INVAL;
+    const int B = c->cfg.batch;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (cu_seqlens[0] != 0) return SPKV_E_INVAL;
+    int n_max = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t n = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+        if (n < 0) return SPKV_E_INVAL;
+        n_max = std::max<int64_t>(n_max, n);
+    }
+    if (n_max == 0) return SPKV_OK;
+    if (k == nullptr || v == nullptr || util_logits == nullptr || q == nullptr || out == nullptr ||
+        workspace == nullptr)
+        return SPKV_E_INVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(util_logits) || !aligned16(q) ||
+        !aligned16(out) || (lse != nullptr && !aligned16(lse)) ||
+        (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return SPKV_E_INVAL;
+    const size_t need = spkv_prefill_workspace_bytes(c, n_max, cu_seqlens[B]);
+    if (need == 0 || workspace_bytes < need) return SPKV_E_INVAL;
+    if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
+    const int rc = reserve_capacity(c, cu_seqlens, s);
+    if (rc != SPKV_OK) return rc;
+
+    SpkvCu cu;
+    std::memcpy(cu.v, cu_seqlens, (size_t)(B + 1) * 4);
+    char* ws = static_cast<char*>(workspace);
+    const size_t prefix_bytes = align_up((size_t)cu_seqlens[B] * c->cfg.n_kv_heads * 4);
+    const int shp = (c->cfg.window + n_max + kHalfTokens - 1) / kHalfTokens;
+    if (spkv_launch_prefill(c->view, static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
+                            util_logits, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
+                            lse, sm_scale, cu, n_max, reinterpret_cast<uint16_t*>(ws + prefix_bytes),
+                            reinterpret_cast<int32_t*>(ws), shp, s) != hipSuccess)
+        return SPKV_E_HIP;
+    commit_lengths(c, cu_seqlens);
+    c->bound_is_loose = true;
     return SPKV_OK;
 }
 

@@ -50,8 +50,10 @@ hipError_t spkv_launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const SpkvCu& cu, hipStream_t s);
+// prefix: null, or where the prefill attention wants the per-token long-term prefix counts.
 hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
-                                   const float* f, const SpkvCu& cu, int n_max, hipStream_t s);
+                                   const float* f, const SpkvCu& cu, int n_max, int32_t* prefix,
+                                   hipStream_t s);
 // Split of every (seq, head) list into work items, chosen by the host per decode call:
 // a pair with n half-pages (32 keys each) is cut evenly into min(ceil(n / hp_per_item),
 // slots) items; item j of pair p owns partial slot p * slots + j.
@@ -70,6 +72,13 @@ hipError_t spkv_launch_decode_chunk(const SpkvView& v, const uint16_t* k, const 
                                     const uint16_t* q, uint16_t* out, float* lse, float sm_scale,
                                     SpkvSplit split, const SpkvCu& cu, int col_groups, hipStream_t s);
 int spkv_chunk_resident_items(int head_dim, int col_groups);
+// Prefill attention of n <= n_max new tokens per sequence plus their append.  stage:
+// n_pairs * shp staging half-pages (shp >= ceil((w + n_max) / 32)); prefix: one int32 per
+// (new token, KV head).
+hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                               const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                               float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
+                               int32_t* prefix, int shp, hipStream_t s);
 // One-wave workgroups of the split-K kernel the current device holds at once (occupancy x
 // compute units); 0 if the runtime cannot tell.
 int spkv_split_resident_items(int head_dim);

@@ -294,8 +294,15 @@ __device__ __forceinline__ int block_excl_scan(int x, int* s_w, int& total) {
 // Stage 2: one workgroup per pair.  Counts the pairs leaving the ring that are kept,
 // turns the segment counts into offsets, allocates every page the call needs with one
 // allocation per page, publishes the new lengths, then moves the kept ring rows.
+//
+// prefix (may be null; used by the prefill attention): for the new token i of the call, at
+// position t = T_old + i, prefix[(row of token i) * H_kv + h] = number of long-term entries,
+// after this call, whose position is <= t - w -- the entries available to query t outside
+// its window (the list is in ascending position, so they are a prefix of it).  Stage 2
+// writes the tokens whose t - w is a ring position, stage 3 the others; tokens with
+// t - w < 0 get no entry (their count is 0).
 template <int D>
-__global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
+__global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int32_t* prefix) {
     const int pair = blockIdx.x;
     const int b = pair / v.Hkv;
     const int n = cu.v[b + 1] - cu.v[b];
@@ -384,6 +391,10 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
         int tot;
         const int rank = block_excl_scan(flag ? 1 : 0, s_w, tot);
         if (flag) s_list[rank] = (uint16_t)tid;
+        if (prefix != nullptr && idx < nr) {
+            const int i = r0 + idx + v.w - T_old;      // the new token whose t - w is this position
+            prefix[((size_t)cu.v[b] + i) * v.Hkv + (pair - b * v.Hkv)] = L_old + done + rank + (flag ? 1 : 0);
+        }
         __syncthreads();
         const int c = lane & 15;
         for (int rb = wave * 4; rb < tot; rb += 16) {
@@ -418,7 +429,8 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu) {
 template <int D>
 __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint16_t* __restrict__ k,
                                                          const uint16_t* __restrict__ vv,
-                                                         const float* __restrict__ f, SpkvCu cu) {
+                                                         const float* __restrict__ f, SpkvCu cu,
+                                                         int32_t* prefix) {
     const int pair = blockIdx.y, seg = blockIdx.x;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int row0 = cu.v[b];
@@ -446,6 +458,9 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
         total += s_cnt[i];
     }
     if (ev) s_list[woff + mbcnt64(mask)] = (uint16_t)tid;
+    if (prefix != nullptr && j < n_ev)       // token j leaves the window of token j + w
+        prefix[((size_t)row0 + j + v.w) * v.Hkv + h] =
+            bi.new_base + v.seg_count[(size_t)pair * v.n_seg_cap + seg] + woff + mbcnt64(mask) + (ev ? 1 : 0);
     __syncthreads();
 
     if (total > 0) {
@@ -531,15 +546,16 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
 }
 
 hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
-                                   const float* f, const SpkvCu& cu, int n_max, hipStream_t s) {
+                                   const float* f, const SpkvCu& cu, int n_max, int32_t* prefix,
+                                   hipStream_t s) {
     const int segs_all = (n_max + kSegTokens - 1) / kSegTokens;
     spkv_bulk_count<<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, f, cu);
     if (v.D == 128) {
-        spkv_bulk_ring<128><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu);
-        spkv_bulk_scatter<128><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu);
+        spkv_bulk_ring<128><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix);
+        spkv_bulk_scatter<128><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
     } else {
-        spkv_bulk_ring<64><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu);
-        spkv_bulk_scatter<64><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu);
+        spkv_bulk_ring<64><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix);
+        spkv_bulk_scatter<64><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
     }
     return hipGetLastError();
 }
@@ -1159,6 +1175,333 @@ int spkv_chunk_resident_items(int head_dim, int col_groups) {
     }
     if (e != hipSuccess || per_cu <= 0 || cus <= 0) return 0;
     return per_cu * cus;
+}
+
+// ------------------------------------------------- prefill attention (any chunk length)
+// n new tokens per sequence attend causally with the availability rule of Eq. 3-4 and are
+// appended, in four steps:
+//   1. spkv_prefill_stage copies the window as it stands (ring, un-rotated into position
+//      order) and the n new K/V rows into staging half-pages in the page layout: staging
+//      row u holds position T_old - w + u, so query i (position T_old + i) has exactly the
+//      rows i < u <= i + w in its window.
+//   2. the bulk append runs and records, per new token, how long a prefix of the long-term
+//      list lies at least w behind it (see spkv_bulk_ring).
+//   3. spkv_prefill_attend: one wave per block of tb = 64 / G consecutive tokens of one
+//      (sequence, KV head) -- 64 MFMA columns (token, head) in four groups of 16 -- walks
+//      the long-term prefix and then the staging rows of the block's windows, one online
+//      softmax per column, and writes the normalised bf16 rows.  No partials, no combine.
+// Window keys and long-term entries are disjoint (positions > t - w against <= t - w), so
+// every available key is counted once.
+
+struct SpkvPrefill {
+    uint16_t* stage;     // [n_pairs][shp] half-pages
+    int32_t*  prefix;    // [total tokens][H_kv]
+    int32_t   shp;       // staging half-pages per pair
+    int32_t   tb;        // tokens per block (64 / G)
+    int32_t   nblk;      // workgroups (spans of 4 tb tokens) per pair in the grid
+    int32_t   pin_xcd;   // 1: all blocks of a pair run on one XCD (shared L2)
+};
+
+// Eight V rows held in LDS (s_rows[row][d]) leave as 16-byte units: eight consecutive keys
+// of one head-dim element, rows dk0 .. dk0 + 7 of page (or half-page) dp.  Lanes < D / 2.
+template <int D>
+__device__ __forceinline__ void store_v_units(uint16_t* dp, int dk0, const uint16_t (*s_rows)[D],
+                                              int lane) {
+    if (lane < D / 2) {
+        unsigned dw[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) dw[r] = *reinterpret_cast<const unsigned*>(&s_rows[r][2 * lane]);
+        uint4 lo, hi;
+        lo.x = (dw[0] & 0xffffu) | (dw[1] << 16);
+        lo.y = (dw[2] & 0xffffu) | (dw[3] << 16);
+        lo.z = (dw[4] & 0xffffu) | (dw[5] << 16);
+        lo.w = (dw[6] & 0xffffu) | (dw[7] << 16);
+        hi.x = (dw[0] >> 16) | (dw[1] & 0xffff0000u);
+        hi.y = (dw[2] >> 16) | (dw[3] & 0xffff0000u);
+        hi.z = (dw[4] >> 16) | (dw[5] & 0xffff0000u);
+        hi.w = (dw[6] >> 16) | (dw[7] & 0xffff0000u);
+        uint16_t* vd = dp + spkv_v_off(D, dk0, 2 * lane);   // unit of d = 2 lane; d + 1 follows
+        *reinterpret_cast<uint4*>(vd) = lo;
+        *reinterpret_cast<uint4*>(vd + 8) = hi;
+    }
+}
+
+// One workgroup per (staging half-page, pair): wave wv fills rows 8 wv .. 8 wv + 7.  Rows
+// without a position (before the sequence start, past the chunk) are zero, so that a
+// masked key never meets a non-finite V element.  Runs BEFORE the append (reads the ring
+// and the token count as they were).
+template <int D>
+__global__ __launch_bounds__(256) void spkv_prefill_stage(SpkvView v, const uint16_t* __restrict__ k,
+                                                          const uint16_t* __restrict__ vv,
+                                                          SpkvCu cu, SpkvPrefill pf) {
+    const int pair = blockIdx.y, sh = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n = cu.v[b + 1] - row0;
+    if (n == 0 || sh * kHalfTokens >= v.w + n) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15;
+    const int T0 = v.t_pair[pair];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[4][8][D];
+    uint16_t* dp = pf.stage + ((size_t)pair * pf.shp + sh) * (size_t)(2 * kHalfTokens * D);
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int row = pass * 4 + (lane >> 4);
+        const int u = sh * kHalfTokens + wave * 8 + row;
+        if (c < D / 8) {
+            uint4 kk = {0u, 0u, 0u, 0u}, vl = {0u, 0u, 0u, 0u};
+            if (u >= v.w) {
+                const int j = u - v.w;
+                if (j < n) {
+                    const size_t src = ((size_t)(row0 + j) * v.Hkv + h) * D + c * 8;
+                    kk = *reinterpret_cast<const uint4*>(k + src);
+                    vl = *reinterpret_cast<const uint4*>(vv + src);
+                }
+            } else {
+                const int s = T0 - v.w + u;
+                if (s >= 0) {
+                    const int slot = s % v.w;
+                    const uint16_t* sp = ring_page(v, pair, slot >> 6);
+                    const int sk = slot & 63;
+                    kk = *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, c * 8));
+                    const uint16_t* vs = sp + spkv_v_off(D, sk, c * 8);
+                    unsigned wd[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        wd[e] = (unsigned)vs[(2 * e) * 8] | ((unsigned)vs[(2 * e + 1) * 8] << 16);
+                    vl = make_uint4(wd[0], wd[1], wd[2], wd[3]);
+                }
+            }
+            *reinterpret_cast<uint4*>(dp + spkv_k_off(D, wave * 8 + row, c * 8)) = kk;
+            *reinterpret_cast<uint4*>(&s_v[wave][row][c * 8]) = vl;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    store_v_units<D>(dp, wave * 8, s_v[wave], lane);
+}
+
+// Bits e = 0..7 set for a <= e <= b (empty if the range misses 0..7).
+__device__ __forceinline__ unsigned bit_range8(int a, int b) {
+    if (b < 0 || a > 7 || a > b) return 0u;
+    return (0xffu << max(a, 0)) & (0xffu >> (7 - min(b, 7))) & 0xffu;
+}
+
+// One workgroup of four waves per span of 4 * tb consecutive tokens of one (sequence, KV
+// head); wave wv owns tokens i0 = span start + wv * tb .. + tb - 1 as its 64 MFMA columns.
+// The four waves walk the same half-pages, so each 16 KB tile is fetched from memory once
+// per workgroup into an LDS double buffer (every wave copies a quarter of the next tile
+// while all four consume the current one) and each wave reads its MFMA A operands from
+// LDS with conflict-free 16-byte reads; 256 query columns share one tile fetch.
+template <int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
+                                                           uint16_t* __restrict__ out,
+                                                           float* __restrict__ lse, float scale_log2e,
+                                                           SpkvPrefill pf, SpkvCu cu) {
+    constexpr int NS = D / 32, NB = D / 16, NQ = 4;
+    constexpr int kHalfElems = 2 * kHalfTokens * D;
+    constexpr int kRows = kHalfElems / 512;     // 1 KB rows of a tile
+    constexpr int kRowsPerWave = kRows / 4;
+    __shared__ __attribute__((aligned(16))) uint16_t s_tile[2][kHalfElems];
+    int pair, qblk;
+    if (pf.pin_xcd) {
+        // workgroups go round-robin to the 8 XCDs: id % 8 picks the XCD, and every pair
+        // lives on XCD pair % 8, so its list is fetched into one L2 and re-read there
+        const int local = blockIdx.x >> 3, lp = local / pf.nblk;
+        qblk = local - lp * pf.nblk;
+        pair = lp * 8 + (blockIdx.x & 7);
+        if (pair >= v.n_pairs) return;
+    } else {
+        pair = blockIdx.x / pf.nblk;
+        qblk = blockIdx.x - pair * pf.nblk;
+    }
+    qblk = pf.nblk - 1 - qblk;            // longest prefixes first
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
+    const int span0 = qblk * 4 * pf.tb;
+    if (span0 >= n_tok) return;
+    const int span_last = min(span0 + 4 * pf.tb, n_tok) - 1;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, kc = lane >> 4, n = lane & 15;
+    const int i0 = span0 + wv * pf.tb;
+    const int tbv = max(0, min(pf.tb, n_tok - i0)), i_last = i0 + tbv - 1, cols = tbv * v.G;
+    const bool active = tbv > 0;
+    // the cache is in the state after the append
+    const int T0 = v.t_pair[pair] - n_tok, L = v.kept_len[pair];
+    const int u_min = max(0, v.w - T0);     // first staging row that holds a position
+
+    auto prefix_of = [&](int i) -> int {   // long-term entries at least w behind token i
+        if (T0 + i - v.w < 0) return 0;
+        return min(max(pf.prefix[((size_t)row0 + i) * v.Hkv + h], 0), L);
+    };
+
+    bf16x8 qb[NQ][NS];
+    int tok[NQ], cnt[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        const int col = c * 16 + n;
+        const int i = i0 + col / v.G, g = col - (col / v.G) * v.G;
+        const bool valid = col < cols;
+        tok[c] = valid ? i : -1;
+        cnt[c] = valid ? prefix_of(i) : 0;
+        const uint16_t* qrow = q + ((size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g) * D + kc * 8;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            uint4 raw = {0u, 0u, 0u, 0u};
+            if (valid) raw = *reinterpret_cast<const uint4*>(qrow + sl * 32);
+            qb[c][sl] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    // long-term half-pages: the workgroup visits those some token of the span can see; this
+    // wave computes on those below its own last count, unmasked below its first count
+    const int nA = (prefix_of(span_last) + kHalfTokens - 1) >> 5;
+    const int nA_wave = active ? (prefix_of(i_last) + kHalfTokens - 1) >> 5 : 0;
+    const int fullA = active ? prefix_of(i0) >> 5 : 0;
+    // staging half-pages: rows (span0, span_last + w] that hold a position; this wave's
+    // windows cover rows [lo_w, hi_w]
+    const int sB0 = max(span0 + 1, u_min) >> 5;
+    const int nB = ((span_last + v.w) >> 5) - sB0 + 1;
+    const int lo_w = max(i0 + 1, u_min), hi_w = i_last + v.w;
+    const int n_hp = nA + nB, last = n_hp - 1;
+
+    const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+    const uint16_t* stage = pf.stage + (size_t)pair * pf.shp * (size_t)kHalfElems;
+    auto base_of = [&](int x) -> const uint16_t* {
+        x = min(x, last);
+        if (x < nA) {
+            const int page = min(max(pt[min(x >> 1, v.pt_cap - 1)], 0), v.n_pages - 1);
+            return pool_page(v, page) + (x & 1) * kHalfElems;
+        }
+        return stage + (size_t)min(sB0 + x - nA, pf.shp - 1) * kHalfElems;
+    };
+
+    f32x4 acc[NQ][NB];
+    float m[NQ], l[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        m[c] = SPKV_NEG_INF;
+        l[c] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) acc[c][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int my_off = (wv * kRowsPerWave * 64 + lane) * 8;     // this lane's part of a tile
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    u32x4 t[kRowsPerWave];
+    {
+        const uint16_t* p = base_of(0) + my_off;
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r)
+            *reinterpret_cast<u32x4*>(&s_tile[0][my_off + r * 512]) = t[r];
+    }
+    const uint16_t* p_next = base_of(1);
+    __syncthreads();
+
+    for (int x = 0; x < n_hp; ++x) {
+        // next tile (after the last one: the same tile again, into the idle buffer), kept
+        // unconditional so that the in-flight quarter stays in registers
+        {
+            const uint16_t* p = p_next + my_off;
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
+        }
+        p_next = base_of(x + 2);
+        const uint16_t* tile = s_tile[x & 1];
+        bool mine;
+        int u_tile = 0;
+        if (x < nA) {
+            mine = x < nA_wave;
+        } else {
+            u_tile = (sB0 + x - nA) * kHalfTokens;
+            mine = active && u_tile <= hi_w && u_tile + kHalfTokens > lo_w;
+        }
+        if (mine) {
+            bf16x8 ka[2][NS], va[NB];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl)
+                    ka[tt][sl] = *reinterpret_cast<const bf16x8*>(tile + (tt * NS + sl) * 512 + lane * 8);
+#pragma unroll
+            for (int db = 0; db < NB; ++db)
+                va[db] = *reinterpret_cast<const bf16x8*>(tile + (2 * NS + db) * 512 + lane * 8);
+            // per column group: which of this lane's eight keys are excluded
+            unsigned kill[NQ];
+            bool any;
+            if (x < nA) {
+                any = x >= fullA;
+                const int k0 = x * kHalfTokens + kc * 8;    // list index of this lane's first key
+#pragma unroll
+                for (int c = 0; c < NQ; ++c)
+                    kill[c] = any ? (bit_range8(0, cnt[c] - k0 - 1) ^ 0xffu) : 0u;
+            } else {
+                any = true;
+                const int u0 = u_tile + kc * 8;
+                // window of token i: rows i < u <= i + w that hold a position
+#pragma unroll
+                for (int c = 0; c < NQ; ++c)
+                    kill[c] = (tok[c] >= 0 ? bit_range8(max(tok[c] + 1, u_min) - u0, tok[c] + v.w - u0)
+                                           : 0u) ^ 0xffu;
+            }
+#pragma unroll
+            for (int c = 0; c < NQ; ++c)
+                attend_half_page<D>(ka, va, qb[c], kill[c], any, scale_log2e, acc[c], m[c], l[c]);
+        }
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r)
+            *reinterpret_cast<u32x4*>(&s_tile[(x + 1) & 1][my_off + r * 512]) = t[r];
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        float lc = l[c];
+        lc += __shfl_xor(lc, 16);
+        lc += __shfl_xor(lc, 32);
+        if (tok[c] >= 0) {
+            const int col = c * 16 + n;
+            const int g = col - (col / v.G) * v.G;
+            const size_t o = (size_t)(row0 + tok[c]) * v.Hq + (size_t)h * v.G + g;
+            const float inv = 1.0f / lc;
+            uint16_t* po = out + o * D + kc * 4;
+#pragma unroll
+            for (int db = 0; db < NB; ++db) {
+                const __bf16 r0 = (__bf16)(acc[c][db][0] * inv), r1 = (__bf16)(acc[c][db][1] * inv);
+                const __bf16 r2 = (__bf16)(acc[c][db][2] * inv), r3 = (__bf16)(acc[c][db][3] * inv);
+                uint2 pk;
+                pk.x = (unsigned)__builtin_bit_cast(uint16_t, r0) | ((unsigned)__builtin_bit_cast(uint16_t, r1) << 16);
+                pk.y = (unsigned)__builtin_bit_cast(uint16_t, r2) | ((unsigned)__builtin_bit_cast(uint16_t, r3) << 16);
+                *reinterpret_cast<uint2*>(po + db * 16) = pk;
+            }
+            if (lse != nullptr && kc == 0) lse[o] = (m[c] + log2f(lc)) * 0.6931471805599453f;
+        }
+    }
+}
+
+hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                               const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                               float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
+                               int32_t* prefix, int shp, hipStream_t s) {
+    SpkvPrefill pf;
+    pf.stage = stage;
+    pf.prefix = prefix;
+    pf.shp = shp;
+    pf.tb = 64 / v.G;
+    pf.nblk = (n_max + 4 * pf.tb - 1) / (4 * pf.tb);      // spans of four waves
+    pf.pin_xcd = (v.n_pairs >= 8 && pf.nblk >= 4) ? 1 : 0;
+    const float sl = sm_scale * 1.4426950408889634f;
+    const int stage_hps = (v.w + n_max + kHalfTokens - 1) / kHalfTokens;
+    const unsigned grid = pf.pin_xcd ? 8u * (unsigned)((v.n_pairs + 7) / 8) * (unsigned)pf.nblk
+                                     : (unsigned)v.n_pairs * (unsigned)pf.nblk;
+    hipError_t e;
+    if (v.D == 128) {
+        spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, cu, pf);
+        if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
+        spkv_prefill_attend<128><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    } else {
+        spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, cu, pf);
+        if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
+        spkv_prefill_attend<64><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    }
+    return hipGetLastError();
 }
 
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
