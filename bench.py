@@ -78,6 +78,81 @@ def build_cache(wl: Workload, instance: int, chunk: int, tau=None, oracle=None, 
     return cache, stream
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def prefill_attention_leg(wl: Workload, chunk: int, timed_calls: int, tau=None, instance=2000):
+    """spkv_prefill_attention: the first ctx - timed_calls * chunk tokens of every sequence
+    are fed by spkv_append (not timed), the rest in `timed_calls` calls of `chunk` tokens per
+    sequence, each timed with events on the launch stream (timed_calls = 0: the whole
+    prompt).  Algorithmic flops: 4 D per (query head, attended key) -- q.k and p.v -- with the
+    attended keys counted from the gate bits of the same logits (window + gated-on keys at
+    least w behind, Eq. 3-4)."""
+    tau = wl.tau if tau is None else tau
+    ctx = int(min(wl.ctx_lens))
+    B, Hkv, D, w = wl.batch, wl.n_kv_heads, wl.head_dim, wl.window
+    n_calls = ctx // chunk if timed_calls <= 0 else min(timed_calls, ctx // chunk)
+    before = ctx - n_calls * chunk
+    if tau <= 0.0:
+        pool = B * Hkv * ctx
+    else:
+        pool = int(B * Hkv * ctx * float(wl.keep.mean()) * 1.1) + B * Hkv * (chunk + 256)
+    cache = spkv.SPKVCache(B, wl.n_q_heads, Hkv, D, max_context=ctx + 64,
+                           max_total_kept_tokens=pool, window=w, tau=tau)
+    theta = cache.threshold_logit()
+    stream = TokenStream(wl, device="cuda", layer=instance)
+    gates = []
+    done = 0
+    while done < before:
+        n = min(4096, before - done)
+        k, v, f, cu = stream.next_tokens([n] * B)
+        cache.append(k, v, f, cu)
+        gates.append((f >= theta).view(B, n, Hkv))
+        done += n
+    calls = []
+    for _ in range(n_calls):
+        k, v, f, cu = stream.next_tokens([chunk] * B)
+        q = stream.next_query(rows=chunk * B)
+        calls.append((k, v, f, cache.make_cu(cu), q))
+        gates.append((f >= theta).view(B, chunk, Hkv))
+    out = torch.empty_like(calls[0][4])
+    ws = torch.empty(cache.prefill_workspace_bytes(chunk, chunk * B), dtype=torch.uint8, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_calls + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i, (k, v, f, cu, q) in enumerate(calls):
+        cache.prefill_attention(k, v, f, q, cu, workspace=ws, out=out)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(n_calls)]
+    st = cache.stats()
+    assert st.device_error == 0 and st.total_tokens == B * ctx
+    # attended keys of every timed query, per KV head
+    cum = torch.cat(gates, dim=1).to(torch.int64).cumsum(dim=1)            # [B, ctx, Hkv]
+    t = torch.arange(before, ctx, device="cuda")
+    win = torch.clamp(t + 1, max=w).view(1, -1, 1)
+    far = torch.where((t >= w).view(1, -1, 1), cum[:, torch.clamp(t - w, min=0), :], 0)
+    attended = (win + far).sum(dim=(0, 2)).view(n_calls, chunk).sum(dim=1).double().cpu().numpy()
+    flops = attended * 4.0 * D * (wl.n_q_heads // Hkv)
+    total_ms = float(sum(ms))
+    res = {
+        "what": "spkv_prefill_attention: attention of every new token (window or gate, causal) "
+                "+ append, chunked; inputs resident",
+        "chunk_tokens_per_sequence": chunk, "context_before_timed_calls": before,
+        "calls_timed": n_calls, "ms_total": total_ms,
+        "ms_per_call_first_last": [ms[0], ms[-1]],
+        "tokens_per_s": B * chunk * n_calls / (total_ms * 1e-3),
+        "attended_keys_per_query_mean": float(attended.sum() / (B * Hkv * chunk * n_calls)),
+        "algorithmic_TFLOP": float(flops.sum() / 1e12),
+        "TFLOPs": float(flops.sum() / (total_ms * 1e-3) / 1e12),
+        "frac_of_bf16_mfma_peak": float(flops.sum() / (total_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS),
+        "TFLOPs_last_call": float(flops[-1] / (ms[-1] * 1e-3) / 1e12),
+        "tau": tau,
+    }
+    cache.close()
+    return res
+
+
 HOST_ISSUE_S = []      # host time spent issuing each timed region (before the final sync)
 
 
@@ -304,6 +379,12 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=4)
     ap.add_argument("--scaling", action="store_true",
                     help="run the keep-rate and context sweeps instead of the benchmark")
+    ap.add_argument("--prefill", action="store_true",
+                    help="run only the prefill-attention leg over the whole prompt "
+                         "(--prefill-chunk tokens per sequence per call, --prefill-tau)")
+    ap.add_argument("--prefill-chunk", type=int, default=2048)
+    ap.add_argument("--prefill-tau", type=float, default=None)
+    ap.add_argument("--prefill-calls", type=int, default=0, help="timed calls (0 = whole prompt)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="run only the plain 1 GiB copy kernel 20 times (profiler calibration)")
     args = ap.parse_args()
@@ -334,6 +415,11 @@ def main():
         return
 
     wl = workload(args.workload)
+    if args.prefill:
+        print(json.dumps({"prefill_attention": prefill_attention_leg(
+            wl, args.prefill_chunk, args.prefill_calls, tau=args.prefill_tau),
+            "config": {"workload": wl.name + ": " + wl.note}}))
+        return
     if wl.n_layers > 1:
         layered_bench(wl, args)
         return
@@ -450,6 +536,15 @@ def main():
         }
         dc.close()
 
+    # Prefill attention: the last two 2048-token chunks of the prompt on a fresh cache.
+    prefill_attn = None
+    if min(wl.ctx_lens) >= 4096:
+        for c in caches:
+            c.close()
+        caches = []
+        torch.cuda.empty_cache()
+        prefill_attn = prefill_attention_leg(wl, 2048, 2)
+
     # CPU baseline last (a long host-only phase lets the GPU clocks drop, so it must not
     # precede a timed region): the oracle mirrors the first sequences of instance 0 up to
     # the end of prefill; give it one more step of instance 0 and time its decode.
@@ -495,6 +590,7 @@ def main():
         "dense_cache": dense,
         "prefill_append": dict(PREFILL_TIMING),
         "decode_chunk": chunk_legs,
+        "prefill_attention": prefill_attn,
         "roofline": {
             "bound": "hbm", "kernel": "spkv_decode_split<128>",
             "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

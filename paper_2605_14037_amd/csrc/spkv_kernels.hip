@@ -1284,6 +1284,118 @@ __device__ __forceinline__ unsigned bit_range8(int a, int b) {
     return (0xffu << max(a, 0)) & (0xffu >> (7 - min(b, 7))) & 0xffu;
 }
 
+// One half-page from LDS for the four column groups of a wave, in pieces so that the
+// accumulators are only ever touched by MFMA inside the tile loop:
+//   tile_scores      S = K Q^T for the four groups (eight independent accumulator chains),
+//                    masked keys to -inf
+//   tile_weights     weights p = 2^(x - m) against the column references m as they stand,
+//                    and their per-lane sums; reports (wave-uniform) whether a reference
+//                    is too low -- some sum above 2^11, so a weight may exceed 2^8 -- or
+//                    not set yet.  Weights up to 2^11 are harmless in bf16 / fp32, so in
+//                    the steady state no maximum is taken and nothing is rescaled.
+//   tile_accumulate  sums and P V with the weights accepted
+//   rescale_columns  raises the references to the column maxima of the tile and rescales
+//                    sums and accumulators; the tile loop leaves its inner loop for this
+//                    (rare once a few tiles have been seen) and then redoes the tile
+constexpr float kWeightSumLimit = 2048.0f;
+
+template <int D>
+__device__ __forceinline__ void tile_scores(const uint16_t* tile, int lane,
+                                            const bf16x8 (&qb)[4][D / 32], const unsigned (&kill)[4],
+                                            bool any_kill, float (&x)[4][8]) {
+    constexpr int NS = D / 32;
+    f32x4 s0[4], s1[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        s0[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        s1[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int sl = 0; sl < NS; ++sl) {
+        const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(tile + sl * 512 + lane * 8);
+        const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(tile + (NS + sl) * 512 + lane * 8);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qb[c][sl], s0[c], 0, 0, 0);
+            s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qb[c][sl], s1[c], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[c][i] = s0[c][i];
+            x[c][4 + i] = s1[c][i];
+        }
+    }
+    if (any_kill) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if ((kill[c] >> e) & 1u) x[c][e] = SPKV_NEG_INF;
+    }
+}
+
+__device__ __forceinline__ bool tile_weights(const float (&x)[4][8], float scale_log2e,
+                                             const float (&m)[4], f32x8 (&p)[4], float (&psum)[4]) {
+    bool low = false;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const bool unset = m[c] == SPKV_NEG_INF;
+        const float neg_ref = unset ? 0.f : -m[c];
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[c][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[c][e], scale_log2e, neg_ref));
+            sum += p[c][e];
+        }
+        psum[c] = sum;
+        low = low || unset || !(sum <= kWeightSumLimit);
+    }
+    return __ballot(low) != 0ull;
+}
+
+template <int D>
+__device__ __forceinline__ void tile_accumulate(const uint16_t* tile, int lane, const f32x8 (&p)[4],
+                                                const float (&psum)[4], f32x4 (&acc)[4][D / 16],
+                                                float (&l)[4]) {
+    constexpr int NS = D / 32, NB = D / 16;
+    bf16x8 va[NB];
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+        va[db] = *reinterpret_cast<const bf16x8*>(tile + (2 * NS + db) * 512 + lane * 8);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        l[c] += psum[c];
+        const bf16x8 pb = __builtin_convertvector(p[c], bf16x8);
+#pragma unroll
+        for (int db = 0; db < NB; ++db)
+            acc[c][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[db], pb, acc[c][db], 0, 0, 0);
+    }
+}
+
+// x: the masked scores of the tile that did not fit the references.  A column whose keys
+// are all excluded so far keeps the reference -inf (its sums and accumulators are zero).
+template <int D>
+__device__ __forceinline__ void rescale_columns(const float (&x)[4][8], float scale_log2e,
+                                                f32x4 (&acc)[4][D / 16], float (&m)[4], float (&l)[4]) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float cm = fmaxf(fmaxf(fmaxf(x[c][0], x[c][1]), fmaxf(x[c][2], x[c][3])),
+                         fmaxf(fmaxf(x[c][4], x[c][5]), fmaxf(x[c][6], x[c][7]))) * scale_log2e;
+        cm = fmaxf(cm, __shfl_xor(cm, 16));
+        cm = fmaxf(cm, __shfl_xor(cm, 32));
+        const float m_new = fmaxf(m[c], cm);
+        const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m[c] - m_ref);
+        l[c] *= alpha;
+#pragma unroll
+        for (int db = 0; db < D / 16; ++db) acc[c][db] *= alpha;
+        m[c] = m_new;
+    }
+}
+
 // One workgroup of four waves per span of 4 * tb consecutive tokens of one (sequence, KV
 // head); wave wv owns tokens i0 = span start + wv * tb .. + tb - 1 as its 64 MFMA columns.
 // The four waves walk the same half-pages, so each 16 KB tile is fetched from memory once
@@ -1306,7 +1418,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         // lives on XCD pair % 8, so its list is fetched into one L2 and re-read there
         const int local = blockIdx.x >> 3, lp = local / pf.nblk;
         qblk = local - lp * pf.nblk;
-        pair = lp * 8 + (blockIdx.x & 7);
+        // rotate inside every full group of 8 pairs by the group index: with 8 KV heads a
+        // plain pair % 8 would give each XCD one head of every sequence, and heads differ
+        // several-fold in kept length
+        const int rot = (lp * 8 + 8 <= v.n_pairs) ? lp : 0;
+        pair = lp * 8 + (((blockIdx.x & 7) + rot) & 7);
         if (pair >= v.n_pairs) return;
     } else {
         pair = blockIdx.x / pf.nblk;
@@ -1395,60 +1511,70 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const uint16_t* p_next = base_of(1);
     __syncthreads();
 
-    for (int x = 0; x < n_hp; ++x) {
-        // next tile (after the last one: the same tile again, into the idle buffer), kept
-        // unconditional so that the in-flight quarter stays in registers
-        {
-            const uint16_t* p = p_next + my_off;
+    // Tile loop.  The inner loop never touches the accumulators except by MFMA; when the
+    // references do not fit a tile the wave leaves it before using the tile, rescales, and
+    // resumes at the same tile (prefetch and barrier of a tile are issued exactly once, so
+    // the four waves stay in step whatever each one does).  After a rescale the references
+    // are at least the tile's column maxima, so the second attempt is accepted; a column
+    // with every key excluded so far keeps m = -inf and is accepted on the retry as well.
+    int x = 0;
+    bool resume = false, pending = false;
+    float xs[NQ][8];
+    while (x < n_hp) {
+        if (pending) rescale_columns<D>(xs, scale_log2e, acc, m, l);
+        for (; x < n_hp; ++x) {
+            if (!resume) {
+                // next tile (after the last one: the same tile again, into the idle buffer)
+                const uint16_t* p = p_next + my_off;
 #pragma unroll
-            for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
-        }
-        p_next = base_of(x + 2);
-        const uint16_t* tile = s_tile[x & 1];
-        bool mine;
-        int u_tile = 0;
-        if (x < nA) {
-            mine = x < nA_wave;
-        } else {
-            u_tile = (sB0 + x - nA) * kHalfTokens;
-            mine = active && u_tile <= hi_w && u_tile + kHalfTokens > lo_w;
-        }
-        if (mine) {
-            bf16x8 ka[2][NS], va[NB];
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int sl = 0; sl < NS; ++sl)
-                    ka[tt][sl] = *reinterpret_cast<const bf16x8*>(tile + (tt * NS + sl) * 512 + lane * 8);
-#pragma unroll
-            for (int db = 0; db < NB; ++db)
-                va[db] = *reinterpret_cast<const bf16x8*>(tile + (2 * NS + db) * 512 + lane * 8);
-            // per column group: which of this lane's eight keys are excluded
-            unsigned kill[NQ];
-            bool any;
+                for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
+                p_next = base_of(x + 2);
+            }
+            resume = false;
+            const uint16_t* tile = s_tile[x & 1];
+            bool mine;
+            int u_tile = 0;
             if (x < nA) {
-                any = x >= fullA;
-                const int k0 = x * kHalfTokens + kc * 8;    // list index of this lane's first key
-#pragma unroll
-                for (int c = 0; c < NQ; ++c)
-                    kill[c] = any ? (bit_range8(0, cnt[c] - k0 - 1) ^ 0xffu) : 0u;
+                mine = x < nA_wave;
             } else {
-                any = true;
-                const int u0 = u_tile + kc * 8;
-                // window of token i: rows i < u <= i + w that hold a position
+                u_tile = (sB0 + x - nA) * kHalfTokens;
+                mine = active && u_tile <= hi_w && u_tile + kHalfTokens > lo_w;
+            }
+            if (mine) {
+                // per column group: which of this lane's eight keys are excluded
+                unsigned kill[NQ] = {0u, 0u, 0u, 0u};
+                bool any = true;
+                if (x < nA) {
+                    any = x >= fullA;
+                    if (any) {
+                        const int k0 = x * kHalfTokens + kc * 8;   // list index of this lane's first key
 #pragma unroll
-                for (int c = 0; c < NQ; ++c)
-                    kill[c] = (tok[c] >= 0 ? bit_range8(max(tok[c] + 1, u_min) - u0, tok[c] + v.w - u0)
-                                           : 0u) ^ 0xffu;
+                        for (int c = 0; c < NQ; ++c) kill[c] = bit_range8(0, cnt[c] - k0 - 1) ^ 0xffu;
+                    }
+                } else {
+                    const int u0 = u_tile + kc * 8;
+                    // window of token i: rows i < u <= i + w that hold a position
+#pragma unroll
+                    for (int c = 0; c < NQ; ++c)
+                        kill[c] = (tok[c] >= 0 ? bit_range8(max(tok[c] + 1, u_min) - u0, tok[c] + v.w - u0)
+                                               : 0u) ^ 0xffu;
+                }
+                tile_scores<D>(tile, lane, qb, kill, any, xs);
+                f32x8 pw[NQ];
+                float psum[NQ];
+                if (tile_weights(xs, scale_log2e, m, pw, psum) && !pending) {
+                    pending = true;
+                    resume = true;
+                    break;
+                }
+                pending = false;
+                tile_accumulate<D>(tile, lane, pw, psum, acc, l);
             }
 #pragma unroll
-            for (int c = 0; c < NQ; ++c)
-                attend_half_page<D>(ka, va, qb[c], kill[c], any, scale_log2e, acc[c], m[c], l[c]);
+            for (int r = 0; r < kRowsPerWave; ++r)
+                *reinterpret_cast<u32x4*>(&s_tile[(x + 1) & 1][my_off + r * 512]) = t[r];
+            __syncthreads();
         }
-#pragma unroll
-        for (int r = 0; r < kRowsPerWave; ++r)
-            *reinterpret_cast<u32x4*>(&s_tile[(x + 1) & 1][my_off + r * 512]) = t[r];
-        __syncthreads();
     }
 
 #pragma unroll
