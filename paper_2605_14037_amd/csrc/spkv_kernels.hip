@@ -1278,10 +1278,10 @@ __global__ __launch_bounds__(256) void spkv_prefill_stage(SpkvView v, const uint
     store_v_units<D>(dp, wave * 8, s_v[wave], lane);
 }
 
-// Bits e = 0..7 set for a <= e <= b (empty if the range misses 0..7).
+// Bits e = 0..7 set for a <= e <= b (empty if the range misses 0..7); branch-free.
 __device__ __forceinline__ unsigned bit_range8(int a, int b) {
-    if (b < 0 || a > 7 || a > b) return 0u;
-    return (0xffu << max(a, 0)) & (0xffu >> (7 - min(b, 7))) & 0xffu;
+    const int lo = min(max(a, 0), 8), hi = max(min(b, 7), -8);
+    return (0xffu << lo) & (0xffu >> (7 - hi)) & 0xffu;
 }
 
 // One half-page from LDS for the four column groups of a wave, in pieces so that the
@@ -1434,7 +1434,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int span0 = qblk * 4 * pf.tb;
     if (span0 >= n_tok) return;
     const int span_last = min(span0 + 4 * pf.tb, n_tok) - 1;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, kc = lane >> 4, n = lane & 15;
+    const int tid = threadIdx.x, lane = tid & 63, kc = lane >> 4, n = lane & 15;
+    // wave index as a scalar: everything derived from it (token range, loop bounds, the
+    // branches on them) then stays in scalar registers and scalar branches
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i0 = span0 + wv * pf.tb;
     const int tbv = max(0, min(pf.tb, n_tok - i0)), i_last = i0 + tbv - 1, cols = tbv * v.G;
     const bool active = tbv > 0;
