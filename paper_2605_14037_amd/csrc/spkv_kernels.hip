@@ -1298,15 +1298,17 @@ __device__ __forceinline__ unsigned bit_range8(int a, int b) {
 //                    sums and accumulators; the tile loop leaves its inner loop for this
 //                    (rare once a few tiles have been seen) and then redoes the tile
 constexpr float kWeightSumLimit = 2048.0f;
+constexpr int kPrefillGroups = 2;    // column groups of 16 per wave
+constexpr int kPrefillWaves = 8;     // waves per workgroup (two per SIMD)
 
-template <int D>
+template <int D, int NQ>
 __device__ __forceinline__ void tile_scores(const uint16_t* tile, int lane,
-                                            const bf16x8 (&qb)[4][D / 32], const unsigned (&kill)[4],
-                                            bool any_kill, float (&x)[4][8]) {
+                                            const bf16x8 (&qb)[NQ][D / 32], const unsigned (&kill)[NQ],
+                                            bool any_kill, float (&x)[NQ][8]) {
     constexpr int NS = D / 32;
-    f32x4 s0[4], s1[4];
+    f32x4 s0[NQ], s1[NQ];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NQ; ++c) {
         s0[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
         s1[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
@@ -1315,13 +1317,13 @@ __device__ __forceinline__ void tile_scores(const uint16_t* tile, int lane,
         const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(tile + sl * 512 + lane * 8);
         const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(tile + (NS + sl) * 512 + lane * 8);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < NQ; ++c) {
             s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qb[c][sl], s0[c], 0, 0, 0);
             s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qb[c][sl], s1[c], 0, 0, 0);
         }
     }
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NQ; ++c) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             x[c][i] = s0[c][i];
@@ -1330,18 +1332,19 @@ __device__ __forceinline__ void tile_scores(const uint16_t* tile, int lane,
     }
     if (any_kill) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
+        for (int c = 0; c < NQ; ++c)
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 if ((kill[c] >> e) & 1u) x[c][e] = SPKV_NEG_INF;
     }
 }
 
-__device__ __forceinline__ bool tile_weights(const float (&x)[4][8], float scale_log2e,
-                                             const float (&m)[4], f32x8 (&p)[4], float (&psum)[4]) {
+template <int NQ>
+__device__ __forceinline__ bool tile_weights(const float (&x)[NQ][8], float scale_log2e,
+                                             const float (&m)[NQ], f32x8 (&p)[NQ], float (&psum)[NQ]) {
     bool low = false;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NQ; ++c) {
         const bool unset = m[c] == SPKV_NEG_INF;
         const float neg_ref = unset ? 0.f : -m[c];
         float sum = 0.f;
@@ -1356,17 +1359,17 @@ __device__ __forceinline__ bool tile_weights(const float (&x)[4][8], float scale
     return __ballot(low) != 0ull;
 }
 
-template <int D>
-__device__ __forceinline__ void tile_accumulate(const uint16_t* tile, int lane, const f32x8 (&p)[4],
-                                                const float (&psum)[4], f32x4 (&acc)[4][D / 16],
-                                                float (&l)[4]) {
+template <int D, int NQ>
+__device__ __forceinline__ void tile_accumulate(const uint16_t* tile, int lane, const f32x8 (&p)[NQ],
+                                                const float (&psum)[NQ], f32x4 (&acc)[NQ][D / 16],
+                                                float (&l)[NQ]) {
     constexpr int NS = D / 32, NB = D / 16;
     bf16x8 va[NB];
 #pragma unroll
     for (int db = 0; db < NB; ++db)
         va[db] = *reinterpret_cast<const bf16x8*>(tile + (2 * NS + db) * 512 + lane * 8);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NQ; ++c) {
         l[c] += psum[c];
         const bf16x8 pb = __builtin_convertvector(p[c], bf16x8);
 #pragma unroll
@@ -1377,11 +1380,11 @@ __device__ __forceinline__ void tile_accumulate(const uint16_t* tile, int lane, 
 
 // x: the masked scores of the tile that did not fit the references.  A column whose keys
 // are all excluded so far keeps the reference -inf (its sums and accumulators are zero).
-template <int D>
-__device__ __forceinline__ void rescale_columns(const float (&x)[4][8], float scale_log2e,
-                                                f32x4 (&acc)[4][D / 16], float (&m)[4], float (&l)[4]) {
+template <int D, int NQ>
+__device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float scale_log2e,
+                                                f32x4 (&acc)[NQ][D / 16], float (&m)[NQ], float (&l)[NQ]) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NQ; ++c) {
         float cm = fmaxf(fmaxf(fmaxf(x[c][0], x[c][1]), fmaxf(x[c][2], x[c][3])),
                          fmaxf(fmaxf(x[c][4], x[c][5]), fmaxf(x[c][6], x[c][7]))) * scale_log2e;
         cm = fmaxf(cm, __shfl_xor(cm, 16));
@@ -1403,14 +1406,14 @@ __device__ __forceinline__ void rescale_columns(const float (&x)[4][8], float sc
 // while all four consume the current one) and each wave reads its MFMA A operands from
 // LDS with conflict-free 16-byte reads; 256 query columns share one tile fetch.
 template <int D>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
                                                            uint16_t* __restrict__ out,
                                                            float* __restrict__ lse, float scale_log2e,
                                                            SpkvPrefill pf, SpkvCu cu) {
-    constexpr int NS = D / 32, NB = D / 16, NQ = 4;
+    constexpr int NS = D / 32, NB = D / 16, NQ = kPrefillGroups, NW = kPrefillWaves;
     constexpr int kHalfElems = 2 * kHalfTokens * D;
     constexpr int kRows = kHalfElems / 512;     // 1 KB rows of a tile
-    constexpr int kRowsPerWave = kRows / 4;
+    constexpr int kRowsPerWave = kRows / NW;
     __shared__ __attribute__((aligned(16))) uint16_t s_tile[2][kHalfElems];
     int pair, qblk;
     if (pf.pin_xcd) {
@@ -1431,9 +1434,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     qblk = pf.nblk - 1 - qblk;            // longest prefixes first
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
-    const int span0 = qblk * 4 * pf.tb;
+    const int span0 = qblk * NW * pf.tb;
     if (span0 >= n_tok) return;
-    const int span_last = min(span0 + 4 * pf.tb, n_tok) - 1;
+    const int span_last = min(span0 + NW * pf.tb, n_tok) - 1;
     const int tid = threadIdx.x, lane = tid & 63, kc = lane >> 4, n = lane & 15;
     // wave index as a scalar: everything derived from it (token range, loop bounds, the
     // branches on them) then stays in scalar registers and scalar branches
@@ -1524,7 +1527,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     bool resume = false, pending = false;
     float xs[NQ][8];
     while (x < n_hp) {
-        if (pending) rescale_columns<D>(xs, scale_log2e, acc, m, l);
+        if (pending) rescale_columns<D, NQ>(xs, scale_log2e, acc, m, l);
         for (; x < n_hp; ++x) {
             if (!resume) {
                 // next tile (after the last one: the same tile again, into the idle buffer)
@@ -1545,7 +1548,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             }
             if (mine) {
                 // per column group: which of this lane's eight keys are excluded
-                unsigned kill[NQ] = {0u, 0u, 0u, 0u};
+                unsigned kill[NQ] = {};
                 bool any = true;
                 if (x < nA) {
                     any = x >= fullA;
@@ -1562,16 +1565,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                         kill[c] = (tok[c] >= 0 ? bit_range8(max(tok[c] + 1, u_min) - u0, tok[c] + v.w - u0)
                                                : 0u) ^ 0xffu;
                 }
-                tile_scores<D>(tile, lane, qb, kill, any, xs);
+                tile_scores<D, NQ>(tile, lane, qb, kill, any, xs);
                 f32x8 pw[NQ];
                 float psum[NQ];
-                if (tile_weights(xs, scale_log2e, m, pw, psum) && !pending) {
+                if (tile_weights<NQ>(xs, scale_log2e, m, pw, psum) && !pending) {
                     pending = true;
                     resume = true;
                     break;
                 }
                 pending = false;
-                tile_accumulate<D>(tile, lane, pw, psum, acc, l);
+                tile_accumulate<D, NQ>(tile, lane, pw, psum, acc, l);
             }
 #pragma unroll
             for (int r = 0; r < kRowsPerWave; ++r)
@@ -1613,8 +1616,8 @@ hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint1
     pf.stage = stage;
     pf.prefix = prefix;
     pf.shp = shp;
-    pf.tb = 64 / v.G;
-    pf.nblk = (n_max + 4 * pf.tb - 1) / (4 * pf.tb);      // spans of four waves
+    pf.tb = (16 * kPrefillGroups) / v.G;
+    pf.nblk = (n_max + kPrefillWaves * pf.tb - 1) / (kPrefillWaves * pf.tb);   // spans of one workgroup
     pf.pin_xcd = (v.n_pairs >= 8 && pf.nblk >= 4) ? 1 : 0;
     const float sl = sm_scale * 1.4426950408889634f;
     const int stage_hps = (v.w + n_max + kHalfTokens - 1) / kHalfTokens;
@@ -1624,11 +1627,11 @@ hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint1
     if (v.D == 128) {
         spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
-        spkv_prefill_attend<128><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        spkv_prefill_attend<128><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
     } else {
         spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
-        spkv_prefill_attend<64><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        spkv_prefill_attend<64><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
     }
     return hipGetLastError();
 }
