@@ -1186,8 +1186,8 @@ int spkv_chunk_resident_items(int head_dim, int col_groups) {
 //      rows i < u <= i + w in its window.
 //   2. the bulk append runs and records, per new token, how long a prefix of the long-term
 //      list lies at least w behind it (see spkv_bulk_ring).
-//   3. spkv_prefill_attend: one wave per block of tb = 64 / G consecutive tokens of one
-//      (sequence, KV head) -- 64 MFMA columns (token, head) in four groups of 16 -- walks
+//   3. spkv_prefill_attend: one wave per block of tb = 32 / G consecutive tokens of one
+//      (sequence, KV head) -- 32 MFMA columns (token, head) in two groups of 16 -- walks
 //      the long-term prefix and then the staging rows of the block's windows, one online
 //      softmax per column, and writes the normalised bf16 rows.  No partials, no combine.
 // Window keys and long-term entries are disjoint (positions > t - w against <= t - w), so
@@ -1197,8 +1197,8 @@ struct SpkvPrefill {
     uint16_t* stage;     // [n_pairs][shp] half-pages
     int32_t*  prefix;    // [total tokens][H_kv]
     int32_t   shp;       // staging half-pages per pair
-    int32_t   tb;        // tokens per block (64 / G)
-    int32_t   nblk;      // workgroups (spans of 4 tb tokens) per pair in the grid
+    int32_t   tb;        // tokens per wave (32 / G)
+    int32_t   nblk;      // workgroups (spans of 8 tb tokens) per pair in the grid
     int32_t   pin_xcd;   // 1: all blocks of a pair run on one XCD (shared L2)
 };
 
@@ -1284,9 +1284,9 @@ __device__ __forceinline__ unsigned bit_range8(int a, int b) {
     return (0xffu << lo) & (0xffu >> (7 - hi)) & 0xffu;
 }
 
-// One half-page from LDS for the four column groups of a wave, in pieces so that the
+// One half-page from LDS for the NQ column groups of a wave, in pieces so that the
 // accumulators are only ever touched by MFMA inside the tile loop:
-//   tile_scores      S = K Q^T for the four groups (eight independent accumulator chains),
+//   tile_scores      S = K Q^T for the groups (2 NQ independent accumulator chains),
 //                    masked keys to -inf
 //   tile_weights     weights p = 2^(x - m) against the column references m as they stand,
 //                    and their per-lane sums; reports (wave-uniform) whether a reference
@@ -1399,12 +1399,17 @@ __device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float s
     }
 }
 
-// One workgroup of four waves per span of 4 * tb consecutive tokens of one (sequence, KV
-// head); wave wv owns tokens i0 = span start + wv * tb .. + tb - 1 as its 64 MFMA columns.
-// The four waves walk the same half-pages, so each 16 KB tile is fetched from memory once
-// per workgroup into an LDS double buffer (every wave copies a quarter of the next tile
-// while all four consume the current one) and each wave reads its MFMA A operands from
-// LDS with conflict-free 16-byte reads; 256 query columns share one tile fetch.
+// One workgroup of kPrefillWaves = 8 waves per span of 8 * tb consecutive tokens of one
+// (sequence, KV head); wave wv owns tokens i0 = span start + wv * tb .. + tb - 1 as its
+// 32 MFMA columns (tb = 32 / G tokens times G heads, two groups of 16).  The waves walk the
+// same half-pages, so each 16 KB tile is fetched from memory once per workgroup into an LDS
+// double buffer (every wave copies an eighth of the next tile while all consume the current
+// one) and each wave reads its MFMA A operands from LDS with conflict-free 16-byte reads;
+// 256 query columns share one tile fetch.  With 32 columns a wave needs about 200 VGPRs and
+// no accumulation registers, so two waves fit a SIMD and one wave's vector work (weights)
+// can run beside the other's MFMAs.  (Measured alternatives: four waves of 64 columns, one
+// per SIMD, 15 % slower -- every latency is exposed; the same with the tile loop software-
+// pipelined by hand, slower still; issue priority for one wave of each SIMD, 27 % slower.)
 template <int D>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
                                                            uint16_t* __restrict__ out,
@@ -1520,7 +1525,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // Tile loop.  The inner loop never touches the accumulators except by MFMA; when the
     // references do not fit a tile the wave leaves it before using the tile, rescales, and
     // resumes at the same tile (prefetch and barrier of a tile are issued exactly once, so
-    // the four waves stay in step whatever each one does).  After a rescale the references
+    // the waves stay in step whatever each one does).  After a rescale the references
     // are at least the tile's column maxima, so the second attempt is accepted; a column
     // with every key excluded so far keeps m = -inf and is accepted on the retry as well.
     int x = 0;
