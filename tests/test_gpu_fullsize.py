@@ -110,3 +110,55 @@ def test_cfg5_one_layer():
         return (h @ W - 1.0364).contiguous()
     st = _run_full("cfg5", layer=3, logits_fn=predictor)
     assert 0.12 < st.density_evicted < 0.18
+
+
+def test_cfg2_prefill_attention_last_chunks():
+    """The prefill-attention leg of bench.py at full size: cfg2's prompt, the first 28672
+    tokens by spkv_append, the last two 2048-token chunks by spkv_prefill_attention.  State
+    bit for bit for every (sequence, head); outputs element by element for sampled rows
+    (first, last and random rows of the chunk) of two sampled sequences."""
+    wl = workload("cfg2")
+    seqs = [0, 9]
+    stream = TokenStream(wl, device="cuda", layer=7)
+    chunk, ctx = 2048, wl.ctx_lens[0]
+    pool = int(wl.expected_kept_tokens() * 1.08) + wl.batch * wl.n_kv_heads * (chunk + 256)
+    cache = H.make_cache(wl, pool_tokens=pool, extra_context=64)
+    gates = SPKVOracle(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, window=wl.window,
+                       tau=wl.tau, track_kv=False)
+    sub = SPKVOracle(len(seqs), wl.n_q_heads, wl.n_kv_heads, wl.head_dim, window=wl.window,
+                     tau=wl.tau)
+
+    def mirror(k, v, f, cu):
+        gates.append(None, None, to_numpy_f32(f), cu)
+        rows, sub_cu = _rows_of(cu, seqs)
+        rows = rows.to(k.device)
+        sub.append(to_numpy_f32(k[rows]), to_numpy_f32(v[rows]), to_numpy_f32(f[rows]), sub_cu)
+        return rows
+
+    done = 0
+    while done < ctx - 2 * chunk:
+        n = min(4096, ctx - 2 * chunk - done)
+        k, v, f, cu = stream.next_tokens([n] * wl.batch)
+        cache.append(k, v, f, cu)
+        mirror(k, v, f, cu)
+        done += n
+    rng = np.random.default_rng(11)
+    ws = torch.empty(cache.prefill_workspace_bytes(chunk, chunk * wl.batch), dtype=torch.uint8,
+                     device="cuda")
+    for call in range(2):
+        k, v, f, cu = stream.next_tokens([chunk] * wl.batch)
+        q = stream.next_query(rows=chunk * wl.batch)
+        out, lse = cache.prefill_attention(k, v, f, q, cu, workspace=ws, want_lse=True)
+        rows = mirror(k, v, f, cu)
+        # packed rows of the sub-oracle: sequence j of seqs holds rows j*chunk .. (j+1)*chunk
+        pick = sorted(set([0, chunk - 1, chunk, 2 * chunk - 1] +
+                          rng.choice(len(seqs) * chunk, size=20, replace=False).tolist()))
+        ref_out, ref_lse = sub.decode_chunk(to_numpy_f32(q[rows]), [chunk] * len(seqs), rows=set(pick))
+        sel = rows[torch.tensor(pick)]
+        m = H.check_output(out[sel], ref_out[pick], f"prefill call {call}")
+        H.check_lse(lse[sel], ref_lse[pick], f"prefill call {call}")
+        assert torch.isfinite(out.float()).all() and out.float().abs().max().item() <= 6.0
+        print(f"prefill call {call}: max |err| {m['max_abs']:.2e}, rel L2 {m['rel_l2']:.2e}", flush=True)
+    st = H.check_state(cache, gates, wl, label="prefill full size")
+    assert st.total_tokens == wl.batch * ctx
+    cache.close()
