@@ -236,6 +236,14 @@ int spkv_cache_kept_positions(spkv_cache_t* cache, int32_t b, int32_t h, int32_t
 /* The fp32 threshold theta the gate compares logits against. */
 int spkv_cache_threshold_logit(const spkv_cache_t* cache, float* theta);
 
+/* Change tau on a live cache ("tau can be adjusted a posteriori", Sec. 3 and the threshold
+ * discussion of the appendix).  The window ring stores every pair's logit, so the new
+ * threshold applies to every pair that leaves the window in calls issued after this one,
+ * including pairs appended under the old value; decisions already taken stand (dropped
+ * pairs are gone, kept pairs stay).  Host-side only: nothing is launched, calls already
+ * enqueued keep the threshold they were issued with.  SPKV_E_INVAL for a NaN tau. */
+int spkv_cache_set_tau(spkv_cache_t* cache, float tau);
+
 /* Tuning and instrumentation; see SPKV_OPT_*. */
 int spkv_cache_set_option(spkv_cache_t* cache, int32_t option, int64_t value);
 

@@ -111,6 +111,10 @@ class SPKVOracle:
         self._vbuf = [np.zeros((0, n_kv_heads, head_dim), store_dtype) for _ in range(batch)]
         self._fbuf = [np.zeros((0, n_kv_heads), np.float32) for _ in range(batch)]
         self._len = [0] * batch
+        # Threshold history per sequence: (tokens stored when it took effect, theta).  With a
+        # threshold that never changes this is one entry and every gate below is the plain
+        # Eq. 2 comparison.
+        self._theta_hist = [[(0, self.theta)] for _ in range(batch)]
 
     # ------------------------------------------------------------------ write
     def append(self, k, v, util_logits, cu_seqlens):
@@ -146,8 +150,26 @@ class SPKVOracle:
             self._fbuf[b][old:new] = f[lo:hi]
             self._len[b] = new
 
+    def set_tau(self, tau):
+        """Change the threshold of a live cache.  A pair's keep-or-drop decision is taken
+        when it leaves the window (when position s + w is stored), with the threshold in
+        force at that moment; decisions already taken stand.  ("tau can be adjusted a
+        posteriori", Sec. 3: here also between steps of one sequence.)"""
+        self.theta = threshold_logit(tau)
+        for b in range(self.B):
+            self._theta_hist[b].append((self._len[b], self.theta))
+
+    def _theta_when_stored(self, b, n_stored):
+        """theta in force when the sequence held n_stored[i] tokens and took one more."""
+        n_stored = np.asarray(n_stored)
+        th = np.empty(n_stored.shape, np.float32)
+        for start, theta in self._theta_hist[b]:        # ascending starts: later entries win
+            th[n_stored >= start] = theta
+        return th
+
     def release_sequence(self, b):
         """Forget sequence b: slot b holds an empty sequence again."""
+        self._theta_hist[b] = [(0, self.theta)]
         self._kbuf[b] = np.zeros((0, self.Hkv, self.D), self.store_dtype)
         self._vbuf[b] = np.zeros((0, self.Hkv, self.D), self.store_dtype)
         self._fbuf[b] = np.zeros((0, self.Hkv), np.float32)
@@ -167,8 +189,20 @@ class SPKVOracle:
         return self._fbuf[b][:self._len[b]]
 
     def gate(self, b, h):
-        """z_s for every stored position of (b, h): fp32 compare f >= theta."""
-        return self._f(b)[:, h] >= self.theta
+        """z_s for every stored position of (b, h): fp32 compare f >= theta (Eq. 2 on the
+        logit), theta being the threshold in force when s left the window, i.e. when
+        position s + w was stored (for positions still inside the window: the current one;
+        their gate is not consulted by Eq. 3-4)."""
+        s = np.arange(self.seq_len(b))
+        theta = self._theta_when_stored(b, s + self.w)
+        theta[s + self.w >= self.seq_len(b)] = self.theta
+        return self._f(b)[:, h] >= theta
+
+    def gate_at_append(self, b, h):
+        """The same comparison with the threshold in force when s itself was stored: the
+        z_s that Eq. 8 sums over all positions."""
+        s = np.arange(self.seq_len(b))
+        return self._f(b)[:, h] >= self._theta_when_stored(b, s)
 
     def kept_positions(self, b, h):
         """Ascending positions held by the long-term cache of (b, h): gated-on
@@ -204,7 +238,7 @@ class SPKVOracle:
         evicted = sum(max(0, self.seq_len(b) - self.w) for b in range(self.B)) * self.Hkv
         window = sum(min(self.seq_len(b), self.w) for b in range(self.B)) * self.Hkv
         kept = int(self.kept_len().sum())
-        gate_on = int(sum(int(self.gate(b, h).sum())
+        gate_on = int(sum(int(self.gate_at_append(b, h).sum())
                           for b in range(self.B) for h in range(self.Hkv)))
         row_bytes = 2 * self.D * 2            # K row + V row, 2 bytes/element
         return dict(

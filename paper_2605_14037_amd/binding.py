@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_reset",
     "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk",
     "spkv_prefill_workspace_bytes", "spkv_prefill_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
-    "spkv_cache_threshold_logit", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
+    "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
     "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
 
@@ -99,6 +99,8 @@ def load_library():
     lib.spkv_cache_kept_positions.argtypes = [vp, i32, i32, P(i32), i32, P(i32), vp]
     lib.spkv_cache_threshold_logit.restype = C.c_int
     lib.spkv_cache_threshold_logit.argtypes = [vp, P(f32)]
+    lib.spkv_cache_set_tau.restype = C.c_int
+    lib.spkv_cache_set_tau.argtypes = [vp, f32]
     lib.spkv_cache_set_option.restype = C.c_int
     lib.spkv_cache_set_option.argtypes = [vp, i32, i64]
     lib.spkv_cache_read_kernel_timing.restype = C.c_int
@@ -353,6 +355,9 @@ class SPKVCache:
         _check(self.lib.spkv_cache_threshold_logit(self.handle, C.byref(th)),
                "spkv_cache_threshold_logit")
         return th.value
+
+    def set_tau(self, tau):
+        _check(self.lib.spkv_cache_set_tau(self.handle, float(tau)), "spkv_cache_set_tau")
 
     def set_option(self, option, value):
         _check(self.lib.spkv_cache_set_option(self.handle, option, int(value)),

@@ -616,6 +616,13 @@ int spkv_cache_threshold_logit(const spkv_cache_t* c, float* theta) {
     return SPKV_OK;
 }
 
+int spkv_cache_set_tau(spkv_cache_t* c, float tau) {
+    if (c == nullptr || tau != tau) return SPKV_E_INVAL;
+    c->cfg.tau = tau;
+    c->view.theta = logit_threshold(tau);
+    return SPKV_OK;
+}
+
 int spkv_cache_set_option(spkv_cache_t* c, int32_t option, int64_t value) {
     if (c == nullptr) return SPKV_E_INVAL;
     switch (option) {

@@ -498,3 +498,53 @@ def test_chunk_rejects_long_chunks():
     cache.decode_chunk(k, v, f, stream.next_query(rows=4), cu)
     assert cache.stats().total_tokens == 4
     cache.close()
+
+
+# ------------------------------------------------------------- live threshold change
+def test_set_tau_between_calls_all_entry_points():
+    """tau changed between calls: pairs leave the window under the threshold in force at
+    that moment, whichever call pushes them out (single append, bulk append, fused step,
+    multi-token step, prefill attention); the oracle keeps the threshold history."""
+    wl = small_workload("tauchg", 3, 8, 2, 64, [0, 0, 0], 0.5, window=32, seed=77)
+    stream = TokenStream(wl, device="cuda")
+    cache = H.make_cache(wl, pool_tokens=3 * 2 * 1200, extra_context=1200)
+    oracle = H.make_oracle(wl)
+
+    def mirror(k, v, f, cu):
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+
+    def check(label):
+        H.check_state(cache, oracle, wl, label=label)
+
+    k, v, f, cu = stream.next_tokens([200, 40, 3]); cache.append(k, v, f, cu); mirror(k, v, f, cu)
+    check("bulk, tau 0.5")
+    for tau in (0.8, 0.2):
+        cache.set_tau(tau); oracle.set_tau(tau)
+        assert cache.threshold_logit() == float(threshold_logit(tau))
+        k, v, f, cu = stream.next_tokens([70, 1, 33]); cache.append(k, v, f, cu); mirror(k, v, f, cu)
+        check(f"bulk, tau {tau}")
+        for _ in range(3):
+            k, v, f, cu = stream.next_tokens([1, 1, 1]); q = stream.next_query()
+            cache.append(k, v, f, cu); mirror(k, v, f, cu)
+            H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0], f"tau {tau}")
+    cache.set_tau(0.6); oracle.set_tau(0.6)
+    for _ in range(40):                                    # fused steps push old-threshold pairs out
+        k, v, f, cu = stream.next_tokens([1, 1, 1]); q = stream.next_query()
+        out = cache.decode_step(k, v, f, q); mirror(k, v, f, cu)
+        H.check_output(out, oracle.decode(to_numpy_f32(q))[0], "fused, tau 0.6")
+    check("fused, tau 0.6")
+    cache.set_tau(0.35); oracle.set_tau(0.35)
+    for counts in ([16, 5, 9], [16, 16, 16]):
+        k, v, f, cu = stream.next_tokens(counts); q = stream.next_query(rows=sum(counts))
+        out = cache.decode_chunk(k, v, f, q, cu); mirror(k, v, f, cu)
+        H.check_output(out, oracle.decode_chunk(to_numpy_f32(q), counts)[0], "chunk, tau 0.35")
+    check("chunk, tau 0.35")
+    cache.set_tau(0.7); oracle.set_tau(0.7)
+    counts = [150, 64, 1]
+    k, v, f, cu = stream.next_tokens(counts); q = stream.next_query(rows=sum(counts))
+    out = cache.prefill_attention(k, v, f, q, cu); mirror(k, v, f, cu)
+    H.check_output(out, oracle.decode_chunk(to_numpy_f32(q), counts)[0], "prefill, tau 0.7")
+    check("prefill, tau 0.7")
+    with pytest.raises(spkv.SPKVError):
+        cache.set_tau(float("nan"))
+    cache.close()

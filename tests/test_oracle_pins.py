@@ -355,6 +355,7 @@ class _ThresholdSignFlipped(SPKVOracle):         # theta with the wrong sign
     def __init__(self, *a, **kw):
         super().__init__(*a, **kw)
         self.theta = np.float32(-self.theta)
+        self._theta_hist = [[(0, self.theta)] for _ in range(self.B)]
 
 
 MUTANTS = [_WindowOffByOne, _StrictGate, _NoScale, _KeptOffByOne, _GateIgnored,
@@ -454,3 +455,63 @@ def test_decode_chunk_matches_sdpa_rows_and_single_steps():
             for b in act:
                 np.testing.assert_allclose(o1[b], out[qoff[b] + i], rtol=1e-12, atol=1e-13)
                 np.testing.assert_allclose(l1[b], lse[qoff[b] + i], rtol=1e-12, atol=1e-13)
+
+
+def test_live_threshold_change_matches_a_step_by_step_cache_simulation():
+    """Pin for set_tau: the appendix describes the cache as a process -- when the window is
+    full, the pair leaving it is kept iff its gate is on (here: with the threshold in force
+    at that moment), otherwise dropped.  A literal simulation of that process (a window list,
+    a kept list, one token at a time, plain Python) must give the oracle's kept lists, its
+    gate-on count and, with explicit softmax loops over kept + window, its decode output."""
+    rng = np.random.default_rng(91)
+    B, Hq, Hkv, D, w = 2, 4, 2, 4, 3
+    taus = {0: 0.5, 7: 0.8, 12: 0.2, 13: 0.65, 20: 0.5}      # step -> new tau
+    o = SPKVOracle(B, Hq, Hkv, D, window=w, tau=taus[0])
+    window = [[[] for _ in range(Hkv)] for _ in range(B)]    # (pos, k, v, f)
+    kept = [[[] for _ in range(Hkv)] for _ in range(B)]
+    n_tok = [0] * B
+    gate_on = 0
+    theta = threshold_logit(taus[0])
+    scale = 1.0 / math.sqrt(D)
+    for step in range(26):
+        if step in taus and step > 0:
+            o.set_tau(taus[step])
+            theta = threshold_logit(taus[step])
+        counts = [1, 1] if step % 5 else [2, 0]               # sequence 1 lags behind
+        total = sum(counts)
+        k = rng.standard_normal((total, Hkv, D)).astype(np.float32)
+        v = rng.standard_normal((total, Hkv, D)).astype(np.float32)
+        f = rng.standard_normal((total, Hkv)).astype(np.float32)
+        cu = [0, counts[0], total]
+        o.append(k, v, f, cu)
+        for b in range(B):
+            for r in range(cu[b], cu[b + 1]):
+                for h in range(Hkv):
+                    if len(window[b][h]) == w:                # window full: one pair leaves
+                        old = window[b][h].pop(0)
+                        if old[3] >= theta:
+                            kept[b][h].append(old)
+                    window[b][h].append((n_tok[b], k[r, h], v[r, h], f[r, h]))
+                    gate_on += int(f[r, h] >= theta)
+                n_tok[b] += 1
+        for b in range(B):
+            for h in range(Hkv):
+                assert o.kept_positions(b, h).tolist() == [e[0] for e in kept[b][h]], (step, b, h)
+        assert o.stats()["gate_on_tokens"] == gate_on
+        if all(n_tok):
+            q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+            out, lse = o.decode(q)
+            for b in range(B):
+                for h in range(Hkv):
+                    entries = kept[b][h] + window[b][h]
+                    for g in range(Hq // Hkv):
+                        j = h * (Hq // Hkv) + g
+                        sc = [scale * math.fsum(float(q[b, j, d]) * float(e[1][d]) for d in range(D))
+                              for e in entries]
+                        mx = max(sc)
+                        wt = [math.exp(x - mx) for x in sc]
+                        z = math.fsum(wt)
+                        for d in range(D):
+                            ref = math.fsum(a * float(e[2][d]) for a, e in zip(wt, entries)) / z
+                            assert abs(out[b, j, d] - ref) < 1e-12
+                        assert abs(lse[b, j] - (mx + math.log(z))) < 1e-12
