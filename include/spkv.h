@@ -110,6 +110,20 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
 /* Free the host object.  Synchronises nothing; the caller frees the arena afterwards. */
 int spkv_cache_destroy(spkv_cache_t* cache);
 
+/* Capacity growth ("Inference Kernels" appendix: the cache is given headroom and grows when
+ * it runs out).  The library never allocates, so growth is a move: the caller provides a new,
+ * larger arena for a configuration with the same shape (batch, heads, head_dim, window) and
+ * max_context / max_total_kept_tokens not smaller than before; the call copies the whole
+ * cache state into it on `stream` (page ids stay valid: pages are indices into the pool) and
+ * the cache continues there.  The old arena must stay untouched until the work enqueued on
+ * `stream` up to and including this call has completed; after that it is the caller's again.
+ * new_cfg->tau is ignored (the live threshold stays).  Typical use: spkv_append returned
+ * SPKV_E_CAPACITY -> grow -> repeat the append.
+ * SPKV_E_INVAL: shape differs, a limit shrinks, arena too small, misaligned or overlapping
+ * the current one (the cache is unchanged). */
+int spkv_cache_grow(spkv_cache_t* cache, const spkv_config_t* new_cfg, void* new_dev_arena,
+                    size_t new_arena_bytes, void* stream);
+
 /* Forget every token (all sequences back to length 0); enqueues the zero fill. */
 int spkv_cache_reset(spkv_cache_t* cache, void* stream);
 

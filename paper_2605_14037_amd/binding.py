@@ -19,7 +19,8 @@ OPT_ITEM_TARGET, OPT_KERNEL_TIMING, OPT_SPLIT_ONLY = 1, 2, 3
 MAX_BATCH, PAGE_TOKENS = 512, 64
 
 EXPORTED_SYMBOLS = [
-    "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_reset",
+    "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_grow",
+    "spkv_cache_reset",
     "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk",
     "spkv_prefill_workspace_bytes", "spkv_prefill_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
@@ -75,6 +76,8 @@ def load_library():
     lib.spkv_cache_create.argtypes = [P(SPKVConfig), vp, C.c_size_t, vp, P(vp)]
     lib.spkv_cache_destroy.restype = C.c_int
     lib.spkv_cache_destroy.argtypes = [vp]
+    lib.spkv_cache_grow.restype = C.c_int
+    lib.spkv_cache_grow.argtypes = [vp, P(SPKVConfig), vp, C.c_size_t, vp]
     lib.spkv_cache_reset.restype = C.c_int
     lib.spkv_cache_reset.argtypes = [vp, vp]
     lib.spkv_append.restype = C.c_int
@@ -190,6 +193,24 @@ class SPKVCache:
         _check(self.lib.spkv_cache_create(C.byref(self.cfg), C.c_void_p(self.arena.data_ptr()),
                                           nbytes, _stream(), C.byref(self.handle)),
                "spkv_cache_create")
+
+    def grow(self, max_context=None, max_total_kept_tokens=None):
+        """Move the cache into a new, larger arena (spkv_cache_grow).  The old arena is
+        released once the copy has completed."""
+        old = self.cfg
+        cfg = SPKVConfig(old.batch, old.n_q_heads, old.n_kv_heads, old.head_dim, old.window, 0,
+                         old.tau,
+                         old.max_context if max_context is None else int(max_context),
+                         old.max_total_kept_tokens if max_total_kept_tokens is None
+                         else int(max_total_kept_tokens))
+        nbytes = required_bytes(cfg)
+        if nbytes == 0:
+            raise SPKVError(E_INVAL, "spkv_cache_required_bytes")
+        arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        _check(self.lib.spkv_cache_grow(self.handle, C.byref(cfg), C.c_void_p(arena.data_ptr()),
+                                        nbytes, _stream()), "spkv_cache_grow")
+        torch.cuda.current_stream(self.device).synchronize()    # the old arena is read until here
+        self.arena, self.cfg = arena, cfg
 
     def close(self):
         if getattr(self, "handle", None) is not None and self.handle.value:

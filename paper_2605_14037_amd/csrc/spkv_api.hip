@@ -123,6 +123,46 @@ struct spkv_cache {
 
 namespace {
 
+// Point the device-side view at the regions of the cache's arena.
+void bind_view(spkv_cache* c) {
+    const spkv_config_t* cfg = &c->cfg;
+    const Carve& k = c->carve;
+    SpkvView& v = c->view;
+    v.B = cfg->batch;
+    v.Hq = cfg->n_q_heads;
+    v.Hkv = cfg->n_kv_heads;
+    v.G = k.G;
+    v.D = cfg->head_dim;
+    v.w = cfg->window;
+    v.n_pairs = k.n_pairs;
+    v.n_ring_pages = k.n_ring_pages;
+    v.pt_cap = k.pt_cap;
+    v.n_pages = k.n_pages;
+    v.n_seg_cap = k.n_seg_cap;
+    v.max_items = k.max_items;
+    v.theta = logit_threshold(cfg->tau);
+    char* a = c->arena;
+    v.ring = reinterpret_cast<uint16_t*>(a + k.ring);
+    v.ring_logit = reinterpret_cast<float*>(a + k.ring_logit);
+    v.t_pair = reinterpret_cast<int32_t*>(a + k.t_pair);
+    v.kept_len = reinterpret_cast<int32_t*>(a + k.kept_len);
+    v.gate_on = reinterpret_cast<int32_t*>(a + k.gate_on);
+    v.pool_next = reinterpret_cast<int32_t*>(a + k.pool_next);
+    v.free_top = reinterpret_cast<int32_t*>(a + k.free_top);
+    v.free_pages = reinterpret_cast<int32_t*>(a + k.free_pages);
+    v.err_flag = reinterpret_cast<int32_t*>(a + k.err_flag);
+    v.page_table = reinterpret_cast<int32_t*>(a + k.page_table);
+    v.pool = reinterpret_cast<uint16_t*>(a + k.pool);
+    v.pos_pool = reinterpret_cast<int32_t*>(a + k.pos_pool);
+    v.seg_count = reinterpret_cast<int32_t*>(a + k.seg_count);
+    v.seg_on = reinterpret_cast<int32_t*>(a + k.seg_on);
+    v.bulk_info = reinterpret_cast<int32_t*>(a + k.bulk_info);
+    v.part_acc = reinterpret_cast<float*>(a + k.part_acc);
+    v.part_ml = reinterpret_cast<float*>(a + k.part_ml);
+    v.pair_items = reinterpret_cast<int32_t*>(a + k.pair_items);
+    v.pos_scratch = reinterpret_cast<int32_t*>(a + k.pos_scratch);
+}
+
 // Read the exact long-term lengths back and tighten the host's bound.  Synchronises.
 int refresh_bound(spkv_cache* c, hipStream_t s, int32_t* kept_len_out) {
     std::vector<int32_t> len(c->carve.n_pairs);
@@ -271,46 +311,67 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->timing = false;
     c->split_only = false;
     c->n_timed = 0;
-    SpkvView& v = c->view;
-    v.B = cfg->batch;
-    v.Hq = cfg->n_q_heads;
-    v.Hkv = cfg->n_kv_heads;
-    v.G = k.G;
-    v.D = cfg->head_dim;
-    v.w = cfg->window;
-    v.n_pairs = k.n_pairs;
-    v.n_ring_pages = k.n_ring_pages;
-    v.pt_cap = k.pt_cap;
-    v.n_pages = k.n_pages;
-    v.n_seg_cap = k.n_seg_cap;
-    v.max_items = k.max_items;
-    v.theta = logit_threshold(cfg->tau);
-    char* a = c->arena;
-    v.ring = reinterpret_cast<uint16_t*>(a + k.ring);
-    v.ring_logit = reinterpret_cast<float*>(a + k.ring_logit);
-    v.t_pair = reinterpret_cast<int32_t*>(a + k.t_pair);
-    v.kept_len = reinterpret_cast<int32_t*>(a + k.kept_len);
-    v.gate_on = reinterpret_cast<int32_t*>(a + k.gate_on);
-    v.pool_next = reinterpret_cast<int32_t*>(a + k.pool_next);
-    v.free_top = reinterpret_cast<int32_t*>(a + k.free_top);
-    v.free_pages = reinterpret_cast<int32_t*>(a + k.free_pages);
-    v.err_flag = reinterpret_cast<int32_t*>(a + k.err_flag);
-    v.page_table = reinterpret_cast<int32_t*>(a + k.page_table);
-    v.pool = reinterpret_cast<uint16_t*>(a + k.pool);
-    v.pos_pool = reinterpret_cast<int32_t*>(a + k.pos_pool);
-    v.seg_count = reinterpret_cast<int32_t*>(a + k.seg_count);
-    v.seg_on = reinterpret_cast<int32_t*>(a + k.seg_on);
-    v.bulk_info = reinterpret_cast<int32_t*>(a + k.bulk_info);
-    v.part_acc = reinterpret_cast<float*>(a + k.part_acc);
-    v.part_ml = reinterpret_cast<float*>(a + k.part_ml);
-    v.pair_items = reinterpret_cast<int32_t*>(a + k.pair_items);
-    v.pos_scratch = reinterpret_cast<int32_t*>(a + k.pos_scratch);
+    bind_view(c);
     if (spkv_launch_fill_zero(c->arena, c->arena_bytes, static_cast<hipStream_t>(stream)) !=
         hipSuccess) {
         delete c;
         return SPKV_E_HIP;
     }
     *out = c;
+    return SPKV_OK;
+}
+
+int spkv_cache_grow(spkv_cache_t* c, const spkv_config_t* cfg, void* dev_arena, size_t arena_bytes,
+                    void* stream) {
+    if (c == nullptr || cfg == nullptr) return SPKV_E_INVAL;
+    const spkv_config_t& o = c->cfg;
+    if (cfg->batch != o.batch || cfg->n_q_heads != o.n_q_heads || cfg->n_kv_heads != o.n_kv_heads ||
+        cfg->head_dim != o.head_dim || cfg->window != o.window)
+        return SPKV_E_INVAL;
+    if (cfg->max_context < o.max_context || cfg->max_total_kept_tokens < o.max_total_kept_tokens)
+        return SPKV_E_INVAL;
+    Carve k;
+    if (!carve(cfg, &k)) return SPKV_E_INVAL;
+    char* na = static_cast<char*>(dev_arena);
+    if (na == nullptr || (reinterpret_cast<uintptr_t>(na) % kAlign) != 0 || arena_bytes < k.total)
+        return SPKV_E_INVAL;
+    // the two arenas must not overlap
+    if (na < c->arena + c->arena_bytes && c->arena < na + k.total) return SPKV_E_INVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Carve& q = c->carve;
+    const size_t page_bytes = (size_t)spkv_page_elems(o.head_dim) * 2;
+    if (spkv_launch_fill_zero(na, k.total, s) != hipSuccess) return SPKV_E_HIP;
+    struct Region { size_t to, from, bytes; };
+    const Region regions[] = {
+        {k.ring, q.ring, (size_t)q.n_pairs * q.n_ring_pages * page_bytes},
+        {k.ring_logit, q.ring_logit, (size_t)q.n_pairs * o.window * 4},
+        {k.t_pair, q.t_pair, (size_t)q.n_pairs * 4},
+        {k.kept_len, q.kept_len, (size_t)q.n_pairs * 4},
+        {k.gate_on, q.gate_on, (size_t)q.n_pairs * 4},
+        {k.pool_next, q.pool_next, 4},
+        {k.free_top, q.free_top, 4},
+        {k.free_pages, q.free_pages, (size_t)q.n_pages * 4},
+        {k.err_flag, q.err_flag, 4},
+        {k.pool, q.pool, (size_t)q.n_pages * page_bytes},
+        {k.pos_pool, q.pos_pool, (size_t)q.n_pages * kPageTokens * 4},
+    };
+    // every region starts on a 256-byte boundary and is padded to one, and no region
+    // shrinks, so copying the padded size stays inside the new region
+    for (const Region& r : regions)
+        if (spkv_launch_copy(na + r.to, c->arena + r.from, align_up(r.bytes), s) != hipSuccess)
+            return SPKV_E_HIP;
+    if (spkv_launch_copy_rows(reinterpret_cast<int32_t*>(na + k.page_table),
+                              reinterpret_cast<const int32_t*>(c->arena + q.page_table), q.n_pairs,
+                              q.pt_cap, k.pt_cap, s) != hipSuccess)
+        return SPKV_E_HIP;
+    const float tau = c->cfg.tau;
+    c->cfg = *cfg;
+    c->cfg.page_tokens = SPKV_PAGE_TOKENS;
+    c->cfg.tau = tau;                    // the live threshold stays (see spkv_cache_set_tau)
+    c->carve = k;
+    c->arena = na;
+    c->arena_bytes = k.total;
+    bind_view(c);
     return SPKV_OK;
 }
 

@@ -48,6 +48,9 @@ struct SpkvCu {
 
 hipError_t spkv_launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// rows rows of src_width int32 into the first columns of rows of dst_width (>= src_width).
+hipError_t spkv_launch_copy_rows(int32_t* dst, const int32_t* src, int rows, int src_width,
+                                 int dst_width, hipStream_t s);
 hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const SpkvCu& cu, hipStream_t s);
 // prefix: null, or where the prefill attention wants the per-token long-term prefix counts.

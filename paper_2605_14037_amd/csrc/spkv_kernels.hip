@@ -14,6 +14,8 @@
 // Eq. 3-4; the window ring holds exactly the keys with 0 <= t - s < w and the long-term
 // pages exactly the gated-on keys with t - s >= w, so the two sets are disjoint and their
 // union is the available set of Eq. 5.
+#include <algorithm>
+
 #include "spkv_internal.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -93,6 +95,25 @@ hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_
     if (blocks > 256 * 64) blocks = 256 * 64;
     spkv_plain_copy<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(
         static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void spkv_copy_rows(int32_t* __restrict__ dst,
+                                                      const int32_t* __restrict__ src, int rows,
+                                                      int src_width, int dst_width) {
+    const size_t n = (size_t)rows * src_width;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const size_t r = i / src_width, c = i - r * src_width;
+        dst[r * dst_width + c] = src[i];
+    }
+}
+
+hipError_t spkv_launch_copy_rows(int32_t* dst, const int32_t* src, int rows, int src_width,
+                                 int dst_width, hipStream_t s) {
+    const size_t n = (size_t)rows * src_width;
+    if (n == 0) return hipSuccess;
+    const size_t blocks = std::min<size_t>((n + 255) / 256, 256 * 16);
+    spkv_copy_rows<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(dst, src, rows, src_width, dst_width);
     return hipGetLastError();
 }
 

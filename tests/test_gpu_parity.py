@@ -548,3 +548,47 @@ def test_set_tau_between_calls_all_entry_points():
     with pytest.raises(spkv.SPKVError):
         cache.set_tau(float("nan"))
     cache.close()
+
+
+# ------------------------------------------------------------------ capacity growth
+def test_grow_after_capacity_error_continues_exactly():
+    """A pool sized for a fraction of the tokens: the append that would overflow it is refused
+    before any launch; after spkv_cache_grow the same append succeeds and the cache -- kept
+    lists, recycled pages, window, statistics, decode output -- is what the oracle says."""
+    wl = small_workload("grow", 3, 8, 2, 128, [0, 0, 0], 0.6, window=64, seed=88)
+    stream = TokenStream(wl, device="cuda")
+    cache = spkv.SPKVCache(3, 8, 2, 128, max_context=700, max_total_kept_tokens=900, window=64)
+    oracle = H.make_oracle(wl)
+
+    def feed(counts):
+        k, v, f, cu = stream.next_tokens(counts)
+        cache.append(k, v, f, cu)
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+
+    feed([300, 150, 40])
+    cache.release_sequence(1); oracle.release_sequence(1)       # some pages on the free stack
+    feed([100, 30, 100])
+    H.check_state(cache, oracle, wl, label="before growth")
+    k, v, f, cu = stream.next_tokens([290, 290, 290])            # 3 * 2 * 290 more pairs could be kept
+    with pytest.raises(spkv.SPKVError) as e:
+        cache.append(k, v, f, cu)
+    assert e.value.code == -3
+    H.check_state(cache, oracle, wl, label="after the refused append")
+    with pytest.raises(spkv.SPKVError):                          # limits may not shrink
+        cache.grow(max_context=600)
+    cache.grow(max_context=4000, max_total_kept_tokens=20000)
+    assert cache.stats().pool_pages_total >= 20000 // 64
+    H.check_state(cache, oracle, wl, label="right after growth")
+    cache.append(k, v, f, cu)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    H.check_state(cache, oracle, wl, label="append after growth")
+    for _ in range(3):
+        k, v, f, cu = stream.next_tokens([1, 1, 1]); q = stream.next_query()
+        out = cache.decode_step(k, v, f, q)
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        H.check_output(out, oracle.decode(to_numpy_f32(q))[0], "decode after growth")
+    feed([1500, 0, 2000])                                        # beyond the old max_context
+    q = stream.next_query()
+    H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0], "long after growth")
+    H.check_state(cache, oracle, wl, label="long after growth")
+    cache.close()
