@@ -94,6 +94,11 @@ typedef struct spkv_stats {
 #define SPKV_OPT_SPLIT_ONLY     3  /* 1: spkv_decode_attention launches the split-K kernel
                                       only (no combine, `out` and `lse` left untouched):
                                       lets a harness time that kernel back to back        */
+#define SPKV_OPT_SINK_TOKENS    4  /* n >= 0: the first n positions of every sequence are always
+                                      kept when they leave the window, whatever their logit
+                                      (attention sinks, an ablation variant in the paper; the
+                                      default 0 is the paper's method).  Only while the cache is
+                                      empty (after create or reset): SPKV_E_STATE otherwise. */
 
 /* Bytes of device arena a cache with this configuration needs (0 if cfg is invalid).
  * Host-only; touches no device.  Capacity rule: the long-term cache can hold

@@ -90,7 +90,7 @@ class SPKVOracle:
     """
 
     def __init__(self, batch, n_q_heads, n_kv_heads, head_dim, window=128,
-                 tau=0.5, sm_scale=None, store_dtype=np.float32, track_kv=True):
+                 tau=0.5, sm_scale=None, store_dtype=np.float32, track_kv=True, n_sink=0):
         if n_q_heads % n_kv_heads != 0:
             raise ValueError("n_q_heads must be a multiple of n_kv_heads")
         if window < 1:
@@ -98,6 +98,9 @@ class SPKVOracle:
         self.B, self.Hq, self.Hkv, self.D = batch, n_q_heads, n_kv_heads, head_dim
         self.G = n_q_heads // n_kv_heads
         self.w = int(window)
+        # Optional attention sinks (the "fixed attention sinks" ablation): the first n_sink
+        # positions of a sequence count as gated on whatever their logit.  0 = the method.
+        self.n_sink = int(n_sink)
         self.theta = threshold_logit(tau)
         self.scale = (1.0 / math.sqrt(head_dim)) if sm_scale is None else float(sm_scale)
         self.store_dtype = store_dtype
@@ -196,13 +199,13 @@ class SPKVOracle:
         s = np.arange(self.seq_len(b))
         theta = self._theta_when_stored(b, s + self.w)
         theta[s + self.w >= self.seq_len(b)] = self.theta
-        return self._f(b)[:, h] >= theta
+        return (self._f(b)[:, h] >= theta) | (s < self.n_sink)
 
     def gate_at_append(self, b, h):
         """The same comparison with the threshold in force when s itself was stored: the
         z_s that Eq. 8 sums over all positions."""
         s = np.arange(self.seq_len(b))
-        return self._f(b)[:, h] >= self._theta_when_stored(b, s)
+        return (self._f(b)[:, h] >= self._theta_when_stored(b, s)) | (s < self.n_sink)
 
     def kept_positions(self, b, h):
         """Ascending positions held by the long-term cache of (b, h): gated-on

@@ -112,6 +112,7 @@ struct spkv_cache {
     int64_t pages_ub;             // sum of pages_for(L_ub): upper bound of pool pages in use
     bool bound_is_loose;          // a bulk append grew L_ub by far more than the truth
     int item_target;
+    int n_sink;                   // always-kept first positions (SPKV_OPT_SINK_TOKENS)
     int one_round_items;          // items the chip runs in one resident round, with a margin
     int chunk_round_items[3];     // the same for the chunk kernel with 1, 2, 4 column groups
     SpkvSplit split;              // partition used by the last decode call
@@ -141,6 +142,7 @@ void bind_view(spkv_cache* c) {
     v.n_seg_cap = k.n_seg_cap;
     v.max_items = k.max_items;
     v.theta = logit_threshold(cfg->tau);
+    v.n_sink = c->n_sink;
     char* a = c->arena;
     v.ring = reinterpret_cast<uint16_t*>(a + k.ring);
     v.ring_logit = reinterpret_cast<float*>(a + k.ring_logit);
@@ -300,6 +302,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->pages_ub = 0;
     c->bound_is_loose = false;
     c->item_target = 0;
+    c->n_sink = 0;
     {
         // Measured on MI355X: up to 94 % of the resident slots run in one round; at 99 % some
         // compute units already queue a second item and the launch takes 15-20 % longer.
@@ -693,6 +696,13 @@ int spkv_cache_set_option(spkv_cache_t* c, int32_t option, int64_t value) {
             return SPKV_OK;
         case SPKV_OPT_SPLIT_ONLY:
             c->split_only = value != 0;
+            return SPKV_OK;
+        case SPKV_OPT_SINK_TOKENS:
+            if (value < 0 || value > c->cfg.max_context) return SPKV_E_INVAL;
+            for (int32_t t : c->T)
+                if (t != 0) return SPKV_E_STATE;
+            c->n_sink = (int)value;
+            c->view.n_sink = (int)value;
             return SPKV_OK;
         case SPKV_OPT_KERNEL_TIMING:
             c->timing = value != 0;

@@ -19,6 +19,7 @@ struct SpkvView {
     int32_t n_seg_cap;      // bulk-append segments per (seq, head)
     int32_t max_items;      // capacity (work-item slots) of the partial buffers
     float   theta;          // gate threshold on the logit
+    int32_t n_sink;         // first positions of every sequence that are always kept (0: none)
 
     uint16_t* ring;         // [n_pairs][n_ring_pages] pages (K and V interleaved by half)
     float*    ring_logit;   // [n_pairs][w]

@@ -51,6 +51,13 @@ __device__ __forceinline__ uint16_t* pool_page(const SpkvView& v, int page) {
     return v.pool + (size_t)page * (size_t)spkv_page_elems(v.D);
 }
 
+// The gate of the pair at position pos with utility logit f: Eq. 2 on the logit, or one of
+// the first n_sink positions of the sequence (optional always-kept attention sinks, the
+// "fixed attention sinks" variant of the ablations; n_sink = 0 is the paper's method).
+__device__ __forceinline__ bool gate_passes(const SpkvView& v, float f, int pos) {
+    return f >= v.theta || pos < v.n_sink;
+}
+
 // One pool page for the caller: a recycled one if the stack of released pages has any,
 // else the next never-used one; -1 if the pool is exhausted.  Pushes onto the stack happen
 // only in spkv_release_sequence, never in the same launch as pops, and a failed pop puts
@@ -177,7 +184,7 @@ __device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T,
     const bool full = T >= v.w;
     const int lp = L >> 6, gk = L & 63;
     const bool have_page = gk != 0 && lp < v.pt_cap;
-    if (full && r.f_old >= v.theta) {                             // Eq. 2 on the logit
+    if (full && gate_passes(v, r.f_old, T - v.w)) {               // Eq. 2 on the logit
         int page = r.page_entry;
         if (!have_page) {                                         // first pair of a new page
             if (tid == 0) {
@@ -204,7 +211,7 @@ __device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T,
     if (tid == 0) {
         v.ring_logit[(size_t)pair * v.w + slot] = r.f_new;
         v.t_pair[pair] = T + 1;
-        if (r.f_new >= v.theta) v.gate_on[pair] += 1;
+        if (gate_passes(v, r.f_new, T)) v.gate_on[pair] += 1;
     }
 }
 
@@ -275,7 +282,7 @@ __global__ __launch_bounds__(256) void spkv_bulk_count(SpkvView v, const float* 
     const int j = seg * kSegTokens + (int)threadIdx.x;
     if (seg * kSegTokens >= n) return;
     __shared__ int s_ev[4], s_on[4];
-    const bool on = j < n && f[((size_t)cu.v[b] + j) * v.Hkv + h] >= v.theta;
+    const bool on = j < n && gate_passes(v, f[((size_t)cu.v[b] + j) * v.Hkv + h], v.t_pair[pair] + j);
     const int c_on = __popcll(__ballot(on));
     const int c_ev = __popcll(__ballot(on && j < n_ev));
     if (lane_id() == 0) {
@@ -345,7 +352,7 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
     int cnt = 0;
     for (int base = 0; base < nr; base += 256) {
         const int idx = base + tid;
-        const bool flag = idx < nr && rl[(r0 + idx) % v.w] >= v.theta;
+        const bool flag = idx < nr && gate_passes(v, rl[(r0 + idx) % v.w], r0 + idx);
         cnt += __popcll(__ballot(flag));
     }
     if (lane == 0) s_w[wave] = cnt;
@@ -408,7 +415,7 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
     int done = 0;
     for (int base = 0; base < nr; base += 256) {
         const int idx = base + tid;
-        const bool flag = idx < nr && rl[(r0 + idx) % v.w] >= v.theta;
+        const bool flag = idx < nr && gate_passes(v, rl[(r0 + idx) % v.w], r0 + idx);
         int tot;
         const int rank = block_excl_scan(flag ? 1 : 0, s_w, tot);
         if (flag) s_list[rank] = (uint16_t)tid;
@@ -467,7 +474,7 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
     __shared__ __attribute__((aligned(16))) uint16_t s_v[4][8][D];
 
     const int j = j0 + tid;
-    const bool on = j < n && f[((size_t)row0 + j) * v.Hkv + h] >= v.theta;
+    const bool on = j < n && gate_passes(v, f[((size_t)row0 + j) * v.Hkv + h], bi.T_old + j);
     const bool ev = on && j < n_ev;
     const unsigned long long mask = __ballot(ev);
     if (lane == 0) s_cnt[wave] = __popcll(mask);
@@ -718,7 +725,7 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
     int drop_hp = -1, drop_r = -1;
     if (FUSED && hp1 > ps.ghp && ps.T >= v.w) {
         const int slot = ps.T % v.w;
-        if (!(v.ring_logit[(size_t)pair * v.w + slot] >= v.theta)) {
+        if (!gate_passes(v, v.ring_logit[(size_t)pair * v.w + slot], ps.T - v.w)) {
             drop_hp = ps.ghp + (slot >> 5);
             drop_r = slot & 31;
         }
@@ -1018,7 +1025,7 @@ __global__ __launch_bounds__(64) void spkv_chunk_split(SpkvView v, const uint16_
                 for (int e = 0; e < 8; ++e) {
                     const int x = x0 + e;
                     age[e] = ps.T >= v.w ? (x - t_mod + v.w) % v.w : x + v.w - ps.T;
-                    if (kc * 8 + e < nvalid && rl[x] >= v.theta) gate_ok |= 1u << e;
+                    if (kc * 8 + e < nvalid && gate_passes(v, rl[x], ps.T - v.w + age[e])) gate_ok |= 1u << e;
                 }
             }
             const uint16_t* kp = base + lane * 8;

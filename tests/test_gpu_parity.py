@@ -592,3 +592,54 @@ def test_grow_after_capacity_error_continues_exactly():
     H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0], "long after growth")
     H.check_state(cache, oracle, wl, label="long after growth")
     cache.close()
+
+
+# ------------------------------------------------------------------ attention sinks
+@pytest.mark.parametrize("n_sink,w", [(4, 32), (1, 128), (40, 16)])
+def test_sink_tokens_every_entry_point(n_sink, w):
+    """SPKV_OPT_SINK_TOKENS: the first n positions of every sequence are kept whatever their
+    logit, through every write path (single, bulk, fused step, multi-token step, prefill) and
+    after a sequence slot is reused; keep rate 5 % so that the sinks matter."""
+    wl = small_workload("sinks", 3, 8, 2, 64, [0, 0, 0], 0.05, window=w, seed=n_sink * 7 + w)
+    stream = TokenStream(wl, device="cuda")
+    cache = H.make_cache(wl, pool_tokens=3 * 2 * 1500, extra_context=1500)
+    cache.set_option(spkv.OPT_SINK_TOKENS, n_sink)
+    oracle = SPKVOracle(3, 8, 2, 64, window=w, tau=0.5, n_sink=n_sink)
+
+    def mirror(k, v, f, cu):
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+
+    k, v, f, cu = stream.next_tokens([1, 0, 0]); cache.append(k, v, f, cu); mirror(k, v, f, cu)
+    with pytest.raises(spkv.SPKVError) as e:                 # only on an empty cache
+        cache.set_option(spkv.OPT_SINK_TOKENS, 2)
+    assert e.value.code == -2
+    for _ in range(w + n_sink + 3):                          # single appends push the sinks out
+        k, v, f, cu = stream.next_tokens([1, 1, 0]); q = stream.next_query()
+        cache.append(k, v, f, cu); mirror(k, v, f, cu)
+    H.check_state(cache, oracle, wl, label="single appends")
+    k, v, f, cu = stream.next_tokens([200, 3, 2 * w + n_sink + 9]); cache.append(k, v, f, cu); mirror(k, v, f, cu)
+    H.check_state(cache, oracle, wl, label="bulk")
+    for _ in range(w + 5):                                   # fused steps
+        k, v, f, cu = stream.next_tokens([1, 1, 1]); q = stream.next_query()
+        out = cache.decode_step(k, v, f, q); mirror(k, v, f, cu)
+        H.check_output(out, oracle.decode(to_numpy_f32(q))[0], "fused")
+    H.check_state(cache, oracle, wl, label="fused")
+    cache.release_sequence(1); oracle.release_sequence(1)
+    n = min(16, w)
+    for counts in ([n, n, n], [n, n, 0], [n, n, 3]) * 3:     # the reused slot grows by chunks
+        k, v, f, cu = stream.next_tokens(counts); q = stream.next_query(rows=sum(counts))
+        out = cache.decode_chunk(k, v, f, q, cu); mirror(k, v, f, cu)
+        H.check_output(out, oracle.decode_chunk(to_numpy_f32(q), counts)[0], "chunk")
+    H.check_state(cache, oracle, wl, label="chunk")
+    cache.release_sequence(2); oracle.release_sequence(2)
+    counts = [70, 1, w + n_sink + 50]
+    k, v, f, cu = stream.next_tokens(counts); q = stream.next_query(rows=sum(counts))
+    out = cache.prefill_attention(k, v, f, q, cu); mirror(k, v, f, cu)
+    H.check_output(out, oracle.decode_chunk(to_numpy_f32(q), counts)[0], "prefill")
+    st = H.check_state(cache, oracle, wl, label="prefill")
+    for b in range(3):
+        for h in range(2):
+            T = oracle.seq_len(b)
+            want = [s for s in range(n_sink) if s <= T - 1 - w]
+            assert cache.kept_positions(b, h)[:len(want)] == want
+    cache.close()

@@ -515,3 +515,32 @@ def test_live_threshold_change_matches_a_step_by_step_cache_simulation():
                             ref = math.fsum(a * float(e[2][d]) for a, e in zip(wt, entries)) / z
                             assert abs(out[b, j, d] - ref) < 1e-12
                         assert abs(lse[b, j] - (mx + math.log(z))) < 1e-12
+
+
+def test_sinks_pinned_to_sdpa_with_the_sink_columns_unmasked():
+    """Pin for n_sink: against torch's fp64 scaled_dot_product_attention with the boolean mask
+    causal & (window | gate | first n_sink columns), last row -- the listing's masked
+    attention with the ablation's always-visible first positions."""
+    rng = np.random.default_rng(5)
+    B, Hq, Hkv, D, w, T, ns = 1, 4, 2, 8, 5, 40, 3
+    k = rng.standard_normal((T, Hkv, D)).astype(np.float32)
+    v = rng.standard_normal((T, Hkv, D)).astype(np.float32)
+    f = rng.standard_normal((T, Hkv)).astype(np.float32) - 1.0
+    q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+    o = SPKVOracle(B, Hq, Hkv, D, window=w, tau=0.5, n_sink=ns)
+    o.append(k, v, f, [0, T])
+    out, _ = o.decode(q)
+    s = torch.arange(T)
+    for h in range(Hkv):
+        mask = ((T - 1 - s) < w) | torch.from_numpy(f[:, h] >= 0.0) | (s < ns)
+        kept = o.kept_positions(0, h).tolist()
+        assert kept == [int(x) for x in s[(torch.from_numpy(f[:, h] >= 0.0) | (s < ns)) & (s <= T - 1 - w)]]
+        for g in range(Hq // Hkv):
+            j = h * (Hq // Hkv) + g
+            ref = torch.nn.functional.scaled_dot_product_attention(
+                torch.from_numpy(q[0, j]).double().view(1, 1, 1, D),
+                torch.from_numpy(k[:, h]).double().view(1, 1, T, D),
+                torch.from_numpy(v[:, h]).double().view(1, 1, T, D),
+                attn_mask=mask.view(1, 1, 1, T))
+            assert np.allclose(out[0, j], ref.view(D).numpy(), atol=1e-12)
+    assert set(range(ns)) <= set(o.kept_positions(0, 0).tolist())
