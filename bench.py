@@ -153,6 +153,37 @@ def prefill_attention_leg(wl: Workload, chunk: int, timed_calls: int, tau=None, 
     return res
 
 
+def soft_gated_leg(batch=4, ctx=16384, n_q_heads=32, n_kv_heads=8, head_dim=128, window=128, reps=3):
+    """spkv_soft_gated_attention (training-time forward, Eq. 6) on whole sequences: dense
+    causal attention with the gate bias; flops = 4 D per (query head, key <= query)."""
+    g = torch.Generator(device="cuda").manual_seed(20260514)
+    total = batch * ctx
+    q = torch.randn(total, n_q_heads, head_dim, generator=g, device="cuda").to(torch.bfloat16)
+    k = torch.randn(total, n_kv_heads, head_dim, generator=g, device="cuda").to(torch.bfloat16)
+    v = torch.randn(total, n_kv_heads, head_dim, generator=g, device="cuda").to(torch.bfloat16)
+    f = (torch.randn(total, n_kv_heads, generator=g, device="cuda") * 2.0 - 1.0).contiguous()
+    cu = [b * ctx for b in range(batch + 1)]
+    lib = spkv.load_library()
+    ws = torch.empty(int(lib.spkv_soft_gated_workspace_bytes(batch, n_kv_heads, head_dim, window, ctx)),
+                     dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(q)
+    spkv.soft_gated_attention(q, k, v, f, cu, window=window, out=out, workspace=ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        spkv.soft_gated_attention(q, k, v, f, cu, window=window, out=out, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    flops = 4.0 * head_dim * n_q_heads * batch * (ctx * (ctx + 1) / 2)
+    return {"what": "spkv_soft_gated_attention: causal attention with bias log u outside the window",
+            "batch": batch, "ctx": ctx, "heads": f"{n_q_heads}q/{n_kv_heads}kv", "head_dim": head_dim,
+            "window": window, "ms_per_call": ms, "tokens_per_s": total / (ms * 1e-3),
+            "algorithmic_TFLOP": flops / 1e12, "TFLOPs": flops / (ms * 1e-3) / 1e12,
+            "frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+
 HOST_ISSUE_S = []      # host time spent issuing each timed region (before the final sync)
 
 
@@ -385,6 +416,8 @@ def main():
     ap.add_argument("--prefill-chunk", type=int, default=2048)
     ap.add_argument("--prefill-tau", type=float, default=None)
     ap.add_argument("--prefill-calls", type=int, default=0, help="timed calls (0 = whole prompt)")
+    ap.add_argument("--soft-gated", action="store_true",
+                    help="run only the soft-gated attention forward leg (batch 4 x 16384 tokens)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="run only the plain 1 GiB copy kernel 20 times (profiler calibration)")
     args = ap.parse_args()
@@ -412,6 +445,10 @@ def main():
 
     if args.scaling:
         scaling_sweep(args)
+        return
+
+    if args.soft_gated:
+        print(json.dumps({"soft_gated_attention": soft_gated_leg()}))
         return
 
     wl = workload(args.workload)

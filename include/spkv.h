@@ -218,6 +218,29 @@ int spkv_prefill_attention(spkv_cache_t* cache, const void* k, const void* v,
                            void* out, float* lse, float sm_scale, void* workspace,
                            size_t workspace_bytes, void* stream);
 
+/* Soft-gated attention forward (training phase 1, Eq. 6 and the soft branch of the
+ * reference listing): causal attention over whole sequences in which a key inside the window
+ * of its query (0 <= t - s < window) attends unchanged and every older key gets the additive
+ * bias log u_s = log sigmoid(f_s) on its pre-softmax score -- the differentiable stand-in for
+ * the hard gate, and the limit it is annealed from.  Stateless: no cache is involved.
+ * log u is taken exactly, from the logit, as -softplus(-f) in fp32 (the listing's
+ * log(u + 1e-8) guards a gradient, not the forward value).
+ *   q, out       device bf16 [total, n_q_heads, head_dim]     lse device fp32 [total, n_q_heads] or NULL
+ *   k, v         device bf16 [total, n_kv_heads, head_dim]    util_logits device fp32 [total, n_kv_heads]
+ *   cu_seqlens   host int32 [batch + 1]: sequence b owns rows cu[b] .. cu[b+1]-1, positions 0..
+ *   workspace    device memory, 256-byte aligned, spkv_soft_gated_workspace_bytes(...) bytes
+ *                for the longest sequence of the call; caller-owned, contents disposable
+ * Same kernels as spkv_prefill_attention (keys staged in the page layout, MFMA tile loop);
+ * cost is that of dense causal attention.  Returns SPKV_E_INVAL for bad shapes, pointers or
+ * a workspace that is too small. */
+size_t spkv_soft_gated_workspace_bytes(int32_t batch, int32_t n_kv_heads, int32_t head_dim,
+                                       int32_t window, int32_t max_tokens_per_sequence);
+int spkv_soft_gated_attention(const void* q, const void* k, const void* v, const float* util_logits,
+                              const int32_t* cu_seqlens, int32_t batch, int32_t n_q_heads,
+                              int32_t n_kv_heads, int32_t head_dim, int32_t window, void* out,
+                              float* lse, float sm_scale, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
 /* Forget sequence b (for example when its request has finished): its window and long-term
  * entries are dropped, its pages return to the pool for reuse by any sequence, and slot b
  * holds an empty sequence that can be appended to again.  (The paper's cache manager grows

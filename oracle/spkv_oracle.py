@@ -81,6 +81,54 @@ def utility_logits(hidden, w1, b1, w2, b2):
     return f
 
 
+def soft_gated_attention(q, k, v, util_logits, cu_seqlens, window, sm_scale=None):
+    """Soft-gated attention forward (training phase 1; Eq. 6 and the soft branch of the
+    listing appendix), fp64, over whole packed sequences.
+
+    For the query at position t of a sequence and every key s <= t: pre-softmax score
+    scale * q_t . k_s, plus the bias log u_s = log sigmoid(f_s) when the key is outside the
+    window (t - s >= window); keys inside the window (0 <= t - s < window) get no bias.
+    q: [total, H_q, D]; k, v: [total, H_kv, D]; util_logits: fp32 [total, H_kv]; query head j
+    reads KV head j // (H_q / H_kv).  log u is taken exactly from the logit
+    (log sigmoid(f) = -log(1 + exp(-f))), not as log(u + 1e-8): that epsilon only keeps a
+    gradient finite.  Returns (out [total, H_q, D], lse [total, H_q])."""
+    q = np.asarray(q, np.float64)
+    k = np.asarray(k, np.float64)
+    v = np.asarray(v, np.float64)
+    f = np.asarray(util_logits)
+    if f.dtype != np.float32:
+        raise TypeError("utility logits must be float32")
+    f = f.astype(np.float64)
+    total, Hq, D = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    scale = (1.0 / math.sqrt(D)) if sm_scale is None else float(sm_scale)
+    log_u = -np.logaddexp(0.0, -f)                       # log sigmoid(f), stable
+    out = np.zeros((total, Hq, D))
+    lse = np.zeros((total, Hq))
+    for b in range(len(cu_seqlens) - 1):
+        lo, hi = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        T = hi - lo
+        if T == 0:
+            continue
+        t = np.arange(T)[:, None]
+        s = np.arange(T)[None, :]
+        causal = s <= t
+        outside = causal & ((t - s) >= window)
+        for h in range(Hkv):
+            bias = np.where(outside, log_u[lo:hi, h][None, :], 0.0)
+            bias = np.where(causal, bias, -np.inf)
+            for g in range(G):
+                j = h * G + g
+                x = scale * (q[lo:hi, j, :] @ k[lo:hi, h, :].T) + bias
+                mx = x.max(axis=1, keepdims=True)
+                e = np.exp(x - mx)
+                den = e.sum(axis=1, keepdims=True)
+                out[lo:hi, j, :] = (e @ v[lo:hi, h, :]) / den
+                lse[lo:hi, j] = (mx + np.log(den))[:, 0]
+    return out, lse
+
+
 class SPKVOracle:
     """Dense-history SP-KV decode attention, one instance per attention layer.
 

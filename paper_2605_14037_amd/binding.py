@@ -22,7 +22,8 @@ EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_grow",
     "spkv_cache_reset",
     "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk",
-    "spkv_prefill_workspace_bytes", "spkv_prefill_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
+    "spkv_prefill_workspace_bytes", "spkv_prefill_attention",
+    "spkv_soft_gated_workspace_bytes", "spkv_soft_gated_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
     "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
@@ -92,6 +93,11 @@ def load_library():
     lib.spkv_prefill_workspace_bytes.argtypes = [vp, i32, i64]
     lib.spkv_prefill_attention.restype = C.c_int
     lib.spkv_prefill_attention.argtypes = [vp, vp, vp, vp, vp, P(i32), vp, vp, f32, vp, C.c_size_t, vp]
+    lib.spkv_soft_gated_workspace_bytes.restype = C.c_size_t
+    lib.spkv_soft_gated_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.spkv_soft_gated_attention.restype = C.c_int
+    lib.spkv_soft_gated_attention.argtypes = [vp, vp, vp, vp, P(i32), i32, i32, i32, i32, i32, vp, vp,
+                                              f32, vp, C.c_size_t, vp]
     lib.spkv_cache_release_sequence.restype = C.c_int
     lib.spkv_cache_release_sequence.argtypes = [vp, i32, vp]
     lib.spkv_utility_logits.restype = C.c_int
@@ -138,6 +144,36 @@ def debug_copy(dst: torch.Tensor, src: torch.Tensor):
         raise ValueError("debug_copy: need contiguous cuda tensors of equal byte size")
     _check(load_library().spkv_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
                                           nbytes, _stream()), "spkv_debug_copy")
+
+
+def soft_gated_attention(q, k, v, util_logits, cu_seqlens, window=128, sm_scale=0.0, out=None,
+                         want_lse=False, workspace=None):
+    """Soft-gated attention forward over packed sequences (spkv_soft_gated_attention).
+    q: bf16 [total, H_q, D]; k, v: bf16 [total, H_kv, D]; util_logits: fp32 [total, H_kv]."""
+    lib = load_library()
+    total, Hq, D = q.shape
+    Hkv = k.shape[1]
+    batch = len(cu_seqlens) - 1
+    cu = (C.c_int32 * (batch + 1))(*[int(x) for x in cu_seqlens])
+    if cu[batch] != total:
+        raise ValueError("cu_seqlens does not cover the rows")
+    qp = _dev_ptr(q, torch.bfloat16, (total, Hq, D), "q")
+    kp = _dev_ptr(k, torch.bfloat16, (total, Hkv, D), "k")
+    vp = _dev_ptr(v, torch.bfloat16, (total, Hkv, D), "v")
+    fp = _dev_ptr(util_logits, torch.float32, (total, Hkv), "util_logits")
+    n_max = max(cu[b + 1] - cu[b] for b in range(batch))
+    if workspace is None:
+        need = int(lib.spkv_soft_gated_workspace_bytes(batch, Hkv, D, int(window), max(n_max, 1)))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if out is None:
+        out = torch.empty_like(q)
+    op = _dev_ptr(out, torch.bfloat16, (total, Hq, D), "out")
+    lse = torch.empty((total, Hq), dtype=torch.float32, device=q.device) if want_lse else None
+    lp = _dev_ptr(lse, torch.float32, (total, Hq), "lse") if lse is not None else None
+    _check(lib.spkv_soft_gated_attention(qp, kp, vp, fp, cu, batch, Hq, Hkv, D, int(window), op, lp,
+                                         float(sm_scale), workspace.data_ptr(), workspace.numel(),
+                                         _stream()), "spkv_soft_gated_attention")
+    return (out, lse) if want_lse else out
 
 
 def utility_logits(hidden, w1, b1, w2, b2, out=None, workspace=None):

@@ -593,6 +593,90 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
     return SPKV_OK;
 }
 
+namespace {
+// Workspace of spkv_soft_gated_attention: [zeros: n_pairs int32][bias][staging half-pages].
+struct SoftCarve {
+    size_t zeros, bias, stage, total;
+    int shp, n_pairs;
+};
+bool soft_carve(int batch, int n_kv_heads, int head_dim, int window, int64_t n_max, SoftCarve* o) {
+    if (batch < 1 || batch > SPKV_MAX_BATCH || n_kv_heads < 1 || (head_dim != 64 && head_dim != 128) ||
+        window < 1 || window > (1 << 20) || n_max < 1 || n_max > (1 << 30) ||
+        (int64_t)batch * n_kv_heads > 16384)
+        return false;
+    o->n_pairs = batch * n_kv_heads;
+    o->shp = (int)((window + n_max + kHalfTokens - 1) / kHalfTokens);
+    const size_t half_bytes = (size_t)2 * kHalfTokens * head_dim * 2;
+    o->zeros = 0;
+    o->bias = align_up((size_t)o->n_pairs * 4);
+    o->stage = o->bias + align_up((size_t)o->n_pairs * o->shp * kHalfTokens * 4);
+    o->total = o->stage + (size_t)o->n_pairs * o->shp * half_bytes;
+    return true;
+}
+}  // namespace
+
+size_t spkv_soft_gated_workspace_bytes(int32_t batch, int32_t n_kv_heads, int32_t head_dim,
+                                       int32_t window, int32_t max_tokens_per_sequence) {
+    SoftCarve k;
+    return soft_carve(batch, n_kv_heads, head_dim, window, max_tokens_per_sequence, &k) ? k.total : 0;
+}
+
+int spkv_soft_gated_attention(const void* q, const void* k, const void* v, const float* util_logits,
+                              const int32_t* cu_seqlens, int32_t batch, int32_t n_q_heads,
+                              int32_t n_kv_heads, int32_t head_dim, int32_t window, void* out,
+                              float* lse, float sm_scale, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    if (cu_seqlens == nullptr || batch < 1 || batch > SPKV_MAX_BATCH || n_kv_heads < 1 ||
+        n_q_heads < 1 || n_q_heads % n_kv_heads != 0 || n_q_heads / n_kv_heads > 16)
+        return SPKV_E_INVAL;
+    if (cu_seqlens[0] != 0) return SPKV_E_INVAL;
+    int64_t n_max = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int64_t n = (int64_t)cu_seqlens[b + 1] - cu_seqlens[b];
+        if (n < 0) return SPKV_E_INVAL;
+        n_max = std::max(n_max, n);
+    }
+    if (n_max == 0) return SPKV_OK;
+    SoftCarve sc;
+    if (!soft_carve(batch, n_kv_heads, head_dim, window, n_max, &sc)) return SPKV_E_INVAL;
+    if (q == nullptr || k == nullptr || v == nullptr || util_logits == nullptr || out == nullptr ||
+        workspace == nullptr || workspace_bytes < sc.total)
+        return SPKV_E_INVAL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(util_logits) || !aligned16(out) ||
+        (lse != nullptr && !aligned16(lse)) || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return SPKV_E_INVAL;
+    if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)head_dim);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    if (spkv_launch_fill_zero(ws + sc.zeros, sc.bias, s) != hipSuccess) return SPKV_E_HIP;
+    // A view that only carries the shape: no sequence holds a token (t_pair = kept_len = 0),
+    // so the kernels take every key from the staging rows of this call.
+    SpkvView vw{};
+    vw.B = batch;
+    vw.Hq = n_q_heads;
+    vw.Hkv = n_kv_heads;
+    vw.G = n_q_heads / n_kv_heads;
+    vw.D = head_dim;
+    vw.w = window;
+    vw.n_pairs = sc.n_pairs;
+    vw.n_ring_pages = (window + kPageTokens - 1) / kPageTokens;
+    vw.pt_cap = 1;
+    vw.n_pages = 1;
+    vw.t_pair = reinterpret_cast<int32_t*>(ws + sc.zeros);
+    vw.kept_len = vw.t_pair;
+    vw.page_table = vw.t_pair;
+    vw.pool = reinterpret_cast<uint16_t*>(ws + sc.stage);
+    vw.ring = vw.pool;
+    SpkvCu cu;
+    std::memcpy(cu.v, cu_seqlens, (size_t)(batch + 1) * 4);
+    if (spkv_launch_soft_gated(vw, static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
+                               util_logits, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
+                               lse, sm_scale, cu, (int)n_max, reinterpret_cast<uint16_t*>(ws + sc.stage),
+                               reinterpret_cast<float*>(ws + sc.bias), sc.shp, s) != hipSuccess)
+        return SPKV_E_HIP;
+    return SPKV_OK;
+}
+
 int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void* stream) {
     if (c == nullptr || st == nullptr) return SPKV_E_INVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -75,6 +75,10 @@ hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const u
 hipError_t spkv_launch_decode_chunk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                     const uint16_t* q, uint16_t* out, float* lse, float sm_scale,
                                     SpkvSplit split, const SpkvCu& cu, int col_groups, hipStream_t s);
+hipError_t spkv_launch_soft_gated(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                  const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                                  float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
+                                  float* bias, int shp, hipStream_t s);
 int spkv_chunk_resident_items(int head_dim, int col_groups);
 // Prefill attention of n <= n_max new tokens per sequence plus their append.  stage:
 // n_pairs * shp staging half-pages (shp >= ceil((w + n_max) / 32)); prefix: one int32 per

@@ -1224,6 +1224,7 @@ int spkv_chunk_resident_items(int head_dim, int col_groups) {
 struct SpkvPrefill {
     uint16_t* stage;     // [n_pairs][shp] half-pages
     int32_t*  prefix;    // [total tokens][H_kv]
+    float*    bias;      // soft gating only: [n_pairs][shp][32] log2 u of every staging row
     int32_t   shp;       // staging half-pages per pair
     int32_t   tb;        // tokens per wave (32 / G)
     int32_t   nblk;      // workgroups (spans of 8 tb tokens) per pair in the grid
@@ -1258,10 +1259,12 @@ __device__ __forceinline__ void store_v_units(uint16_t* dp, int dk0, const uint1
 // without a position (before the sequence start, past the chunk) are zero, so that a
 // masked key never meets a non-finite V element.  Runs BEFORE the append (reads the ring
 // and the token count as they were).
+// With pf.bias set (soft gating) it also stores log2 u = log2 sigmoid(f) of every new row.
 template <int D>
 __global__ __launch_bounds__(256) void spkv_prefill_stage(SpkvView v, const uint16_t* __restrict__ k,
                                                           const uint16_t* __restrict__ vv,
-                                                          SpkvCu cu, SpkvPrefill pf) {
+                                                          const float* __restrict__ f, SpkvCu cu,
+                                                          SpkvPrefill pf) {
     const int pair = blockIdx.y, sh = blockIdx.x;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int row0 = cu.v[b], n = cu.v[b + 1] - row0;
@@ -1300,6 +1303,16 @@ __global__ __launch_bounds__(256) void spkv_prefill_stage(SpkvView v, const uint
             }
             *reinterpret_cast<uint4*>(dp + spkv_k_off(D, wave * 8 + row, c * 8)) = kk;
             *reinterpret_cast<uint4*>(&s_v[wave][row][c * 8]) = vl;
+        }
+        if (pf.bias != nullptr && c == 0) {
+            float lb = 0.f;
+            if (u >= v.w && u - v.w < n) {
+                // log u = log sigmoid(f) = -softplus(-f) (Eq. 1 and the soft gate), in log2
+                const float x = f[((size_t)row0 + (u - v.w)) * v.Hkv + h];
+                const float ls = x < -20.f ? x : -log1pf(__expf(-x));
+                lb = ls * 1.4426950408889634f;
+            }
+            pf.bias[((size_t)pair * pf.shp + sh) * kHalfTokens + wave * 8 + row] = lb;
         }
     }
     __builtin_amdgcn_wave_barrier();
@@ -1438,7 +1451,7 @@ __device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float s
 // can run beside the other's MFMAs.  (Measured alternatives: four waves of 64 columns, one
 // per SIMD, 15 % slower -- every latency is exposed; the same with the tile loop software-
 // pipelined by hand, slower still; issue priority for one wave of each SIMD, 27 % slower.)
-template <int D>
+template <int D, bool SOFT>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
                                                            uint16_t* __restrict__ out,
                                                            float* __restrict__ lse, float scale_log2e,
@@ -1478,11 +1491,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int tbv = max(0, min(pf.tb, n_tok - i0)), i_last = i0 + tbv - 1, cols = tbv * v.G;
     const bool active = tbv > 0;
     // the cache is in the state after the append
-    const int T0 = v.t_pair[pair] - n_tok, L = v.kept_len[pair];
+    const int T0 = SOFT ? 0 : v.t_pair[pair] - n_tok, L = SOFT ? 0 : v.kept_len[pair];
     const int u_min = max(0, v.w - T0);     // first staging row that holds a position
 
     auto prefix_of = [&](int i) -> int {   // long-term entries at least w behind token i
-        if (T0 + i - v.w < 0) return 0;
+        if (SOFT || T0 + i - v.w < 0) return 0;
         return min(max(pf.prefix[((size_t)row0 + i) * v.Hkv + h], 0), L);
     };
 
@@ -1510,9 +1523,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int fullA = active ? prefix_of(i0) >> 5 : 0;
     // staging half-pages: rows (span0, span_last + w] that hold a position; this wave's
     // windows cover rows [lo_w, hi_w]
-    const int sB0 = max(span0 + 1, u_min) >> 5;
+    const int sB0 = (SOFT ? u_min : max(span0 + 1, u_min)) >> 5;
     const int nB = ((span_last + v.w) >> 5) - sB0 + 1;
-    const int lo_w = max(i0 + 1, u_min), hi_w = i_last + v.w;
+    const int lo_w = SOFT ? u_min : max(i0 + 1, u_min), hi_w = i_last + v.w;
     const int n_hp = nA + nB, last = n_hp - 1;
 
     const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
@@ -1560,7 +1573,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     bool resume = false, pending = false;
     float xs[NQ][8];
     while (x < n_hp) {
-        if (pending) rescale_columns<D, NQ>(xs, scale_log2e, acc, m, l);
+        if (pending) rescale_columns<D, NQ>(xs, SOFT ? 1.0f : scale_log2e, acc, m, l);
         for (; x < n_hp; ++x) {
             if (!resume) {
                 // next tile (after the last one: the same tile again, into the idle buffer)
@@ -1591,17 +1604,45 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                         for (int c = 0; c < NQ; ++c) kill[c] = bit_range8(0, cnt[c] - k0 - 1) ^ 0xffu;
                     }
                 } else {
+                    // soft gating: a tile of rows that all hold a position and all lie at or
+                    // before every token of the wave needs no mask
+                    if (SOFT && u_tile >= u_min && u_tile + kHalfTokens - 1 <= i0 + v.w) any = false;
                     const int u0 = u_tile + kc * 8;
-                    // window of token i: rows i < u <= i + w that hold a position
+                    // window of token i: rows i < u <= i + w that hold a position (soft
+                    // gating: every earlier row as well)
 #pragma unroll
                     for (int c = 0; c < NQ; ++c)
-                        kill[c] = (tok[c] >= 0 ? bit_range8(max(tok[c] + 1, u_min) - u0, tok[c] + v.w - u0)
+                        kill[c] = (tok[c] >= 0 ? bit_range8((SOFT ? u_min : max(tok[c] + 1, u_min)) - u0,
+                                                            tok[c] + v.w - u0)
                                                : 0u) ^ 0xffu;
                 }
                 tile_scores<D, NQ>(tile, lane, qb, kill, any, xs);
+                if (SOFT) {
+                    // scores to the log2 domain plus the gate bias log2 u of every key outside
+                    // the window of its query (row u <= i); masked scores stay -inf
+                    const int u0 = u_tile + kc * 8;
+                    const float4* bp = reinterpret_cast<const float4*>(
+                        pf.bias + ((size_t)pair * pf.shp + (u_tile >> 5)) * kHalfTokens + kc * 8);
+                    const float4 b0 = bp[0], b1 = bp[1];
+                    const float bias[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+                    if (u_tile + kHalfTokens - 1 <= i0) {       // outside every window of the wave
+#pragma unroll
+                        for (int c = 0; c < NQ; ++c)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                xs[c][e] = __builtin_fmaf(xs[c][e], scale_log2e, bias[e]);
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < NQ; ++c)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                xs[c][e] = __builtin_fmaf(xs[c][e], scale_log2e,
+                                                          u0 + e <= tok[c] ? bias[e] : 0.f);
+                    }
+                }
                 f32x8 pw[NQ];
                 float psum[NQ];
-                if (tile_weights<NQ>(xs, scale_log2e, m, pw, psum) && !pending) {
+                if (tile_weights<NQ>(xs, SOFT ? 1.0f : scale_log2e, m, pw, psum) && !pending) {
                     pending = true;
                     resume = true;
                     break;
@@ -1641,30 +1682,63 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 }
 
-hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
-                               const float* f, const uint16_t* q, uint16_t* out, float* lse,
-                               float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
-                               int32_t* prefix, int shp, hipStream_t s) {
+static SpkvPrefill prefill_params(const SpkvView& v, int n_max, uint16_t* stage, int32_t* prefix,
+                                  float* bias, int shp) {
     SpkvPrefill pf;
     pf.stage = stage;
     pf.prefix = prefix;
+    pf.bias = bias;
     pf.shp = shp;
     pf.tb = (16 * kPrefillGroups) / v.G;
     pf.nblk = (n_max + kPrefillWaves * pf.tb - 1) / (kPrefillWaves * pf.tb);   // spans of one workgroup
     pf.pin_xcd = (v.n_pairs >= 8 && pf.nblk >= 4) ? 1 : 0;
+    return pf;
+}
+
+static unsigned prefill_grid(const SpkvView& v, const SpkvPrefill& pf) {
+    return pf.pin_xcd ? 8u * (unsigned)((v.n_pairs + 7) / 8) * (unsigned)pf.nblk
+                      : (unsigned)v.n_pairs * (unsigned)pf.nblk;
+}
+
+hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                               const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                               float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
+                               int32_t* prefix, int shp, hipStream_t s) {
+    const SpkvPrefill pf = prefill_params(v, n_max, stage, prefix, nullptr, shp);
     const float sl = sm_scale * 1.4426950408889634f;
     const int stage_hps = (v.w + n_max + kHalfTokens - 1) / kHalfTokens;
-    const unsigned grid = pf.pin_xcd ? 8u * (unsigned)((v.n_pairs + 7) / 8) * (unsigned)pf.nblk
-                                     : (unsigned)v.n_pairs * (unsigned)pf.nblk;
+    const unsigned grid = prefill_grid(v, pf);
     hipError_t e;
     if (v.D == 128) {
-        spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, cu, pf);
+        spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
-        spkv_prefill_attend<128><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        spkv_prefill_attend<128, false><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
     } else {
-        spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, cu, pf);
+        spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
-        spkv_prefill_attend<64><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        spkv_prefill_attend<64, false><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    }
+    return hipGetLastError();
+}
+
+// Soft-gated attention of whole sequences (no cache): the same staging and the same tile
+// loop with every earlier row visible and the bias log2 u on the rows outside the window.
+// v: a view that only describes the shape (B, heads, D, w, n_pairs) and whose t_pair points
+// at n_pairs zeros.
+hipError_t spkv_launch_soft_gated(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                  const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                                  float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
+                                  float* bias, int shp, hipStream_t s) {
+    const SpkvPrefill pf = prefill_params(v, n_max, stage, nullptr, bias, shp);
+    const float sl = sm_scale * 1.4426950408889634f;
+    const int stage_hps = (v.w + n_max + kHalfTokens - 1) / kHalfTokens;
+    const unsigned grid = prefill_grid(v, pf);
+    if (v.D == 128) {
+        spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
+        spkv_prefill_attend<128, true><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    } else {
+        spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
+        spkv_prefill_attend<64, true><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
     }
     return hipGetLastError();
 }

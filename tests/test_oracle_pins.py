@@ -544,3 +544,61 @@ def test_sinks_pinned_to_sdpa_with_the_sink_columns_unmasked():
                 attn_mask=mask.view(1, 1, 1, T))
             assert np.allclose(out[0, j], ref.view(D).numpy(), atol=1e-12)
     assert set(range(ns)) <= set(o.kept_positions(0, 0).tolist())
+
+
+def test_soft_gated_attention_pins():
+    """Pins for the soft-gated forward (Eq. 6): (i) torch's fp64 scaled_dot_product_attention
+    with the listing's additive mask (0 inside the window, log u outside, -inf for the
+    future); (ii) gates fully open (f = +40, log u = 0 to 4e-18) = dense causal attention;
+    (iii) gates shut (f = -60: weight e^-60) = sliding-window attention within 1e-20;
+    (iv) window >= T = dense causal attention whatever the gates; (v) the listing's
+    log(u + 1e-8) agrees for moderate logits."""
+    from oracle.spkv_oracle import soft_gated_attention
+    rng = np.random.default_rng(17)
+    Hq, Hkv, D, w = 4, 2, 8, 4
+    cu = [0, 19, 19, 30]
+    total = cu[-1]
+    q = rng.standard_normal((total, Hq, D)).astype(np.float32)
+    k = rng.standard_normal((total, Hkv, D)).astype(np.float32)
+    v = rng.standard_normal((total, Hkv, D)).astype(np.float32)
+    f = (2.0 * rng.standard_normal((total, Hkv))).astype(np.float32)
+
+    def sdpa(fl, window, eps=0.0):
+        out = np.zeros((total, Hq, D))
+        for b in range(len(cu) - 1):
+            lo, hi = cu[b], cu[b + 1]
+            T = hi - lo
+            if T == 0:
+                continue
+            qi = torch.arange(T).unsqueeze(1)
+            ki = torch.arange(T).unsqueeze(0)
+            causal = ki <= qi
+            in_window = causal & ((qi - ki) < window)
+            for j in range(Hq):
+                h = j // (Hq // Hkv)
+                u = torch.sigmoid(torch.from_numpy(fl[lo:hi, h]).double())
+                gate = torch.log(u + eps)
+                mask = torch.where(in_window, 0.0, torch.where(causal, gate[None, :], float("-inf")))
+                o = torch.nn.functional.scaled_dot_product_attention(
+                    torch.from_numpy(q[lo:hi, j]).double()[None, None],
+                    torch.from_numpy(k[lo:hi, h]).double()[None, None],
+                    torch.from_numpy(v[lo:hi, h]).double()[None, None], attn_mask=mask[None, None])
+                out[lo:hi, j] = o[0, 0].numpy()
+        return out
+
+    out, lse = soft_gated_attention(q, k, v, f, cu, w)
+    assert np.allclose(out, sdpa(f, w), atol=1e-12)                          # (i)
+    assert np.allclose(out, sdpa(f, w, eps=1e-8), atol=1e-5)                 # (v)
+    f_open = np.full_like(f, 40.0)
+    dense = sdpa(f_open, 10 ** 6)
+    assert np.allclose(soft_gated_attention(q, k, v, f_open, cu, w)[0], dense, atol=1e-12)   # (ii)
+    f_shut = np.full_like(f, -60.0)
+    swa = sdpa(np.full_like(f, -1e4), w)          # log u = -1e4: exactly no weight outside the window
+    assert np.allclose(soft_gated_attention(q, k, v, f_shut, cu, w)[0], swa, atol=1e-20 + 1e-12)  # (iii)
+    assert np.allclose(soft_gated_attention(q, k, v, f, cu, 64)[0], dense, atol=1e-12)       # (iv)
+    # lse: log of the biased partition sum, checked on one row by hand
+    t, j, lo = 9, 3, 0
+    h = j // (Hq // Hkv)
+    xs = [float(q[lo + t, j].astype(np.float64) @ k[lo + s, h].astype(np.float64)) / math.sqrt(D)
+          + (0.0 if t - s < w else -math.log1p(math.exp(-float(f[lo + s, h])))) for s in range(t + 1)]
+    assert abs(lse[lo + t, j] - math.log(math.fsum(math.exp(x) for x in xs))) < 1e-12
