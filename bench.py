@@ -10,7 +10,8 @@ HBM before the timed region.  The workload is the Llama-3-8B-shaped layer: batch
 rates U[0.10, 0.33].  Several independent cache instances are rotated so that the working
 set is far larger than the 256 MB Infinity Cache and every step reads its K/V from HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: the metric, its value and unit, the step time, `roofline` (dominant
+kernel against the HBM peak) and `cpu_baseline` (the fp64 oracle on a bounded sample).
 """
 
 from __future__ import annotations
@@ -423,7 +424,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (every sequence and "
-              "KV head is independent; see DESIGN.md for how it would shard). Use --gpus 1.",
+              "KV head is independent, so the path shards by sequence or by head without exchange). Use --gpus 1.",
               file=sys.stderr)
         sys.exit(2)
     assert torch.cuda.is_available(), "bench.py needs an MI355X"

@@ -9,7 +9,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspkv.so")
-SOURCES = ["spkv_api.hip", "spkv_kernels.hip"]
+SOURCES = ["spkv_api.hip", "spkv_write.hip", "spkv_decode.hip", "spkv_prefill.hip",
+           "spkv_predictor.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

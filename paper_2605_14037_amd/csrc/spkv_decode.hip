@@ -1,0 +1,589 @@
+// Read path of the SP-KV cache on gfx950 (MI355X, wave64, MFMA):
+//   spkv_decode_split    split-K flash decoding, one wave per work item, K/V tiles consumed
+//                        as MFMA operands straight from the page layout
+//   spkv_decode_combine  log-sum-exp merge of the partials
+//   fused step           spkv_decode_split<.., true> + spkv_combine_append: append and decode
+//                        of one token per sequence in two launches instead of three
+//   multi-token step     spkv_chunk_split + spkv_chunk_combine: up to 16 new tokens per sequence
+#include "spkv_device.h"
+
+// One wavefront per work item.  The G <= 16 query heads of the GQA group are the N = 16
+// columns of every MFMA, so each K/V tile is read exactly once per group.  Every wave-wide
+// load is 1 KB contiguous.
+// Block id = pair * slots + j with an odd slot count: workgroups go round-robin to the 8
+// XCDs, so the items of every pair -- long or short -- spread evenly over all of them
+// (heads differ in kept length by several times; pinning a head to one XCD would leave
+// the others idle), and the odd stride keeps the per-pair remainders from piling up on
+// the low XCDs.
+//
+// FUSED = false: the cache already holds the newest token (spkv_append ran before).
+// FUSED = true (spkv_decode_step): the cache is in the state before the append of the
+// newest token.  The kernel then excludes the ring slot that token will overwrite unless
+// the pair in it passes the gate (it is the pair leaving the window: kept -> it stays
+// attended, as the next long-term entry; dropped -> it is gone), and publishes every
+// pair's item count for spkv_combine_append, which adds the new token's own term.
+template <int D, bool FUSED>
+__global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
+                                                        float scale_log2e, SpkvSplit sp) {
+    constexpr int NS = D / 32;   // head-dim slabs of one K tile
+    constexpr int NB = D / 16;   // 16-wide output blocks
+    const int pair = blockIdx.x / sp.slots;
+    const int j = blockIdx.x - pair * sp.slots;
+    const PairSplit ps = pair_split(v, pair, sp);
+    if (FUSED && j == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.items;
+    if (j >= ps.items) return;
+    const int hbase = ps.nhp / ps.items, hrem = ps.nhp - hbase * ps.items;
+    const int hp0 = j * hbase + min(j, hrem);
+    const int hp1 = hp0 + hbase + (j < hrem ? 1 : 0);
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int lane = threadIdx.x, kc = lane >> 4, n = lane & 15;
+
+    bf16x8 qb[NS];
+    {
+        const uint16_t* qrow = q + ((size_t)b * v.Hq + (size_t)h * v.G + n) * D + kc * 8;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            uint4 raw = {0u, 0u, 0u, 0u};
+            if (n < v.G) raw = *reinterpret_cast<const uint4*>(qrow + sl * 32);
+            qb[sl] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    f32x4 acc[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m = SPKV_NEG_INF, l = 0.f;
+    const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+
+    // Fused step: which ring key (if any) must be left out.  Only items that reach into
+    // the ring look (most do not), and only after their query loads are under way.
+    int drop_hp = -1, drop_r = -1;
+    if (FUSED && hp1 > ps.ghp && ps.T >= v.w) {
+        const int slot = ps.T % v.w;
+        if (!gate_passes(v, v.ring_logit[(size_t)pair * v.w + slot], ps.T - v.w)) {
+            drop_hp = ps.ghp + (slot >> 5);
+            drop_r = slot & 31;
+        }
+    }
+
+    int hp = hp0;
+    while (hp < hp1) {
+        // Page ids of the next 64 logical pages, one per lane; read back with readlane so
+        // that no half-page waits on a dependent table lookup.
+        const int pbase = hp >> 1;
+        const int my_page = pt[min(pbase + lane, v.pt_cap - 1)];
+        const int hp_end = min(hp1, (pbase + 64) << 1);
+        for (; hp < hp_end; ++hp) {
+            const uint16_t* base;
+            int nvalid;
+            if (hp < ps.ghp) {
+                const int page = __builtin_amdgcn_readlane(my_page, (hp >> 1) - pbase);
+                base = pool_page(v, page) + (hp & 1) * (2 * kHalfTokens * D);
+                nvalid = min(kHalfTokens, ps.L - hp * kHalfTokens);
+            } else {
+                const int r = hp - ps.ghp;
+                base = ring_page(v, pair, r >> 1) + (r & 1) * (2 * kHalfTokens * D);
+                nvalid = min(kHalfTokens, ps.Tw - r * kHalfTokens);
+            }
+            // keys past the valid length, and (fused step) the pair leaving the window
+            const int masked_r = (FUSED && hp == drop_hp) ? drop_r : -1;
+            const bool any_kill = nvalid < kHalfTokens || masked_r >= 0;
+            unsigned kill = 0u;
+            if (any_kill) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (kc * 8 + e >= nvalid || kc * 8 + e == masked_r) kill |= 1u << e;
+            }
+            const uint16_t* kp = base + lane * 8;
+            const uint16_t* vp = base + kHalfTokens * D + lane * 8;
+            bf16x8 ka[2][NS], va[NB];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl)
+                    ka[t][sl] = load_stream_b128(kp + (t * (D / 8) + sl * 4) * 128);
+#pragma unroll
+            for (int db = 0; db < NB; ++db) va[db] = load_stream_b128(vp + db * 512);
+            // (Forcing all 16 loads ahead of the first MFMA with a scheduling barrier was
+            // measured 2 % slower than the compiler's interleaving of loads and MFMAs.)
+            attend_half_page<D>(ka, va, qb, kill, any_kill, scale_log2e, acc, m, l);
+        }
+    }
+
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (n < v.G) {
+        const size_t slot = (size_t)pair * sp.slots + j;
+        float* pa = v.part_acc + (slot * v.G + n) * D + kc * 4;
+#pragma unroll
+        for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[db];
+        if (kc == 0) {
+            float* pm = v.part_ml + (slot * v.G + n) * 2;
+            pm[0] = m;
+            pm[1] = l;
+        }
+    }
+}
+
+// One wave folds the partials of one (pair, head) into a running (max, sum, acc) triple:
+// with M the running max,  acc = sum_i 2^(m_i - M) acc_i,  den = sum_i 2^(m_i - M) l_i.
+// The loads of successive items are independent; only the cheap rescaling is chained.
+// Lane owns E = D / 64 output elements.
+template <int D>
+__device__ __forceinline__ void fold_items(const SpkvView& v, size_t slot0, int g, int first,
+                                           int stride, int items, int lane, float& mw, float& den,
+                                           float (&num)[D / 64]) {
+    constexpr int E = D / 64;
+    mw = SPKV_NEG_INF;
+    den = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) num[e] = 0.f;
+#pragma unroll 8
+    for (int i = first; i < items; i += stride) {
+        const float* pm = v.part_ml + ((slot0 + i) * v.G + g) * 2;
+        const float* pa = v.part_acc + ((slot0 + i) * v.G + g) * D + lane * E;
+        const float mi = pm[0], li = pm[1];
+        float a[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) a[e] = pa[e];
+        const float m_new = fmaxf(mw, mi);
+        const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;   // items with no key: weight 0
+        const float so = __builtin_amdgcn_exp2f(mw - m_ref), si = __builtin_amdgcn_exp2f(mi - m_ref);
+        den = den * so + li * si;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] = num[e] * so + a[e] * si;
+        mw = m_new;
+    }
+}
+
+// Merge the partials of one (sequence, query head):
+//   out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i,  lse = (M + log2(sum)) ln 2.
+// One workgroup of 4 waves per (pair, head): the waves take the items round-robin, each
+// lane owns D/64 output elements, and the four wave results meet in LDS.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t* __restrict__ out,
+                                                           float* __restrict__ lse, SpkvSplit sp) {
+    constexpr int E = D / 64;
+    const int pair = blockIdx.x / v.G, g = blockIdx.x - pair * v.G;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int items = pair_split(v, pair, sp).items;
+    const size_t slot0 = (size_t)pair * sp.slots;
+    __shared__ float s_m[4];
+    __shared__ float s_den[4];
+    __shared__ float s_acc[4][D];
+
+    float mw, den, num[E];
+    fold_items<D>(v, slot0, g, wave, 4, items, lane, mw, den, num);
+#pragma unroll
+    for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
+    if (lane == 0) {
+        s_m[wave] = mw;
+        s_den[wave] = den;
+    }
+    __syncthreads();
+    if (tid < D) {
+        const float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+        float nsum = 0.f, dsum = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) {
+            const float sc = __builtin_amdgcn_exp2f(s_m[wv] - M);   // 0 for a wave without items
+            nsum += s_acc[wv][tid] * sc;
+            dsum += s_den[wv] * sc;
+        }
+        const size_t o = ((size_t)b * v.Hq + (size_t)h * v.G + g);
+        const __bf16 r = (__bf16)(nsum / dsum);
+        out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
+        if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
+    }
+}
+
+// Second launch of the fused step: one workgroup per (sequence, query head) merges the
+// partials as spkv_decode_combine does, plus one more term for the new token itself, taken
+// straight from the caller's k_new / v_new (score q . k_new in fp32, weight sum 1, value
+// v_new); the workgroup of the group's first head then performs the append of the new
+// token exactly as spkv_append_step does.  The item
+// count of the pair comes from pair_items (written by the split kernel), not from the
+// counters, so the other heads' workgroups never read what the append is changing.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t* __restrict__ out,
+                                                           float* __restrict__ lse, SpkvSplit sp,
+                                                           const uint16_t* __restrict__ k_new,
+                                                           const uint16_t* __restrict__ v_new,
+                                                           const float* __restrict__ f_new,
+                                                           const uint16_t* __restrict__ q,
+                                                           float scale_log2e) {
+    constexpr int E = D / 64;
+    const int pair = blockIdx.x / v.G, g = blockIdx.x - pair * v.G;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int items = v.pair_items[pair];
+    const size_t kv_row = ((size_t)b * v.Hkv + h) * D;
+    const size_t q_row = ((size_t)b * v.Hq + (size_t)h * v.G + g) * D;
+    // score of the new token for this head (every wave computes it; 6 shuffles)
+    float dot = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const unsigned qe = q[q_row + lane * E + e], ke = k_new[kv_row + lane * E + e];
+        dot += __builtin_bit_cast(float, qe << 16) * __builtin_bit_cast(float, ke << 16);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+    const float m_tok = dot * scale_log2e;
+    const size_t slot0 = (size_t)pair * sp.slots;
+    __shared__ float s_m[4];
+    __shared__ float s_den[4];
+    __shared__ float s_acc[4][D];
+    __shared__ int s_page;
+    // The append's loads are issued before the merge and consumed after it.
+    int T = 0, L = 0;
+    AppendRegs<D> ar;
+    if (g == 0) {
+        T = v.t_pair[pair];
+        L = v.kept_len[pair];
+        ar = append_load<D>(v, pair, h, b, T, L, k_new, v_new, f_new, tid);
+    }
+
+    float mw, den, num[E];
+    fold_items<D>(v, slot0, g, wave, 4, items, lane, mw, den, num);
+#pragma unroll
+    for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
+    if (lane == 0) {
+        s_m[wave] = mw;
+        s_den[wave] = den;
+    }
+    __syncthreads();
+    if (tid < D) {
+        const float M = fmaxf(fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3])), m_tok);
+        const float w_tok = __builtin_amdgcn_exp2f(m_tok - M);
+        const unsigned ve = v_new[kv_row + tid];
+        float nsum = __builtin_bit_cast(float, ve << 16) * w_tok, dsum = w_tok;
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) {
+            const float sc = __builtin_amdgcn_exp2f(s_m[wv] - M);
+            nsum += s_acc[wv][tid] * sc;
+            dsum += s_den[wv] * sc;
+        }
+        const size_t o = ((size_t)b * v.Hq + (size_t)h * v.G + g);
+        const __bf16 r = (__bf16)(nsum / dsum);
+        out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
+        if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
+    }
+    if (g == 0) append_store<D>(v, pair, T, L, ar, tid, &s_page);
+}
+
+// ------------------------------------------------------- multi-token step (chunk)
+// Up to 16 new tokens per sequence attend in one pass (speculative-decoding verification,
+// prompt feed in 16-token chunks): the MFMA columns are (token i, head g) pairs, col =
+// i G + g, in NQ groups of 16, so every K/V tile is still read once per (sequence, KV head).
+// The cache is in the state before the chunk's append.  Long-term keys are available to
+// every token of the chunk (they are at least w + 1 positions behind).  A ring key of age
+// a (0 = oldest, position T - w) is inside the window of chunk token i iff a > i (the window
+// indicator 0 <= t - s < w with t = T + i); otherwise it counts only if its logit passes the
+// gate (Eq. 3-4).  The chunk's own keys (causal, always inside the window because the
+// chunk is not longer than the window) are added by spkv_chunk_combine.
+template <int D, int NQ>
+__global__ __launch_bounds__(64) void spkv_chunk_split(SpkvView v, const uint16_t* __restrict__ q,
+                                                       float scale_log2e, SpkvSplit sp, SpkvCu cu) {
+    constexpr int NS = D / 32, NB = D / 16;
+    const int pair = blockIdx.x / sp.slots;
+    const int j = blockIdx.x - pair * sp.slots;
+    const PairSplit ps = pair_split(v, pair, sp);
+    if (j == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.items;
+    if (j >= ps.items) return;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
+    if (n_tok == 0) return;
+    const int cols = n_tok * v.G;
+    const int hbase = ps.nhp / ps.items, hrem = ps.nhp - hbase * ps.items;
+    const int hp0 = j * hbase + min(j, hrem);
+    const int hp1 = hp0 + hbase + (j < hrem ? 1 : 0);
+    const int lane = threadIdx.x, kc = lane >> 4, n = lane & 15;
+
+    bf16x8 qb[NQ][NS];
+    int tok_of_col[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        const int col = c * 16 + n;
+        const int i = col / v.G, g = col - i * v.G;
+        tok_of_col[c] = i;
+        const uint16_t* qrow = q + ((size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g) * D + kc * 8;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            uint4 raw = {0u, 0u, 0u, 0u};
+            if (col < cols) raw = *reinterpret_cast<const uint4*>(qrow + sl * 32);
+            qb[c][sl] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    f32x4 acc[NQ][NB];
+    float m[NQ], l[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        m[c] = SPKV_NEG_INF;
+        l[c] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) acc[c][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+    const float* rl = v.ring_logit + (size_t)pair * v.w;
+    const int t_mod = ps.T % v.w;
+
+    int hp = hp0;
+    while (hp < hp1) {
+        const int pbase = hp >> 1;
+        const int my_page = pt[min(pbase + lane, v.pt_cap - 1)];
+        const int hp_end = min(hp1, (pbase + 64) << 1);
+        for (; hp < hp_end; ++hp) {
+            const uint16_t* base;
+            int nvalid;
+            const bool ring = hp >= ps.ghp;
+            if (!ring) {
+                const int page = __builtin_amdgcn_readlane(my_page, (hp >> 1) - pbase);
+                base = pool_page(v, page) + (hp & 1) * (2 * kHalfTokens * D);
+                nvalid = min(kHalfTokens, ps.L - hp * kHalfTokens);
+            } else {
+                const int r = hp - ps.ghp;
+                base = ring_page(v, pair, r >> 1) + (r & 1) * (2 * kHalfTokens * D);
+                nvalid = min(kHalfTokens, ps.Tw - r * kHalfTokens);
+            }
+            // keys past the valid length (same for every column)
+            unsigned kill_len = 0u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (kc * 8 + e >= nvalid) kill_len |= 1u << e;
+            // ring keys: age and gate of this lane's eight keys
+            int age[8];
+            unsigned gate_ok = 0u;
+            if (ring) {
+                const int x0 = (hp - ps.ghp) * kHalfTokens + kc * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int x = x0 + e;
+                    age[e] = ps.T >= v.w ? (x - t_mod + v.w) % v.w : x + v.w - ps.T;
+                    if (kc * 8 + e < nvalid && gate_passes(v, rl[x], ps.T - v.w + age[e])) gate_ok |= 1u << e;
+                }
+            }
+            const uint16_t* kp = base + lane * 8;
+            const uint16_t* vp = base + kHalfTokens * D + lane * 8;
+            bf16x8 ka[2][NS], va[NB];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl)
+                    ka[t][sl] = load_stream_b128(kp + (t * (D / 8) + sl * 4) * 128);
+#pragma unroll
+            for (int db = 0; db < NB; ++db) va[db] = load_stream_b128(vp + db * 512);
+
+#pragma unroll
+            for (int c = 0; c < NQ; ++c) {
+                unsigned kill = kill_len;
+                if (ring) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (!(age[e] > tok_of_col[c] || ((gate_ok >> e) & 1u))) kill |= 1u << e;
+                }
+                attend_half_page<D>(ka, va, qb[c], kill, ring || nvalid < kHalfTokens, scale_log2e,
+                                    acc[c], m[c], l[c]);
+            }
+        }
+    }
+
+    const size_t slot = (size_t)pair * sp.slots + j;
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        float lc = l[c];
+        lc += __shfl_xor(lc, 16);
+        lc += __shfl_xor(lc, 32);
+        const int col = c * 16 + n;
+        if (col < cols) {
+            float* pa = v.part_acc + ((slot * (NQ * 16) + col) * D) + kc * 4;
+#pragma unroll
+            for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[c][db];
+            if (kc == 0) {
+                float* pm = v.part_ml + (slot * (NQ * 16) + col) * 2;
+                pm[0] = m[c];
+                pm[1] = lc;
+            }
+        }
+    }
+}
+
+// Merge for one (pair, column = token i, head g): the split-K partials plus one term per
+// chunk token j <= i taken from the caller's k / v rows (score q_i . k_j in fp32, sum 1,
+// value v_j); bf16 output row cu[b] + i.  The waves share the partials and the chunk
+// tokens round-robin and meet in LDS, as in spkv_decode_combine.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_chunk_combine(SpkvView v, const uint16_t* __restrict__ q,
+                                                          const uint16_t* __restrict__ k_new,
+                                                          const uint16_t* __restrict__ v_new,
+                                                          uint16_t* __restrict__ out,
+                                                          float* __restrict__ lse, float scale_log2e,
+                                                          SpkvSplit sp, SpkvCu cu, int cstride) {
+    constexpr int E = D / 64;
+    const int pair = blockIdx.x / cstride, col = blockIdx.x - pair * cstride;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
+    if (col >= n_tok * v.G) return;
+    const int i = col / v.G, g = col - i * v.G;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int items = v.pair_items[pair];
+    const size_t slot0 = (size_t)pair * sp.slots;
+    __shared__ float s_m[4];
+    __shared__ float s_den[4];
+    __shared__ float s_acc[4][D];
+
+    float mw = SPKV_NEG_INF, den = 0.f, num[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) num[e] = 0.f;
+#pragma unroll 8
+    for (int it = wave; it < items; it += 4) {
+        const size_t idx = (slot0 + it) * cstride + col;
+        const float mi = v.part_ml[idx * 2], li = v.part_ml[idx * 2 + 1];
+        float a[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) a[e] = v.part_acc[idx * D + lane * E + e];
+        const float m_new = fmaxf(mw, mi);
+        const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;
+        const float so = __builtin_amdgcn_exp2f(mw - m_ref), si = __builtin_amdgcn_exp2f(mi - m_ref);
+        den = den * so + li * si;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] = num[e] * so + a[e] * si;
+        mw = m_new;
+    }
+    // the chunk's own tokens 0..i
+    const size_t q_row = ((size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g) * D;
+    float qf[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+        qf[e] = __builtin_bit_cast(float, (unsigned)q[q_row + lane * E + e] << 16);
+    for (int jt = wave; jt <= i; jt += 4) {
+        const size_t kv_row = ((size_t)(row0 + jt) * v.Hkv + h) * D;
+        float dot = 0.f, vj[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            dot += qf[e] * __builtin_bit_cast(float, (unsigned)k_new[kv_row + lane * E + e] << 16);
+            vj[e] = __builtin_bit_cast(float, (unsigned)v_new[kv_row + lane * E + e] << 16);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+        const float mi = dot * scale_log2e;
+        const float m_new = fmaxf(mw, mi);
+        const float so = __builtin_amdgcn_exp2f(mw - m_new), si = __builtin_amdgcn_exp2f(mi - m_new);
+        den = den * so + si;
+#pragma unroll
+        for (int e = 0; e < E; ++e) num[e] = num[e] * so + vj[e] * si;
+        mw = m_new;
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
+    if (lane == 0) {
+        s_m[wave] = mw;
+        s_den[wave] = den;
+    }
+    __syncthreads();
+    if (tid < D) {
+        const float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));   // wave 0 has token 0
+        float nsum = 0.f, dsum = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) {
+            const float sc = __builtin_amdgcn_exp2f(s_m[wv] - M);
+            nsum += s_acc[wv][tid] * sc;
+            dsum += s_den[wv] * sc;
+        }
+        const size_t o = (size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g;
+        const __bf16 r = (__bf16)(nsum / dsum);
+        out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
+        if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
+    }
+}
+
+template <int D, int NQ>
+static hipError_t launch_chunk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                               const uint16_t* q, uint16_t* out, float* lse, float scale_log2e,
+                               SpkvSplit sp, const SpkvCu& cu, hipStream_t s) {
+    const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
+    spkv_chunk_split<D, NQ><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp, cu);
+    spkv_chunk_combine<D><<<dim3(v.n_pairs * NQ * 16), dim3(256), 0, s>>>(
+        v, q, k, vv, out, lse, scale_log2e, sp, cu, NQ * 16);
+    return hipGetLastError();
+}
+
+hipError_t spkv_launch_decode_chunk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                    const uint16_t* q, uint16_t* out, float* lse, float sm_scale,
+                                    SpkvSplit sp, const SpkvCu& cu, int col_groups, hipStream_t s) {
+    const float sl = sm_scale * 1.4426950408889634f;
+    if (v.D == 128) {
+        if (col_groups <= 1) return launch_chunk<128, 1>(v, k, vv, q, out, lse, sl, sp, cu, s);
+        if (col_groups == 2) return launch_chunk<128, 2>(v, k, vv, q, out, lse, sl, sp, cu, s);
+        return launch_chunk<128, 4>(v, k, vv, q, out, lse, sl, sp, cu, s);
+    }
+    if (col_groups <= 1) return launch_chunk<64, 1>(v, k, vv, q, out, lse, sl, sp, cu, s);
+    if (col_groups == 2) return launch_chunk<64, 2>(v, k, vv, q, out, lse, sl, sp, cu, s);
+    return launch_chunk<64, 4>(v, k, vv, q, out, lse, sl, sp, cu, s);
+}
+
+int spkv_chunk_resident_items(int head_dim, int col_groups) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    hipError_t e;
+    if (head_dim == 128) {
+        if (col_groups <= 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<128, 1>, 64, 0);
+        else if (col_groups == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<128, 2>, 64, 0);
+        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<128, 4>, 64, 0);
+    } else {
+        if (col_groups <= 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<64, 1>, 64, 0);
+        else if (col_groups == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<64, 2>, 64, 0);
+        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_chunk_split<64, 4>, 64, 0);
+    }
+    if (e != hipSuccess || per_cu <= 0 || cus <= 0) return 0;
+    return per_cu * cus;
+}
+
+hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
+                              float sm_scale, SpkvSplit sp, bool split_only, hipEvent_t ev0,
+                              hipEvent_t ev1, hipStream_t s) {
+    const float scale_log2e = sm_scale * 1.4426950408889634f;
+    const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
+    hipError_t e;
+    if (ev0 != nullptr && (e = hipEventRecord(ev0, s)) != hipSuccess) return e;
+    if (v.D == 128)
+        spkv_decode_split<128, false><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+    else
+        spkv_decode_split<64, false><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
+    if (split_only) return hipSuccess;
+    if (v.D == 128)
+        spkv_decode_combine<128><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
+    else
+        spkv_decode_combine<64><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
+    return hipGetLastError();
+}
+
+int spkv_split_resident_items(int head_dim) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    const hipError_t e =
+        head_dim == 128
+            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<128, false>, 64, 0)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<64, false>, 64, 0);
+    if (e != hipSuccess || per_cu <= 0 || cus <= 0) return 0;
+    return per_cu * cus;
+}
+
+hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                                   float sm_scale, SpkvSplit sp, hipStream_t s) {
+    const float scale_log2e = sm_scale * 1.4426950408889634f;
+    const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
+    if (v.D == 128) {
+        spkv_decode_split<128, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+        spkv_combine_append<128><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
+    } else {
+        spkv_decode_split<64, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+        spkv_combine_append<64><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
+    }
+    return hipGetLastError();
+}
+

@@ -1,4 +1,5 @@
-// Shared between the host API (spkv_api.hip) and the kernels (spkv_kernels.hip).
+// Shared between the host API (spkv_api.hip) and the kernel files (spkv_write.hip,
+// spkv_decode.hip, spkv_prefill.hip, spkv_predictor.hip).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -35,7 +36,7 @@ struct SpkvView {
     int32_t*  pos_pool;     // [n_pages][64] position of every long-term entry
     int32_t*  seg_count;    // [n_pairs][n_seg_cap] bulk scratch: kept per segment, then offsets
     int32_t*  seg_on;       // [n_pairs][n_seg_cap] bulk scratch: gate-on tokens per segment
-    int32_t*  bulk_info;    // [n_pairs][8] bulk scratch, see BulkInfo in spkv_kernels.hip
+    int32_t*  bulk_info;    // [n_pairs][8] bulk scratch, see BulkInfo in spkv_write.hip
     float*    part_acc;     // [max_items][G][D] un-normalised partial outputs
     float*    part_ml;      // [max_items][G][2] running max (log2 domain) and sum
     int32_t*  pair_items;   // [n_pairs] fused step: item count of every pair, split -> combine

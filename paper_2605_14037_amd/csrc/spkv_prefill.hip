@@ -1,0 +1,519 @@
+// Prefill attention (chunks of any length over the cache, then the append) and the
+// soft-gated attention forward, on gfx950: keys staged in the page layout, tiles shared by a
+// workgroup through LDS, MFMA tile loop with lazily raised softmax references.
+#include "spkv_device.h"
+
+// ------------------------------------------------- prefill attention (any chunk length)
+// n new tokens per sequence attend causally with the availability rule of Eq. 3-4 and are
+// appended, in four steps:
+//   1. spkv_prefill_stage copies the window as it stands (ring, un-rotated into position
+//      order) and the n new K/V rows into staging half-pages in the page layout: staging
+//      row u holds position T_old - w + u, so query i (position T_old + i) has exactly the
+//      rows i < u <= i + w in its window.
+//   2. the bulk append runs and records, per new token, how long a prefix of the long-term
+//      list lies at least w behind it (see spkv_bulk_ring).
+//   3. spkv_prefill_attend: one wave per block of tb = 32 / G consecutive tokens of one
+//      (sequence, KV head) -- 32 MFMA columns (token, head) in two groups of 16 -- walks
+//      the long-term prefix and then the staging rows of the block's windows, one online
+//      softmax per column, and writes the normalised bf16 rows.  No partials, no combine.
+// Window keys and long-term entries are disjoint (positions > t - w against <= t - w), so
+// every available key is counted once.
+
+struct SpkvPrefill {
+    uint16_t* stage;     // [n_pairs][shp] half-pages
+    int32_t*  prefix;    // [total tokens][H_kv]
+    float*    bias;      // soft gating only: [n_pairs][shp][32] log2 u of every staging row
+    int32_t   shp;       // staging half-pages per pair
+    int32_t   tb;        // tokens per wave (32 / G)
+    int32_t   nblk;      // workgroups (spans of 8 tb tokens) per pair in the grid
+    int32_t   pin_xcd;   // 1: all blocks of a pair run on one XCD (shared L2)
+};
+
+// One workgroup per (staging half-page, pair): wave wv fills rows 8 wv .. 8 wv + 7.  Rows
+// without a position (before the sequence start, past the chunk) are zero, so that a
+// masked key never meets a non-finite V element.  Runs BEFORE the append (reads the ring
+// and the token count as they were).
+// With pf.bias set (soft gating) it also stores log2 u = log2 sigmoid(f) of every new row.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_prefill_stage(SpkvView v, const uint16_t* __restrict__ k,
+                                                          const uint16_t* __restrict__ vv,
+                                                          const float* __restrict__ f, SpkvCu cu,
+                                                          SpkvPrefill pf) {
+    const int pair = blockIdx.y, sh = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n = cu.v[b + 1] - row0;
+    if (n == 0 || sh * kHalfTokens >= v.w + n) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15;
+    const int T0 = v.t_pair[pair];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[4][8][D];
+    uint16_t* dp = pf.stage + ((size_t)pair * pf.shp + sh) * (size_t)(2 * kHalfTokens * D);
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int row = pass * 4 + (lane >> 4);
+        const int u = sh * kHalfTokens + wave * 8 + row;
+        if (c < D / 8) {
+            uint4 kk = {0u, 0u, 0u, 0u}, vl = {0u, 0u, 0u, 0u};
+            if (u >= v.w) {
+                const int j = u - v.w;
+                if (j < n) {
+                    const size_t src = ((size_t)(row0 + j) * v.Hkv + h) * D + c * 8;
+                    kk = *reinterpret_cast<const uint4*>(k + src);
+                    vl = *reinterpret_cast<const uint4*>(vv + src);
+                }
+            } else {
+                const int s = T0 - v.w + u;
+                if (s >= 0) {
+                    const int slot = s % v.w;
+                    const uint16_t* sp = ring_page(v, pair, slot >> 6);
+                    const int sk = slot & 63;
+                    kk = *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, c * 8));
+                    const uint16_t* vs = sp + spkv_v_off(D, sk, c * 8);
+                    unsigned wd[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        wd[e] = (unsigned)vs[(2 * e) * 8] | ((unsigned)vs[(2 * e + 1) * 8] << 16);
+                    vl = make_uint4(wd[0], wd[1], wd[2], wd[3]);
+                }
+            }
+            *reinterpret_cast<uint4*>(dp + spkv_k_off(D, wave * 8 + row, c * 8)) = kk;
+            *reinterpret_cast<uint4*>(&s_v[wave][row][c * 8]) = vl;
+        }
+        if (pf.bias != nullptr && c == 0) {
+            float lb = 0.f;
+            if (u >= v.w && u - v.w < n) {
+                // log u = log sigmoid(f) = -softplus(-f) (Eq. 1 and the soft gate), in log2
+                const float x = f[((size_t)row0 + (u - v.w)) * v.Hkv + h];
+                const float ls = x < -20.f ? x : -log1pf(__expf(-x));
+                lb = ls * 1.4426950408889634f;
+            }
+            pf.bias[((size_t)pair * pf.shp + sh) * kHalfTokens + wave * 8 + row] = lb;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    store_v_units<D>(dp, wave * 8, s_v[wave], lane);
+}
+
+// Bits e = 0..7 set for a <= e <= b (empty if the range misses 0..7); branch-free.
+__device__ __forceinline__ unsigned bit_range8(int a, int b) {
+    const int lo = min(max(a, 0), 8), hi = max(min(b, 7), -8);
+    return (0xffu << lo) & (0xffu >> (7 - hi)) & 0xffu;
+}
+
+// One half-page from LDS for the NQ column groups of a wave, in pieces so that the
+// accumulators are only ever touched by MFMA inside the tile loop:
+//   tile_scores      S = K Q^T for the groups (2 NQ independent accumulator chains),
+//                    masked keys to -inf
+//   tile_weights     weights p = 2^(x - m) against the column references m as they stand,
+//                    and their per-lane sums; reports (wave-uniform) whether a reference
+//                    is too low -- some sum above 2^11, so a weight may exceed 2^8 -- or
+//                    not set yet.  Weights up to 2^11 are harmless in bf16 / fp32, so in
+//                    the steady state no maximum is taken and nothing is rescaled.
+//   tile_accumulate  sums and P V with the weights accepted
+//   rescale_columns  raises the references to the column maxima of the tile and rescales
+//                    sums and accumulators; the tile loop leaves its inner loop for this
+//                    (rare once a few tiles have been seen) and then redoes the tile
+constexpr float kWeightSumLimit = 2048.0f;
+constexpr int kPrefillGroups = 2;    // column groups of 16 per wave
+constexpr int kPrefillWaves = 8;     // waves per workgroup (two per SIMD)
+
+template <int D, int NQ>
+__device__ __forceinline__ void tile_scores(const uint16_t* tile, int lane,
+                                            const bf16x8 (&qb)[NQ][D / 32], const unsigned (&kill)[NQ],
+                                            bool any_kill, float (&x)[NQ][8]) {
+    constexpr int NS = D / 32;
+    f32x4 s0[NQ], s1[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        s0[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        s1[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int sl = 0; sl < NS; ++sl) {
+        const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(tile + sl * 512 + lane * 8);
+        const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(tile + (NS + sl) * 512 + lane * 8);
+#pragma unroll
+        for (int c = 0; c < NQ; ++c) {
+            s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qb[c][sl], s0[c], 0, 0, 0);
+            s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qb[c][sl], s1[c], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[c][i] = s0[c][i];
+            x[c][4 + i] = s1[c][i];
+        }
+    }
+    if (any_kill) {
+#pragma unroll
+        for (int c = 0; c < NQ; ++c)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if ((kill[c] >> e) & 1u) x[c][e] = SPKV_NEG_INF;
+    }
+}
+
+template <int NQ>
+__device__ __forceinline__ bool tile_weights(const float (&x)[NQ][8], float scale_log2e,
+                                             const float (&m)[NQ], f32x8 (&p)[NQ], float (&psum)[NQ]) {
+    bool low = false;
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        const bool unset = m[c] == SPKV_NEG_INF;
+        const float neg_ref = unset ? 0.f : -m[c];
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[c][e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[c][e], scale_log2e, neg_ref));
+            sum += p[c][e];
+        }
+        psum[c] = sum;
+        low = low || unset || !(sum <= kWeightSumLimit);
+    }
+    return __ballot(low) != 0ull;
+}
+
+template <int D, int NQ>
+__device__ __forceinline__ void tile_accumulate(const uint16_t* tile, int lane, const f32x8 (&p)[NQ],
+                                                const float (&psum)[NQ], f32x4 (&acc)[NQ][D / 16],
+                                                float (&l)[NQ]) {
+    constexpr int NS = D / 32, NB = D / 16;
+    bf16x8 va[NB];
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+        va[db] = *reinterpret_cast<const bf16x8*>(tile + (2 * NS + db) * 512 + lane * 8);
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        l[c] += psum[c];
+        const bf16x8 pb = __builtin_convertvector(p[c], bf16x8);
+#pragma unroll
+        for (int db = 0; db < NB; ++db)
+            acc[c][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[db], pb, acc[c][db], 0, 0, 0);
+    }
+}
+
+// x: the masked scores of the tile that did not fit the references.  A column whose keys
+// are all excluded so far keeps the reference -inf (its sums and accumulators are zero).
+template <int D, int NQ>
+__device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float scale_log2e,
+                                                f32x4 (&acc)[NQ][D / 16], float (&m)[NQ], float (&l)[NQ]) {
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        float cm = fmaxf(fmaxf(fmaxf(x[c][0], x[c][1]), fmaxf(x[c][2], x[c][3])),
+                         fmaxf(fmaxf(x[c][4], x[c][5]), fmaxf(x[c][6], x[c][7]))) * scale_log2e;
+        cm = fmaxf(cm, __shfl_xor(cm, 16));
+        cm = fmaxf(cm, __shfl_xor(cm, 32));
+        const float m_new = fmaxf(m[c], cm);
+        const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m[c] - m_ref);
+        l[c] *= alpha;
+#pragma unroll
+        for (int db = 0; db < D / 16; ++db) acc[c][db] *= alpha;
+        m[c] = m_new;
+    }
+}
+
+// One workgroup of kPrefillWaves = 8 waves per span of 8 * tb consecutive tokens of one
+// (sequence, KV head); wave wv owns tokens i0 = span start + wv * tb .. + tb - 1 as its
+// 32 MFMA columns (tb = 32 / G tokens times G heads, two groups of 16).  The waves walk the
+// same half-pages, so each 16 KB tile is fetched from memory once per workgroup into an LDS
+// double buffer (every wave copies an eighth of the next tile while all consume the current
+// one) and each wave reads its MFMA A operands from LDS with conflict-free 16-byte reads;
+// 256 query columns share one tile fetch.  With 32 columns a wave needs about 200 VGPRs and
+// no accumulation registers, so two waves fit a SIMD and one wave's vector work (weights)
+// can run beside the other's MFMAs.  (Measured alternatives: four waves of 64 columns, one
+// per SIMD, 15 % slower -- every latency is exposed; the same with the tile loop software-
+// pipelined by hand, slower still; issue priority for one wave of each SIMD, 27 % slower.)
+template <int D, bool SOFT>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
+                                                           uint16_t* __restrict__ out,
+                                                           float* __restrict__ lse, float scale_log2e,
+                                                           SpkvPrefill pf, SpkvCu cu) {
+    constexpr int NS = D / 32, NB = D / 16, NQ = kPrefillGroups, NW = kPrefillWaves;
+    constexpr int kHalfElems = 2 * kHalfTokens * D;
+    constexpr int kRows = kHalfElems / 512;     // 1 KB rows of a tile
+    constexpr int kRowsPerWave = kRows / NW;
+    __shared__ __attribute__((aligned(16))) uint16_t s_tile[2][kHalfElems];
+    int pair, qblk;
+    if (pf.pin_xcd) {
+        // workgroups go round-robin to the 8 XCDs: id % 8 picks the XCD, and every pair
+        // lives on XCD pair % 8, so its list is fetched into one L2 and re-read there
+        const int local = blockIdx.x >> 3, lp = local / pf.nblk;
+        qblk = local - lp * pf.nblk;
+        // rotate inside every full group of 8 pairs by the group index: with 8 KV heads a
+        // plain pair % 8 would give each XCD one head of every sequence, and heads differ
+        // several-fold in kept length
+        const int rot = (lp * 8 + 8 <= v.n_pairs) ? lp : 0;
+        pair = lp * 8 + (((blockIdx.x & 7) + rot) & 7);
+        if (pair >= v.n_pairs) return;
+    } else {
+        pair = blockIdx.x / pf.nblk;
+        qblk = blockIdx.x - pair * pf.nblk;
+    }
+    qblk = pf.nblk - 1 - qblk;            // longest prefixes first
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
+    const int span0 = qblk * NW * pf.tb;
+    if (span0 >= n_tok) return;
+    const int span_last = min(span0 + NW * pf.tb, n_tok) - 1;
+    const int tid = threadIdx.x, lane = tid & 63, kc = lane >> 4, n = lane & 15;
+    // wave index as a scalar: everything derived from it (token range, loop bounds, the
+    // branches on them) then stays in scalar registers and scalar branches
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i0 = span0 + wv * pf.tb;
+    const int tbv = max(0, min(pf.tb, n_tok - i0)), i_last = i0 + tbv - 1, cols = tbv * v.G;
+    const bool active = tbv > 0;
+    // the cache is in the state after the append
+    const int T0 = SOFT ? 0 : v.t_pair[pair] - n_tok, L = SOFT ? 0 : v.kept_len[pair];
+    const int u_min = max(0, v.w - T0);     // first staging row that holds a position
+
+    auto prefix_of = [&](int i) -> int {   // long-term entries at least w behind token i
+        if (SOFT || T0 + i - v.w < 0) return 0;
+        return min(max(pf.prefix[((size_t)row0 + i) * v.Hkv + h], 0), L);
+    };
+
+    bf16x8 qb[NQ][NS];
+    int tok[NQ], cnt[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        const int col = c * 16 + n;
+        const int i = i0 + col / v.G, g = col - (col / v.G) * v.G;
+        const bool valid = col < cols;
+        tok[c] = valid ? i : -1;
+        cnt[c] = valid ? prefix_of(i) : 0;
+        const uint16_t* qrow = q + ((size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g) * D + kc * 8;
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) {
+            uint4 raw = {0u, 0u, 0u, 0u};
+            if (valid) raw = *reinterpret_cast<const uint4*>(qrow + sl * 32);
+            qb[c][sl] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    // long-term half-pages: the workgroup visits those some token of the span can see; this
+    // wave computes on those below its own last count, unmasked below its first count
+    const int nA = (prefix_of(span_last) + kHalfTokens - 1) >> 5;
+    const int nA_wave = active ? (prefix_of(i_last) + kHalfTokens - 1) >> 5 : 0;
+    const int fullA = active ? prefix_of(i0) >> 5 : 0;
+    // staging half-pages: rows (span0, span_last + w] that hold a position; this wave's
+    // windows cover rows [lo_w, hi_w]
+    const int sB0 = (SOFT ? u_min : max(span0 + 1, u_min)) >> 5;
+    const int nB = ((span_last + v.w) >> 5) - sB0 + 1;
+    const int lo_w = SOFT ? u_min : max(i0 + 1, u_min), hi_w = i_last + v.w;
+    const int n_hp = nA + nB, last = n_hp - 1;
+
+    const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+    const uint16_t* stage = pf.stage + (size_t)pair * pf.shp * (size_t)kHalfElems;
+    auto base_of = [&](int x) -> const uint16_t* {
+        x = min(x, last);
+        if (x < nA) {
+            const int page = min(max(pt[min(x >> 1, v.pt_cap - 1)], 0), v.n_pages - 1);
+            return pool_page(v, page) + (x & 1) * kHalfElems;
+        }
+        return stage + (size_t)min(sB0 + x - nA, pf.shp - 1) * kHalfElems;
+    };
+
+    f32x4 acc[NQ][NB];
+    float m[NQ], l[NQ];
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        m[c] = SPKV_NEG_INF;
+        l[c] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) acc[c][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int my_off = (wv * kRowsPerWave * 64 + lane) * 8;     // this lane's part of a tile
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    u32x4 t[kRowsPerWave];
+    {
+        const uint16_t* p = base_of(0) + my_off;
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r)
+            *reinterpret_cast<u32x4*>(&s_tile[0][my_off + r * 512]) = t[r];
+    }
+    const uint16_t* p_next = base_of(1);
+    __syncthreads();
+
+    // Tile loop.  The inner loop never touches the accumulators except by MFMA; when the
+    // references do not fit a tile the wave leaves it before using the tile, rescales, and
+    // resumes at the same tile (prefetch and barrier of a tile are issued exactly once, so
+    // the waves stay in step whatever each one does).  After a rescale the references
+    // are at least the tile's column maxima, so the second attempt is accepted; a column
+    // with every key excluded so far keeps m = -inf and is accepted on the retry as well.
+    int x = 0;
+    bool resume = false, pending = false;
+    float xs[NQ][8];
+    while (x < n_hp) {
+        if (pending) rescale_columns<D, NQ>(xs, SOFT ? 1.0f : scale_log2e, acc, m, l);
+        for (; x < n_hp; ++x) {
+            if (!resume) {
+                // next tile (after the last one: the same tile again, into the idle buffer)
+                const uint16_t* p = p_next + my_off;
+#pragma unroll
+                for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
+                p_next = base_of(x + 2);
+            }
+            resume = false;
+            const uint16_t* tile = s_tile[x & 1];
+            bool mine;
+            int u_tile = 0;
+            if (x < nA) {
+                mine = x < nA_wave;
+            } else {
+                u_tile = (sB0 + x - nA) * kHalfTokens;
+                mine = active && u_tile <= hi_w && u_tile + kHalfTokens > lo_w;
+            }
+            if (mine) {
+                // per column group: which of this lane's eight keys are excluded
+                unsigned kill[NQ] = {};
+                bool any = true;
+                if (x < nA) {
+                    any = x >= fullA;
+                    if (any) {
+                        const int k0 = x * kHalfTokens + kc * 8;   // list index of this lane's first key
+#pragma unroll
+                        for (int c = 0; c < NQ; ++c) kill[c] = bit_range8(0, cnt[c] - k0 - 1) ^ 0xffu;
+                    }
+                } else {
+                    // soft gating: a tile of rows that all hold a position and all lie at or
+                    // before every token of the wave needs no mask
+                    if (SOFT && u_tile >= u_min && u_tile + kHalfTokens - 1 <= i0 + v.w) any = false;
+                    const int u0 = u_tile + kc * 8;
+                    // window of token i: rows i < u <= i + w that hold a position (soft
+                    // gating: every earlier row as well)
+#pragma unroll
+                    for (int c = 0; c < NQ; ++c)
+                        kill[c] = (tok[c] >= 0 ? bit_range8((SOFT ? u_min : max(tok[c] + 1, u_min)) - u0,
+                                                            tok[c] + v.w - u0)
+                                               : 0u) ^ 0xffu;
+                }
+                tile_scores<D, NQ>(tile, lane, qb, kill, any, xs);
+                if (SOFT) {
+                    // scores to the log2 domain plus the gate bias log2 u of every key outside
+                    // the window of its query (row u <= i); masked scores stay -inf
+                    const int u0 = u_tile + kc * 8;
+                    const float4* bp = reinterpret_cast<const float4*>(
+                        pf.bias + ((size_t)pair * pf.shp + (u_tile >> 5)) * kHalfTokens + kc * 8);
+                    const float4 b0 = bp[0], b1 = bp[1];
+                    const float bias[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+                    if (u_tile + kHalfTokens - 1 <= i0) {       // outside every window of the wave
+#pragma unroll
+                        for (int c = 0; c < NQ; ++c)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                xs[c][e] = __builtin_fmaf(xs[c][e], scale_log2e, bias[e]);
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < NQ; ++c)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                xs[c][e] = __builtin_fmaf(xs[c][e], scale_log2e,
+                                                          u0 + e <= tok[c] ? bias[e] : 0.f);
+                    }
+                }
+                f32x8 pw[NQ];
+                float psum[NQ];
+                if (tile_weights<NQ>(xs, SOFT ? 1.0f : scale_log2e, m, pw, psum) && !pending) {
+                    pending = true;
+                    resume = true;
+                    break;
+                }
+                pending = false;
+                tile_accumulate<D, NQ>(tile, lane, pw, psum, acc, l);
+            }
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r)
+                *reinterpret_cast<u32x4*>(&s_tile[(x + 1) & 1][my_off + r * 512]) = t[r];
+            __syncthreads();
+        }
+    }
+
+#pragma unroll
+    for (int c = 0; c < NQ; ++c) {
+        float lc = l[c];
+        lc += __shfl_xor(lc, 16);
+        lc += __shfl_xor(lc, 32);
+        if (tok[c] >= 0) {
+            const int col = c * 16 + n;
+            const int g = col - (col / v.G) * v.G;
+            const size_t o = (size_t)(row0 + tok[c]) * v.Hq + (size_t)h * v.G + g;
+            const float inv = 1.0f / lc;
+            uint16_t* po = out + o * D + kc * 4;
+#pragma unroll
+            for (int db = 0; db < NB; ++db) {
+                const __bf16 r0 = (__bf16)(acc[c][db][0] * inv), r1 = (__bf16)(acc[c][db][1] * inv);
+                const __bf16 r2 = (__bf16)(acc[c][db][2] * inv), r3 = (__bf16)(acc[c][db][3] * inv);
+                uint2 pk;
+                pk.x = (unsigned)__builtin_bit_cast(uint16_t, r0) | ((unsigned)__builtin_bit_cast(uint16_t, r1) << 16);
+                pk.y = (unsigned)__builtin_bit_cast(uint16_t, r2) | ((unsigned)__builtin_bit_cast(uint16_t, r3) << 16);
+                *reinterpret_cast<uint2*>(po + db * 16) = pk;
+            }
+            if (lse != nullptr && kc == 0) lse[o] = (m[c] + log2f(lc)) * 0.6931471805599453f;
+        }
+    }
+}
+
+static SpkvPrefill prefill_params(const SpkvView& v, int n_max, uint16_t* stage, int32_t* prefix,
+                                  float* bias, int shp) {
+    SpkvPrefill pf;
+    pf.stage = stage;
+    pf.prefix = prefix;
+    pf.bias = bias;
+    pf.shp = shp;
+    pf.tb = (16 * kPrefillGroups) / v.G;
+    pf.nblk = (n_max + kPrefillWaves * pf.tb - 1) / (kPrefillWaves * pf.tb);   // spans of one workgroup
+    pf.pin_xcd = (v.n_pairs >= 8 && pf.nblk >= 4) ? 1 : 0;
+    return pf;
+}
+
+static unsigned prefill_grid(const SpkvView& v, const SpkvPrefill& pf) {
+    return pf.pin_xcd ? 8u * (unsigned)((v.n_pairs + 7) / 8) * (unsigned)pf.nblk
+                      : (unsigned)v.n_pairs * (unsigned)pf.nblk;
+}
+
+hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                               const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                               float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
+                               int32_t* prefix, int shp, hipStream_t s) {
+    const SpkvPrefill pf = prefill_params(v, n_max, stage, prefix, nullptr, shp);
+    const float sl = sm_scale * 1.4426950408889634f;
+    const int stage_hps = (v.w + n_max + kHalfTokens - 1) / kHalfTokens;
+    const unsigned grid = prefill_grid(v, pf);
+    hipError_t e;
+    if (v.D == 128) {
+        spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
+        if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
+        spkv_prefill_attend<128, false><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    } else {
+        spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
+        if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
+        spkv_prefill_attend<64, false><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    }
+    return hipGetLastError();
+}
+
+// Soft-gated attention of whole sequences (no cache): the same staging and the same tile
+// loop with every earlier row visible and the bias log2 u on the rows outside the window.
+// v: a view that only describes the shape (B, heads, D, w, n_pairs) and whose t_pair points
+// at n_pairs zeros.
+hipError_t spkv_launch_soft_gated(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                  const float* f, const uint16_t* q, uint16_t* out, float* lse,
+                                  float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
+                                  float* bias, int shp, hipStream_t s) {
+    const SpkvPrefill pf = prefill_params(v, n_max, stage, nullptr, bias, shp);
+    const float sl = sm_scale * 1.4426950408889634f;
+    const int stage_hps = (v.w + n_max + kHalfTokens - 1) / kHalfTokens;
+    const unsigned grid = prefill_grid(v, pf);
+    if (v.D == 128) {
+        spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
+        spkv_prefill_attend<128, true><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    } else {
+        spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
+        spkv_prefill_attend<64, true><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    }
+    return hipGetLastError();
+}
+

@@ -1,0 +1,474 @@
+// Write path of the SP-KV cache on gfx950: zero fill and copies, the append of one token per
+// sequence (fused gate + evict + ring write), the bulk append (ballot + mbcnt stream
+// compaction in stable order), sequence release and the read-back of kept positions.
+//
+// Gate: Eq. 2 of the paper taken on the logit, z = 1[f >= theta].  The window ring holds
+// exactly the keys with 0 <= t - s < w and the long-term pages exactly the gated-on keys with
+// t - s >= w (Eq. 3-4), so the two sets are disjoint and their union is what Eq. 5 attends to.
+#include "spkv_device.h"
+
+// ------------------------------------------------------------------------ zero fill
+__global__ __launch_bounds__(256) void spkv_fill_zero(uint4* p, size_t n16) {
+    const uint4 z = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = z;
+}
+
+hipError_t spkv_launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    spkv_fill_zero<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(static_cast<uint4*>(p), n16);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------- plain copy (reference)
+__global__ __launch_bounds__(256) void spkv_plain_copy(uint4* __restrict__ d,
+                                                       const uint4* __restrict__ s, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+         i += (size_t)gridDim.x * blockDim.x)
+        d[i] = s[i];
+}
+
+hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    spkv_plain_copy<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(
+        static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void spkv_copy_rows(int32_t* __restrict__ dst,
+                                                      const int32_t* __restrict__ src, int rows,
+                                                      int src_width, int dst_width) {
+    const size_t n = (size_t)rows * src_width;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const size_t r = i / src_width, c = i - r * src_width;
+        dst[r * dst_width + c] = src[i];
+    }
+}
+
+hipError_t spkv_launch_copy_rows(int32_t* dst, const int32_t* src, int rows, int src_width,
+                                 int dst_width, hipStream_t s) {
+    const size_t n = (size_t)rows * src_width;
+    if (n == 0) return hipSuccess;
+    const size_t blocks = std::min<size_t>((n + 255) / 256, 256 * 16);
+    spkv_copy_rows<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(dst, src, rows, src_width, dst_width);
+    return hipGetLastError();
+}
+
+template <int D>
+__global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t* __restrict__ k,
+                                                      const uint16_t* __restrict__ vv,
+                                                      const float* __restrict__ f, SpkvCu cu) {
+    const int pair = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row = cu.v[b];
+    if (cu.v[b + 1] - row == 0) return;
+    __shared__ int s_page;
+    const int T = v.t_pair[pair];
+    const int L = v.kept_len[pair];
+    const AppendRegs<D> r = append_load<D>(v, pair, h, row, T, L, k, vv, f, threadIdx.x);
+    append_store<D>(v, pair, T, L, r, threadIdx.x, &s_page);
+}
+
+hipError_t spkv_launch_append_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const SpkvCu& cu, hipStream_t s) {
+    if (v.D == 128)
+        spkv_append_step<128><<<dim3(v.n_pairs), dim3(128), 0, s>>>(v, k, vv, f, cu);
+    else
+        spkv_append_step<64><<<dim3(v.n_pairs), dim3(64), 0, s>>>(v, k, vv, f, cu);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------- write path, many tokens (bulk)
+// For (sequence, head) with n new tokens, T_old stored: positions that leave the window
+// are [max(0, T_old - w), T_old + n - w).  Those below T_old sit in the ring (<= w of
+// them, handled by spkv_bulk_ring); the others are new tokens j in [0, n - w) that enter
+// and leave the window within this call (handled per 256-token segment, one token per
+// thread).  The last min(n, w) new tokens land in the ring.  Long-term order is ascending
+// position: ring-evicted first, then new tokens; ranks come from ballot + mbcnt prefix
+// sums inside a wave, popcounts across the four waves of a segment, and a scan of the
+// per-segment counts across segments.
+//
+// Rows are moved 16 at a time per workgroup: 16 lanes per row, each lane one 16-byte K
+// chunk and the 8 V elements of the same head-dim range (loads coalesced per row; the V
+// elements go out as 2-byte stores at 16-byte stride, which is what the page layout asks).
+
+// Per-pair scratch written by spkv_bulk_ring for spkv_bulk_scatter.
+struct BulkInfo {
+    int32_t T_old;        // tokens held before this call
+    int32_t new_base;     // long-term index of the first kept NEW token (after ring-evicted ones)
+    int32_t ok;           // 0: capacity error, the call writes nothing more for this pair
+    int32_t pad[5];
+};
+
+// Lane (r = lane / 16, c = lane % 16) moves chunk c of one row into row dk of page dp.
+template <int D>
+__device__ __forceinline__ void store_row_chunk(uint16_t* dp, int dk, int c, uint4 kk, uint4 vv) {
+    *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk, c * 8)) = kk;
+    uint16_t* vd = dp + spkv_v_off(D, dk, c * 8);      // element e of the chunk is 8 e further
+    const unsigned w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vd[e * 8] = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+}
+
+// Stage 1: per (segment, pair): how many of the segment's new tokens pass the gate, and how
+// many of those also leave the window within this call (j < n - w).
+__global__ __launch_bounds__(256) void spkv_bulk_count(SpkvView v, const float* __restrict__ f,
+                                                       SpkvCu cu) {
+    const int pair = blockIdx.y, seg = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int n = cu.v[b + 1] - cu.v[b];
+    const int n_ev = max(0, n - v.w);
+    const int j = seg * kSegTokens + (int)threadIdx.x;
+    if (seg * kSegTokens >= n) return;
+    __shared__ int s_ev[4], s_on[4];
+    const bool on = j < n && gate_passes(v, f[((size_t)cu.v[b] + j) * v.Hkv + h], v.t_pair[pair] + j);
+    const int c_on = __popcll(__ballot(on));
+    const int c_ev = __popcll(__ballot(on && j < n_ev));
+    if (lane_id() == 0) {
+        s_on[threadIdx.x >> 6] = c_on;
+        s_ev[threadIdx.x >> 6] = c_ev;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        v.seg_count[(size_t)pair * v.n_seg_cap + seg] = s_ev[0] + s_ev[1] + s_ev[2] + s_ev[3];
+        v.seg_on[(size_t)pair * v.n_seg_cap + seg] = s_on[0] + s_on[1] + s_on[2] + s_on[3];
+    }
+}
+
+// Block-wide exclusive scan of one int per thread (256 threads); returns the exclusive
+// prefix and the block total.  s_w: 4 ints of shared memory.
+__device__ __forceinline__ int block_excl_scan(int x, int* s_w, int& total) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    int incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    __syncthreads();
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    int woff = 0;
+    total = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (i < wave) woff += s_w[i];
+        total += s_w[i];
+    }
+    return woff + incl - x;
+}
+
+// Stage 2: one workgroup per pair.  Counts the pairs leaving the ring that are kept,
+// turns the segment counts into offsets, allocates every page the call needs with one
+// allocation per page, publishes the new lengths, then moves the kept ring rows.
+//
+// prefix (may be null; used by the prefill attention): for the new token i of the call, at
+// position t = T_old + i, prefix[(row of token i) * H_kv + h] = number of long-term entries,
+// after this call, whose position is <= t - w -- the entries available to query t outside
+// its window (the list is in ascending position, so they are a prefix of it).  Stage 2
+// writes the tokens whose t - w is a ring position, stage 3 the others; tokens with
+// t - w < 0 get no entry (their count is 0).
+template <int D>
+__global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int32_t* prefix) {
+    const int pair = blockIdx.x;
+    const int b = pair / v.Hkv;
+    const int n = cu.v[b + 1] - cu.v[b];
+    if (n == 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int T_old = v.t_pair[pair], T_new = T_old + n, L_old = v.kept_len[pair];
+    const int r0 = max(0, T_old - v.w);
+    const int r1 = min(T_old, max(0, T_new - v.w));
+    const int nr = max(0, r1 - r0);
+    const int n_ev = max(0, n - v.w);
+    const int nseg = (n_ev + kSegTokens - 1) / kSegTokens;
+    const float* rl = v.ring_logit + (size_t)pair * v.w;
+    int32_t* sc = v.seg_count + (size_t)pair * v.n_seg_cap;
+    __shared__ int s_w[4];
+    __shared__ BulkInfo s_bi;
+    __shared__ uint16_t s_list[256];
+
+    // (a) how many ring pairs are kept
+    int cnt = 0;
+    for (int base = 0; base < nr; base += 256) {
+        const int idx = base + tid;
+        const bool flag = idx < nr && gate_passes(v, rl[(r0 + idx) % v.w], r0 + idx);
+        cnt += __popcll(__ballot(flag));
+    }
+    if (lane == 0) s_w[wave] = cnt;
+    __syncthreads();
+    const int ring_kept = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+
+    // (b) segment counts -> exclusive offsets (in place)
+    int carry = 0;
+    for (int base = 0; base < nseg; base += 256) {
+        const int i = base + tid;
+        const int c = i < nseg ? sc[i] : 0;
+        int tot;
+        const int ex = block_excl_scan(c, s_w, tot);
+        if (i < nseg) sc[i] = carry + ex;
+        carry += tot;
+    }
+    const int total_new = ring_kept + carry;
+
+    // gate-on count of the call (Eq. 8 numerator), summed here so that no kernel needs
+    // same-address atomics
+    {
+        const int nseg_all = (n + kSegTokens - 1) / kSegTokens;
+        const int32_t* so = v.seg_on + (size_t)pair * v.n_seg_cap;
+        int on = 0;
+        for (int i = tid; i < nseg_all; i += 256) on += so[i];
+        for (int o = 32; o > 0; o >>= 1) on += __shfl_xor(on, o);
+        __syncthreads();
+        if (lane == 0) s_w[wave] = on;
+        __syncthreads();
+        if (tid == 0) v.gate_on[pair] += s_w[0] + s_w[1] + s_w[2] + s_w[3];
+    }
+
+    // (c) pages: one allocation per new logical page, in parallel; the table entries are
+    //     visible to the whole workgroup after the barrier and to stage 3 after the launch
+    const int first = (L_old + kPageTokens - 1) / kPageTokens;
+    const int last = (L_old + total_new + kPageTokens - 1) / kPageTokens;
+    const int need = last <= v.pt_cap ? last - first : 0;
+    int bad = last > v.pt_cap ? 1 : 0;
+    for (int i = tid; i < need; i += 256) {
+        const int page = alloc_page(v);
+        if (page < 0) bad = 1;
+        else v.page_table[(size_t)pair * v.pt_cap + first + i] = page;
+    }
+    const int any_bad = __syncthreads_or(bad);
+    if (tid == 0) {
+        if (any_bad) *v.err_flag = 1;
+        s_bi.T_old = T_old;
+        s_bi.new_base = L_old + ring_kept;
+        s_bi.ok = any_bad ? 0 : 1;
+        *reinterpret_cast<BulkInfo*>(v.bulk_info + (size_t)pair * 8) = s_bi;
+        if (!any_bad) v.kept_len[pair] = L_old + total_new;
+        v.t_pair[pair] = T_new;
+    }
+    __threadfence_block();
+    __syncthreads();
+    if (any_bad) return;
+    const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+
+    // (d) move the kept ring rows, 256 ring positions at a time
+    int done = 0;
+    for (int base = 0; base < nr; base += 256) {
+        const int idx = base + tid;
+        const bool flag = idx < nr && gate_passes(v, rl[(r0 + idx) % v.w], r0 + idx);
+        int tot;
+        const int rank = block_excl_scan(flag ? 1 : 0, s_w, tot);
+        if (flag) s_list[rank] = (uint16_t)tid;
+        if (prefix != nullptr && idx < nr) {
+            const int i = r0 + idx + v.w - T_old;      // the new token whose t - w is this position
+            prefix[((size_t)cu.v[b] + i) * v.Hkv + (pair - b * v.Hkv)] = L_old + done + rank + (flag ? 1 : 0);
+        }
+        __syncthreads();
+        const int c = lane & 15;
+        for (int rb = wave * 4; rb < tot; rb += 16) {
+            const int r = rb + (lane >> 4);
+            if (r < tot && c < D / 8) {
+                const int s = r0 + base + s_list[r];
+                const int slot = s % v.w;
+                const uint16_t* sp = ring_page(v, pair, slot >> 6);
+                const int sk = slot & 63;
+                const uint4 kk = *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, c * 8));
+                const uint16_t* vs = sp + spkv_v_off(D, sk, c * 8);
+                unsigned w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] = (unsigned)vs[(2 * e) * 8] | ((unsigned)vs[(2 * e + 1) * 8] << 16);
+                const int gi = L_old + done + r;
+                const int page = pt[gi >> 6];
+                store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, make_uint4(w[0], w[1], w[2], w[3]));
+                if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = s;
+            }
+        }
+        done += tot;
+        __syncthreads();
+    }
+}
+
+// Stage 3: per (256-token segment, pair).  Thread i owns token j0 + i: gate flag, rank
+// (mbcnt inside the wave + the popcounts of the lower waves + the segment offset from
+// stage 2); the kept tokens' indices are compacted into LDS and their rows moved in groups
+// of eight consecutive destination rows (whole 16-byte V units, transposed through LDS),
+// stragglers row by row; the last min(n, w) tokens of the call are written into the ring.
+template <int D>
+__global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint16_t* __restrict__ k,
+                                                         const uint16_t* __restrict__ vv,
+                                                         const float* __restrict__ f, SpkvCu cu,
+                                                         int32_t* prefix) {
+    const int pair = blockIdx.y, seg = blockIdx.x;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b];
+    const int n = cu.v[b + 1] - row0;
+    const int j0 = seg * kSegTokens;
+    if (j0 >= n) return;
+    const BulkInfo bi = *reinterpret_cast<const BulkInfo*>(v.bulk_info + (size_t)pair * 8);
+    if (bi.ok == 0) return;
+    const int n_ev = max(0, n - v.w);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15;
+    __shared__ int s_cnt[4];
+    __shared__ uint16_t s_list[256];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[4][8][D];
+
+    const int j = j0 + tid;
+    const bool on = j < n && gate_passes(v, f[((size_t)row0 + j) * v.Hkv + h], bi.T_old + j);
+    const bool ev = on && j < n_ev;
+    const unsigned long long mask = __ballot(ev);
+    if (lane == 0) s_cnt[wave] = __popcll(mask);
+    __syncthreads();
+    int woff = 0, total = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (i < wave) woff += s_cnt[i];
+        total += s_cnt[i];
+    }
+    if (ev) s_list[woff + mbcnt64(mask)] = (uint16_t)tid;
+    if (prefix != nullptr && j < n_ev)       // token j leaves the window of token j + w
+        prefix[((size_t)row0 + j + v.w) * v.Hkv + h] =
+            bi.new_base + v.seg_count[(size_t)pair * v.n_seg_cap + seg] + woff + mbcnt64(mask) + (ev ? 1 : 0);
+    __syncthreads();
+
+    if (total > 0) {
+        const int g0 = bi.new_base + v.seg_count[(size_t)pair * v.n_seg_cap + seg];
+        const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+        const int gend = g0 + total;
+        const int ga = min(gend, (g0 + 7) & ~7);   // destination indices [ga, gb) are whole
+        const int gb = max(ga, gend & ~7);         // groups of 8 aligned to 8: whole V units
+
+        // Whole groups, one wave each: K chunks go straight out; the eight V rows meet in
+        // LDS and leave as 16-byte units (eight keys of one head-dim element).
+        for (int G8 = ga + wave * 8; G8 < gb; G8 += 32) {
+            const int page = pt[G8 >> 6];
+            uint16_t* dp = pool_page(v, page);
+            const int dk0 = G8 & 63;
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const int row = pass * 4 + (lane >> 4);
+                if (c < D / 8) {
+                    const int jj = j0 + s_list[G8 - g0 + row];
+                    const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
+                    const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
+                    const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
+                    *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk0 + row, c * 8)) = kk;
+                    *reinterpret_cast<uint4*>(&s_v[wave][row][c * 8]) = vl;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane < D / 2) {
+                unsigned dw[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    dw[r] = *reinterpret_cast<const unsigned*>(&s_v[wave][r][2 * lane]);
+                uint4 lo, hi;
+                lo.x = (dw[0] & 0xffffu) | (dw[1] << 16);
+                lo.y = (dw[2] & 0xffffu) | (dw[3] << 16);
+                lo.z = (dw[4] & 0xffffu) | (dw[5] << 16);
+                lo.w = (dw[6] & 0xffffu) | (dw[7] << 16);
+                hi.x = (dw[0] >> 16) | (dw[1] & 0xffff0000u);
+                hi.y = (dw[2] >> 16) | (dw[3] & 0xffff0000u);
+                hi.z = (dw[4] >> 16) | (dw[5] & 0xffff0000u);
+                hi.w = (dw[6] >> 16) | (dw[7] & 0xffff0000u);
+                uint16_t* vd = dp + spkv_v_off(D, dk0, 2 * lane);   // unit of d = 2 lane; d + 1 follows
+                *reinterpret_cast<uint4*>(vd) = lo;
+                *reinterpret_cast<uint4*>(vd + 8) = hi;
+            }
+            if (lane < 8)
+                v.pos_pool[(size_t)page * kPageTokens + dk0 + lane] =
+                    bi.T_old + j0 + s_list[G8 - g0 + lane];
+            __builtin_amdgcn_wave_barrier();
+        }
+        // The rows before the first and after the last whole group, one row per 16 lanes,
+        // V elements as 2-byte stores.
+        const int n_head = ga - g0, n_tail = gend - gb;
+        for (int rb = wave * 4; rb < n_head + n_tail; rb += 16) {
+            const int x = rb + (lane >> 4);
+            if (x < n_head + n_tail && c < D / 8) {
+                const int r = x < n_head ? x : (gb - g0) + (x - n_head);
+                const int jj = j0 + s_list[r];
+                const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
+                const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
+                const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
+                const int gi = g0 + r;
+                const int page = pt[gi >> 6];
+                store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, vl);
+                if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = bi.T_old + jj;
+            }
+        }
+    }
+    const int ja = max(j0, n_ev), jb = min(n, j0 + kSegTokens);
+    for (int rb = ja + wave * 4; rb < jb; rb += 16) {
+        const int jj = rb + (lane >> 4);
+        if (jj < jb && c < D / 8) {
+            const int slot = (bi.T_old + jj) % v.w;
+            const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
+            const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
+            const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
+            store_row_chunk<D>(ring_page(v, pair, slot >> 6), slot & 63, c, kk, vl);
+            if (c == 0)
+                v.ring_logit[(size_t)pair * v.w + slot] = f[((size_t)row0 + jj) * v.Hkv + h];
+        }
+    }
+}
+
+hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                   const float* f, const SpkvCu& cu, int n_max, int32_t* prefix,
+                                   hipStream_t s) {
+    const int segs_all = (n_max + kSegTokens - 1) / kSegTokens;
+    spkv_bulk_count<<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, f, cu);
+    if (v.D == 128) {
+        spkv_bulk_ring<128><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix);
+        spkv_bulk_scatter<128><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
+    } else {
+        spkv_bulk_ring<64><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix);
+        spkv_bulk_scatter<64><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- release a sequence
+// One workgroup per KV head of the sequence: its pages go onto the stack of recycled pages
+// and its counters back to zero (the ring needs no clearing: with T = 0 no slot is valid).
+__global__ __launch_bounds__(256) void spkv_release_sequence(SpkvView v, int b) {
+    const int pair = b * v.Hkv + blockIdx.x;
+    const int tid = threadIdx.x;
+    const int np = (v.kept_len[pair] + kPageTokens - 1) / kPageTokens;
+    __shared__ int s_base;
+    if (tid == 0) s_base = np > 0 ? atomicAdd(v.free_top, np) : 0;
+    __syncthreads();
+    for (int i = tid; i < np; i += 256)
+        v.free_pages[s_base + i] = v.page_table[(size_t)pair * v.pt_cap + i];
+    if (tid == 0) {
+        v.kept_len[pair] = 0;
+        v.t_pair[pair] = 0;
+        v.gate_on[pair] = 0;
+    }
+}
+
+hipError_t spkv_launch_release_sequence(const SpkvView& v, int b, hipStream_t s) {
+    spkv_release_sequence<<<dim3(v.Hkv), dim3(256), 0, s>>>(v, b);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------ kept positions (debug)
+__global__ __launch_bounds__(256) void spkv_gather_positions(SpkvView v, int pair) {
+    const int L = v.kept_len[pair];
+    for (int gi = blockIdx.x * blockDim.x + threadIdx.x; gi < L; gi += gridDim.x * blockDim.x) {
+        const int page = v.page_table[(size_t)pair * v.pt_cap + (gi >> 6)];
+        v.pos_scratch[gi] = v.pos_pool[(size_t)page * kPageTokens + (gi & 63)];
+    }
+}
+
+hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s) {
+    spkv_gather_positions<<<dim3(64), dim3(256), 0, s>>>(v, pair);
+    return hipGetLastError();
+}
+
