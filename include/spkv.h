@@ -265,6 +265,23 @@ int spkv_utility_logits(const void* hidden, const void* w1, const float* b1, con
                         const float* b2, float* logits, float* workspace, int32_t n_tokens,
                         int32_t d_model, int32_t d_hidden, int32_t n_kv_heads, void* stream);
 
+/* Replaying captured steps.  spkv_append (one token per sequence), spkv_decode_attention and
+ * spkv_decode_step enqueue kernels only -- no allocation, no copy, no synchronisation as long
+ * as the capacity bound holds -- so a serving loop may capture them into a HIP graph (one
+ * graph node sequence per layer) and replay the graph step after step with new contents in the
+ * same input buffers.  A replay bypasses the host's bookkeeping, hence two calls:
+ *   spkv_cache_safe_steps  the "safe-step budget" of the appendix: how many further steps of
+ *                          one token per sequence are guaranteed to fit (max_context, and the
+ *                          pool even if every pair leaving a window is kept).  Reads the exact
+ *                          lengths back first: synchronises `stream`.  Call it outside capture.
+ *   spkv_cache_advance     tells the cache that n such steps were executed by replays.
+ *                          SPKV_E_CAPACITY (nothing changed) if n exceeds what was safe.
+ * The work partition frozen in a captured launch stays valid as the lists grow (work items
+ * get longer, never out of bounds); re-capture now and then to rebalance it.  The threshold
+ * and the sink count are frozen with the launch too. */
+int spkv_cache_safe_steps(spkv_cache_t* cache, void* stream, int64_t* n_steps);
+int spkv_cache_advance(spkv_cache_t* cache, int64_t n_steps);
+
 /* Gate density and sizes (Eq. 8).  Synchronises `stream`.  kept_len (host int32
  * [batch * n_kv_heads], or NULL) receives the long-term length of every (seq, head). */
 int spkv_cache_stats(spkv_cache_t* cache, spkv_stats_t* stats, int32_t* kept_len, void* stream);

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "spkv_cache_reset",
     "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk",
     "spkv_prefill_workspace_bytes", "spkv_prefill_attention",
-    "spkv_soft_gated_workspace_bytes", "spkv_soft_gated_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_stats", "spkv_cache_kept_positions",
+    "spkv_soft_gated_workspace_bytes", "spkv_soft_gated_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_safe_steps", "spkv_cache_advance", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
     "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
@@ -102,6 +102,10 @@ def load_library():
     lib.spkv_cache_release_sequence.argtypes = [vp, i32, vp]
     lib.spkv_utility_logits.restype = C.c_int
     lib.spkv_utility_logits.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    lib.spkv_cache_safe_steps.restype = C.c_int
+    lib.spkv_cache_safe_steps.argtypes = [vp, vp, P(i64)]
+    lib.spkv_cache_advance.restype = C.c_int
+    lib.spkv_cache_advance.argtypes = [vp, i64]
     lib.spkv_cache_stats.restype = C.c_int
     lib.spkv_cache_stats.argtypes = [vp, P(SPKVStats), P(i32), vp]
     lib.spkv_cache_kept_positions.restype = C.c_int
@@ -412,6 +416,17 @@ class SPKVCache:
         _check(self.lib.spkv_cache_threshold_logit(self.handle, C.byref(th)),
                "spkv_cache_threshold_logit")
         return th.value
+
+    def safe_steps(self):
+        """Single-token steps guaranteed to fit (spkv_cache_safe_steps; synchronises)."""
+        n = C.c_int64()
+        _check(self.lib.spkv_cache_safe_steps(self.handle, _stream(), C.byref(n)),
+               "spkv_cache_safe_steps")
+        return n.value
+
+    def advance(self, n_steps):
+        """Account for n_steps steps executed by graph replays (spkv_cache_advance)."""
+        _check(self.lib.spkv_cache_advance(self.handle, int(n_steps)), "spkv_cache_advance")
 
     def set_tau(self, tau):
         _check(self.lib.spkv_cache_set_tau(self.handle, float(tau)), "spkv_cache_set_tau")

@@ -4,6 +4,7 @@
 // bound trips), and kernel launches.  See include/spkv.h for the contract.
 #include <algorithm>
 #include <cmath>
+#include <cstdint>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -674,6 +675,60 @@ int spkv_soft_gated_attention(const void* q, const void* k, const void* v, const
                                lse, sm_scale, cu, (int)n_max, reinterpret_cast<uint16_t*>(ws + sc.stage),
                                reinterpret_cast<float*>(ws + sc.bias), sc.shp, s) != hipSuccess)
         return SPKV_E_HIP;
+    return SPKV_OK;
+}
+
+namespace {
+// Pool pages the host's bound would reach after `n` more single-token steps of every
+// sequence with every pair that leaves a window kept.
+int64_t pages_after_steps(const spkv_cache* c, int64_t n) {
+    const int B = c->cfg.batch, Hkv = c->cfg.n_kv_heads, w = c->cfg.window;
+    int64_t pages = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t ev = std::max<int64_t>(0, (int64_t)c->T[b] + n - w) -
+                           std::max<int64_t>(0, (int64_t)c->T[b] - w);
+        for (int h = 0; h < Hkv; ++h) pages += pages_for((int64_t)c->L_ub[b * Hkv + h] + ev);
+    }
+    return pages;
+}
+}  // namespace
+
+int spkv_cache_safe_steps(spkv_cache_t* c, void* stream, int64_t* n_steps) {
+    if (c == nullptr || n_steps == nullptr) return SPKV_E_INVAL;
+    const int rc = refresh_bound(c, static_cast<hipStream_t>(stream), nullptr);
+    if (rc != SPKV_OK) return rc;
+    int64_t hi = INT64_MAX;
+    for (int b = 0; b < c->cfg.batch; ++b)
+        hi = std::min<int64_t>(hi, (int64_t)c->cfg.max_context - c->T[b]);
+    hi = std::max<int64_t>(hi, 0);
+    int64_t lo = 0;                      // largest n known to fit
+    if (pages_after_steps(c, 0) > c->carve.n_pages) hi = 0;
+    while (lo < hi) {                    // pages_after_steps is non-decreasing in n
+        const int64_t mid = lo + (hi - lo + 1) / 2;
+        if (pages_after_steps(c, mid) <= c->carve.n_pages) lo = mid;
+        else hi = mid - 1;
+    }
+    *n_steps = lo;
+    return SPKV_OK;
+}
+
+int spkv_cache_advance(spkv_cache_t* c, int64_t n_steps) {
+    if (c == nullptr || n_steps < 0) return SPKV_E_INVAL;
+    if (n_steps == 0) return SPKV_OK;
+    for (int b = 0; b < c->cfg.batch; ++b)
+        if ((int64_t)c->T[b] + n_steps > c->cfg.max_context) return SPKV_E_CAPACITY;
+    if (pages_after_steps(c, n_steps) > c->carve.n_pages) return SPKV_E_CAPACITY;
+    const int B = c->cfg.batch, Hkv = c->cfg.n_kv_heads, w = c->cfg.window;
+    for (int b = 0; b < B; ++b) {
+        const int64_t ev = std::max<int64_t>(0, (int64_t)c->T[b] + n_steps - w) -
+                           std::max<int64_t>(0, (int64_t)c->T[b] - w);
+        c->T[b] += (int32_t)n_steps;
+        for (int h = 0; h < Hkv; ++h) {
+            int32_t& L = c->L_ub[b * Hkv + h];
+            c->pages_ub += pages_for((int64_t)L + ev) - pages_for(L);
+            L += (int32_t)ev;
+        }
+    }
     return SPKV_OK;
 }
 

@@ -643,3 +643,59 @@ def test_sink_tokens_every_entry_point(n_sink, w):
             want = [s for s in range(n_sink) if s <= T - 1 - w]
             assert cache.kept_positions(b, h)[:len(want)] == want
     cache.close()
+
+
+# ------------------------------------------------------------- replay from a HIP graph
+def test_decode_step_replayed_from_a_hip_graph():
+    """The fused step captured once into a HIP graph and replayed with new inputs in the same
+    buffers: every replay (with eager copies, checks and synchronisations between them) must
+    equal the oracle's step, the host's bookkeeping is carried by spkv_cache_advance, and the
+    number of replays stays inside spkv_cache_safe_steps."""
+    wl = small_workload("graph", 3, 8, 2, 128, [700, 300, 40], [[0.4, 0.1]], window=64, seed=61)
+    stream = TokenStream(wl, device="cuda")
+    cache = H.make_cache(wl, pool_tokens=3 * 2 * 900, extra_context=200)
+    oracle = H.make_oracle(wl)
+    H.prefill(cache, oracle, stream, wl, 4096)
+
+    def next_inputs():
+        k, v, f, cu = stream.next_tokens([1, 1, 1])
+        return k, v, f, cu, stream.next_query()
+
+    k, v, f, cu, q = next_inputs()                    # one eager step: tightens the host's bound
+    out = cache.decode_step(k, v, f, q)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    H.check_output(out, oracle.decode(to_numpy_f32(q))[0], "eager step")
+
+    n_safe = cache.safe_steps()
+    assert n_safe == 200 + 1 - 1                      # max_context is the binding limit here
+    ks, vs, fs, qs = (torch.empty_like(t) for t in (k, v, f, q))
+    outs = torch.empty_like(q)
+    k, v, f, cu, q = next_inputs()
+    for dst, src in ((ks, k), (vs, v), (fs, f), (qs, q)):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):                     # records the two launches; runs nothing
+        cache.decode_step(ks, vs, fs, qs, out=outs)
+    n_replays = 70                                    # crosses page boundaries of the short lists
+    for i in range(n_replays):
+        if i > 0:                                     # the captured call itself counted one step
+            k, v, f, cu, q = next_inputs()
+            for dst, src in ((ks, k), (vs, v), (fs, f), (qs, q)):
+                dst.copy_(src)
+            cache.advance(1)
+        graph.replay()
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        torch.cuda.synchronize()
+        H.check_output(outs, oracle.decode(to_numpy_f32(q))[0], f"replay {i}")
+    H.check_state(cache, oracle, wl, label="after the replays")
+    assert cache.safe_steps() == n_safe - n_replays
+    with pytest.raises(spkv.SPKVError) as e:
+        cache.advance(n_safe)                         # more than fits: refused, nothing changes
+    assert e.value.code == -3
+    k, v, f, cu, q = next_inputs()                    # eager calls go on as before
+    out = cache.decode_step(k, v, f, q)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    H.check_output(out, oracle.decode(to_numpy_f32(q))[0], "eager step after the replays")
+    H.check_state(cache, oracle, wl, label="eager after replays")
+    cache.close()
