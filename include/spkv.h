@@ -208,8 +208,8 @@ int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const f
  *                 spkv_prefill_workspace_bytes(cache, max_b n_b, sum_b n_b) bytes; contents
  *                 need not survive between calls; caller-owned
  * Work is cut per (sequence, KV head) into spans of 256 / group-size consecutive tokens, one
- * workgroup each; for chunks of at most SPKV_MAX_CHUNK_TOKENS tokens on a long cache
- * spkv_decode_chunk (split over the list) is the faster call.
+ * workgroup each; calls whose chunks all fit spkv_decode_chunk are handed to it (it splits
+ * the lists over the chip), the workspace is then not touched.
  * Errors as for spkv_append; SPKV_E_INVAL if the workspace is too small. */
 size_t spkv_prefill_workspace_bytes(const spkv_cache_t* cache, int32_t max_tokens_per_sequence,
                                     int64_t max_total_tokens);

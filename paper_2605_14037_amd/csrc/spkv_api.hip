@@ -566,6 +566,10 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
         n_max = std::max<int64_t>(n_max, n);
     }
     if (n_max == 0) return SPKV_OK;
+    // Short chunks: the multi-token step splits the long-term lists over the whole chip,
+    // where this call would give one workgroup per (sequence, KV head) a whole list to walk.
+    if (n_max <= SPKV_MAX_CHUNK_TOKENS && n_max <= c->cfg.window && n_max * c->carve.G <= 64)
+        return spkv_decode_chunk(c, k, v, util_logits, q, cu_seqlens, out, lse, sm_scale, stream);
     if (k == nullptr || v == nullptr || util_logits == nullptr || q == nullptr || out == nullptr ||
         workspace == nullptr)
         return SPKV_E_INVAL;
