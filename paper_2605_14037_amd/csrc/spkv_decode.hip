@@ -200,10 +200,10 @@ __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t*
 // Second launch of the fused step: one workgroup per (sequence, query head) merges the
 // partials as spkv_decode_combine does, plus one more term for the new token itself, taken
 // straight from the caller's k_new / v_new (score q . k_new in fp32, weight sum 1, value
-// v_new); the workgroup of the group's first head then performs the append of the new
-// token exactly as spkv_append_step does.  The item
-// count of the pair comes from pair_items (written by the split kernel), not from the
-// counters, so the other heads' workgroups never read what the append is changing.
+// v_new).  n_pairs further workgroups of the same launch perform the append of the new
+// token exactly as spkv_append_step does, beside the merges instead of after them.  The
+// item count of a pair comes from pair_items (written by the split kernel), not from the
+// counters, so no merging workgroup reads what the appends are changing.
 template <int D>
 __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t* __restrict__ out,
                                                            float* __restrict__ lse, SpkvSplit sp,
@@ -213,6 +213,15 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
                                                            const uint16_t* __restrict__ q,
                                                            float scale_log2e) {
     constexpr int E = D / 64;
+    __shared__ int s_page;
+    if ((int)blockIdx.x >= v.n_pairs * v.G) {                // the appends
+        const int pair = blockIdx.x - v.n_pairs * v.G;
+        const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+        const int T = v.t_pair[pair], L = v.kept_len[pair];
+        const AppendRegs<D> ar = append_load<D>(v, pair, h, b, T, L, k_new, v_new, f_new, threadIdx.x);
+        append_store<D>(v, pair, T, L, ar, threadIdx.x, &s_page);
+        return;
+    }
     const int pair = blockIdx.x / v.G, g = blockIdx.x - pair * v.G;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -233,15 +242,6 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
     __shared__ float s_m[4];
     __shared__ float s_den[4];
     __shared__ float s_acc[4][D];
-    __shared__ int s_page;
-    // The append's loads are issued before the merge and consumed after it.
-    int T = 0, L = 0;
-    AppendRegs<D> ar;
-    if (g == 0) {
-        T = v.t_pair[pair];
-        L = v.kept_len[pair];
-        ar = append_load<D>(v, pair, h, b, T, L, k_new, v_new, f_new, tid);
-    }
 
     float mw, den, num[E];
     fold_items<D>(v, slot0, g, wave, 4, items, lane, mw, den, num);
@@ -268,7 +268,6 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
         out[o * D + tid] = __builtin_bit_cast(uint16_t, r);
         if (lse != nullptr && tid == 0) lse[o] = (M + log2f(dsum)) * 0.6931471805599453f;
     }
-    if (g == 0) append_store<D>(v, pair, T, L, ar, tid, &s_page);
 }
 
 // ------------------------------------------------------- multi-token step (chunk)
@@ -579,10 +578,10 @@ hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const u
     const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
     if (v.D == 128) {
         spkv_decode_split<128, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
-        spkv_combine_append<128><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
+        spkv_combine_append<128><<<dim3(v.n_pairs * v.G + v.n_pairs), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
     } else {
         spkv_decode_split<64, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
-        spkv_combine_append<64><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
+        spkv_combine_append<64><<<dim3(v.n_pairs * v.G + v.n_pairs), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
     }
     return hipGetLastError();
 }
