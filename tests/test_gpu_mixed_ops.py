@@ -1,0 +1,103 @@
+"""Random sequences of every state-changing call against the fp64 oracle: bulk and single
+appends, fused steps, multi-token steps, prefill attention, sequence release, threshold
+changes and capacity growth, on random small shapes.  After every call that returns outputs
+they are compared element by element; after every call the cache state is compared bit for
+bit (kept lengths, kept positions, statistics)."""
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_14037_amd as spkv
+from oracle.spkv_oracle import SPKVOracle
+from paper_2605_14037_amd.inputs import TokenStream, small_workload, to_numpy_f32
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [(64, 4, 2), (128, 8, 2), (128, 16, 2), (64, 6, 2), (128, 4, 4), (128, 16, 1)]
+
+
+@pytest.mark.parametrize("trial", range(12))
+def test_random_call_sequences(trial):
+    rng = np.random.default_rng(9000 + trial)
+    D, Hq, Hkv = SHAPES[trial % len(SHAPES)]
+    B = int(rng.integers(1, 5))
+    w = int(rng.choice([8, 16, 33, 64, 128]))
+    keep = float(rng.choice([0.1, 0.3, 0.6]))
+    n_sink = int(rng.choice([0, 0, 3]))
+    wl = small_workload("mixed", B, Hq, Hkv, D, [0] * B, keep, window=w, seed=500 + trial)
+    stream = TokenStream(wl, device="cuda")
+    max_ctx, pool = 700, B * Hkv * 260                   # small on purpose: growth will be needed
+    cache = spkv.SPKVCache(B, Hq, Hkv, D, max_context=max_ctx, max_total_kept_tokens=pool, window=w)
+    oracle = SPKVOracle(B, Hq, Hkv, D, window=w, tau=0.5, n_sink=n_sink)
+    if n_sink:
+        cache.set_option(spkv.OPT_SINK_TOKENS, n_sink)
+    G = Hq // Hkv
+    log = []
+
+    def with_growth(call):
+        """Run a cache call; on a capacity refusal grow the cache and repeat it once."""
+        nonlocal max_ctx, pool
+        try:
+            return call()
+        except spkv.SPKVError as e:
+            assert e.code == -3, log
+            max_ctx, pool = max_ctx * 3, pool * 4
+            cache.grow(max_context=max_ctx, max_total_kept_tokens=pool)
+            log.append("grow")
+            return call()
+
+    for step in range(18):
+        op = rng.choice(["bulk", "single", "fused", "chunk", "prefill", "release", "tau"],
+                        p=[0.2, 0.1, 0.2, 0.15, 0.2, 0.1, 0.05])
+        log.append(str(op))
+        if op == "release":
+            b = int(rng.integers(0, B))
+            cache.release_sequence(b)
+            oracle.release_sequence(b)
+        elif op == "tau":
+            tau = float(rng.choice([0.2, 0.5, 0.8]))
+            cache.set_tau(tau)
+            oracle.set_tau(tau)
+        else:
+            if op == "bulk":
+                counts = [int(rng.integers(0, 180)) for _ in range(B)]
+            elif op in ("single", "fused"):
+                counts = [1] * B
+            elif op == "chunk":
+                n_cap = min(16, w, 64 // G)
+                counts = [int(rng.integers(0, n_cap + 1)) for _ in range(B)]
+            else:
+                counts = [int(rng.integers(0, 150)) for _ in range(B)]
+            total = sum(counts)
+            if total == 0:
+                continue
+            k, v, f, cu = stream.next_tokens(counts)
+            q = stream.next_query(rows=total)
+            ref = None
+            if op == "bulk":
+                with_growth(lambda: cache.append(k, v, f, cu))
+                oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+                out = None
+            elif op == "single":
+                with_growth(lambda: cache.append(k, v, f, cu))
+                oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+                out = cache.decode_attention(q)
+                ref = oracle.decode(to_numpy_f32(q))[0]
+            elif op == "fused":
+                out = with_growth(lambda: cache.decode_step(k, v, f, q))
+                oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+                ref = oracle.decode(to_numpy_f32(q))[0]
+            elif op == "chunk":
+                out = with_growth(lambda: cache.decode_chunk(k, v, f, q, cu))
+                oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+                ref = oracle.decode_chunk(to_numpy_f32(q), counts)[0]
+            else:
+                out = with_growth(lambda: cache.prefill_attention(k, v, f, q, cu))
+                oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+                ref = oracle.decode_chunk(to_numpy_f32(q), counts)[0]
+            if ref is not None:
+                H.check_output(out, ref, f"trial {trial} after {log}")
+        H.check_state(cache, oracle, wl, label=f"trial {trial} after {log}")
+    cache.close()
