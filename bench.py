@@ -97,7 +97,7 @@ def prefill_attention_leg(wl: Workload, chunk: int, timed_calls: int, tau=None, 
     if tau <= 0.0:
         pool = B * Hkv * ctx
     else:
-        pool = int(B * Hkv * ctx * float(wl.keep.mean()) * 1.1) + B * Hkv * (chunk + 256)
+        pool = int(B * Hkv * ctx * float(wl.keep.mean()) * 1.1) + B * Hkv * (max(chunk, 4096) + 256)
     cache = spkv.SPKVCache(B, wl.n_q_heads, Hkv, D, max_context=ctx + 64,
                            max_total_kept_tokens=pool, window=w, tau=tau)
     theta = cache.threshold_logit()

@@ -207,9 +207,10 @@ int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const f
  *   workspace     device memory, 256-byte aligned, at least
  *                 spkv_prefill_workspace_bytes(cache, max_b n_b, sum_b n_b) bytes; contents
  *                 need not survive between calls; caller-owned
- * Work is cut per (sequence, KV head) into spans of 256 / group-size consecutive tokens, one
- * workgroup each; calls whose chunks all fit spkv_decode_chunk are handed to it (it splits
- * the lists over the chip), the workspace is then not touched.
+ * Work is cut per (sequence, KV head) into spans of 256 / group-size consecutive tokens; when
+ * the spans alone would not fill the chip, every span's keys are cut into ranges as well
+ * (one workgroup each, merged by a second launch).  Calls whose chunks all fit
+ * spkv_decode_chunk are handed to it; the workspace is then not touched.
  * Errors as for spkv_append; SPKV_E_INVAL if the workspace is too small. */
 size_t spkv_prefill_workspace_bytes(const spkv_cache_t* cache, int32_t max_tokens_per_sequence,
                                     int64_t max_total_tokens);

@@ -543,13 +543,26 @@ int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float
     return SPKV_OK;
 }
 
+namespace {
+// Few spans (short chunks, small batch) leave most of the chip idle while each workgroup
+// walks a whole list: cut every span's tiles into up to this many ranges (about two
+// workgroups per compute unit in all).
+int prefill_split_cap(int spans) {
+    const int kWorkgroupsWanted = 512;
+    if (spans <= 0 || spans >= kWorkgroupsWanted / 2) return 1;
+    return std::min(16, (kWorkgroupsWanted + spans - 1) / spans);
+}
+}  // namespace
+
 size_t spkv_prefill_workspace_bytes(const spkv_cache_t* c, int32_t max_tokens_per_sequence,
                                     int64_t max_total_tokens) {
     if (c == nullptr || max_tokens_per_sequence <= 0 || max_total_tokens <= 0) return 0;
     const size_t prefix = align_up((size_t)max_total_tokens * c->cfg.n_kv_heads * 4);
     const size_t shp = ((size_t)c->cfg.window + max_tokens_per_sequence + kHalfTokens - 1) / kHalfTokens;
     const size_t half_bytes = (size_t)2 * kHalfTokens * c->cfg.head_dim * 2;
-    return prefix + (size_t)c->carve.n_pairs * shp * half_bytes;
+    const int spans = spkv_prefill_spans(c->carve.n_pairs, c->carve.G, max_tokens_per_sequence);
+    return prefix + align_up((size_t)c->carve.n_pairs * shp * half_bytes) +
+           spkv_prefill_partial_bytes(spans, prefill_split_cap(spans), c->cfg.head_dim);
 }
 
 int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
@@ -588,10 +601,20 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
     char* ws = static_cast<char*>(workspace);
     const size_t prefix_bytes = align_up((size_t)cu_seqlens[B] * c->cfg.n_kv_heads * 4);
     const int shp = (c->cfg.window + n_max + kHalfTokens - 1) / kHalfTokens;
+    const size_t stage_bytes =
+        align_up((size_t)c->carve.n_pairs * shp * ((size_t)2 * kHalfTokens * c->cfg.head_dim * 2));
+    // split-K over every span's tiles when the spans alone would not fill the chip; each
+    // range keeps at least a few tiles (lengths from the host's upper bound)
+    const int spans = spkv_prefill_spans(c->carve.n_pairs, c->carve.G, n_max);
+    int64_t tiles = 0;
+    for (int p = 0; p < c->carve.n_pairs; ++p) tiles = std::max<int64_t>(tiles, c->L_ub[p] / kHalfTokens);
+    tiles += (c->cfg.window + 64) / kHalfTokens;
+    const int ks = (int)std::max<int64_t>(1, std::min<int64_t>(prefill_split_cap(spans), tiles / 4));
     if (spkv_launch_prefill(c->view, static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                             util_logits, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
                             lse, sm_scale, cu, n_max, reinterpret_cast<uint16_t*>(ws + prefix_bytes),
-                            reinterpret_cast<int32_t*>(ws), shp, s) != hipSuccess)
+                            reinterpret_cast<int32_t*>(ws), shp, ks,
+                            reinterpret_cast<float*>(ws + prefix_bytes + stage_bytes), s) != hipSuccess)
         return SPKV_E_HIP;
     commit_lengths(c, cu_seqlens);
     c->bound_is_loose = true;

@@ -27,6 +27,8 @@ struct SpkvPrefill {
     int32_t   tb;        // tokens per wave (32 / G)
     int32_t   nblk;      // workgroups (spans of 8 tb tokens) per pair in the grid
     int32_t   pin_xcd;   // 1: all blocks of a pair run on one XCD (shared L2)
+    int32_t   ks;        // workgroups per span: the span's tiles are cut into ks ranges (split-K)
+    float*    part;      // ks > 1: partial (acc, m, l) of every (span, range, column)
 };
 
 // One workgroup per (staging half-page, pair): wave wv fills rows 8 wv .. 8 wv + 7.  Rows
@@ -235,12 +237,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr int kRows = kHalfElems / 512;     // 1 KB rows of a tile
     constexpr int kRowsPerWave = kRows / NW;
     __shared__ __attribute__((aligned(16))) uint16_t s_tile[2][kHalfElems];
-    int pair, qblk;
+    int pair, qblk, kr;      // (sequence, KV head), span, tile range of the span
     if (pf.pin_xcd) {
         // workgroups go round-robin to the 8 XCDs: id % 8 picks the XCD, and every pair
         // lives on XCD pair % 8, so its list is fetched into one L2 and re-read there
-        const int local = blockIdx.x >> 3, lp = local / pf.nblk;
-        qblk = local - lp * pf.nblk;
+        const int local = blockIdx.x >> 3, lp = local / (pf.nblk * pf.ks);
+        const int rem = local - lp * pf.nblk * pf.ks;
+        qblk = rem / pf.ks;
+        kr = rem - qblk * pf.ks;
         // rotate inside every full group of 8 pairs by the group index: with 8 KV heads a
         // plain pair % 8 would give each XCD one head of every sequence, and heads differ
         // several-fold in kept length
@@ -248,8 +252,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         pair = lp * 8 + (((blockIdx.x & 7) + rot) & 7);
         if (pair >= v.n_pairs) return;
     } else {
-        pair = blockIdx.x / pf.nblk;
-        qblk = blockIdx.x - pair * pf.nblk;
+        pair = blockIdx.x / (pf.nblk * pf.ks);
+        const int rem = blockIdx.x - pair * pf.nblk * pf.ks;
+        qblk = rem / pf.ks;
+        kr = rem - qblk * pf.ks;
     }
     qblk = pf.nblk - 1 - qblk;            // longest prefixes first
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
@@ -301,6 +307,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int nB = ((span_last + v.w) >> 5) - sB0 + 1;
     const int lo_w = SOFT ? u_min : max(i0 + 1, u_min), hi_w = i_last + v.w;
     const int n_hp = nA + nB, last = n_hp - 1;
+    // split-K: this workgroup takes tiles [x_begin, x_end) of the span's n_hp
+    const int x_begin = (int)(((long long)kr * n_hp) / pf.ks);
+    const int x_end = (int)(((long long)(kr + 1) * n_hp) / pf.ks);
 
     const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
     const uint16_t* stage = pf.stage + (size_t)pair * pf.shp * (size_t)kHalfElems;
@@ -327,14 +336,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
     u32x4 t[kRowsPerWave];
     {
-        const uint16_t* p = base_of(0) + my_off;
+        const uint16_t* p = base_of(x_begin) + my_off;
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r)
             *reinterpret_cast<u32x4*>(&s_tile[0][my_off + r * 512]) = t[r];
     }
-    const uint16_t* p_next = base_of(1);
+    const uint16_t* p_next = base_of(x_begin + 1);
     __syncthreads();
 
     // Tile loop.  The inner loop never touches the accumulators except by MFMA; when the
@@ -343,12 +352,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // the waves stay in step whatever each one does).  After a rescale the references
     // are at least the tile's column maxima, so the second attempt is accepted; a column
     // with every key excluded so far keeps m = -inf and is accepted on the retry as well.
-    int x = 0;
+    int x = x_begin;
     bool resume = false, pending = false;
     float xs[NQ][8];
-    while (x < n_hp) {
+    while (x < x_end) {
         if (pending) rescale_columns<D, NQ>(xs, SOFT ? 1.0f : scale_log2e, acc, m, l);
-        for (; x < n_hp; ++x) {
+        for (; x < x_end; ++x) {
             if (!resume) {
                 // next tile (after the last one: the same tile again, into the idle buffer)
                 const uint16_t* p = p_next + my_off;
@@ -357,7 +366,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 p_next = base_of(x + 2);
             }
             resume = false;
-            const uint16_t* tile = s_tile[x & 1];
+            const uint16_t* tile = s_tile[(x - x_begin) & 1];
             bool mine;
             int u_tile = 0;
             if (x < nA) {
@@ -426,7 +435,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
 #pragma unroll
             for (int r = 0; r < kRowsPerWave; ++r)
-                *reinterpret_cast<u32x4*>(&s_tile[(x + 1) & 1][my_off + r * 512]) = t[r];
+                *reinterpret_cast<u32x4*>(&s_tile[(x + 1 - x_begin) & 1][my_off + r * 512]) = t[r];
             __syncthreads();
         }
     }
@@ -436,7 +445,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         float lc = l[c];
         lc += __shfl_xor(lc, 16);
         lc += __shfl_xor(lc, 32);
-        if (tok[c] >= 0) {
+        if (tok[c] >= 0 && pf.ks > 1) {
+            // partial of this tile range: un-normalised accumulators, reference, sum
+            // layout: [all columns][D] accumulators, then [all columns][2] (m, l)
+            const size_t n_cols = (size_t)v.n_pairs * pf.nblk * pf.ks * (NW * NQ * 16);
+            const size_t pc = (((size_t)pair * pf.nblk + qblk) * pf.ks + kr) * (NW * NQ * 16) +
+                              wv * (NQ * 16) + c * 16 + n;
+            float* pa = pf.part + pc * D + kc * 4;
+#pragma unroll
+            for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[c][db];
+            if (kc == 0) {
+                pf.part[n_cols * D + pc * 2] = m[c];
+                pf.part[n_cols * D + pc * 2 + 1] = lc;
+            }
+        } else if (tok[c] >= 0) {
             const int col = c * 16 + n;
             const int g = col - (col / v.G) * v.G;
             const size_t o = (size_t)(row0 + tok[c]) * v.Hq + (size_t)h * v.G + g;
@@ -456,29 +478,75 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 }
 
+// Merge of the tile ranges of one (span, column): out = sum_r 2^(m_r - M) acc_r /
+// sum_r 2^(m_r - M) l_r.  One workgroup of D threads per column of a span.
+template <int D>
+__global__ __launch_bounds__(D) void spkv_prefill_combine(SpkvView v, uint16_t* __restrict__ out,
+                                                          float* __restrict__ lse, SpkvPrefill pf,
+                                                          SpkvCu cu) {
+    constexpr int kCols = kPrefillWaves * kPrefillGroups * 16;
+    const int span = blockIdx.x / kCols, cs = blockIdx.x - span * kCols;
+    const int pair = span / pf.nblk, qblk = span - pair * pf.nblk;
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
+    const int wv = cs / (kPrefillGroups * 16), col = cs - wv * (kPrefillGroups * 16);
+    const int i0 = qblk * kPrefillWaves * pf.tb + wv * pf.tb;
+    const int tbv = max(0, min(pf.tb, n_tok - i0));
+    if (col >= tbv * v.G) return;
+    const int i = i0 + col / v.G, g = col - (col / v.G) * v.G;
+    const int d = threadIdx.x;
+    const size_t n_cols = (size_t)v.n_pairs * pf.nblk * pf.ks * kCols;
+    const size_t pc0 = (size_t)span * pf.ks * kCols + cs;      // range r: pc0 + r * kCols
+    const float* ml = pf.part + n_cols * D;
+    float M = SPKV_NEG_INF;
+    for (int r = 0; r < pf.ks; ++r) M = fmaxf(M, ml[(pc0 + (size_t)r * kCols) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int r = 0; r < pf.ks; ++r) {
+        const size_t pc = pc0 + (size_t)r * kCols;
+        const float sc = __builtin_amdgcn_exp2f(ml[pc * 2] - M);      // 0 for a range without keys
+        num += pf.part[pc * D + d] * sc;
+        den += ml[pc * 2 + 1] * sc;
+    }
+    const size_t o = (size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g;
+    const __bf16 r16 = (__bf16)(num / den);
+    out[o * D + d] = __builtin_bit_cast(uint16_t, r16);
+    if (lse != nullptr && d == 0) lse[o] = (M + log2f(den)) * 0.6931471805599453f;
+}
+
 static SpkvPrefill prefill_params(const SpkvView& v, int n_max, uint16_t* stage, int32_t* prefix,
-                                  float* bias, int shp) {
+                                  float* bias, int shp, int ks = 1, float* part = nullptr) {
     SpkvPrefill pf;
+    pf.ks = ks;
+    pf.part = part;
     pf.stage = stage;
     pf.prefix = prefix;
     pf.bias = bias;
     pf.shp = shp;
     pf.tb = (16 * kPrefillGroups) / v.G;
     pf.nblk = (n_max + kPrefillWaves * pf.tb - 1) / (kPrefillWaves * pf.tb);   // spans of one workgroup
-    pf.pin_xcd = (v.n_pairs >= 8 && pf.nblk >= 4) ? 1 : 0;
+    pf.pin_xcd = (v.n_pairs >= 8 && pf.nblk * pf.ks >= 4) ? 1 : 0;
     return pf;
 }
 
 static unsigned prefill_grid(const SpkvView& v, const SpkvPrefill& pf) {
-    return pf.pin_xcd ? 8u * (unsigned)((v.n_pairs + 7) / 8) * (unsigned)pf.nblk
-                      : (unsigned)v.n_pairs * (unsigned)pf.nblk;
+    return pf.pin_xcd ? 8u * (unsigned)((v.n_pairs + 7) / 8) * (unsigned)(pf.nblk * pf.ks)
+                      : (unsigned)v.n_pairs * (unsigned)(pf.nblk * pf.ks);
+}
+
+int spkv_prefill_spans(int n_pairs, int group, int n_max) {
+    const int tb = (16 * kPrefillGroups) / group;
+    return n_pairs * ((n_max + kPrefillWaves * tb - 1) / (kPrefillWaves * tb));
+}
+
+size_t spkv_prefill_partial_bytes(int spans, int ks, int head_dim) {
+    return ks > 1 ? (size_t)spans * ks * (kPrefillWaves * kPrefillGroups * 16) * (head_dim + 2) * 4 : 0;
 }
 
 hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                const float* f, const uint16_t* q, uint16_t* out, float* lse,
                                float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
-                               int32_t* prefix, int shp, hipStream_t s) {
-    const SpkvPrefill pf = prefill_params(v, n_max, stage, prefix, nullptr, shp);
+                               int32_t* prefix, int shp, int ks, float* part, hipStream_t s) {
+    const SpkvPrefill pf = prefill_params(v, n_max, stage, prefix, nullptr, shp, ks, part);
     const float sl = sm_scale * 1.4426950408889634f;
     const int stage_hps = (v.w + n_max + kHalfTokens - 1) / kHalfTokens;
     const unsigned grid = prefill_grid(v, pf);
@@ -487,10 +555,14 @@ hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint1
         spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
         spkv_prefill_attend<128, false><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        if (ks > 1)
+            spkv_prefill_combine<128><<<dim3(v.n_pairs * pf.nblk * kPrefillWaves * kPrefillGroups * 16), dim3(128), 0, s>>>(v, out, lse, pf, cu);
     } else {
         spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
         spkv_prefill_attend<64, false><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        if (ks > 1)
+            spkv_prefill_combine<64><<<dim3(v.n_pairs * pf.nblk * kPrefillWaves * kPrefillGroups * 16), dim3(64), 0, s>>>(v, out, lse, pf, cu);
     }
     return hipGetLastError();
 }
