@@ -204,14 +204,18 @@ int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const f
  * gated-off keys outside the window are never read, the block skipping of Sec. 2.2 at the
  * granularity of single keys).
  *   k, v, util_logits, q, cu_seqlens, out, lse, sm_scale   as for spkv_decode_chunk
- *   workspace     device memory, 256-byte aligned, at least
- *                 spkv_prefill_workspace_bytes(cache, max_b n_b, sum_b n_b) bytes; contents
- *                 need not survive between calls; caller-owned
- * Work is cut per (sequence, KV head) into spans of 256 / group-size consecutive tokens; when
- * the spans alone would not fill the chip, every span's keys are cut into ranges as well
- * (one workgroup each, merged by a second launch).  Calls whose chunks all fit
- * spkv_decode_chunk are handed to it; the workspace is then not touched.
- * Errors as for spkv_append; SPKV_E_INVAL if the workspace is too small. */
+ *   workspace     device memory, 256-byte aligned; spkv_prefill_workspace_bytes(cache, n, t)
+ *                 bytes are enough for every call with at most n tokens per sequence and
+ *                 t tokens in all (a call with shorter chunks may need less, never more);
+ *                 contents need not survive between calls; caller-owned
+ * Work is cut per (sequence, KV head) into spans of consecutive tokens, one workgroup each:
+ * 256 / group-size tokens on eight waves, or a half or a quarter of that on four or two
+ * waves when no sequence brings more.  When the spans alone would not fill the chip, every
+ * span's keys are cut into ranges as well (one workgroup each, merged by a second launch).
+ * Calls whose chunks all fit spkv_decode_chunk are handed to it; the workspace is then not
+ * touched.
+ * Errors as for spkv_append; SPKV_E_INVAL if the workspace cannot hold what the call
+ * writes (checked before anything is written). */
 size_t spkv_prefill_workspace_bytes(const spkv_cache_t* cache, int32_t max_tokens_per_sequence,
                                     int64_t max_total_tokens);
 int spkv_prefill_attention(spkv_cache_t* cache, const void* k, const void* v,

@@ -547,10 +547,10 @@ namespace {
 // Few spans (short chunks, small batch) leave most of the chip idle while each workgroup
 // walks a whole list: cut every span's tiles into up to this many ranges (about two
 // workgroups per compute unit in all).
-int prefill_split_cap(int spans) {
-    const int kWorkgroupsWanted = 512;
-    if (spans <= 0 || spans >= kWorkgroupsWanted / 2) return 1;
-    return std::min(16, (kWorkgroupsWanted + spans - 1) / spans);
+int prefill_split_cap(int spans, int nw) {
+    const int wanted = 512 * 8 / nw;       // a compute unit holds 8 / nw workgroups at a time
+    if (spans <= 0 || spans >= wanted / 2) return 1;
+    return std::min(32, (wanted + spans - 1) / spans);
 }
 }  // namespace
 
@@ -560,9 +560,15 @@ size_t spkv_prefill_workspace_bytes(const spkv_cache_t* c, int32_t max_tokens_pe
     const size_t prefix = align_up((size_t)max_total_tokens * c->cfg.n_kv_heads * 4);
     const size_t shp = ((size_t)c->cfg.window + max_tokens_per_sequence + kHalfTokens - 1) / kHalfTokens;
     const size_t half_bytes = (size_t)2 * kHalfTokens * c->cfg.head_dim * 2;
-    const int spans = spkv_prefill_spans(c->carve.n_pairs, c->carve.G, max_tokens_per_sequence);
-    return prefix + align_up((size_t)c->carve.n_pairs * shp * half_bytes) +
-           spkv_prefill_partial_bytes(spans, prefill_split_cap(spans), c->cfg.head_dim);
+    // Split-K partials.  A call cuts its spans into ks = ceil(wanted / spans) ranges only
+    // while spans < wanted / 2, with wanted = 4096 / nw workgroups of nw waves, so it never
+    // holds more than 1.5 * wanted workgroups of nw * 32 columns: 1.5 * 4096 * 32 columns,
+    // whatever the chunk length.  Caches with so many (sequence, head) pairs that even the
+    // shortest chunks fill the chip never split.
+    const size_t partial = c->carve.n_pairs < 1024
+                               ? align_up((size_t)6144 * 32 * (c->cfg.head_dim + 2) * 4)
+                               : 0;
+    return prefix + align_up((size_t)c->carve.n_pairs * shp * half_bytes) + partial;
 }
 
 int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
@@ -579,9 +585,11 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
         n_max = std::max<int64_t>(n_max, n);
     }
     if (n_max == 0) return SPKV_OK;
-    // Short chunks: the multi-token step splits the long-term lists over the whole chip,
-    // where this call would give one workgroup per (sequence, KV head) a whole list to walk.
-    if (n_max <= SPKV_MAX_CHUNK_TOKENS && n_max <= c->cfg.window && n_max * c->carve.G <= 64)
+    // The shortest chunks go to the multi-token step: with up to 32 query columns its
+    // one-wave items read the lists at the decode step's rate, and it needs fewer launches
+    // (measured on 16 sequences of 32k tokens: 4 tokens 129 us against 148 us here, 8 tokens
+    // 145 against 152; from 16 tokens on this call's two-wave workgroups win, 173 against 203).
+    if (n_max <= SPKV_MAX_CHUNK_TOKENS && n_max <= c->cfg.window && n_max * c->carve.G <= 32)
         return spkv_decode_chunk(c, k, v, util_logits, q, cu_seqlens, out, lse, sm_scale, stream);
     if (k == nullptr || v == nullptr || util_logits == nullptr || q == nullptr || out == nullptr ||
         workspace == nullptr)
@@ -590,8 +598,7 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
         !aligned16(out) || (lse != nullptr && !aligned16(lse)) ||
         (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
         return SPKV_E_INVAL;
-    const size_t need = spkv_prefill_workspace_bytes(c, n_max, cu_seqlens[B]);
-    if (need == 0 || workspace_bytes < need) return SPKV_E_INVAL;
+    if (cu_seqlens[B] <= 0) return SPKV_E_INVAL;
     if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
     const int rc = reserve_capacity(c, cu_seqlens, s);
     if (rc != SPKV_OK) return rc;
@@ -609,7 +616,12 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
     int64_t tiles = 0;
     for (int p = 0; p < c->carve.n_pairs; ++p) tiles = std::max<int64_t>(tiles, c->L_ub[p] / kHalfTokens);
     tiles += (c->cfg.window + 64) / kHalfTokens;
-    const int ks = (int)std::max<int64_t>(1, std::min<int64_t>(prefill_split_cap(spans), tiles / 4));
+    const int nw = spkv_prefill_waves(c->carve.G, n_max);
+    const int ks = (int)std::max<int64_t>(1, std::min<int64_t>(prefill_split_cap(spans, nw), tiles / 4));
+    // exactly what this call writes must fit the workspace
+    if (prefix_bytes + stage_bytes + spkv_prefill_partial_bytes(spans, ks, nw, c->cfg.head_dim) >
+        workspace_bytes)
+        return SPKV_E_INVAL;
     if (spkv_launch_prefill(c->view, static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
                             util_logits, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
                             lse, sm_scale, cu, n_max, reinterpret_cast<uint16_t*>(ws + prefix_bytes),

@@ -93,7 +93,8 @@ hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint1
 // Workgroups (spans of tokens per (sequence, KV head)) of a prefill call, and the bytes of
 // split-K partials for them.
 int spkv_prefill_spans(int n_pairs, int group, int n_max);
-size_t spkv_prefill_partial_bytes(int spans, int ks, int head_dim);
+int spkv_prefill_waves(int group, int n_max);      // waves per workgroup for chunks of n_max tokens
+size_t spkv_prefill_partial_bytes(int spans, int ks, int nw, int head_dim);
 // One-wave workgroups of the split-K kernel the current device holds at once (occupancy x
 // compute units); 0 if the runtime cannot tell.
 int spkv_split_resident_items(int head_dim);

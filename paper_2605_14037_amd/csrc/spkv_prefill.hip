@@ -27,6 +27,7 @@ struct SpkvPrefill {
     int32_t   tb;        // tokens per wave (32 / G)
     int32_t   nblk;      // workgroups (spans of 8 tb tokens) per pair in the grid
     int32_t   pin_xcd;   // 1: all blocks of a pair run on one XCD (shared L2)
+    int32_t   nw;        // waves per workgroup (2, 4 or 8): a span is nw * tb tokens
     int32_t   ks;        // workgroups per span: the span's tiles are cut into ks ranges (split-K)
     float*    part;      // ks > 1: partial (acc, m, l) of every (span, range, column)
 };
@@ -116,7 +117,13 @@ __device__ __forceinline__ unsigned bit_range8(int a, int b) {
 //                    (rare once a few tiles have been seen) and then redoes the tile
 constexpr float kWeightSumLimit = 2048.0f;
 constexpr int kPrefillGroups = 2;    // column groups of 16 per wave
-constexpr int kPrefillWaves = 8;     // waves per workgroup (two per SIMD)
+// Waves per workgroup: 8 (two per SIMD, one workgroup per compute unit) for long chunks; 4
+// or 2 for chunks of fewer tokens than eight waves hold, so that no wave idles and several
+// workgroups -- several tiles in flight -- share a compute unit.
+__host__ __device__ inline int prefill_waves(int group, int n_max) {
+    const int tb = (16 * kPrefillGroups) / group;
+    return n_max <= 2 * tb ? 2 : (n_max <= 4 * tb ? 4 : 8);
+}
 
 template <int D, int NQ>
 __device__ __forceinline__ void tile_scores(const uint16_t* tile, int lane,
@@ -216,7 +223,7 @@ __device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float s
     }
 }
 
-// One workgroup of kPrefillWaves = 8 waves per span of 8 * tb consecutive tokens of one
+// One workgroup of NW (8, for short chunks 4 or 2) waves per span of NW * tb consecutive tokens of one
 // (sequence, KV head); wave wv owns tokens i0 = span start + wv * tb .. + tb - 1 as its
 // 32 MFMA columns (tb = 32 / G tokens times G heads, two groups of 16).  The waves walk the
 // same half-pages, so each 16 KB tile is fetched from memory once per workgroup into an LDS
@@ -227,12 +234,12 @@ __device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float s
 // can run beside the other's MFMAs.  (Measured alternatives: four waves of 64 columns, one
 // per SIMD, 15 % slower -- every latency is exposed; the same with the tile loop software-
 // pipelined by hand, slower still; issue priority for one wave of each SIMD, 27 % slower.)
-template <int D, bool SOFT>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
+template <int D, bool SOFT, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
                                                            uint16_t* __restrict__ out,
                                                            float* __restrict__ lse, float scale_log2e,
                                                            SpkvPrefill pf, SpkvCu cu) {
-    constexpr int NS = D / 32, NB = D / 16, NQ = kPrefillGroups, NW = kPrefillWaves;
+    constexpr int NS = D / 32, NB = D / 16, NQ = kPrefillGroups;
     constexpr int kHalfElems = 2 * kHalfTokens * D;
     constexpr int kRows = kHalfElems / 512;     // 1 KB rows of a tile
     constexpr int kRowsPerWave = kRows / NW;
@@ -484,13 +491,13 @@ template <int D>
 __global__ __launch_bounds__(D) void spkv_prefill_combine(SpkvView v, uint16_t* __restrict__ out,
                                                           float* __restrict__ lse, SpkvPrefill pf,
                                                           SpkvCu cu) {
-    constexpr int kCols = kPrefillWaves * kPrefillGroups * 16;
+    const int kCols = pf.nw * kPrefillGroups * 16;
     const int span = blockIdx.x / kCols, cs = blockIdx.x - span * kCols;
     const int pair = span / pf.nblk, qblk = span - pair * pf.nblk;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
     const int wv = cs / (kPrefillGroups * 16), col = cs - wv * (kPrefillGroups * 16);
-    const int i0 = qblk * kPrefillWaves * pf.tb + wv * pf.tb;
+    const int i0 = qblk * pf.nw * pf.tb + wv * pf.tb;
     const int tbv = max(0, min(pf.tb, n_tok - i0));
     if (col >= tbv * v.G) return;
     const int i = i0 + col / v.G, g = col - (col / v.G) * v.G;
@@ -523,7 +530,8 @@ static SpkvPrefill prefill_params(const SpkvView& v, int n_max, uint16_t* stage,
     pf.bias = bias;
     pf.shp = shp;
     pf.tb = (16 * kPrefillGroups) / v.G;
-    pf.nblk = (n_max + kPrefillWaves * pf.tb - 1) / (kPrefillWaves * pf.tb);   // spans of one workgroup
+    pf.nw = prefill_waves(v.G, n_max);
+    pf.nblk = (n_max + pf.nw * pf.tb - 1) / (pf.nw * pf.tb);   // spans of one workgroup
     pf.pin_xcd = (v.n_pairs >= 8 && pf.nblk * pf.ks >= 4) ? 1 : 0;
     return pf;
 }
@@ -534,12 +542,14 @@ static unsigned prefill_grid(const SpkvView& v, const SpkvPrefill& pf) {
 }
 
 int spkv_prefill_spans(int n_pairs, int group, int n_max) {
-    const int tb = (16 * kPrefillGroups) / group;
-    return n_pairs * ((n_max + kPrefillWaves * tb - 1) / (kPrefillWaves * tb));
+    const int tb = (16 * kPrefillGroups) / group, nw = prefill_waves(group, n_max);
+    return n_pairs * ((n_max + nw * tb - 1) / (nw * tb));
 }
 
-size_t spkv_prefill_partial_bytes(int spans, int ks, int head_dim) {
-    return ks > 1 ? (size_t)spans * ks * (kPrefillWaves * kPrefillGroups * 16) * (head_dim + 2) * 4 : 0;
+int spkv_prefill_waves(int group, int n_max) { return prefill_waves(group, n_max); }
+
+size_t spkv_prefill_partial_bytes(int spans, int ks, int nw, int head_dim) {
+    return ks > 1 ? (size_t)spans * ks * (nw * kPrefillGroups * 16) * (head_dim + 2) * 4 : 0;
 }
 
 hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
@@ -554,15 +564,19 @@ hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint1
     if (v.D == 128) {
         spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
-        spkv_prefill_attend<128, false><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        if (pf.nw == 2) spkv_prefill_attend<128, false, 2><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        else if (pf.nw == 4) spkv_prefill_attend<128, false, 4><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        else spkv_prefill_attend<128, false, 8><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
         if (ks > 1)
-            spkv_prefill_combine<128><<<dim3(v.n_pairs * pf.nblk * kPrefillWaves * kPrefillGroups * 16), dim3(128), 0, s>>>(v, out, lse, pf, cu);
+            spkv_prefill_combine<128><<<dim3(v.n_pairs * pf.nblk * pf.nw * kPrefillGroups * 16), dim3(128), 0, s>>>(v, out, lse, pf, cu);
     } else {
         spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
-        spkv_prefill_attend<64, false><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        if (pf.nw == 2) spkv_prefill_attend<64, false, 2><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        else if (pf.nw == 4) spkv_prefill_attend<64, false, 4><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        else spkv_prefill_attend<64, false, 8><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
         if (ks > 1)
-            spkv_prefill_combine<64><<<dim3(v.n_pairs * pf.nblk * kPrefillWaves * kPrefillGroups * 16), dim3(64), 0, s>>>(v, out, lse, pf, cu);
+            spkv_prefill_combine<64><<<dim3(v.n_pairs * pf.nblk * pf.nw * kPrefillGroups * 16), dim3(64), 0, s>>>(v, out, lse, pf, cu);
     }
     return hipGetLastError();
 }
@@ -581,10 +595,14 @@ hipError_t spkv_launch_soft_gated(const SpkvView& v, const uint16_t* k, const ui
     const unsigned grid = prefill_grid(v, pf);
     if (v.D == 128) {
         spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
-        spkv_prefill_attend<128, true><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        if (pf.nw == 2) spkv_prefill_attend<128, true, 2><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        else if (pf.nw == 4) spkv_prefill_attend<128, true, 4><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        else spkv_prefill_attend<128, true, 8><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
     } else {
         spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
-        spkv_prefill_attend<64, true><<<dim3(grid), dim3(64 * kPrefillWaves), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        if (pf.nw == 2) spkv_prefill_attend<64, true, 2><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        else if (pf.nw == 4) spkv_prefill_attend<64, true, 4><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        else spkv_prefill_attend<64, true, 8><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
     }
     return hipGetLastError();
 }

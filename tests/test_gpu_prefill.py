@@ -13,9 +13,11 @@ from paper_2605_14037_amd.inputs import TokenStream, small_workload, to_numpy_f3
 pytestmark = pytest.mark.gpu
 
 
-def _run_prefill(wl, chunk_counts, pre_chunk=4096, q_gain=1.0, sample=None, seed=0, decode_after=0):
+def _run_prefill(wl, chunk_counts, pre_chunk=4096, q_gain=1.0, sample=None, seed=0, decode_after=0,
+                 shared_workspace=False):
     """Feeds wl.ctx_lens through spkv_append, then every entry of chunk_counts through
-    spkv_prefill_attention; compares all rows (or `sample` random rows per call)."""
+    spkv_prefill_attention; compares all rows (or `sample` random rows per call).
+    shared_workspace: one workspace, sized once for the longest chunk, serves every call."""
     stream = TokenStream(wl, device="cuda", q_gain=q_gain)
     extra = sum(max(c) for c in chunk_counts) + decode_after + 8
     pool = sum(c + extra for c in wl.ctx_lens) * wl.n_kv_heads      # room for "everything kept"
@@ -23,11 +25,16 @@ def _run_prefill(wl, chunk_counts, pre_chunk=4096, q_gain=1.0, sample=None, seed
     oracle = H.make_oracle(wl)
     H.prefill(cache, oracle, stream, wl, pre_chunk)
     rng = np.random.default_rng(seed)
+    ws = None
+    if shared_workspace:
+        n_top = max(max(c) for c in chunk_counts)
+        ws = torch.empty(cache.prefill_workspace_bytes(n_top, n_top * wl.batch), dtype=torch.uint8,
+                         device="cuda")
     for counts in chunk_counts:
         total = sum(counts)
         k, v, f, cu = stream.next_tokens(counts)
         q = stream.next_query(rows=total)
-        res = cache.prefill_attention(k, v, f, q, cu, want_lse=True)
+        res = cache.prefill_attention(k, v, f, q, cu, workspace=ws, want_lse=True)
         oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
         if total:
             out, lse = res
@@ -128,6 +135,16 @@ def test_prefill_same_state_and_outputs_as_chunk_calls():
     ca.close(); cb.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (32, 8)])
+def test_prefill_one_workspace_for_every_chunk_length(Hq, Hkv):
+    """Chunk lengths across the 2-, 4- and 8-wave workgroup shapes and across the split
+    counts (the lists are long enough to be cut into ranges), all in a workspace sized once
+    for the longest chunk."""
+    wl = small_workload("pws", 2, Hq, Hkv, 128, [2500, 900], 0.6, seed=41 + Hq)
+    lens = [520, 300, 130, 70, 40, 33, 24, 17]
+    _run_prefill(wl, [[n, max(1, n // 3)] for n in lens], sample=24, seed=Hq, shared_workspace=True)
+
+
 def test_prefill_rejects_small_workspace_and_leaves_cache_unchanged():
     wl = small_workload("pbad", 1, 8, 2, 64, [0], 0.5, seed=2)
     stream = TokenStream(wl, device="cuda")
@@ -136,7 +153,8 @@ def test_prefill_rejects_small_workspace_and_leaves_cache_unchanged():
     q = stream.next_query(rows=200)
     need = cache.prefill_workspace_bytes(200, 200)
     assert need > 0
-    ws = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    # the staging area of this call alone is (64 + 200) rows * 2 heads * 64 * 2 * 2 bytes
+    ws = torch.empty(128 * 1024, dtype=torch.uint8, device="cuda")
     with pytest.raises(spkv.SPKVError) as e:
         cache.prefill_attention(k, v, f, q, cu, workspace=ws)
     assert e.value.code == -1
