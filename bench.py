@@ -266,11 +266,52 @@ def scaling_sweep(args):
     return rows
 
 
+def predictor_step_leg(caches, steps_in, wl, K):
+    """The step with the utility predictor of the paper's appendix (Linear d_model -> 256,
+    SiLU, Linear 256 -> H_kv; d_model 4096, random weights, logits centred on the workload's
+    mean): spkv_decode_step_predict, and the same predictor as a call of its own followed by
+    spkv_decode_step."""
+    B, Hkv, DM, DH, R = wl.batch, wl.n_kv_heads, 4096, 256, len(caches)
+    g = torch.Generator(device="cuda").manual_seed(wl.seed + 77)
+    w1 = (torch.randn(DH, DM, generator=g, device="cuda") / DM ** 0.5).to(torch.bfloat16)
+    w2 = (torch.randn(Hkv, DH, generator=g, device="cuda") / (0.36 * DH) ** 0.5).to(torch.bfloat16)
+    b1 = torch.zeros(DH, device="cuda")
+    b2 = torch.full((Hkv,), float(wl.mu.mean()), device="cuda")
+    hs = [torch.randn(B, DM, generator=g, device="cuda").to(torch.bfloat16) for _ in range(8)]
+    f = torch.empty(B, Hkv, device="cuda")
+    ws = torch.empty(spkv.load_library().spkv_decode_step_predict_workspace_bytes(B, DH),
+                     dtype=torch.uint8, device="cuda")
+    act = torch.empty(B * DH, dtype=torch.float32, device="cuda")
+
+    def run(n, inside):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            k, v, _, cu, q, out = steps_in[i % len(steps_in)]
+            if inside:
+                caches[i % R].decode_step_predict(hs[i % 8], w1, b1, w2, b2, k, v, q, out=out,
+                                                  util_logits=f, workspace=ws)
+            else:
+                spkv.utility_logits(hs[i % 8], w1, b1, w2, b2, out=f, workspace=act)
+                caches[i % R].decode_step(k, v, f, q, out=out)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    run(max(R, 10), True)
+    t_in = run(K, True)
+    run(max(R, 10), False)
+    t_sep = run(K, False)
+    return {"what": f"predictor {DM}->{DH}->{Hkv} + append + decode per step",
+            "us_per_step_predictor_inside_the_step": t_in * 1e6,
+            "us_per_step_predictor_as_its_own_call": t_sep * 1e6, "steps_timed": K}
+
+
 def layered_bench(wl, args):
     """The 32-layer configuration: one cache per layer; a step runs, for every layer, the
-    stand-in utility predictor (logits = h W_l + b, a [B, 4096] x [4096, H_kv] product done
-    by torch outside the C ABI), spkv_append and spkv_decode_attention.  The layers' caches
-    (10.8 GB of kept K/V) are the cold rotation.  Dense baseline: the same loop over
+    utility predictor on the new tokens' hidden states, the append and the decode attention:
+    spkv_decode_step_predict.  Also timed: the same predictor as a call of its own, and the
+    linear stand-in (logits = h W_l + b, one torch product) before spkv_decode_step.  The
+    layers' caches (10.8 GB of kept K/V) are the cold rotation.  Dense baseline: the same loop over
     tau = 0 caches of `dense_layers` layers, scaled to all layers (stated in the output)."""
     Lyr, B, Hkv = wl.n_layers, wl.batch, wl.n_kv_heads
     caches, streams = [], []
@@ -292,22 +333,54 @@ def layered_bench(wl, args):
                               torch.empty(B, Hkv, device="cuda")))
         ring.append(per_layer)
 
-    def run(cs, n_steps, offset, layers):
+    # The predictor of the paper's appendix (Linear 4096 -> 256, SiLU, Linear 256 -> H_kv) per
+    # layer, random weights; the output layer is rescaled so that the logits of random hidden
+    # states have the workload's mean and unit spread (the keep rate of the configuration).
+    DH = 256
+    mlp = []
+    for l in range(Lyr):
+        w1 = (torch.randn(DH, 4096, generator=g, device="cuda") / 64.0).to(torch.bfloat16)
+        w2 = torch.randn(Hkv, DH, generator=g, device="cuda") / 16.0
+        probe = torch.randn(2048, 4096, generator=g, device="cuda").to(torch.bfloat16)
+        f0 = spkv.utility_logits(probe, w1, None, w2.to(torch.bfloat16), None)
+        w2 = (w2 / f0.std(dim=0)[:, None]).to(torch.bfloat16)
+        f1 = spkv.utility_logits(probe, w1, None, w2, None)
+        b2 = (float(wl.mu.mean()) - f1.mean(dim=0)).contiguous()
+        mlp.append((w1, torch.zeros(DH, device="cuda"), w2, b2))
+    hb = [[t[2].to(torch.bfloat16) for t in per_layer] for per_layer in ring]
+    pws = torch.empty(spkv.load_library().spkv_decode_step_predict_workspace_bytes(B, DH),
+                      dtype=torch.uint8, device="cuda")
+    act_ws = torch.empty(B * DH, dtype=torch.float32, device="cuda")
+
+    def run(cs, n_steps, offset, layers, mode="linear"):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(n_steps):
             for l in range(layers):
                 k, v, h, cu, q, out, f = ring[(offset + i) % 4][l]
-                torch.addmm(bias, h, W[l], out=f)
-                cs[l].decode_step(k, v, f, q, out=out)
+                if mode == "linear":        # stand-in predictor: one torch product per layer
+                    torch.addmm(bias, h, W[l], out=f)
+                    cs[l].decode_step(k, v, f, q, out=out)
+                elif mode == "mlp_separate":
+                    w1, b1, w2, b2 = mlp[l]
+                    spkv.utility_logits(hb[(offset + i) % 4][l], w1, b1, w2, b2, out=f, workspace=act_ws)
+                    cs[l].decode_step(k, v, f, q, out=out)
+                else:                       # the predictor inside the step's two launches
+                    w1, b1, w2, b2 = mlp[l]
+                    cs[l].decode_step_predict(hb[(offset + i) % 4][l], w1, b1, w2, b2, k, v, q,
+                                              out=out, util_logits=f, workspace=pws)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / n_steps
 
     W_, K_ = max(2, args.warmup // 10), max(5, args.steps // 10)
     run(caches, W_, 0, Lyr)
-    dt = run(caches, K_, W_, Lyr)
-    # The same step captured once into a HIP graph (all layers: predictor product + fused
-    # step) and replayed: no per-launch host work, no gaps between the 3 x layers launches.
+    dt_linear = run(caches, K_, W_, Lyr)
+    run(caches, 1, 0, Lyr, "mlp_separate")
+    dt_sep = run(caches, K_, 1, Lyr, "mlp_separate")
+    run(caches, 1, 0, Lyr, "fused")
+    dt = run(caches, K_, 1, Lyr, "fused")
+    # The same step captured once into a HIP graph (all layers) and replayed: no per-launch
+    # host work, no gaps between the 2 x layers launches.
     graph_us = None
     n_rep = K_
     if min(c.safe_steps() for c in caches) > n_rep + 1:
@@ -315,8 +388,9 @@ def layered_bench(wl, args):
         with torch.cuda.graph(graph):
             for l in range(Lyr):
                 k, v, h, cu, q, out, f = ring[0][l]
-                torch.addmm(bias, h, W[l], out=f)
-                caches[l].decode_step(k, v, f, q, out=out)
+                w1, b1, w2, b2 = mlp[l]
+                caches[l].decode_step_predict(hb[0][l], w1, b1, w2, b2, k, v, q, out=out,
+                                              util_logits=f, workspace=pws)
         graph.replay()                       # the step the captured calls accounted for
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -349,8 +423,8 @@ def layered_bench(wl, args):
     if not args.no_dense:
         DL = 8
         dcs = [build_cache(wl, 1000 + l, args.chunk, tau=0.0)[0] for l in range(DL)]
-        run(dcs, 1, 0, DL)
-        ddt = run(dcs, max(3, K_ // 2), 1, DL)
+        run(dcs, 1, 0, DL, "fused")
+        ddt = run(dcs, max(3, K_ // 2), 1, DL, "fused")
         dense = {"what": f"same loop over tau = 0 caches of {DL} layers, scaled x{Lyr // DL} to {Lyr} layers",
                  "us_per_step": ddt * Lyr / DL * 1e6, "kv_bytes_per_step": dense_bytes,
                  "GBps": dense_bytes / (ddt * Lyr / DL) / 1e9, "speedup_of_spkv": ddt * Lyr / DL / dt}
@@ -363,11 +437,17 @@ def layered_bench(wl, args):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {Lyr} layers x (batch {B}, {wl.n_q_heads}q/{Hkv}kv heads, "
                                f"head_dim {wl.head_dim}, ctx {max(wl.ctx_lens)}, window {wl.window}, "
-                               f"tau {wl.tau}), linear 4096->{Hkv} stand-in predictor per layer",
+                               f"tau {wl.tau}), utility predictor 4096->{DH}->{Hkv} per layer, inside the step",
                    "kept_kv_bytes_per_step": kept, "dense_kv_bytes_per_step": dense_bytes,
                    "cache_arena_bytes": arena,
                    "density_evicted": float(np.mean([s.density_evicted for s in stats]))},
         "frac_of_hbm_peak_step": kept / dt / 1e9 / HBM_PEAK_GBPS,
+        "step_entry": "spkv_decode_step_predict (predictor + append + decode, 2 launches per layer)",
+        "other_predictor_paths": {
+            "mlp_by_spkv_utility_logits_then_decode_step": {"us_per_step": dt_sep * 1e6,
+                                                            "GBps": kept / dt_sep / 1e9},
+            "linear_stand_in_by_torch_then_decode_step": {"us_per_step": dt_linear * 1e6,
+                                                          "GBps": kept / dt_linear / 1e9}},
         "hip_graph_replay": None if graph_us is None else {
             "what": "the same step captured once (all layers) and replayed; host bookkeeping by "
                     "spkv_cache_advance", "us_per_step": graph_us, "replays_timed": n_rep,
@@ -548,6 +628,8 @@ def main():
     dt_dec = timed_steps(caches, steps_in, K, W + 2 * K, do_append=False)
     dt_app = timed_steps(caches, steps_in, K, W + 3 * K, do_decode=False)
 
+    predictor_leg = predictor_step_leg(caches, steps_in, wl, K)
+
     # Multi-token steps (spkv_decode_chunk): 4 and 16 new tokens per sequence per call.
     chunk_legs = {}
     for n_tok in (4, 16):
@@ -647,6 +729,7 @@ def main():
         "step_entry": ("spkv_decode_step (fused append + decode, 2 launches)" if fused else
                        "spkv_append + spkv_decode_attention (3 launches)"),
         "us_per_step_other_entry": dt_other / K * 1e6,
+        "step_with_predictor": predictor_leg,
         "host_issue_us_per_step": host_issue_us,
         "decode_only_us": dt_dec / K * 1e6,
         "append_only_us": dt_app / K * 1e6,

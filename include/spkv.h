@@ -270,6 +270,28 @@ int spkv_utility_logits(const void* hidden, const void* w1, const float* b1, con
                         const float* b2, float* logits, float* workspace, int32_t n_tokens,
                         int32_t d_model, int32_t d_hidden, int32_t n_kv_heads, void* stream);
 
+/* Fused step with the utility predictor: spkv_decode_step whose util_logits are not passed
+ * in but computed here from the new tokens' hidden states (Eq. 1, the predictor of
+ * spkv_utility_logits), at no launch of their own: the hidden layer runs in workgroups of
+ * the split-K launch, the output layer in the append workgroups of the merge launch.  The
+ * new token's logit decides nothing before the token leaves the window (Eq. 3-4), so the
+ * attention of the step does not wait for it.
+ *   hidden       device bf16 [batch, d_model], row b: hidden state of sequence b's new token
+ *   w1 b1 w2 b2  as for spkv_utility_logits; d_model a multiple of 128, d_hidden of 16
+ *   k, v, q, out, lse, sm_scale   as for spkv_decode_step
+ *   util_logits  device fp32 [batch, n_kv_heads], OUTPUT: the logits the tokens were stored
+ *                with (fp32 sums in this call's own order: equal to spkv_utility_logits'
+ *                up to fp32 rounding, and the ones that decide the gate)
+ *   workspace    device memory, 16-byte aligned, at least
+ *                spkv_decode_step_predict_workspace_bytes(batch, d_hidden) bytes; caller-owned
+ * Errors as for spkv_decode_step; SPKV_E_INVAL for a bad shape or a workspace too small. */
+size_t spkv_decode_step_predict_workspace_bytes(int32_t batch, int32_t d_hidden);
+int spkv_decode_step_predict(spkv_cache_t* cache, const void* hidden, const void* w1,
+                             const float* b1, const void* w2, const float* b2, int32_t d_model,
+                             int32_t d_hidden, const void* k, const void* v, const void* q,
+                             void* out, float* lse, float* util_logits, void* workspace,
+                             size_t workspace_bytes, float sm_scale, void* stream);
+
 /* Replaying captured steps.  spkv_append (one token per sequence), spkv_decode_attention and
  * spkv_decode_step enqueue kernels only -- no allocation, no copy, no synchronisation as long
  * as the capacity bound holds -- so a serving loop may capture them into a HIP graph (one

@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_grow",
     "spkv_cache_reset",
     "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk",
+    "spkv_decode_step_predict_workspace_bytes", "spkv_decode_step_predict",
     "spkv_prefill_workspace_bytes", "spkv_prefill_attention",
     "spkv_soft_gated_workspace_bytes", "spkv_soft_gated_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_safe_steps", "spkv_cache_advance", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
@@ -87,6 +88,11 @@ def load_library():
     lib.spkv_decode_attention.argtypes = [vp, vp, vp, vp, f32, vp]
     lib.spkv_decode_step.restype = C.c_int
     lib.spkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, vp]
+    lib.spkv_decode_step_predict_workspace_bytes.restype = C.c_size_t
+    lib.spkv_decode_step_predict_workspace_bytes.argtypes = [i32, i32]
+    lib.spkv_decode_step_predict.restype = C.c_int
+    lib.spkv_decode_step_predict.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp,
+                                             vp, vp, C.c_size_t, f32, vp]
     lib.spkv_decode_chunk.restype = C.c_int
     lib.spkv_decode_chunk.argtypes = [vp, vp, vp, vp, vp, P(i32), vp, vp, f32, vp]
     lib.spkv_prefill_workspace_bytes.restype = C.c_size_t
@@ -315,6 +321,44 @@ class SPKVCache:
         _check(self.lib.spkv_decode_step(self.handle, kp, vp, fp, qp, op, lp, float(sm_scale),
                                          _stream()), "spkv_decode_step")
         return (out, lse) if lse is not None else out
+
+    def decode_step_predict(self, hidden, w1, b1, w2, b2, k, v, q, out=None, lse=None,
+                            util_logits=None, workspace=None, sm_scale=0.0, want_lse=False):
+        """Fused step whose gate logits come from the utility predictor, computed inside the
+        step's two launches (spkv_decode_step_predict).  Returns (out, util_logits) or
+        (out, lse, util_logits)."""
+        cfg = self.cfg
+        kv_shape = (cfg.batch, cfg.n_kv_heads, cfg.head_dim)
+        shape = (cfg.batch, cfg.n_q_heads, cfg.head_dim)
+        d_model, d_hidden = hidden.shape[1], w1.shape[0]
+        hp = _dev_ptr(hidden, torch.bfloat16, (cfg.batch, d_model), "hidden")
+        w1p = _dev_ptr(w1, torch.bfloat16, (d_hidden, d_model), "w1")
+        w2p = _dev_ptr(w2, torch.bfloat16, (cfg.n_kv_heads, d_hidden), "w2")
+        b1p = _dev_ptr(b1, torch.float32, (d_hidden,), "b1") if b1 is not None else None
+        b2p = _dev_ptr(b2, torch.float32, (cfg.n_kv_heads,), "b2") if b2 is not None else None
+        kp = _dev_ptr(k, torch.bfloat16, kv_shape, "k")
+        vp = _dev_ptr(v, torch.bfloat16, kv_shape, "v")
+        qp = _dev_ptr(q, torch.bfloat16, shape, "q")
+        if out is None:
+            out = torch.empty(shape, dtype=torch.bfloat16, device=q.device)
+        op = _dev_ptr(out, torch.bfloat16, shape, "out")
+        if lse is None and want_lse:
+            lse = torch.empty(shape[:2], dtype=torch.float32, device=q.device)
+        lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
+        if util_logits is None:
+            util_logits = torch.empty(kv_shape[:2], dtype=torch.float32, device=q.device)
+        fp = _dev_ptr(util_logits, torch.float32, kv_shape[:2], "util_logits")
+        if workspace is None:
+            need = self.lib.spkv_decode_step_predict_workspace_bytes(cfg.batch, d_hidden)
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous uint8 device tensor")
+        _check(self.lib.spkv_decode_step_predict(self.handle, hp, w1p, b1p, w2p, b2p, d_model,
+                                                 d_hidden, kp, vp, qp, op, lp, fp,
+                                                 workspace.data_ptr(), workspace.numel(),
+                                                 float(sm_scale), _stream()),
+               "spkv_decode_step_predict")
+        return (out, lse, util_logits) if lse is not None else (out, util_logits)
 
     def decode_chunk(self, k, v, util_logits, q, cu_seqlens, out=None, lse=None, sm_scale=0.0,
                      want_lse=False):

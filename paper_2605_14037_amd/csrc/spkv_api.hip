@@ -453,6 +453,58 @@ int spkv_decode_step(spkv_cache_t* c, const void* k, const void* v, const float*
     return SPKV_OK;
 }
 
+size_t spkv_decode_step_predict_workspace_bytes(int32_t batch, int32_t d_hidden) {
+    if (batch <= 0 || d_hidden <= 0) return 0;
+    return (size_t)kPredictSplit * batch * d_hidden * sizeof(float);
+}
+
+int spkv_decode_step_predict(spkv_cache_t* c, const void* hidden, const void* w1, const float* b1,
+                             const void* w2, const float* b2, int32_t d_model, int32_t d_hidden,
+                             const void* k, const void* v, const void* q, void* out, float* lse,
+                             float* util_logits, void* workspace, size_t workspace_bytes,
+                             float sm_scale, void* stream) {
+    if (c == nullptr || hidden == nullptr || w1 == nullptr || w2 == nullptr || k == nullptr ||
+        v == nullptr || q == nullptr || out == nullptr || util_logits == nullptr || workspace == nullptr)
+        return SPKV_E_INVAL;
+    if (d_model <= 0 || d_model % 128 != 0 || d_hidden <= 0 || d_hidden % 16 != 0) return SPKV_E_INVAL;
+    if (!aligned16(hidden) || !aligned16(w1) || !aligned16(w2) || !aligned16(k) || !aligned16(v) ||
+        !aligned16(q) || !aligned16(out) || !aligned16(util_logits) || !aligned16(workspace) ||
+        (b1 != nullptr && !aligned16(b1)) || (b2 != nullptr && !aligned16(b2)) ||
+        (lse != nullptr && !aligned16(lse)))
+        return SPKV_E_INVAL;
+    if (workspace_bytes < spkv_decode_step_predict_workspace_bytes(c->cfg.batch, d_hidden))
+        return SPKV_E_INVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
+    if (c->bound_is_loose) {
+        const int rc = refresh_bound(c, s, nullptr);
+        if (rc != SPKV_OK) return rc;
+    }
+    const int rc = reserve_capacity(c, nullptr, s);
+    if (rc != SPKV_OK) return rc;
+    // the predictor's workgroups share the launch: leave them room in the resident round
+    const int n_pred = spkv_predict_blocks(c->cfg.batch, d_hidden);
+    c->split = choose_split(c, std::max(c->carve.n_pairs, c->one_round_items - n_pred),
+                            c->carve.max_items);
+    SpkvPredict pr = {};
+    pr.x = static_cast<const uint16_t*>(hidden);
+    pr.w1 = static_cast<const uint16_t*>(w1);
+    pr.b1 = b1;
+    pr.w2 = static_cast<const uint16_t*>(w2);
+    pr.b2 = b2;
+    pr.part = static_cast<float*>(workspace);
+    pr.logits = util_logits;
+    pr.d_model = d_model;
+    pr.d_hidden = d_hidden;
+    if (spkv_launch_decode_step_predict(c->view, static_cast<const uint16_t*>(k),
+                                        static_cast<const uint16_t*>(v),
+                                        static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
+                                        lse, sm_scale, c->split, pr, s) != hipSuccess)
+        return SPKV_E_HIP;
+    commit_lengths(c, nullptr);
+    return SPKV_OK;
+}
+
 int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse, float sm_scale,
                           void* stream) {
     if (c == nullptr || q == nullptr || out == nullptr) return SPKV_E_INVAL;

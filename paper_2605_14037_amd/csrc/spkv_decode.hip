@@ -3,7 +3,8 @@
 //                        as MFMA operands straight from the page layout
 //   spkv_decode_combine  log-sum-exp merge of the partials
 //   fused step           spkv_decode_split<.., true> + spkv_combine_append: append and decode
-//                        of one token per sequence in two launches instead of three
+//                        of one token per sequence in two launches instead of three; with
+//                        the utility predictor riding along: spkv_decode_split_predict
 //   multi-token step     spkv_chunk_split + spkv_chunk_combine: up to 16 new tokens per sequence
 #include "spkv_device.h"
 
@@ -23,12 +24,12 @@
 // attended, as the next long-term entry; dropped -> it is gone), and publishes every
 // pair's item count for spkv_combine_append, which adds the new token's own term.
 template <int D, bool FUSED>
-__global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
-                                                        float scale_log2e, SpkvSplit sp) {
+__device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint16_t* __restrict__ q,
+                                                  float scale_log2e, SpkvSplit sp, int item) {
     constexpr int NS = D / 32;   // head-dim slabs of one K tile
     constexpr int NB = D / 16;   // 16-wide output blocks
-    const int pair = blockIdx.x / sp.slots;
-    const int j = blockIdx.x - pair * sp.slots;
+    const int pair = item / sp.slots;
+    const int j = item - pair * sp.slots;
     const PairSplit ps = pair_split(v, pair, sp);
     if (FUSED && j == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.items;
     if (j >= ps.items) return;
@@ -124,6 +125,45 @@ __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16
     }
 }
 
+template <int D, bool FUSED>
+__global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
+                                                        float scale_log2e, SpkvSplit sp) {
+    decode_split_item<D, FUSED>(v, q, scale_log2e, sp, blockIdx.x);
+}
+
+// Fused step with the utility predictor (Eq. 1; the appendix builds it as Linear - SiLU -
+// Linear per token): the hidden layer rides in the split launch, the output layer in the
+// append workgroups of the second launch, so the gate logits of the new tokens cost no
+// launch of their own.  The first pr.n_blocks one-wave workgroups of this launch compute
+// partial sums of the hidden layer: workgroup (jb, tb, ks) takes 16 hidden units, 16 tokens
+// and the ks-th of kPredictSplit ranges of d_model on MFMA 16x16x32 (W1 rows as A operand,
+// tokens as the 16 columns) and stores part[ks][token][unit], without bias.  The other
+// workgroups are the work items of spkv_decode_split<D, true>.
+template <int D>
+__global__ __launch_bounds__(64) void spkv_decode_split_predict(SpkvView v,
+                                                                const uint16_t* __restrict__ q,
+                                                                float scale_log2e, SpkvSplit sp,
+                                                                SpkvPredict pr) {
+    if ((int)blockIdx.x >= pr.n_blocks) {
+        decode_split_item<D, true>(v, q, scale_log2e, sp, (int)blockIdx.x - pr.n_blocks);
+        return;
+    }
+    const int n_jb = pr.d_hidden / 16;
+    const int ks = blockIdx.x % kPredictSplit, rest = blockIdx.x / kPredictSplit;
+    const int jb = rest % n_jb, tb = rest / n_jb;
+    const int lane = threadIdx.x, kc = lane >> 4, n = lane & 15;
+    const int kq = pr.d_model / kPredictSplit;            // a multiple of 32
+    const int tok = tb * 16 + n;
+    const bool tok_ok = tok < v.B;
+    // (columns past the last token read token 0's row; their results are never stored)
+    const uint16_t* wrow = pr.w1 + (size_t)(jb * 16 + n) * pr.d_model + ks * kq + kc * 8;
+    const uint16_t* xrow = pr.x + (size_t)(tok_ok ? tok : 0) * pr.d_model + ks * kq + kc * 8;
+    const f32x4 acc = predictor_contract(wrow, xrow, kq);
+    // lane (kc, n) holds hidden units jb * 16 + 4 kc + i of token tb * 16 + n
+    if (tok_ok)
+        *reinterpret_cast<f32x4*>(pr.part + ((size_t)ks * v.B + tok) * pr.d_hidden + jb * 16 + 4 * kc) = acc;
+}
+
 // One wave folds the partials of one (pair, head) into a running (max, sum, acc) triple:
 // with M the running max,  acc = sum_i 2^(m_i - M) acc_i,  den = sum_i 2^(m_i - M) l_i.
 // The loads of successive items are independent; only the cheap rescaling is chained.
@@ -204,21 +244,48 @@ __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t*
 // token exactly as spkv_append_step does, beside the merges instead of after them.  The
 // item count of a pair comes from pair_items (written by the split kernel), not from the
 // counters, so no merging workgroup reads what the appends are changing.
-template <int D>
+//
+// PRED (step with the utility predictor): f_new is not an input.  The append workgroup of
+// (sequence b, head h) first finishes the predictor for its token and head -- hidden
+// activations a_j = SiLU(b1_j + sum of the kPredictSplit partial sums the split launch left),
+// logit = b2_h + sum_j W2[h, j] a_j, all in fp32 -- stores the logit for the caller and
+// appends with it.
+template <int D, bool PRED>
 __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t* __restrict__ out,
                                                            float* __restrict__ lse, SpkvSplit sp,
                                                            const uint16_t* __restrict__ k_new,
                                                            const uint16_t* __restrict__ v_new,
                                                            const float* __restrict__ f_new,
                                                            const uint16_t* __restrict__ q,
-                                                           float scale_log2e) {
+                                                           float scale_log2e, SpkvPredict pr) {
     constexpr int E = D / 64;
     __shared__ int s_page;
     if ((int)blockIdx.x >= v.n_pairs * v.G) {                // the appends
         const int pair = blockIdx.x - v.n_pairs * v.G;
         const int b = pair / v.Hkv, h = pair - b * v.Hkv;
         const int T = v.t_pair[pair], L = v.kept_len[pair];
-        const AppendRegs<D> ar = append_load<D>(v, pair, h, b, T, L, k_new, v_new, f_new, threadIdx.x);
+        float f_tok;
+        if (PRED) {
+            __shared__ float s_sum[4];
+            float sum = 0.f;
+            for (int j = threadIdx.x; j < pr.d_hidden; j += 256) {
+                float a = pr.b1 != nullptr ? pr.b1[j] : 0.f;
+#pragma unroll
+                for (int ks = 0; ks < kPredictSplit; ++ks)
+                    a += pr.part[((size_t)ks * v.B + b) * pr.d_hidden + j];
+                const unsigned wbits = pr.w2[(size_t)h * pr.d_hidden + j];
+                sum += __builtin_bit_cast(float, wbits << 16) * (a / (1.f + __expf(-a)));   // SiLU
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            if ((threadIdx.x & 63) == 0) s_sum[threadIdx.x >> 6] = sum;
+            __syncthreads();
+            f_tok = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]) + (pr.b2 != nullptr ? pr.b2[h] : 0.f);
+            if (threadIdx.x == 0) pr.logits[(size_t)b * v.Hkv + h] = f_tok;
+        } else {
+            f_tok = f_new[(size_t)b * v.Hkv + h];
+        }
+        const AppendRegs<D> ar = append_load<D>(v, pair, h, b, T, L, k_new, v_new, f_tok, threadIdx.x);
         append_store<D>(v, pair, T, L, ar, threadIdx.x, &s_page);
         return;
     }
@@ -576,12 +643,36 @@ hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const u
                                    float sm_scale, SpkvSplit sp, hipStream_t s) {
     const float scale_log2e = sm_scale * 1.4426950408889634f;
     const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
+    const SpkvPredict none = {};
+    const dim3 grid2(v.n_pairs * v.G + v.n_pairs);
     if (v.D == 128) {
         spkv_decode_split<128, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
-        spkv_combine_append<128><<<dim3(v.n_pairs * v.G + v.n_pairs), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
+        spkv_combine_append<128, false><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
     } else {
         spkv_decode_split<64, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
-        spkv_combine_append<64><<<dim3(v.n_pairs * v.G + v.n_pairs), dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e);
+        spkv_combine_append<64, false><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
+    }
+    return hipGetLastError();
+}
+
+int spkv_predict_blocks(int n_tokens, int d_hidden) {
+    return (d_hidden / 16) * ((n_tokens + 15) / 16) * kPredictSplit;
+}
+
+hipError_t spkv_launch_decode_step_predict(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                           const uint16_t* q, uint16_t* out, float* lse,
+                                           float sm_scale, SpkvSplit sp, SpkvPredict pr,
+                                           hipStream_t s) {
+    const float scale_log2e = sm_scale * 1.4426950408889634f;
+    pr.n_blocks = spkv_predict_blocks(v.B, pr.d_hidden);
+    const unsigned grid = (unsigned)pr.n_blocks + (unsigned)v.n_pairs * (unsigned)sp.slots;
+    const dim3 grid2(v.n_pairs * v.G + v.n_pairs);
+    if (v.D == 128) {
+        spkv_decode_split_predict<128><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp, pr);
+        spkv_combine_append<128, true><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
+    } else {
+        spkv_decode_split_predict<64><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp, pr);
+        spkv_combine_append<64, true><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
     }
     return hipGetLastError();
 }

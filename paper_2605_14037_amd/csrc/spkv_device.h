@@ -60,6 +60,33 @@ __device__ __forceinline__ int alloc_page(const SpkvView& v) {
     return page < v.n_pages ? page : -1;
 }
 
+// ------------------------------------------------------------------ utility predictor
+// Hidden layer of the predictor (Eq. 1) for 16 hidden units x 16 tokens over kq (a multiple
+// of 32) elements of d_model: lane (kc, n) passes its row of W1 (unit n) and of the tokens'
+// hidden states (token n), both offset by kc * 8 elements; it gets the sums of units
+// 4 kc .. 4 kc + 3 for token n.  Loads go out eight steps at a time so that the memory
+// round trips overlap (the tail repeats the last step's loads and skips its MFMAs).
+__device__ __forceinline__ f32x4 predictor_contract(const uint16_t* __restrict__ wrow,
+                                                    const uint16_t* __restrict__ xrow, int kq) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < kq; k0 += 256) {
+        uint4 a[8], bv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = min(k0 + u * 32, kq - 32);
+            a[u] = *reinterpret_cast<const uint4*>(wrow + k);
+            bv[u] = *reinterpret_cast<const uint4*>(xrow + k);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k0 + u * 32 < kq)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[u]),
+                                                              __builtin_bit_cast(bf16x8, bv[u]),
+                                                              acc, 0, 0, 0);
+    }
+    return acc;
+}
+
 // ------------------------------------------------- write path, one token per sequence
 // Appendix "Inference Kernels": write the new pair into the next ring slot; if the slot
 // held a pair (window full), that pair leaves the window: keep it (append to the head's
@@ -69,8 +96,8 @@ __device__ __forceinline__ int alloc_page(const SpkvView& v) {
 // Append of one token to one (sequence, head), shared by spkv_append_step (workgroup of D
 // threads) and spkv_combine_append (256 threads, the first D of them move data), in two
 // halves so that a caller can put other work between the loads and the stores.
-// `row` indexes the new token in k/vv/f; T and L are the pair's counters as read by every
-// thread before any of them is updated.
+// `row` indexes the new token in k/vv, f_new is its logit for this head; T and L are the
+// pair's counters as read by every thread before any of them is updated.
 template <int D>
 struct AppendRegs {
     float f_old, f_new;
@@ -85,7 +112,7 @@ template <int D>
 __device__ __forceinline__ AppendRegs<D> append_load(const SpkvView& v, int pair, int h, int row,
                                                      int T, int L, const uint16_t* __restrict__ k,
                                                      const uint16_t* __restrict__ vv,
-                                                     const float* __restrict__ f, int tid) {
+                                                     float f_new, int tid) {
     AppendRegs<D> r;
     const bool mover = tid < D, kmover = tid < D / 8;
     const int slot = T % v.w;
@@ -96,7 +123,7 @@ __device__ __forceinline__ AppendRegs<D> append_load(const SpkvView& v, int pair
     const size_t src = ((size_t)row * v.Hkv + h) * D;
     r.f_old = full ? v.ring_logit[(size_t)pair * v.w + slot] : 0.f;
     r.page_entry = (gk != 0 && lp < v.pt_cap) ? v.page_table[(size_t)pair * v.pt_cap + lp] : -1;
-    r.f_new = f[(size_t)row * v.Hkv + h];
+    r.f_new = f_new;
     r.v_new = 0;
     r.v_old = 0;
     r.k_new = make_uint4(0u, 0u, 0u, 0u);

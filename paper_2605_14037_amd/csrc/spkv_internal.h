@@ -73,6 +73,25 @@ hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* ou
 hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const uint16_t* q, uint16_t* out, float* lse,
                                    float sm_scale, SpkvSplit split, hipStream_t s);
+// Utility predictor riding in the fused step (Eq. 1): inputs, the fp32 partial sums of the
+// hidden layer between the two launches, and the logits it leaves for the caller.
+constexpr int kPredictSplit = 4;      // ranges d_model is cut into
+struct SpkvPredict {
+    const uint16_t* x;      // [B][d_model] hidden states of the new tokens
+    const uint16_t* w1;     // [d_hidden][d_model]
+    const float* b1;        // [d_hidden] or null
+    const uint16_t* w2;     // [Hkv][d_hidden]
+    const float* b2;        // [Hkv] or null
+    float* part;            // [kPredictSplit][B][d_hidden]
+    float* logits;          // [B][Hkv]
+    int32_t d_model, d_hidden;
+    int32_t n_blocks;       // workgroups of the split launch that belong to the predictor
+};
+int spkv_predict_blocks(int n_tokens, int d_hidden);
+hipError_t spkv_launch_decode_step_predict(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
+                                           const uint16_t* q, uint16_t* out, float* lse,
+                                           float sm_scale, SpkvSplit split, SpkvPredict pr,
+                                           hipStream_t s);
 hipError_t spkv_launch_decode_chunk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                     const uint16_t* q, uint16_t* out, float* lse, float sm_scale,
                                     SpkvSplit split, const SpkvCu& cu, int col_groups, hipStream_t s);

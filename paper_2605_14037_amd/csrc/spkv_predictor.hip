@@ -19,13 +19,7 @@ __global__ __launch_bounds__(256) void spkv_predictor_hidden(const uint16_t* __r
     const bool tok_ok = t0 + n < n_tokens;
     const uint16_t* xrow = x + (size_t)(tok_ok ? t0 + n : 0) * d_model + wave * kq + kc * 8;
     // (columns past the last token read token 0's row; their results are never stored)
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int k = 0; k < kq; k += 32) {            // kq is a multiple of 32 (d_model of 128)
-        const uint4 a = *reinterpret_cast<const uint4*>(wrow + k);
-        const uint4 bv = *reinterpret_cast<const uint4*>(xrow + k);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                      __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
-    }
+    const f32x4 acc = predictor_contract(wrow, xrow, kq);   // kq is a multiple of 32 (d_model of 128)
     // lane (kc, n) holds hidden units j0 + 4 kc + i of token t0 + n
     __shared__ float s_part[4][16][17];
 #pragma unroll

@@ -72,7 +72,8 @@ __global__ __launch_bounds__(D) void spkv_append_step(SpkvView v, const uint16_t
     __shared__ int s_page;
     const int T = v.t_pair[pair];
     const int L = v.kept_len[pair];
-    const AppendRegs<D> r = append_load<D>(v, pair, h, row, T, L, k, vv, f, threadIdx.x);
+    const AppendRegs<D> r =
+        append_load<D>(v, pair, h, row, T, L, k, vv, f[(size_t)row * v.Hkv + h], threadIdx.x);
     append_store<D>(v, pair, T, L, r, threadIdx.x, &s_page);
 }
 

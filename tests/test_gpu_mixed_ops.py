@@ -1,5 +1,6 @@
 """Random sequences of every state-changing call against the fp64 oracle: bulk and single
-appends, fused steps, multi-token steps, prefill attention, sequence release, threshold
+appends, fused steps (with the logits passed in, and with the predictor inside the step),
+multi-token steps, prefill attention, sequence release, threshold
 changes and capacity growth, on random small shapes.  After every call that returns outputs
 they are compared element by element; after every call the cache state is compared bit for
 bit (kept lengths, kept positions, statistics)."""
@@ -35,6 +36,13 @@ def test_random_call_sequences(trial):
         cache.set_option(spkv.OPT_SINK_TOKENS, n_sink)
     G = Hq // Hkv
     log = []
+    # predictor of the steps that compute their own logits
+    gw = torch.Generator(device="cuda").manual_seed(700 + trial)
+    dm, dh = 128 * int(rng.integers(1, 4)), 16 * int(rng.integers(1, 6))
+    w1 = (torch.randn(dh, dm, generator=gw, device="cuda") / dm ** 0.5).to(torch.bfloat16)
+    w2 = (3.0 * torch.randn(Hkv, dh, generator=gw, device="cuda") / dh ** 0.5).to(torch.bfloat16)
+    b1 = torch.randn(dh, generator=gw, device="cuda")
+    b2 = torch.randn(Hkv, generator=gw, device="cuda")
 
     def with_growth(call):
         """Run a cache call; on a capacity refusal grow the cache and repeat it once."""
@@ -49,8 +57,8 @@ def test_random_call_sequences(trial):
             return call()
 
     for step in range(18):
-        op = rng.choice(["bulk", "single", "fused", "chunk", "prefill", "release", "tau"],
-                        p=[0.2, 0.1, 0.2, 0.15, 0.2, 0.1, 0.05])
+        op = rng.choice(["bulk", "single", "fused", "fused_pred", "chunk", "prefill", "release", "tau"],
+                        p=[0.2, 0.1, 0.1, 0.1, 0.15, 0.2, 0.1, 0.05])
         log.append(str(op))
         if op == "release":
             b = int(rng.integers(0, B))
@@ -63,7 +71,7 @@ def test_random_call_sequences(trial):
         else:
             if op == "bulk":
                 counts = [int(rng.integers(0, 180)) for _ in range(B)]
-            elif op in ("single", "fused"):
+            elif op in ("single", "fused", "fused_pred"):
                 counts = [1] * B
             elif op == "chunk":
                 n_cap = min(16, w, 64 // G)
@@ -87,6 +95,12 @@ def test_random_call_sequences(trial):
                 ref = oracle.decode(to_numpy_f32(q))[0]
             elif op == "fused":
                 out = with_growth(lambda: cache.decode_step(k, v, f, q))
+                oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+                ref = oracle.decode(to_numpy_f32(q))[0]
+            elif op == "fused_pred":
+                x = torch.randn(B, dm, generator=gw, device="cuda").to(torch.bfloat16)
+                out, f = with_growth(lambda: cache.decode_step_predict(x, w1, b1, w2, b2, k, v, q))
+                assert (f - spkv.utility_logits(x, w1, b1, w2, b2)).abs().max().item() <= 1e-4
                 oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
                 ref = oracle.decode(to_numpy_f32(q))[0]
             elif op == "chunk":

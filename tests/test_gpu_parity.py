@@ -442,6 +442,58 @@ def test_utility_predictor(n, dm, dh, Hk):
         cache.close()
 
 
+@pytest.mark.parametrize("B,Hq,Hk,D,dm,dh,bias", [(16, 32, 8, 128, 4096, 256, True),
+                                                   (3, 8, 2, 64, 256, 48, True),
+                                                   (33, 16, 4, 128, 1024, 64, False),
+                                                   (1, 4, 1, 128, 128, 16, True)])
+def test_decode_step_with_the_predictor_inside(B, Hq, Hk, D, dm, dh, bias):
+    """spkv_decode_step_predict: the logits it computes and stores match the fp64 predictor
+    and the standalone call; fed to the oracle as the fp32 values they are, every later gate
+    decision (the window is short, so tokens appended here are pushed out within the test)
+    and every output match."""
+    from oracle.spkv_oracle import utility_logits as oracle_logits
+    w = 16
+    ctx = [(37 * b) % 90 for b in range(B)]          # includes an empty sequence
+    wl = small_workload("predstep", B, Hq, Hk, D, ctx, 0.5, window=w, seed=B + dm)
+    stream = TokenStream(wl, device="cuda")
+    steps = w + 12
+    pool = sum(c + steps for c in ctx) * Hk + 64 * B * Hk
+    cache = H.make_cache(wl, pool_tokens=pool, extra_context=steps + 8)
+    oracle = H.make_oracle(wl)
+    H.prefill(cache, oracle, stream, wl, 4096)
+    g = torch.Generator(device="cuda").manual_seed(B * 7 + dh)
+    w1 = (torch.randn(dh, dm, generator=g, device="cuda") / dm ** 0.5).to(torch.bfloat16)
+    w2 = (2.0 * torch.randn(Hk, dh, generator=g, device="cuda") / dh ** 0.5).to(torch.bfloat16)
+    b1 = torch.randn(dh, generator=g, device="cuda") if bias else None
+    b2 = 0.3 * torch.randn(Hk, generator=g, device="cuda") if bias else None
+    n32 = lambda t: None if t is None else to_numpy_f32(t)
+    kept_by_gate = 0
+    for i in range(steps):
+        x = torch.randn(B, dm, generator=g, device="cuda").to(torch.bfloat16)
+        k, v, _, cu = stream.next_tokens([1] * B)
+        q = stream.next_query()
+        out, lse, f = cache.decode_step_predict(x, w1, b1, w2, b2, k, v, q, want_lse=True)
+        ref_f = oracle_logits(to_numpy_f32(x), to_numpy_f32(w1), n32(b1), to_numpy_f32(w2), n32(b2))
+        err = np.abs(f.cpu().numpy().astype(np.float64) - ref_f).max()
+        assert err <= 1e-4 + 1e-4 * np.abs(ref_f).max(), (i, err)
+        alone = spkv.utility_logits(x, w1, b1, w2, b2)
+        assert (f - alone).abs().max().item() <= 2e-5 * (1.0 + alone.abs().max().item())
+        kept_by_gate += int((f >= 0).sum().item())
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        ref_out, ref_lse = oracle.decode(to_numpy_f32(q))
+        H.check_output(out, ref_out, f"step {i}")
+        H.check_lse(lse, ref_lse, f"step {i}")
+        if i % 5 == 4 or i == steps - 1:
+            H.check_state(cache, oracle, wl, label=f"step {i}")
+    assert 0 < kept_by_gate < steps * B * Hk             # the gate took both decisions
+    # bad shapes are refused before anything is launched
+    with pytest.raises(spkv.SPKVError):
+        cache.decode_step_predict(x, w1, b1, w2, b2, k, v, q,
+                                  workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    H.check_state(cache, oracle, wl, label="after the refused call")
+    cache.close()
+
+
 # ---------------------------------------------------- multi-token step (chunks <= 16)
 def _run_chunks(wl, chunk_counts, chunk_prefill=4096, q_gain=1.0):
     stream = TokenStream(wl, device="cuda", q_gain=q_gain)
