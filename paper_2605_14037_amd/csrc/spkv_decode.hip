@@ -125,6 +125,13 @@ __device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint1
     }
 }
 
+// Merge workgroups of 16 waves instead of 4: when pairs are cut into more than 32 items and
+// the merge launch has at most one workgroup per compute unit (few long sequences; measured
+// on 4 sequences of 128k: 1.1 us less per step; with 512 merge workgroups, 3 us more).
+static bool wide_merge(const SpkvView& v, const SpkvSplit& sp) {
+    return sp.slots > 32 && v.n_pairs * v.G <= 256;
+}
+
 template <int D, bool FUSED>
 __global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
                                                         float scale_log2e, SpkvSplit sp) {
@@ -167,24 +174,20 @@ __global__ __launch_bounds__(64) void spkv_decode_split_predict(SpkvView v,
 // One wave folds the partials of one (pair, head) into a running (max, sum, acc) triple:
 // with M the running max,  acc = sum_i 2^(m_i - M) acc_i,  den = sum_i 2^(m_i - M) l_i.
 // The loads of successive items are independent; only the cheap rescaling is chained.
-// Lane owns E = D / 64 output elements.
+// Lane owns E = D / 64 output elements.  The wave takes items first, first + stride, ...;
+// the loads of its first eight go out before `items` is looked at (slots beyond the count
+// are valid memory whose contents are then ignored), so that the round trip that fetches the
+// count and the one that fetches the partials overlap.
 template <int D>
 __device__ __forceinline__ void fold_items(const SpkvView& v, size_t slot0, int g, int first,
-                                           int stride, int items, int lane, float& mw, float& den,
-                                           float (&num)[D / 64]) {
-    constexpr int E = D / 64;
+                                           int stride, int slots, int items, int lane, float& mw,
+                                           float& den, float (&num)[D / 64]) {
+    constexpr int E = D / 64, U = 8;
     mw = SPKV_NEG_INF;
     den = 0.f;
 #pragma unroll
     for (int e = 0; e < E; ++e) num[e] = 0.f;
-#pragma unroll 8
-    for (int i = first; i < items; i += stride) {
-        const float* pm = v.part_ml + ((slot0 + i) * v.G + g) * 2;
-        const float* pa = v.part_acc + ((slot0 + i) * v.G + g) * D + lane * E;
-        const float mi = pm[0], li = pm[1];
-        float a[E];
-#pragma unroll
-        for (int e = 0; e < E; ++e) a[e] = pa[e];
+    auto fold = [&](float mi, float li, const float (&a)[E]) {
         const float m_new = fmaxf(mw, mi);
         const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;   // items with no key: weight 0
         const float so = __builtin_amdgcn_exp2f(mw - m_ref), si = __builtin_amdgcn_exp2f(mi - m_ref);
@@ -192,28 +195,53 @@ __device__ __forceinline__ void fold_items(const SpkvView& v, size_t slot0, int 
 #pragma unroll
         for (int e = 0; e < E; ++e) num[e] = num[e] * so + a[e] * si;
         mw = m_new;
+    };
+    float m0[U], l0[U], a0[U][E];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = min(first + u * stride, slots - 1);
+        const float* pm = v.part_ml + ((slot0 + i) * v.G + g) * 2;
+        const float* pa = v.part_acc + ((slot0 + i) * v.G + g) * D + lane * E;
+        m0[u] = pm[0];
+        l0[u] = pm[1];
+#pragma unroll
+        for (int e = 0; e < E; ++e) a0[u][e] = pa[e];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (first + u * stride < items) fold(m0[u], l0[u], a0[u]);
+#pragma unroll 8
+    for (int i = first + U * stride; i < items; i += stride) {
+        const float* pm = v.part_ml + ((slot0 + i) * v.G + g) * 2;
+        const float* pa = v.part_acc + ((slot0 + i) * v.G + g) * D + lane * E;
+        const float mi = pm[0], li = pm[1];
+        float a[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) a[e] = pa[e];
+        fold(mi, li, a);
     }
 }
 
 // Merge the partials of one (sequence, query head):
 //   out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i,  lse = (M + log2(sum)) ln 2.
-// One workgroup of 4 waves per (pair, head): the waves take the items round-robin, each
-// lane owns D/64 output elements, and the four wave results meet in LDS.
-template <int D>
-__global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t* __restrict__ out,
-                                                           float* __restrict__ lse, SpkvSplit sp) {
+// One workgroup of NWM waves per (pair, head): the waves take the items round-robin, each
+// lane owns D/64 output elements, and the wave results meet in LDS.  NWM = 4, or 16 (see
+// wide_merge) so that every wave still gets its items in one round of loads.
+template <int D, int NWM>
+__global__ __launch_bounds__(64 * NWM) void spkv_decode_combine(SpkvView v, uint16_t* __restrict__ out,
+                                                                float* __restrict__ lse, SpkvSplit sp) {
     constexpr int E = D / 64;
     const int pair = blockIdx.x / v.G, g = blockIdx.x - pair * v.G;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int items = pair_split(v, pair, sp).items;
     const size_t slot0 = (size_t)pair * sp.slots;
-    __shared__ float s_m[4];
-    __shared__ float s_den[4];
-    __shared__ float s_acc[4][D];
+    __shared__ float s_m[NWM];
+    __shared__ float s_den[NWM];
+    __shared__ float s_acc[NWM][D];
 
     float mw, den, num[E];
-    fold_items<D>(v, slot0, g, wave, 4, items, lane, mw, den, num);
+    fold_items<D>(v, slot0, g, wave, NWM, sp.slots, items, lane, mw, den, num);
 #pragma unroll
     for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
     if (lane == 0) {
@@ -222,10 +250,12 @@ __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t*
     }
     __syncthreads();
     if (tid < D) {
-        const float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+        float M = s_m[0];
+#pragma unroll
+        for (int wv = 1; wv < NWM; ++wv) M = fmaxf(M, s_m[wv]);
         float nsum = 0.f, dsum = 0.f;
 #pragma unroll
-        for (int wv = 0; wv < 4; ++wv) {
+        for (int wv = 0; wv < NWM; ++wv) {
             const float sc = __builtin_amdgcn_exp2f(s_m[wv] - M);   // 0 for a wave without items
             nsum += s_acc[wv][tid] * sc;
             dsum += s_den[wv] * sc;
@@ -250,8 +280,8 @@ __global__ __launch_bounds__(256) void spkv_decode_combine(SpkvView v, uint16_t*
 // activations a_j = SiLU(b1_j + sum of the kPredictSplit partial sums the split launch left),
 // logit = b2_h + sum_j W2[h, j] a_j, all in fp32 -- stores the logit for the caller and
 // appends with it.
-template <int D, bool PRED>
-__global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t* __restrict__ out,
+template <int D, bool PRED, int NWM>
+__global__ __launch_bounds__(64 * NWM) void spkv_combine_append(SpkvView v, uint16_t* __restrict__ out,
                                                            float* __restrict__ lse, SpkvSplit sp,
                                                            const uint16_t* __restrict__ k_new,
                                                            const uint16_t* __restrict__ v_new,
@@ -266,9 +296,9 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
         const int T = v.t_pair[pair], L = v.kept_len[pair];
         float f_tok;
         if (PRED) {
-            __shared__ float s_sum[4];
+            __shared__ float s_sum[NWM];
             float sum = 0.f;
-            for (int j = threadIdx.x; j < pr.d_hidden; j += 256) {
+            for (int j = threadIdx.x; j < pr.d_hidden; j += 64 * NWM) {
                 float a = pr.b1 != nullptr ? pr.b1[j] : 0.f;
 #pragma unroll
                 for (int ks = 0; ks < kPredictSplit; ++ks)
@@ -280,7 +310,9 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
             for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
             if ((threadIdx.x & 63) == 0) s_sum[threadIdx.x >> 6] = sum;
             __syncthreads();
-            f_tok = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]) + (pr.b2 != nullptr ? pr.b2[h] : 0.f);
+            f_tok = pr.b2 != nullptr ? pr.b2[h] : 0.f;
+#pragma unroll
+            for (int wv = 0; wv < NWM; ++wv) f_tok += s_sum[wv];
             if (threadIdx.x == 0) pr.logits[(size_t)b * v.Hkv + h] = f_tok;
         } else {
             f_tok = f_new[(size_t)b * v.Hkv + h];
@@ -306,12 +338,12 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
     for (int o = 32; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
     const float m_tok = dot * scale_log2e;
     const size_t slot0 = (size_t)pair * sp.slots;
-    __shared__ float s_m[4];
-    __shared__ float s_den[4];
-    __shared__ float s_acc[4][D];
+    __shared__ float s_m[NWM];
+    __shared__ float s_den[NWM];
+    __shared__ float s_acc[NWM][D];
 
     float mw, den, num[E];
-    fold_items<D>(v, slot0, g, wave, 4, items, lane, mw, den, num);
+    fold_items<D>(v, slot0, g, wave, NWM, sp.slots, items, lane, mw, den, num);
 #pragma unroll
     for (int e = 0; e < E; ++e) s_acc[wave][lane * E + e] = num[e];
     if (lane == 0) {
@@ -320,12 +352,14 @@ __global__ __launch_bounds__(256) void spkv_combine_append(SpkvView v, uint16_t*
     }
     __syncthreads();
     if (tid < D) {
-        const float M = fmaxf(fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3])), m_tok);
+        float M = m_tok;
+#pragma unroll
+        for (int wv = 0; wv < NWM; ++wv) M = fmaxf(M, s_m[wv]);
         const float w_tok = __builtin_amdgcn_exp2f(m_tok - M);
         const unsigned ve = v_new[kv_row + tid];
         float nsum = __builtin_bit_cast(float, ve << 16) * w_tok, dsum = w_tok;
 #pragma unroll
-        for (int wv = 0; wv < 4; ++wv) {
+        for (int wv = 0; wv < NWM; ++wv) {
             const float sc = __builtin_amdgcn_exp2f(s_m[wv] - M);
             nsum += s_acc[wv][tid] * sc;
             dsum += s_den[wv] * sc;
@@ -619,10 +653,14 @@ hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* ou
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
     if (split_only) return hipSuccess;
-    if (v.D == 128)
-        spkv_decode_combine<128><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
-    else
-        spkv_decode_combine<64><<<dim3(v.n_pairs * v.G), dim3(256), 0, s>>>(v, out, lse, sp);
+    const dim3 grid2(v.n_pairs * v.G);
+    if (wide_merge(v, sp)) {
+        if (v.D == 128) spkv_decode_combine<128, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp);
+        else spkv_decode_combine<64, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp);
+    } else {
+        if (v.D == 128) spkv_decode_combine<128, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp);
+        else spkv_decode_combine<64, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp);
+    }
     return hipGetLastError();
 }
 
@@ -645,12 +683,15 @@ hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const u
     const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
     const SpkvPredict none = {};
     const dim3 grid2(v.n_pairs * v.G + v.n_pairs);
+    const bool wide = wide_merge(v, sp);
     if (v.D == 128) {
         spkv_decode_split<128, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
-        spkv_combine_append<128, false><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
+        if (wide) spkv_combine_append<128, false, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
+        else spkv_combine_append<128, false, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
     } else {
         spkv_decode_split<64, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
-        spkv_combine_append<64, false><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
+        if (wide) spkv_combine_append<64, false, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
+        else spkv_combine_append<64, false, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
     }
     return hipGetLastError();
 }
@@ -667,12 +708,15 @@ hipError_t spkv_launch_decode_step_predict(const SpkvView& v, const uint16_t* k,
     pr.n_blocks = spkv_predict_blocks(v.B, pr.d_hidden);
     const unsigned grid = (unsigned)pr.n_blocks + (unsigned)v.n_pairs * (unsigned)sp.slots;
     const dim3 grid2(v.n_pairs * v.G + v.n_pairs);
+    const bool wide = wide_merge(v, sp);
     if (v.D == 128) {
         spkv_decode_split_predict<128><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp, pr);
-        spkv_combine_append<128, true><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
+        if (wide) spkv_combine_append<128, true, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
+        else spkv_combine_append<128, true, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
     } else {
         spkv_decode_split_predict<64><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp, pr);
-        spkv_combine_append<64, true><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
+        if (wide) spkv_combine_append<64, true, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
+        else spkv_combine_append<64, true, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
     }
     return hipGetLastError();
 }

@@ -94,7 +94,7 @@ __device__ __forceinline__ f32x4 predictor_contract(const uint16_t* __restrict__
 // its stored logit passes the gate, else drop it.  One workgroup of D threads per
 // (sequence, KV head); thread d moves V element d, threads < D/8 move one 16-byte K chunk.
 // Append of one token to one (sequence, head), shared by spkv_append_step (workgroup of D
-// threads) and spkv_combine_append (256 threads, the first D of them move data), in two
+// threads) and spkv_combine_append (256 or 1024 threads, the first D of them move data), in two
 // halves so that a caller can put other work between the loads and the stores.
 // `row` indexes the new token in k/vv, f_new is its logit for this head; T and L are the
 // pair's counters as read by every thread before any of them is updated.

@@ -158,6 +158,42 @@ def test_split_count_invariance():
         assert (o - outs[0]).abs().max().item() <= 2e-2 * max(1.0, outs[0].abs().max().item())
 
 
+@pytest.mark.parametrize("D,Hq,Hk", [(128, 8, 2), (64, 4, 1), (128, 16, 1)])
+def test_fused_steps_with_many_items_per_pair(D, Hq, Hk):
+    """More than 32 work items per (sequence, head): the merges run in 16-wave workgroups
+    (fused step, step with the predictor, and the plain decode)."""
+    from oracle.spkv_oracle import utility_logits as oracle_logits
+    B = 2
+    wl = small_workload("wide", B, Hq, Hk, D, [5000, 900], 0.5, seed=77 + D + Hq)
+    stream = TokenStream(wl, device="cuda")
+    cache = H.make_cache(wl, pool_tokens=(5900 + 64) * Hk + 128 * B * Hk, extra_context=16)
+    oracle = H.make_oracle(wl)
+    cache.set_option(spkv.OPT_ITEM_TARGET, 32768)         # one item per half-page
+    H.prefill(cache, oracle, stream, wl, 4096)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    dm, dh = 256, 32
+    w1 = (torch.randn(dh, dm, generator=g, device="cuda") / dm ** 0.5).to(torch.bfloat16)
+    w2 = (torch.randn(Hk, dh, generator=g, device="cuda") / dh ** 0.5).to(torch.bfloat16)
+    for i in range(6):
+        k, v, f, cu = stream.next_tokens([1] * B)
+        q = stream.next_query()
+        if i % 3 == 0:
+            out = cache.decode_step(k, v, f, q)
+        elif i % 3 == 1:
+            x = torch.randn(B, dm, generator=g, device="cuda").to(torch.bfloat16)
+            out, f = cache.decode_step_predict(x, w1, None, w2, None, k, v, q)
+            ref_f = oracle_logits(to_numpy_f32(x), to_numpy_f32(w1), None, to_numpy_f32(w2), None)
+            assert np.abs(f.cpu().numpy() - ref_f).max() <= 1e-4 + 1e-4 * np.abs(ref_f).max()
+        else:
+            cache.append(k, v, f, cu)
+            out = cache.decode_attention(q)
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        H.check_output(out, oracle.decode(to_numpy_f32(q))[0], f"step {i}")
+        st = H.check_state(cache, oracle, wl, label=f"step {i}")
+    assert st.n_work_items > 32 * B * Hk
+    cache.close()
+
+
 def test_errors_from_the_host_side():
     wl = small_workload("err", 2, 4, 2, 64, [10, 10], 1.0, seed=1)
     stream = TokenStream(wl, device="cuda")
