@@ -15,7 +15,7 @@ SOURCES = ["spkv_api.hip", "spkv_write.hip", "spkv_decode.hip", "spkv_prefill.hi
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage",
+    "-Wall", "-Wno-unused-function", "-Wno-inline-asm", "-Rpass-analysis=kernel-resource-usage",
 ]
 
 # Waves per SIMD the decode kernels are expected to reach (registers decide it, and the

@@ -125,6 +125,26 @@ __host__ __device__ inline int prefill_waves(int group, int n_max) {
     return n_max <= 2 * tb ? 2 : (n_max <= 4 * tb ? 4 : 8);
 }
 
+// One wave-wide 16-byte load from global memory straight into LDS: lane i's 16 bytes at
+// `src` land at LDS byte address lds_row + 16 i (lds_row wave-uniform).  The load counts
+// as a vector memory load in flight until its data is in LDS.  (No memory clobber: the
+// compiler would then stop treating the page table as read-only and turn its scalar lookups
+// into vector loads that wait for these copies.  What orders the copies against the LDS
+// reads is the workgroup barrier, which neither the asm nor the reads may cross.)
+__device__ __forceinline__ void load_row_to_lds(const uint16_t* src, unsigned lds_row) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(lds_row)
+                 : "m0");
+}
+
+// Waits until at most N of this wave's vector memory loads are still in flight (they
+// complete in the order issued).
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N));
+}
+
 template <int D, int NQ>
 __device__ __forceinline__ void tile_scores(const uint16_t* tile, int lane,
                                             const bf16x8 (&qb)[NQ][D / 32], const unsigned (&kill)[NQ],
@@ -226,10 +246,10 @@ __device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float s
 // One workgroup of NW (8, for short chunks 4 or 2) waves per span of NW * tb consecutive tokens of one
 // (sequence, KV head); wave wv owns tokens i0 = span start + wv * tb .. + tb - 1 as its
 // 32 MFMA columns (tb = 32 / G tokens times G heads, two groups of 16).  The waves walk the
-// same half-pages, so each 16 KB tile is fetched from memory once per workgroup into an LDS
-// double buffer (every wave copies an eighth of the next tile while all consume the current
-// one) and each wave reads its MFMA A operands from LDS with conflict-free 16-byte reads;
-// 256 query columns share one tile fetch.  With 32 columns a wave needs about 200 VGPRs and
+// same half-pages, so each 16 KB tile is fetched from memory once per workgroup into a ring
+// of LDS buffers (every wave copies its share of a tile straight from memory into LDS, two
+// tiles ahead of the one all waves consume) and each wave reads its MFMA A operands from LDS
+// with conflict-free 16-byte reads; 256 query columns share one tile fetch.  With 32 columns a wave needs about 200 VGPRs and
 // no accumulation registers, so two waves fit a SIMD and one wave's vector work (weights)
 // can run beside the other's MFMAs.  (Measured alternatives: four waves of 64 columns, one
 // per SIMD, 15 % slower -- every latency is exposed; the same with the tile loop software-
@@ -243,7 +263,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int kHalfElems = 2 * kHalfTokens * D;
     constexpr int kRows = kHalfElems / 512;     // 1 KB rows of a tile
     constexpr int kRowsPerWave = kRows / NW;
-    __shared__ __attribute__((aligned(16))) uint16_t s_tile[2][kHalfElems];
+    // tiles in flight ahead of the one in use (three ahead measured no faster than two; the
+    // two-wave workgroups of short chunks keep two buffers so that four of them fit a unit)
+    constexpr int kAhead = NW == 2 ? 1 : 2, kBufs = kAhead + 1;
+    __shared__ __attribute__((aligned(16))) uint16_t s_tile[kBufs][kHalfElems];
     int pair, qblk, kr;      // (sequence, KV head), span, tile range of the span
     if (pf.pin_xcd) {
         // workgroups go round-robin to the 8 XCDs: id % 8 picks the XCD, and every pair
@@ -320,10 +343,22 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     const int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
     const uint16_t* stage = pf.stage + (size_t)pair * pf.shp * (size_t)kHalfElems;
+    // Page ids are fetched 64 at a time, one per lane, and picked by readlane: the tile
+    // loop then issues no memory load of its own whose wait would also wait for the tile
+    // copies in flight (a fetch happens once per 128 tiles and is waited for on the spot).
+    int page_lane0 = -64, my_page = 0;      // logical page held by lane 0; this lane's page id
+    auto page_of = [&](int lp) -> int {     // lp wave-uniform, never decreasing
+        if (lp >= page_lane0 + 64) {
+            page_lane0 = lp;
+            my_page = pt[min(lp + lane, v.pt_cap - 1)];
+            __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0)
+        }
+        return __builtin_amdgcn_readlane(my_page, lp - page_lane0);
+    };
     auto base_of = [&](int x) -> const uint16_t* {
         x = min(x, last);
         if (x < nA) {
-            const int page = min(max(pt[min(x >> 1, v.pt_cap - 1)], 0), v.n_pages - 1);
+            const int page = min(max(page_of(min(x >> 1, v.pt_cap - 1)), 0), v.n_pages - 1);
             return pool_page(v, page) + (x & 1) * kHalfElems;
         }
         return stage + (size_t)min(sB0 + x - nA, pf.shp - 1) * kHalfElems;
@@ -339,18 +374,29 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int i = 0; i < NB; ++i) acc[c][i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
+    // Tiles go from memory straight into LDS (no registers in between), two tiles ahead of
+    // their use: the copy of tile x + 2 is issued when tile x is begun, into the buffer that
+    // tile x - 1 vacated, and has a whole tile's time more than it needs before the barrier
+    // that ends tile x + 1's wait.  Every wave copies its kRowsPerWave 1 KB rows of a tile;
+    // a wave-wide 16-byte load lands at the row's LDS address plus 16 bytes per lane.
     const int my_off = (wv * kRowsPerWave * 64 + lane) * 8;     // this lane's part of a tile
-    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-    u32x4 t[kRowsPerWave];
-    {
-        const uint16_t* p = base_of(x_begin) + my_off;
-#pragma unroll
-        for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
+    const unsigned lds_rows = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&s_tile[0][0] +
+                              (unsigned)wv * (kRowsPerWave * 1024);
+    auto stage_tile = [&](const uint16_t* base, int buf) {
+        const uint16_t* p = base + my_off;
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r)
-            *reinterpret_cast<u32x4*>(&s_tile[0][my_off + r * 512]) = t[r];
-    }
-    const uint16_t* p_next = base_of(x_begin + 1);
+            load_row_to_lds(p + r * 512, lds_rows + (unsigned)buf * (kHalfElems * 2) + r * 1024);
+    };
+    // Everything loaded so far (queries, counts) is waited for here, once: left pending, the
+    // first use inside the tile loop would carry a wait for all loads in flight -- on every
+    // tile, tile copies included.
+    __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0)
+    stage_tile(base_of(x_begin), 0);
+#pragma unroll
+    for (int a = 1; a < kAhead; ++a) stage_tile(base_of(x_begin + a), a);
+    const uint16_t* p_next = base_of(x_begin + kAhead);
+    wait_loads_but<(kAhead - 1) * kRowsPerWave>();        // tile x_begin has landed
     __syncthreads();
 
     // Tile loop.  The inner loop never touches the accumulators except by MFMA; when the
@@ -359,21 +405,19 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // the waves stay in step whatever each one does).  After a rescale the references
     // are at least the tile's column maxima, so the second attempt is accepted; a column
     // with every key excluded so far keeps m = -inf and is accepted on the retry as well.
-    int x = x_begin;
+    int x = x_begin, buf = 0;            // buf: LDS buffer of tile x
     bool resume = false, pending = false;
     float xs[NQ][8];
     while (x < x_end) {
         if (pending) rescale_columns<D, NQ>(xs, SOFT ? 1.0f : scale_log2e, acc, m, l);
         for (; x < x_end; ++x) {
             if (!resume) {
-                // next tile (after the last one: the same tile again, into the idle buffer)
-                const uint16_t* p = p_next + my_off;
-#pragma unroll
-                for (int r = 0; r < kRowsPerWave; ++r) t[r] = *reinterpret_cast<const u32x4*>(p + r * 512);
-                p_next = base_of(x + 2);
+                // the tile after next (past the last one: the last tile again, never used)
+                stage_tile(p_next, buf >= 1 ? buf - 1 : kBufs - 1);
+                p_next = base_of(x + kAhead + 1);
             }
             resume = false;
-            const uint16_t* tile = s_tile[(x - x_begin) & 1];
+            const uint16_t* tile = s_tile[buf];
             bool mine;
             int u_tile = 0;
             if (x < nA) {
@@ -440,12 +484,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 pending = false;
                 tile_accumulate<D, NQ>(tile, lane, pw, psum, acc, l);
             }
-#pragma unroll
-            for (int r = 0; r < kRowsPerWave; ++r)
-                *reinterpret_cast<u32x4*>(&s_tile[(x + 1 - x_begin) & 1][my_off + r * 512]) = t[r];
+            wait_loads_but<(kAhead - 1) * kRowsPerWave>();    // all but the newest copies: tile x + 1 has landed
             __syncthreads();
+            buf = buf == kBufs - 1 ? 0 : buf + 1;
         }
     }
+    wait_loads_but<0>();
 
 #pragma unroll
     for (int c = 0; c < NQ; ++c) {
