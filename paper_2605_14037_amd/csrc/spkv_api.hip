@@ -597,12 +597,16 @@ int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float
 
 namespace {
 // Few spans (short chunks, small batch) leave most of the chip idle while each workgroup
-// walks a whole list: cut every span's tiles into up to this many ranges (about two
-// workgroups per compute unit in all).
+// walks a whole list: cut every span's tiles into ranges so that the launch has about as
+// many workgroups as the chip holds at once -- one eight-wave workgroup per compute unit,
+// two of four or two waves (measured: more ranges than that only add partial results to
+// write and merge; 16 sequences x 16 tokens at 32k context, 175 us per call with four
+// times as many, 150 us with this).
+constexpr int kPrefillResident8 = 256, kPrefillResident = 512;
 int prefill_split_cap(int spans, int nw) {
-    const int wanted = 512 * 8 / nw;       // a compute unit holds 8 / nw workgroups at a time
-    if (spans <= 0 || spans >= wanted / 2) return 1;
-    return std::min(32, (wanted + spans - 1) / spans);
+    const int resident = nw == 8 ? kPrefillResident8 : kPrefillResident;
+    if (spans <= 0) return 1;
+    return std::max(1, std::min(32, (resident + spans / 2) / spans));
 }
 }  // namespace
 
@@ -612,13 +616,12 @@ size_t spkv_prefill_workspace_bytes(const spkv_cache_t* c, int32_t max_tokens_pe
     const size_t prefix = align_up((size_t)max_total_tokens * c->cfg.n_kv_heads * 4);
     const size_t shp = ((size_t)c->cfg.window + max_tokens_per_sequence + kHalfTokens - 1) / kHalfTokens;
     const size_t half_bytes = (size_t)2 * kHalfTokens * c->cfg.head_dim * 2;
-    // Split-K partials.  A call cuts its spans into ks = ceil(wanted / spans) ranges only
-    // while spans < wanted / 2, with wanted = 4096 / nw workgroups of nw waves, so it never
-    // holds more than 1.5 * wanted workgroups of nw * 32 columns: 1.5 * 4096 * 32 columns,
-    // whatever the chunk length.  Caches with so many (sequence, head) pairs that even the
-    // shortest chunks fill the chip never split.
-    const size_t partial = c->carve.n_pairs < 1024
-                               ? align_up((size_t)6144 * 32 * (c->cfg.head_dim + 2) * 4)
+    // Split-K partials.  A call cuts its spans into ks = round(resident / spans) ranges, which
+    // is above one only while spans <= 2/3 resident, so it never holds more than 4/3 resident
+    // workgroups of nw * 32 columns: 4/3 * 65536 columns (256 x 8 x 32 = 512 x 4 x 32),
+    // whatever the chunk length.  Caches with more (sequence, head) pairs than that never split.
+    const size_t partial = c->carve.n_pairs <= kPrefillResident * 2 / 3
+                               ? align_up(((size_t)65536 * 4 / 3 + 64) * (c->cfg.head_dim + 2) * 4)
                                : 0;
     return prefix + align_up((size_t)c->carve.n_pairs * shp * half_bytes) + partial;
 }
@@ -637,11 +640,12 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
         n_max = std::max<int64_t>(n_max, n);
     }
     if (n_max == 0) return SPKV_OK;
-    // The shortest chunks go to the multi-token step: with up to 32 query columns its
+    // The shortest chunks go to the multi-token step: with one group of 16 query columns its
     // one-wave items read the lists at the decode step's rate, and it needs fewer launches
-    // (measured on 16 sequences of 32k tokens: 4 tokens 129 us against 148 us here, 8 tokens
-    // 145 against 152; from 16 tokens on this call's two-wave workgroups win, 173 against 203).
-    if (n_max <= SPKV_MAX_CHUNK_TOKENS && n_max <= c->cfg.window && n_max * c->carve.G <= 32)
+    // (measured on 16 sequences of 32k tokens: 2 tokens 122 us against 140 us here, 4 tokens
+    // 128 against 140, 8 tokens 144 against 141; on 4 sequences of 128k this call is ahead
+    // from 2 tokens on, by 4 %).
+    if (n_max <= SPKV_MAX_CHUNK_TOKENS && n_max <= c->cfg.window && n_max * c->carve.G <= 16)
         return spkv_decode_chunk(c, k, v, util_logits, q, cu_seqlens, out, lse, sm_scale, stream);
     if (k == nullptr || v == nullptr || util_logits == nullptr || q == nullptr || out == nullptr ||
         workspace == nullptr)

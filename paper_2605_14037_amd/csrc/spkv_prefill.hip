@@ -263,9 +263,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int kHalfElems = 2 * kHalfTokens * D;
     constexpr int kRows = kHalfElems / 512;     // 1 KB rows of a tile
     constexpr int kRowsPerWave = kRows / NW;
-    // tiles in flight ahead of the one in use (three ahead measured no faster than two; the
-    // two-wave workgroups of short chunks keep two buffers so that four of them fit a unit)
-    constexpr int kAhead = NW == 2 ? 1 : 2, kBufs = kAhead + 1;
+    // Tiles in flight ahead of the one in use (three measured no faster than two, for long
+    // chunks and for the two-wave workgroups of short ones alike).
+    constexpr int kAhead = 2, kBufs = kAhead + 1;
     __shared__ __attribute__((aligned(16))) uint16_t s_tile[kBufs][kHalfElems];
     int pair, qblk, kr;      // (sequence, KV head), span, tile range of the span
     if (pf.pin_xcd) {
