@@ -212,8 +212,9 @@ int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const f
  * 256 / group-size tokens on eight waves, or a half or a quarter of that on four or two
  * waves when no sequence brings more.  When the spans alone would not fill the chip, every
  * span's keys are cut into ranges as well (one workgroup each, merged by a second launch).
- * Calls whose chunks all fit spkv_decode_chunk are handed to it; the workspace is then not
- * touched.
+ * Calls that bring exactly one token for every sequence are handed to spkv_decode_step,
+ * calls whose chunks all fit one group of 16 query columns (16 / group-size tokens) to
+ * spkv_decode_chunk; the workspace is then not touched.
  * Errors as for spkv_append; SPKV_E_INVAL if the workspace cannot hold what the call
  * writes (checked before anything is written). */
 size_t spkv_prefill_workspace_bytes(const spkv_cache_t* cache, int32_t max_tokens_per_sequence,

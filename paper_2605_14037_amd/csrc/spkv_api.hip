@@ -640,6 +640,10 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
         n_max = std::max<int64_t>(n_max, n);
     }
     if (n_max == 0) return SPKV_OK;
+    bool one_each = true;
+    for (int b = 0; b < B; ++b) one_each = one_each && cu_seqlens[b + 1] - cu_seqlens[b] == 1;
+    if (one_each)       // a plain decode step
+        return spkv_decode_step(c, k, v, util_logits, q, out, lse, sm_scale, stream);
     // The shortest chunks go to the multi-token step: with one group of 16 query columns its
     // one-wave items read the lists at the decode step's rate, and it needs fewer launches
     // (measured on 16 sequences of 32k tokens: 2 tokens 122 us against 140 us here, 4 tokens

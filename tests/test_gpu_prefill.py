@@ -145,6 +145,13 @@ def test_prefill_one_workspace_for_every_chunk_length(Hq, Hkv):
     _run_prefill(wl, [[n, max(1, n // 3)] for n in lens], sample=24, seed=Hq, shared_workspace=True)
 
 
+def test_prefill_calls_with_the_shortest_chunks():
+    """One token for every sequence (handed to the fused decode step), one or two tokens for
+    some (the multi-token step), then lengths just above the hand-over."""
+    wl = small_workload("ptiny", 3, 8, 2, 128, [300, 40, 0], 0.5, seed=23)
+    _run_prefill(wl, [[1, 1, 1], [1, 0, 2], [1, 1, 1], [4, 3, 1], [5, 4, 4], [1, 1, 1]])
+
+
 def test_prefill_rejects_small_workspace_and_leaves_cache_unchanged():
     wl = small_workload("pbad", 1, 8, 2, 64, [0], 0.5, seed=2)
     stream = TokenStream(wl, device="cuda")
