@@ -176,8 +176,16 @@ __device__ __forceinline__ int block_excl_scan(int x, int* s_w, int& total) {
 // its window (the list is in ascending position, so they are a prefix of it).  Stage 2
 // writes the tokens whose t - w is a ring position, stage 3 the others; tokens with
 // t - w < 0 get no entry (their count is 0).
-template <int D>
-__global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int32_t* prefix) {
+//
+// SMALL: every sequence brings at most min(w, 256) tokens, so no new token leaves the window
+// within the call and this launch is the whole append: it also counts the gate-on tokens from
+// the logits (stage 1's job otherwise) and, once the kept rows have left the ring, writes
+// the new tokens into it (stage 3's job otherwise).
+template <int D, bool SMALL>
+__global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int32_t* prefix,
+                                                      const uint16_t* __restrict__ k,
+                                                      const uint16_t* __restrict__ vv,
+                                                      const float* __restrict__ f) {
     const int pair = blockIdx.x;
     const int b = pair / v.Hkv;
     const int n = cu.v[b + 1] - cu.v[b];
@@ -221,10 +229,16 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
     // gate-on count of the call (Eq. 8 numerator), summed here so that no kernel needs
     // same-address atomics
     {
-        const int nseg_all = (n + kSegTokens - 1) / kSegTokens;
-        const int32_t* so = v.seg_on + (size_t)pair * v.n_seg_cap;
         int on = 0;
-        for (int i = tid; i < nseg_all; i += 256) on += so[i];
+        if (SMALL) {
+            const bool flag = tid < n && gate_passes(v, f[((size_t)cu.v[b] + tid) * v.Hkv + (pair - b * v.Hkv)],
+                                                     T_old + tid);
+            on = flag ? 1 : 0;
+        } else {
+            const int nseg_all = (n + kSegTokens - 1) / kSegTokens;
+            const int32_t* so = v.seg_on + (size_t)pair * v.n_seg_cap;
+            for (int i = tid; i < nseg_all; i += 256) on += so[i];
+        }
         for (int o = 32; o > 0; o >>= 1) on += __shfl_xor(on, o);
         __syncthreads();
         if (lane == 0) s_w[wave] = on;
@@ -293,6 +307,21 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
         }
         done += tot;
         __syncthreads();
+    }
+    if (SMALL) {        // the new tokens into the ring slots the oldest pairs have just left
+        const int h = pair - b * v.Hkv, row0 = cu.v[b], c = lane & 15;
+        for (int rb = wave * 4; rb < n; rb += 16) {
+            const int jj = rb + (lane >> 4);
+            if (jj < n && c < D / 8) {
+                const int slot = (T_old + jj) % v.w;
+                const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
+                const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
+                const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
+                store_row_chunk<D>(ring_page(v, pair, slot >> 6), slot & 63, c, kk, vl);
+                if (c == 0)
+                    v.ring_logit[(size_t)pair * v.w + slot] = f[((size_t)row0 + jj) * v.Hkv + h];
+            }
+        }
     }
 }
 
@@ -423,13 +452,18 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
 hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const SpkvCu& cu, int n_max, int32_t* prefix,
                                    hipStream_t s) {
+    if (n_max <= v.w && n_max <= kSegTokens) {      // short chunks: one launch
+        if (v.D == 128) spkv_bulk_ring<128, true><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
+        else spkv_bulk_ring<64, true><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
+        return hipGetLastError();
+    }
     const int segs_all = (n_max + kSegTokens - 1) / kSegTokens;
     spkv_bulk_count<<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, f, cu);
     if (v.D == 128) {
-        spkv_bulk_ring<128><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix);
+        spkv_bulk_ring<128, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
         spkv_bulk_scatter<128><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
     } else {
-        spkv_bulk_ring<64><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix);
+        spkv_bulk_ring<64, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
         spkv_bulk_scatter<64><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
     }
     return hipGetLastError();
