@@ -676,10 +676,10 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
     int64_t tiles = 0;
     for (int p = 0; p < c->carve.n_pairs; ++p) tiles = std::max<int64_t>(tiles, c->L_ub[p] / kHalfTokens);
     tiles += (c->cfg.window + 64) / kHalfTokens;
-    const int nw = spkv_prefill_waves(c->carve.G, n_max);
-    const int ks = (int)std::max<int64_t>(1, std::min<int64_t>(prefill_split_cap(spans, nw), tiles / 4));
+    const SpkvPrefillShape sh = spkv_prefill_shape(c->carve.G, n_max);
+    const int ks = (int)std::max<int64_t>(1, std::min<int64_t>(prefill_split_cap(spans, sh.nw), tiles / 4));
     // exactly what this call writes must fit the workspace
-    if (prefix_bytes + stage_bytes + spkv_prefill_partial_bytes(spans, ks, nw, c->cfg.head_dim) >
+    if (prefix_bytes + stage_bytes + spkv_prefill_partial_bytes(spans, ks, sh, c->cfg.head_dim) >
         workspace_bytes)
         return SPKV_E_INVAL;
     if (spkv_launch_prefill(c->view, static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),

@@ -104,16 +104,19 @@ int spkv_chunk_resident_items(int head_dim, int col_groups);
 // n_pairs * shp staging half-pages (shp >= ceil((w + n_max) / 32)); prefix: one int32 per
 // (new token, KV head).
 // ks > 1: every span's tiles are cut into ks ranges, one workgroup each, and merged by a
-// combine launch; part: spkv_prefill_partial_bytes(spans, ks, head_dim) bytes.
+// combine launch; part: spkv_prefill_partial_bytes(spans, ks, shape, head_dim) bytes.
 hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                const float* f, const uint16_t* q, uint16_t* out, float* lse,
                                float sm_scale, const SpkvCu& cu, int n_max, uint16_t* stage,
                                int32_t* prefix, int shp, int ks, float* part, hipStream_t s);
 // Workgroups (spans of tokens per (sequence, KV head)) of a prefill call, and the bytes of
 // split-K partials for them.
+struct SpkvPrefillShape {
+    int nq, nw, tb;       // column groups of 16 per wave, waves per workgroup, tokens per wave
+};
+SpkvPrefillShape spkv_prefill_shape(int group, int n_max);   // for chunks of at most n_max tokens
 int spkv_prefill_spans(int n_pairs, int group, int n_max);
-int spkv_prefill_waves(int group, int n_max);      // waves per workgroup for chunks of n_max tokens
-size_t spkv_prefill_partial_bytes(int spans, int ks, int nw, int head_dim);
+size_t spkv_prefill_partial_bytes(int spans, int ks, SpkvPrefillShape sh, int head_dim);
 // One-wave workgroups of the split-K kernel the current device holds at once (occupancy x
 // compute units); 0 if the runtime cannot tell.
 int spkv_split_resident_items(int head_dim);

@@ -13,9 +13,11 @@
 //   2. the bulk append runs and records, per new token, how long a prefix of the long-term
 //      list lies at least w behind it (see spkv_bulk_ring).
 //   3. spkv_prefill_attend: one wave per block of tb = 32 / G consecutive tokens of one
-//      (sequence, KV head) -- 32 MFMA columns (token, head) in two groups of 16 -- walks
-//      the long-term prefix and then the staging rows of the block's windows, one online
-//      softmax per column, and writes the normalised bf16 rows.  No partials, no combine.
+//      (sequence, KV head) -- 32 MFMA columns (token, head) in two groups of 16; one group
+//      for the shortest chunks -- walks the long-term prefix and then the staging rows of
+//      the block's windows, one online softmax per column, and writes the normalised bf16
+//      rows (or, when a span's keys are cut into ranges, partial results that
+//      spkv_prefill_combine merges).
 // Window keys and long-term entries are disjoint (positions > t - w against <= t - w), so
 // every available key is counted once.
 
@@ -24,10 +26,11 @@ struct SpkvPrefill {
     int32_t*  prefix;    // [total tokens][H_kv]
     float*    bias;      // soft gating only: [n_pairs][shp][32] log2 u of every staging row
     int32_t   shp;       // staging half-pages per pair
-    int32_t   tb;        // tokens per wave (32 / G)
-    int32_t   nblk;      // workgroups (spans of 8 tb tokens) per pair in the grid
+    int32_t   tb;        // tokens per wave (16 nq / G)
+    int32_t   nblk;      // workgroups (spans of nw tb tokens) per pair in the grid
     int32_t   pin_xcd;   // 1: all blocks of a pair run on one XCD (shared L2)
     int32_t   nw;        // waves per workgroup (2, 4 or 8): a span is nw * tb tokens
+    int32_t   nq;        // column groups of 16 per wave (1 or 2)
     int32_t   ks;        // workgroups per span: the span's tiles are cut into ks ranges (split-K)
     float*    part;      // ks > 1: partial (acc, m, l) of every (span, range, column)
 };
@@ -116,13 +119,25 @@ __device__ __forceinline__ unsigned bit_range8(int a, int b) {
 //                    sums and accumulators; the tile loop leaves its inner loop for this
 //                    (rare once a few tiles have been seen) and then redoes the tile
 constexpr float kWeightSumLimit = 2048.0f;
-constexpr int kPrefillGroups = 2;    // column groups of 16 per wave
-// Waves per workgroup: 8 (two per SIMD, one workgroup per compute unit) for long chunks; 4
-// or 2 for chunks of fewer tokens than eight waves hold, so that no wave idles and several
-// workgroups -- several tiles in flight -- share a compute unit.
-__host__ __device__ inline int prefill_waves(int group, int n_max) {
-    const int tb = (16 * kPrefillGroups) / group;
-    return n_max <= 2 * tb ? 2 : (n_max <= 4 * tb ? 4 : 8);
+// Shape of a workgroup: long chunks take eight waves of two column groups of 16 (two waves
+// per SIMD, one workgroup per compute unit, 256 query columns per tile fetch).  Chunks of
+// fewer tokens than eight such waves hold would leave waves without a token, so they get
+// four waves of two groups, and the shortest four or two waves of one group each (measured
+// on 16-token chunks: as fast as two waves of two groups on 16 sequences at 32k, 10 % faster
+// on 4 sequences at 128k; eight waves of one group for 32 tokens were 15 % slower than four
+// of two -- twice the waves read every tile from LDS).
+static SpkvPrefillShape prefill_shape(int group, int n_max) {
+    SpkvPrefillShape sh;
+    const int tb1 = 16 / group, tb2 = 32 / group;    // tokens of one, two column groups (group <= 16)
+    if (n_max <= 4 * tb1) {
+        sh.nq = 1;
+        sh.nw = n_max <= 2 * tb1 ? 2 : 4;
+    } else {
+        sh.nq = 2;
+        sh.nw = n_max <= 4 * tb2 ? 4 : 8;
+    }
+    sh.tb = 16 * sh.nq / group;
+    return sh;
 }
 
 // One wave-wide 16-byte load from global memory straight into LDS: lane i's 16 bytes at
@@ -245,7 +260,8 @@ __device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float s
 
 // One workgroup of NW (8, for short chunks 4 or 2) waves per span of NW * tb consecutive tokens of one
 // (sequence, KV head); wave wv owns tokens i0 = span start + wv * tb .. + tb - 1 as its
-// 32 MFMA columns (tb = 32 / G tokens times G heads, two groups of 16).  The waves walk the
+// 16 NQ MFMA columns (tb = 16 NQ / G tokens times G heads; NQ = 2 groups of 16, one for the
+// shortest chunks).  The waves walk the
 // same half-pages, so each 16 KB tile is fetched from memory once per workgroup into a ring
 // of LDS buffers (every wave copies its share of a tile straight from memory into LDS, two
 // tiles ahead of the one all waves consume) and each wave reads its MFMA A operands from LDS
@@ -254,12 +270,12 @@ __device__ __forceinline__ void rescale_columns(const float (&x)[NQ][8], float s
 // can run beside the other's MFMAs.  (Measured alternatives: four waves of 64 columns, one
 // per SIMD, 15 % slower -- every latency is exposed; the same with the tile loop software-
 // pipelined by hand, slower still; issue priority for one wave of each SIMD, 27 % slower.)
-template <int D, bool SOFT, int NW>
+template <int D, bool SOFT, int NW, int NQ>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void spkv_prefill_attend(SpkvView v, const uint16_t* __restrict__ q,
                                                            uint16_t* __restrict__ out,
                                                            float* __restrict__ lse, float scale_log2e,
                                                            SpkvPrefill pf, SpkvCu cu) {
-    constexpr int NS = D / 32, NB = D / 16, NQ = kPrefillGroups;
+    constexpr int NS = D / 32, NB = D / 16;
     constexpr int kHalfElems = 2 * kHalfTokens * D;
     constexpr int kRows = kHalfElems / 512;     // 1 KB rows of a tile
     constexpr int kRowsPerWave = kRows / NW;
@@ -535,12 +551,12 @@ template <int D>
 __global__ __launch_bounds__(D) void spkv_prefill_combine(SpkvView v, uint16_t* __restrict__ out,
                                                           float* __restrict__ lse, SpkvPrefill pf,
                                                           SpkvCu cu) {
-    const int kCols = pf.nw * kPrefillGroups * 16;
+    const int kCols = pf.nw * pf.nq * 16;
     const int span = blockIdx.x / kCols, cs = blockIdx.x - span * kCols;
     const int pair = span / pf.nblk, qblk = span - pair * pf.nblk;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
-    const int wv = cs / (kPrefillGroups * 16), col = cs - wv * (kPrefillGroups * 16);
+    const int wv = cs / (pf.nq * 16), col = cs - wv * (pf.nq * 16);
     const int i0 = qblk * pf.nw * pf.tb + wv * pf.tb;
     const int tbv = max(0, min(pf.tb, n_tok - i0));
     if (col >= tbv * v.G) return;
@@ -573,8 +589,10 @@ static SpkvPrefill prefill_params(const SpkvView& v, int n_max, uint16_t* stage,
     pf.prefix = prefix;
     pf.bias = bias;
     pf.shp = shp;
-    pf.tb = (16 * kPrefillGroups) / v.G;
-    pf.nw = prefill_waves(v.G, n_max);
+    const SpkvPrefillShape sh = prefill_shape(v.G, n_max);
+    pf.tb = sh.tb;
+    pf.nw = sh.nw;
+    pf.nq = sh.nq;
     pf.nblk = (n_max + pf.nw * pf.tb - 1) / (pf.nw * pf.tb);   // spans of one workgroup
     pf.pin_xcd = (v.n_pairs >= 8 && pf.nblk * pf.ks >= 4) ? 1 : 0;
     return pf;
@@ -585,15 +603,29 @@ static unsigned prefill_grid(const SpkvView& v, const SpkvPrefill& pf) {
                       : (unsigned)v.n_pairs * (unsigned)(pf.nblk * pf.ks);
 }
 
+SpkvPrefillShape spkv_prefill_shape(int group, int n_max) { return prefill_shape(group, n_max); }
+
 int spkv_prefill_spans(int n_pairs, int group, int n_max) {
-    const int tb = (16 * kPrefillGroups) / group, nw = prefill_waves(group, n_max);
-    return n_pairs * ((n_max + nw * tb - 1) / (nw * tb));
+    const SpkvPrefillShape sh = prefill_shape(group, n_max);
+    return n_pairs * ((n_max + sh.nw * sh.tb - 1) / (sh.nw * sh.tb));
 }
 
-int spkv_prefill_waves(int group, int n_max) { return prefill_waves(group, n_max); }
+size_t spkv_prefill_partial_bytes(int spans, int ks, SpkvPrefillShape sh, int head_dim) {
+    return ks > 1 ? (size_t)spans * ks * (sh.nw * sh.nq * 16) * (head_dim + 2) * 4 : 0;
+}
 
-size_t spkv_prefill_partial_bytes(int spans, int ks, int nw, int head_dim) {
-    return ks > 1 ? (size_t)spans * ks * (nw * kPrefillGroups * 16) * (head_dim + 2) * 4 : 0;
+// The attention launch of the shape chosen for the call.
+template <int D, bool SOFT>
+static void launch_attend(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse, float sl,
+                          const SpkvPrefill& pf, const SpkvCu& cu, unsigned grid, hipStream_t s) {
+    if (pf.nq == 2 && pf.nw == 8)
+        spkv_prefill_attend<D, SOFT, 8, 2><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    else if (pf.nq == 2)
+        spkv_prefill_attend<D, SOFT, 4, 2><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    else if (pf.nw == 4)
+        spkv_prefill_attend<D, SOFT, 4, 1><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
+    else
+        spkv_prefill_attend<D, SOFT, 2, 1><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
 }
 
 hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
@@ -608,19 +640,15 @@ hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint1
     if (v.D == 128) {
         spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
-        if (pf.nw == 2) spkv_prefill_attend<128, false, 2><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
-        else if (pf.nw == 4) spkv_prefill_attend<128, false, 4><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
-        else spkv_prefill_attend<128, false, 8><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        launch_attend<128, false>(v, q, out, lse, sl, pf, cu, grid, s);
         if (ks > 1)
-            spkv_prefill_combine<128><<<dim3(v.n_pairs * pf.nblk * pf.nw * kPrefillGroups * 16), dim3(128), 0, s>>>(v, out, lse, pf, cu);
+            spkv_prefill_combine<128><<<dim3(v.n_pairs * pf.nblk * pf.nw * pf.nq * 16), dim3(128), 0, s>>>(v, out, lse, pf, cu);
     } else {
         spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
-        if (pf.nw == 2) spkv_prefill_attend<64, false, 2><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
-        else if (pf.nw == 4) spkv_prefill_attend<64, false, 4><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
-        else spkv_prefill_attend<64, false, 8><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        launch_attend<64, false>(v, q, out, lse, sl, pf, cu, grid, s);
         if (ks > 1)
-            spkv_prefill_combine<64><<<dim3(v.n_pairs * pf.nblk * pf.nw * kPrefillGroups * 16), dim3(64), 0, s>>>(v, out, lse, pf, cu);
+            spkv_prefill_combine<64><<<dim3(v.n_pairs * pf.nblk * pf.nw * pf.nq * 16), dim3(64), 0, s>>>(v, out, lse, pf, cu);
     }
     return hipGetLastError();
 }
@@ -639,14 +667,10 @@ hipError_t spkv_launch_soft_gated(const SpkvView& v, const uint16_t* k, const ui
     const unsigned grid = prefill_grid(v, pf);
     if (v.D == 128) {
         spkv_prefill_stage<128><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
-        if (pf.nw == 2) spkv_prefill_attend<128, true, 2><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
-        else if (pf.nw == 4) spkv_prefill_attend<128, true, 4><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
-        else spkv_prefill_attend<128, true, 8><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        launch_attend<128, true>(v, q, out, lse, sl, pf, cu, grid, s);
     } else {
         spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
-        if (pf.nw == 2) spkv_prefill_attend<64, true, 2><<<dim3(grid), dim3(128), 0, s>>>(v, q, out, lse, sl, pf, cu);
-        else if (pf.nw == 4) spkv_prefill_attend<64, true, 4><<<dim3(grid), dim3(256), 0, s>>>(v, q, out, lse, sl, pf, cu);
-        else spkv_prefill_attend<64, true, 8><<<dim3(grid), dim3(512), 0, s>>>(v, q, out, lse, sl, pf, cu);
+        launch_attend<64, true>(v, q, out, lse, sl, pf, cu, grid, s);
     }
     return hipGetLastError();
 }
