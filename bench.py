@@ -630,7 +630,9 @@ def main():
 
     predictor_leg = predictor_step_leg(caches, steps_in, wl, K)
 
-    # Multi-token steps (spkv_decode_chunk): 4 and 16 new tokens per sequence per call.
+    # Multi-token steps: 4 and 16 new tokens per sequence per call, through
+    # spkv_decode_chunk and through spkv_prefill_attention (which hands the shortest chunks
+    # to the former itself).
     chunk_legs = {}
     for n_tok in (4, 16):
         if n_tok * (wl.n_q_heads // wl.n_kv_heads) > 64:
@@ -640,20 +642,29 @@ def main():
             k, v, f, cu = streams[j % R].next_tokens([n_tok] * wl.batch)
             q = streams[j % R].next_query(rows=n_tok * wl.batch)
             ins.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
-        for j in range(R):
-            k, v, f, cu, q, o = ins[j]
-            caches[j % R].decode_chunk(k, v, f, q, cu, out=o)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
+        ws = torch.empty(caches[0].prefill_workspace_bytes(n_tok, n_tok * wl.batch),
+                         dtype=torch.uint8, device="cuda")
         Kc = max(R, K // 8)
-        for j in range(Kc):
-            k, v, f, cu, q, o = ins[j % len(ins)]
-            caches[j % R].decode_chunk(k, v, f, q, cu, out=o)
-        torch.cuda.synchronize()
-        dtc = (time.perf_counter() - t0) / Kc
-        chunk_legs[f"{n_tok}_tokens_per_sequence"] = {
-            "us_per_call": dtc * 1e6, "us_per_token_position": dtc * 1e6 / n_tok,
-            "calls_timed": Kc}
+        leg = {"calls_timed": Kc}
+        for name in ("decode_chunk", "prefill_attention"):
+            def call(j):
+                k, v, f, cu, q, o = ins[j % len(ins)]
+                if name == "decode_chunk":
+                    caches[j % R].decode_chunk(k, v, f, q, cu, out=o)
+                else:
+                    caches[j % R].prefill_attention(k, v, f, q, cu, workspace=ws, out=o)
+            for j in range(R):
+                call(j)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for j in range(Kc):
+                call(j)
+            torch.cuda.synchronize()
+            dtc = (time.perf_counter() - t0) / Kc
+            leg[f"us_per_call_{name}"] = dtc * 1e6
+        leg["us_per_token_position"] = min(leg["us_per_call_decode_chunk"],
+                                           leg["us_per_call_prefill_attention"]) / n_tok
+        chunk_legs[f"{n_tok}_tokens_per_sequence"] = leg
 
     stats = [c.stats() for c in caches]
     kept_bytes = float(np.mean([s.kept_kv_bytes for s in stats]))
@@ -736,7 +747,7 @@ def main():
         "frac_of_hbm_peak_step": kept_bytes / (dt / K) / 1e9 / HBM_PEAK_GBPS,
         "dense_cache": dense,
         "prefill_append": dict(PREFILL_TIMING),
-        "decode_chunk": chunk_legs,
+        "multi_token_step": chunk_legs,
         "prefill_attention": prefill_attn,
         "roofline": {
             "bound": "hbm", "kernel": "spkv_decode_split<128>",

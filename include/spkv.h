@@ -190,7 +190,9 @@ int spkv_decode_step(spkv_cache_t* cache, const void* k, const void* v, const fl
  *   cu_seqlens   host int32 [batch + 1]
  * Afterwards the cache holds the chunk exactly as after spkv_append of the same tokens.
  * One pass over the cache serves all tokens of a chunk (each K/V tile is read once per
- * (sequence, KV head)).  Errors as for spkv_append; SPKV_E_INVAL if a chunk is too long. */
+ * (sequence, KV head)).  Needs no workspace.  For chunks of more than 16 / group-size tokens
+ * spkv_prefill_attention is the faster call (it picks this one itself for shorter chunks).
+ * Errors as for spkv_append; SPKV_E_INVAL if a chunk is too long. */
 int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const float* util_logits,
                       const void* q, const int32_t* cu_seqlens, void* out, float* lse,
                       float sm_scale, void* stream);
