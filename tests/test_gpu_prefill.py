@@ -135,13 +135,13 @@ def test_prefill_same_state_and_outputs_as_chunk_calls():
     ca.close(); cb.close()
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (32, 8)])
-def test_prefill_one_workspace_for_every_chunk_length(Hq, Hkv):
-    """Chunk lengths across the 2-, 4- and 8-wave workgroup shapes and across the split
-    counts (the lists are long enough to be cut into ranges), all in a workspace sized once
-    for the longest chunk."""
-    wl = small_workload("pws", 2, Hq, Hkv, 128, [2500, 900], 0.6, seed=41 + Hq)
-    lens = [520, 300, 130, 70, 40, 33, 24, 17]
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 8, 128), (16, 8, 128), (32, 8, 128), (8, 2, 64), (6, 2, 128)])
+def test_prefill_one_workspace_for_every_chunk_length(Hq, Hkv, D):
+    """Chunk lengths across the workgroup shapes (2, 4 or 8 waves of one or two column
+    groups) and across the split counts (the lists are long enough to be cut into ranges),
+    all in a workspace sized once for the longest chunk."""
+    wl = small_workload("pws", 2, Hq, Hkv, D, [2500, 900], 0.6, seed=41 + Hq)
+    lens = [520, 300, 130, 70, 40, 33, 24, 17, 12, 7, 5]
     _run_prefill(wl, [[n, max(1, n // 3)] for n in lens], sample=24, seed=Hq, shared_workspace=True)
 
 
