@@ -153,6 +153,14 @@ __device__ __forceinline__ void load_row_to_lds(const uint16_t* src, unsigned ld
                  : "m0");
 }
 
+// The same for one dword per lane: lane i's 4 bytes land at lds_row + 4 i.
+__device__ __forceinline__ void load_word_to_lds(const float* src, unsigned lds_row) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :
+                 : "v"(src), "s"(lds_row)
+                 : "m0");
+}
+
 // Waits until at most N of this wave's vector memory loads are still in flight (they
 // complete in the order issued).
 template <int N>
@@ -398,21 +406,33 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int my_off = (wv * kRowsPerWave * 64 + lane) * 8;     // this lane's part of a tile
     const unsigned lds_rows = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&s_tile[0][0] +
                               (unsigned)wv * (kRowsPerWave * 1024);
-    auto stage_tile = [&](const uint16_t* base, int buf) {
+    // Soft gating: the 32 biases log2 u of a tile's rows travel the same way, every wave
+    // fetching a copy of its own (lanes 32-63 repeat lanes 0-31), so that the tile loop
+    // issues no load whose wait would also wait for the copies in flight.
+    __shared__ __attribute__((aligned(16))) float s_bias[SOFT ? kBufs : 1][SOFT ? NW : 1][SOFT ? 64 : 4];
+    const unsigned lds_bias = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)&s_bias[0][0][0] +
+                              (unsigned)wv * 256;
+    constexpr int kCopiesPerTile = kRowsPerWave + (SOFT ? 1 : 0);   // loads a wave issues per tile
+    auto stage_tile = [&](const uint16_t* base, int xt, int buf) {    // tile xt (for the biases)
         const uint16_t* p = base + my_off;
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r)
             load_row_to_lds(p + r * 512, lds_rows + (unsigned)buf * (kHalfElems * 2) + r * 1024);
+        if (SOFT) {
+            const int hp = min(sB0 + min(xt, last) - nA, pf.shp - 1);
+            load_word_to_lds(pf.bias + ((size_t)pair * pf.shp + hp) * kHalfTokens + (lane & 31),
+                             lds_bias + (unsigned)buf * (NW * 256));
+        }
     };
     // Everything loaded so far (queries, counts) is waited for here, once: left pending, the
     // first use inside the tile loop would carry a wait for all loads in flight -- on every
     // tile, tile copies included.
     __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0)
-    stage_tile(base_of(x_begin), 0);
+    stage_tile(base_of(x_begin), x_begin, 0);
 #pragma unroll
-    for (int a = 1; a < kAhead; ++a) stage_tile(base_of(x_begin + a), a);
+    for (int a = 1; a < kAhead; ++a) stage_tile(base_of(x_begin + a), x_begin + a, a);
     const uint16_t* p_next = base_of(x_begin + kAhead);
-    wait_loads_but<(kAhead - 1) * kRowsPerWave>();        // tile x_begin has landed
+    wait_loads_but<(kAhead - 1) * kCopiesPerTile>();        // tile x_begin has landed
     __syncthreads();
 
     // Tile loop.  The inner loop never touches the accumulators except by MFMA; when the
@@ -429,7 +449,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (; x < x_end; ++x) {
             if (!resume) {
                 // the tile after next (past the last one: the last tile again, never used)
-                stage_tile(p_next, buf >= 1 ? buf - 1 : kBufs - 1);
+                stage_tile(p_next, x + kAhead, buf >= 1 ? buf - 1 : kBufs - 1);
                 p_next = base_of(x + kAhead + 1);
             }
             resume = false;
@@ -471,8 +491,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                     // scores to the log2 domain plus the gate bias log2 u of every key outside
                     // the window of its query (row u <= i); masked scores stay -inf
                     const int u0 = u_tile + kc * 8;
-                    const float4* bp = reinterpret_cast<const float4*>(
-                        pf.bias + ((size_t)pair * pf.shp + (u_tile >> 5)) * kHalfTokens + kc * 8);
+                    const float4* bp = reinterpret_cast<const float4*>(&s_bias[SOFT ? buf : 0][SOFT ? wv : 0][SOFT ? kc * 8 : 0]);
                     const float4 b0 = bp[0], b1 = bp[1];
                     const float bias[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
                     if (u_tile + kHalfTokens - 1 <= i0) {       // outside every window of the wave
@@ -500,7 +519,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 pending = false;
                 tile_accumulate<D, NQ>(tile, lane, pw, psum, acc, l);
             }
-            wait_loads_but<(kAhead - 1) * kRowsPerWave>();    // all but the newest copies: tile x + 1 has landed
+            wait_loads_but<(kAhead - 1) * kCopiesPerTile>();    // all but the newest copies: tile x + 1 has landed
             __syncthreads();
             buf = buf == kBufs - 1 ? 0 : buf + 1;
         }
