@@ -12,6 +12,7 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2605_14037_amd as spkv
 from oracle.spkv_oracle import SPKVOracle
 from paper_2605_14037_amd.inputs import TokenStream, prefill_chunks, to_numpy_f32, workload
 from tests import harness as H
@@ -38,7 +39,7 @@ def _rows_of(cu, seqs):
     return torch.cat(idx), sub_cu
 
 
-def _run_full(name, chunk=1024, layer=0, logits_fn=None):
+def _run_full(name, chunk=1024, layer=0, logits_fn=None, predictor=None):
     wl = workload(name)
     seqs = _sample_sequences(wl)
     print(f"{name}: sampled sequences {seqs}", flush=True)
@@ -50,8 +51,9 @@ def _run_full(name, chunk=1024, layer=0, logits_fn=None):
     sub = SPKVOracle(len(seqs), wl.n_q_heads, wl.n_kv_heads, wl.head_dim, window=wl.window,
                      tau=wl.tau)
 
-    def feed(k, v, f, cu):
-        cache.append(k, v, f, cu)
+    def feed(k, v, f, cu, to_cache=True):
+        if to_cache:
+            cache.append(k, v, f, cu)
         gates.append(None, None, to_numpy_f32(f), cu)
         rows, sub_cu = _rows_of(cu, seqs)
         rows = rows.to(k.device)
@@ -60,11 +62,17 @@ def _run_full(name, chunk=1024, layer=0, logits_fn=None):
     for counts in prefill_chunks(wl.ctx_lens, chunk):
         feed(*stream.next_tokens(counts))
     k, v, f, cu = stream.next_tokens([1] * wl.batch)
-    if logits_fn is not None:
-        f = logits_fn(stream)
-    feed(k, v, f, cu)
     q = stream.next_query()
-    out, lse = cache.decode_attention(q, want_lse=True)
+    if predictor is not None:
+        # the step computes the logits itself; the oracles get the fp32 values it stored
+        x, w1, b1, w2, b2 = predictor
+        out, lse, f = cache.decode_step_predict(x, w1, b1, w2, b2, k, v, q, want_lse=True)
+        feed(k, v, f, cu, to_cache=False)
+    else:
+        if logits_fn is not None:
+            f = logits_fn(stream)
+        feed(k, v, f, cu)
+        out, lse = cache.decode_attention(q, want_lse=True)
 
     # every (sequence, head): lengths, positions, statistics -- bit exact
     st = H.check_state(cache, gates, wl, label=name)
@@ -110,6 +118,25 @@ def test_cfg5_one_layer():
         return (h @ W - 1.0364).contiguous()
     st = _run_full("cfg5", layer=3, logits_fn=predictor)
     assert 0.12 < st.density_evicted < 0.18
+
+
+def test_cfg5_one_layer_with_the_predictor_inside_the_step():
+    """The same layer, its decode step taken by spkv_decode_step_predict with the predictor of
+    the layered bench (4096 -> 256 -> 8, random weights): logits against the fp64 predictor,
+    state and outputs against the oracle fed with the logits the step stored."""
+    from oracle.spkv_oracle import utility_logits as oracle_logits
+    g = torch.Generator(device="cuda").manual_seed(57)
+    x = torch.randn(32, 4096, generator=g, device="cuda").to(torch.bfloat16)
+    w1 = (torch.randn(256, 4096, generator=g, device="cuda") / 64.0).to(torch.bfloat16)
+    b1 = 0.1 * torch.randn(256, generator=g, device="cuda")
+    w2 = (torch.randn(8, 256, generator=g, device="cuda") / 9.6).to(torch.bfloat16)
+    b2 = torch.full((8,), -1.0364, device="cuda")
+    st = _run_full("cfg5", layer=5, predictor=(x, w1, b1, w2, b2))
+    assert 0.12 < st.density_evicted < 0.18
+    got = spkv.utility_logits(x, w1, b1, w2, b2).cpu().numpy().astype(np.float64)
+    ref = oracle_logits(to_numpy_f32(x), to_numpy_f32(w1), to_numpy_f32(b1), to_numpy_f32(w2),
+                        to_numpy_f32(b2))
+    assert np.abs(got - ref).max() <= 1e-4 + 1e-4 * np.abs(ref).max()
 
 
 def test_cfg2_prefill_attention_last_chunks():
