@@ -211,9 +211,9 @@ int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const f
  *                 t tokens in all (a call with shorter chunks may need less, never more);
  *                 contents need not survive between calls; caller-owned
  * Work is cut per (sequence, KV head) into spans of consecutive tokens, one workgroup each:
- * 256 / group-size tokens on eight waves, or a half or a quarter of that on four or two
- * waves when no sequence brings more.  When the spans alone would not fill the chip, every
- * span's keys are cut into ranges as well (one workgroup each, merged by a second launch).
+ * 256 / group-size tokens on eight waves, fewer tokens on four or two waves when no sequence
+ * brings more.  When the spans alone would not fill the chip, every span's keys are cut into
+ * ranges as well (one workgroup each, merged by a second launch).
  * Calls that bring exactly one token for every sequence are handed to spkv_decode_step,
  * calls whose chunks all fit one group of 16 query columns (16 / group-size tokens) to
  * spkv_decode_chunk; the workspace is then not touched.
