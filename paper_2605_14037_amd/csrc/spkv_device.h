@@ -60,6 +60,35 @@ __device__ __forceinline__ int alloc_page(const SpkvView& v) {
     return page < v.n_pages ? page : -1;
 }
 
+// ------------------------------------------------------------------ memory -> LDS copies
+// One wave-wide 16-byte load from global memory straight into LDS: lane i's 16 bytes at
+// `src` land at LDS byte address lds_row + 16 i (lds_row wave-uniform).  The load counts
+// as a vector memory load in flight until its data is in LDS.  (No memory clobber: the
+// compiler would then stop treating the page table as read-only and turn its scalar lookups
+// into vector loads that wait for these copies.  What orders the copies against the LDS
+// reads is the workgroup barrier, which neither the asm nor the reads may cross.)
+__device__ __forceinline__ void load_row_to_lds(const uint16_t* src, unsigned lds_row) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(lds_row)
+                 : "m0");
+}
+
+// The same for one dword per lane: lane i's 4 bytes land at lds_row + 4 i.
+__device__ __forceinline__ void load_word_to_lds(const float* src, unsigned lds_row) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :
+                 : "v"(src), "s"(lds_row)
+                 : "m0");
+}
+
+// Waits until at most N of this wave's vector memory loads are still in flight (they
+// complete in the order issued).
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N));
+}
+
 // ------------------------------------------------------------------ utility predictor
 // Hidden layer of the predictor (Eq. 1) for 16 hidden units x 16 tokens over kq (a multiple
 // of 32) elements of d_model: lane (kc, n) passes its row of W1 (unit n) and of the tokens'

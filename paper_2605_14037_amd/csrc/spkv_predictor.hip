@@ -163,13 +163,142 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 }
 
+// Many tokens, d_hidden <= 256: the same tiling with the operands staged through LDS.  The
+// register-tiled kernel above fetches its MFMA operands straight from memory in 64-byte
+// pieces, 16 cache lines per load instruction, and every wave fetches the token rows again;
+// that, not the MFMAs, sets its speed.  Here a workgroup (one wave per 64 hidden units) copies
+// a block of 64 elements of d_model -- 128 bytes of every W1 row and of every one of its 64
+// token rows -- straight into LDS, eight lanes per row (whole cache lines, each fetched once
+// per workgroup), one block ahead of the one it computes on.  Chunk c (16 bytes) of row r is
+// stored at position c ^ (r & 7) of the row, so that the eight lanes of an operand read that
+// share a bank phase hit eight different bank groups.
+constexpr int kGemmTokens = 64;      // tokens per workgroup
+constexpr int kGemmK = 64;           // elements of d_model per stage
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void spkv_predictor_gemm(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
+    const uint16_t* __restrict__ w2, const float* __restrict__ b2, float* __restrict__ logits,
+    int n_tokens, int d_model, int d_hidden, int n_kv_heads) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
+    const int tid = threadIdx.x, lane = tid & 63, kc = lane >> 4, n = lane & 15;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6), n_waves = d_hidden / 64;
+    const int t0 = blockIdx.x * kGemmTokens;
+    const int rows = d_hidden + kGemmTokens;               // rows of a stage: W1 rows, then token rows
+    const unsigned stage_bytes = (unsigned)rows * 128;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)s_raw;
+    // this wave's copies: 8 rows (1 KB) per load, rows 8 i .. 8 i + 7 for i = wv, wv + n_waves, ...
+    const int r_in = lane >> 3, c_in = (lane & 7) ^ r_in;  // row within the 8, chunk fetched (swizzle)
+    auto copy_stage = [&](int k0, int buf) {
+        for (int i = wv; i < rows / 8; i += n_waves) {
+            const int r = i * 8 + r_in;
+            const uint16_t* src = r < d_hidden
+                                      ? w1 + (size_t)r * d_model
+                                      : x + (size_t)min(t0 + r - d_hidden, n_tokens - 1) * d_model;
+            load_row_to_lds(src + k0 + c_in * 8,
+                            __builtin_amdgcn_readfirstlane(lds0 + (unsigned)buf * stage_bytes + (unsigned)i * 1024));
+        }
+    };
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int hs = 0; hs < 4; ++hs)
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts) acc[hs][ts] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    __builtin_amdgcn_s_waitcnt(0x0f70);          // nothing of ours is in flight yet: vmcnt(0)
+    copy_stage(0, 0);
+    wait_loads_but<0>();
+    __syncthreads();
+    const int n_stages = d_model / kGemmK;
+    for (int st = 0; st < n_stages; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < n_stages) copy_stage((st + 1) * kGemmK, buf ^ 1);
+        const unsigned char* tile = s_raw + (size_t)buf * stage_bytes;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {            // two MFMA steps of 32 per stage
+            bf16x8 a[4], b[4];
+            const int c = 4 * u + kc;            // chunk of the row this lane feeds
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int ra = wv * 64 + i * 16 + n, rb = d_hidden + i * 16 + n;
+                a[i] = *reinterpret_cast<const bf16x8*>(tile + ra * 128 + ((c ^ (ra & 7)) << 4));
+                b[i] = *reinterpret_cast<const bf16x8*>(tile + rb * 128 + ((c ^ (rb & 7)) << 4));
+            }
+#pragma unroll
+            for (int hs = 0; hs < 4; ++hs)
+#pragma unroll
+                for (int ts = 0; ts < 4; ++ts)
+                    acc[hs][ts] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[hs], b[ts], acc[hs][ts], 0, 0, 0);
+        }
+        wait_loads_but<0>();
+        __syncthreads();
+    }
+    // lane (kc, n) holds hidden units 64 wv + 16 hs + 4 kc + i of tokens t0 + 16 ts + n
+    const int j0 = wv * 64;
+#pragma unroll
+    for (int hs = 0; hs < 4; ++hs)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float bias = b1 != nullptr ? b1[j0 + hs * 16 + 4 * kc + i] : 0.f;
+#pragma unroll
+            for (int ts = 0; ts < 4; ++ts) {
+                const float h = acc[hs][ts][i] + bias;
+                acc[hs][ts][i] = h / (1.f + __expf(-h));                           // SiLU
+            }
+        }
+    float* s_logit = reinterpret_cast<float*>(s_raw);      // [waves][64 tokens][n_kv_heads]
+    for (int hd = 0; hd < n_kv_heads; ++hd) {
+        float w[4][4];
+#pragma unroll
+        for (int hs = 0; hs < 4; ++hs)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned bits = w2[(size_t)hd * d_hidden + j0 + hs * 16 + 4 * kc + i];
+                w[hs][i] = __builtin_bit_cast(float, bits << 16);
+            }
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts) {
+            float p = 0.f;
+#pragma unroll
+            for (int hs = 0; hs < 4; ++hs)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) p += w[hs][i] * acc[hs][ts][i];
+            p += __shfl_xor(p, 16);
+            p += __shfl_xor(p, 32);
+            if (kc == 0) s_logit[((size_t)wv * 64 + ts * 16 + n) * n_kv_heads + hd] = p;
+        }
+    }
+    __syncthreads();
+    for (int o = tid; o < kGemmTokens * n_kv_heads; o += 64 * n_waves) {
+        const int tok = o / n_kv_heads, hd = o - tok * n_kv_heads;
+        if (t0 + tok >= n_tokens) continue;
+        float sum = b2 != nullptr ? b2[hd] : 0.f;
+        for (int w8 = 0; w8 < n_waves; ++w8) sum += s_logit[((size_t)w8 * 64 + tok) * n_kv_heads + hd];
+        logits[(size_t)(t0 + tok) * n_kv_heads + hd] = sum;
+    }
+}
+
 hipError_t spkv_launch_predictor(const uint16_t* x, const uint16_t* w1, const float* b1,
                                  const uint16_t* w2, const float* b2, float* logits, float* act,
                                  int n_tokens, int d_model, int d_hidden, int n_kv_heads,
                                  hipStream_t s) {
-    // One workgroup of the tiled kernel takes about 120 us for d_model = 4096 however many
-    // tokens there are (its W1 and token rows come in 64-byte pieces), so it pays from a few
-    // thousand tokens on: 32 768 tokens 242 us against 1.0 ms, 4096 tokens on a par.
+    // A workgroup of the LDS-staged kernel takes about 80 us for d_model = 4096 (64 stages, each
+    // waiting for its copy), so it pays once there are enough tokens to fill the chip with
+    // workgroups: 32 768 tokens 125 us, 4096 tokens 83 us (two-kernel path: 1.0 ms, 128 us).
+    if (n_tokens >= 4096 && d_hidden % 64 == 0 && d_hidden <= 256 && d_model % kGemmK == 0 &&
+        n_kv_heads <= 64) {
+        const int n_waves = d_hidden / 64;
+        const size_t lds = std::max((size_t)2 * (d_hidden + kGemmTokens) * 128,
+                                    (size_t)n_waves * 64 * n_kv_heads * sizeof(float));
+        // more than the 64 KB of dynamic LDS a kernel gets by default
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(spkv_predictor_gemm),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        spkv_predictor_gemm<<<dim3((n_tokens + kGemmTokens - 1) / kGemmTokens), dim3(64 * n_waves), lds, s>>>(
+            x, w1, b1, w2, b2, logits, n_tokens, d_model, d_hidden, n_kv_heads);
+        return hipGetLastError();
+    }
+    // Wider hidden layers (up to 512 units): the register-tiled kernel, about 120 us per
+    // workgroup for d_model = 4096 (32 768 tokens: 242 us).
     if (n_tokens >= 4096 && d_hidden % 64 == 0 && d_hidden <= 512 && n_kv_heads <= 64) {
         const int n_waves = d_hidden / 64;
         const size_t lds = (size_t)n_waves * 64 * n_kv_heads * sizeof(float);

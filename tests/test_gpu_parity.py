@@ -447,7 +447,8 @@ def test_release_and_reuse_sequences():
 @pytest.mark.parametrize("n,dm,dh,Hk", [(16, 4096, 256, 8), (1, 128, 16, 1), (37, 1024, 48, 3),
                                         (64, 4096, 512, 8), (300, 512, 64, 2), (63, 256, 64, 2),
                                         (4096 + 17, 1024, 256, 8), (4200, 128, 512, 5),
-                                        (4100, 384, 192, 4), (5000, 256, 1024, 3)])
+                                        (4100, 384, 192, 4), (5000, 256, 1024, 3),
+                                        (4096, 4096, 256, 8), (4500, 256, 64, 1), (4096 + 33, 384, 128, 3), (4100, 128, 192, 2)])
 def test_utility_predictor(n, dm, dh, Hk):
     """The fused two-layer predictor against the fp64 oracle; and fed into the cache, the
     logits it produces gate exactly like the same fp32 values in the oracle."""
