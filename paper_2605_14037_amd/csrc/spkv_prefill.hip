@@ -537,13 +537,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 }
 
 // Merge of the tile ranges of one (span, column): out = sum_r 2^(m_r - M) acc_r /
-// sum_r 2^(m_r - M) l_r.  One workgroup of D threads per column of a span.
+// sum_r 2^(m_r - M) l_r.  A workgroup of 256 threads takes 256 / (D / 4) consecutive columns
+// of a span's workgroup; a thread owns four consecutive output elements of one column.
 template <int D>
-__global__ __launch_bounds__(D) void spkv_prefill_combine(SpkvView v, uint16_t* __restrict__ out,
-                                                          float* __restrict__ lse, SpkvPrefill pf,
-                                                          SpkvCu cu) {
-    const int kCols = pf.nw * pf.nq * 16;
-    const int span = blockIdx.x / kCols, cs = blockIdx.x - span * kCols;
+__global__ __launch_bounds__(256) void spkv_prefill_combine(SpkvView v, uint16_t* __restrict__ out,
+                                                            float* __restrict__ lse, SpkvPrefill pf,
+                                                            SpkvCu cu) {
+    constexpr int TPC = D / 4, CPB = 256 / TPC;          // threads per column, columns per block
+    const int kCols = pf.nw * pf.nq * 16;               // a multiple of CPB (of 16)
+    const int blocks_per_span = kCols / CPB;
+    const int span = blockIdx.x / blocks_per_span;
+    const int cs = (blockIdx.x - span * blocks_per_span) * CPB + (int)threadIdx.x / TPC;
+    const int d = ((int)threadIdx.x % TPC) * 4;
     const int pair = span / pf.nblk, qblk = span - pair * pf.nblk;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int row0 = cu.v[b], n_tok = cu.v[b + 1] - row0;
@@ -552,22 +557,27 @@ __global__ __launch_bounds__(D) void spkv_prefill_combine(SpkvView v, uint16_t* 
     const int tbv = max(0, min(pf.tb, n_tok - i0));
     if (col >= tbv * v.G) return;
     const int i = i0 + col / v.G, g = col - (col / v.G) * v.G;
-    const int d = threadIdx.x;
     const size_t n_cols = (size_t)v.n_pairs * pf.nblk * pf.ks * kCols;
     const size_t pc0 = (size_t)span * pf.ks * kCols + cs;      // range r: pc0 + r * kCols
     const float* ml = pf.part + n_cols * D;
     float M = SPKV_NEG_INF;
     for (int r = 0; r < pf.ks; ++r) M = fmaxf(M, ml[(pc0 + (size_t)r * kCols) * 2]);
-    float num = 0.f, den = 0.f;
+    f32x4 num = {0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
     for (int r = 0; r < pf.ks; ++r) {
         const size_t pc = pc0 + (size_t)r * kCols;
         const float sc = __builtin_amdgcn_exp2f(ml[pc * 2] - M);      // 0 for a range without keys
-        num += pf.part[pc * D + d] * sc;
+        num += *reinterpret_cast<const f32x4*>(pf.part + pc * D + d) * sc;
         den += ml[pc * 2 + 1] * sc;
     }
     const size_t o = (size_t)(row0 + i) * v.Hq + (size_t)h * v.G + g;
-    const __bf16 r16 = (__bf16)(num / den);
-    out[o * D + d] = __builtin_bit_cast(uint16_t, r16);
+    const float inv = 1.0f / den;
+    uint2 packed;
+    packed.x = (unsigned)__builtin_bit_cast(uint16_t, (__bf16)(num[0] * inv)) |
+               ((unsigned)__builtin_bit_cast(uint16_t, (__bf16)(num[1] * inv)) << 16);
+    packed.y = (unsigned)__builtin_bit_cast(uint16_t, (__bf16)(num[2] * inv)) |
+               ((unsigned)__builtin_bit_cast(uint16_t, (__bf16)(num[3] * inv)) << 16);
+    *reinterpret_cast<uint2*>(out + o * D + d) = packed;
     if (lse != nullptr && d == 0) lse[o] = (M + log2f(den)) * 0.6931471805599453f;
 }
 
@@ -633,13 +643,13 @@ hipError_t spkv_launch_prefill(const SpkvView& v, const uint16_t* k, const uint1
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
         launch_attend<128, false>(v, q, out, lse, sl, pf, cu, grid, s);
         if (ks > 1)
-            spkv_prefill_combine<128><<<dim3(v.n_pairs * pf.nblk * pf.nw * pf.nq * 16), dim3(128), 0, s>>>(v, out, lse, pf, cu);
+            spkv_prefill_combine<128><<<dim3(v.n_pairs * pf.nblk * pf.nw * pf.nq * 16 / 8), dim3(256), 0, s>>>(v, out, lse, pf, cu);
     } else {
         spkv_prefill_stage<64><<<dim3(stage_hps, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, pf);
         if ((e = spkv_launch_append_bulk(v, k, vv, f, cu, n_max, prefix, s)) != hipSuccess) return e;
         launch_attend<64, false>(v, q, out, lse, sl, pf, cu, grid, s);
         if (ks > 1)
-            spkv_prefill_combine<64><<<dim3(v.n_pairs * pf.nblk * pf.nw * pf.nq * 16), dim3(64), 0, s>>>(v, out, lse, pf, cu);
+            spkv_prefill_combine<64><<<dim3(v.n_pairs * pf.nblk * pf.nw * pf.nq * 16 / 16), dim3(256), 0, s>>>(v, out, lse, pf, cu);
     }
     return hipGetLastError();
 }
