@@ -71,6 +71,31 @@ def test_create_rejects_bad_arguments_without_a_gpu():
     assert lib.spkv_decode_attention(None, None, None, None, 0.0, None) == -1
 
 
+def test_stateless_size_queries_and_null_handles():
+    """The size queries that need no cache, and every entry point's refusal of a null cache
+    (argument checks come before any GPU call, so they run here)."""
+    lib = spkv.load_library()
+    assert lib.spkv_decode_step_predict_workspace_bytes(32, 256) == 4 * 32 * 256 * 4
+    assert lib.spkv_decode_step_predict_workspace_bytes(0, 256) == 0
+    assert lib.spkv_decode_step_predict_workspace_bytes(32, -1) == 0
+    need = lib.spkv_soft_gated_workspace_bytes(4, 8, 128, 128, 1000)
+    assert need > 0 and need % 256 == 0
+    assert lib.spkv_soft_gated_workspace_bytes(4, 8, 128, 128, 2000) > need
+    assert lib.spkv_soft_gated_workspace_bytes(0, 8, 128, 128, 1000) == 0
+    assert lib.spkv_soft_gated_workspace_bytes(4, 8, 96, 128, 1000) == 0
+    assert lib.spkv_prefill_workspace_bytes(None, 16, 16) == 0
+    cu = (C.c_int32 * 3)(0, 1, 2)
+    assert lib.spkv_append(None, None, None, None, cu, None) == -1
+    assert lib.spkv_decode_step(None, None, None, None, None, None, None, 0.0, None) == -1
+    assert lib.spkv_decode_chunk(None, None, None, None, None, cu, None, None, 0.0, None) == -1
+    assert lib.spkv_prefill_attention(None, None, None, None, None, cu, None, None, 0.0, None, 0, None) == -1
+    assert lib.spkv_decode_step_predict(None, None, None, None, None, None, 128, 16, None, None, None,
+                                        None, None, None, None, 0, 0.0, None) == -1
+    assert lib.spkv_cache_release_sequence(None, 0, None) == -1
+    assert lib.spkv_cache_set_tau(None, 0.5) == -1
+    assert lib.spkv_cache_advance(None, 1) == -1
+
+
 @pytest.mark.parametrize("D", [64, 128])
 def test_page_layout_is_a_bijection_in_mfma_operand_order(D):
     n = 64 * D
