@@ -197,6 +197,20 @@ int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const f
                       const void* q, const int32_t* cu_seqlens, void* out, float* lse,
                       float sm_scale, void* stream);
 
+/* Scoring of draft tokens (speculative decoding): the attention outputs of
+ * spkv_decode_chunk for the same chunks, with the cache left exactly as it was -- nothing is
+ * appended, no length changes.  Draft token i of a sequence attends as if drafts 0 .. i - 1
+ * had been appended before it (Eq. 3-5; all of them lie inside its window, so their utility
+ * logits play no part and are not passed).  The caller then appends the accepted prefix of
+ * every sequence with spkv_append (rejected drafts never touch the cache; a token that
+ * entered the window could not be taken back, because it overwrites the slot of the pair it
+ * pushes out).
+ *   k, v, q, cu_seqlens, out, lse, sm_scale   as for spkv_decode_chunk, same limits
+ * Errors: SPKV_E_INVAL as for spkv_decode_chunk; never SPKV_E_CAPACITY. */
+int spkv_score_chunk(spkv_cache_t* cache, const void* k, const void* v, const void* q,
+                     const int32_t* cu_seqlens, void* out, float* lse, float sm_scale,
+                     void* stream);
+
 /* Prefill attention: the multi-token step without a length limit.  Every sequence b
  * receives n_b >= 0 new tokens and gets the attention output of each, token i (position
  * T_b + i) attending to the positions s <= T_b + i inside its window or passing the gate

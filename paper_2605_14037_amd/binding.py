@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_grow",
     "spkv_cache_reset",
     "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk",
-    "spkv_decode_step_predict_workspace_bytes", "spkv_decode_step_predict",
+    "spkv_decode_step_predict_workspace_bytes", "spkv_decode_step_predict", "spkv_score_chunk",
     "spkv_prefill_workspace_bytes", "spkv_prefill_attention",
     "spkv_soft_gated_workspace_bytes", "spkv_soft_gated_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_safe_steps", "spkv_cache_advance", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
@@ -95,6 +95,8 @@ def load_library():
                                              vp, vp, C.c_size_t, f32, vp]
     lib.spkv_decode_chunk.restype = C.c_int
     lib.spkv_decode_chunk.argtypes = [vp, vp, vp, vp, vp, P(i32), vp, vp, f32, vp]
+    lib.spkv_score_chunk.restype = C.c_int
+    lib.spkv_score_chunk.argtypes = [vp, vp, vp, vp, P(i32), vp, vp, f32, vp]
     lib.spkv_prefill_workspace_bytes.restype = C.c_size_t
     lib.spkv_prefill_workspace_bytes.argtypes = [vp, i32, i64]
     lib.spkv_prefill_attention.restype = C.c_int
@@ -385,6 +387,31 @@ class SPKVCache:
         lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
         _check(self.lib.spkv_decode_chunk(self.handle, kp, vp, fp, qp, cu, op, lp, float(sm_scale),
                                           _stream()), "spkv_decode_chunk")
+        return (out, lse) if lse is not None else out
+
+    def score_chunk(self, k, v, q, cu_seqlens, out=None, lse=None, sm_scale=0.0, want_lse=False):
+        """Attention outputs of up to 16 draft tokens per sequence, the cache left unchanged
+        (spkv_score_chunk)."""
+        cfg = self.cfg
+        cu = cu_seqlens if isinstance(cu_seqlens, C.Array) else self.make_cu(cu_seqlens)
+        total = cu[cfg.batch]
+        if total == 0:
+            _check(self.lib.spkv_score_chunk(self.handle, None, None, None, cu, None, None,
+                                             float(sm_scale), _stream()), "spkv_score_chunk")
+            return None
+        kv_shape = (total, cfg.n_kv_heads, cfg.head_dim)
+        shape = (total, cfg.n_q_heads, cfg.head_dim)
+        kp = _dev_ptr(k, torch.bfloat16, kv_shape, "k")
+        vp = _dev_ptr(v, torch.bfloat16, kv_shape, "v")
+        qp = _dev_ptr(q, torch.bfloat16, shape, "q")
+        if out is None:
+            out = torch.empty(shape, dtype=torch.bfloat16, device=q.device)
+        op = _dev_ptr(out, torch.bfloat16, shape, "out")
+        if lse is None and want_lse:
+            lse = torch.empty(shape[:2], dtype=torch.float32, device=q.device)
+        lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
+        _check(self.lib.spkv_score_chunk(self.handle, kp, vp, qp, cu, op, lp, float(sm_scale),
+                                         _stream()), "spkv_score_chunk")
         return (out, lse) if lse is not None else out
 
     def prefill_workspace_bytes(self, max_tokens_per_sequence, max_total_tokens):

@@ -539,9 +539,27 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
     return SPKV_OK;
 }
 
+namespace {
+int chunk_call(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
+               const void* q, const int32_t* cu_seqlens, void* out, float* lse, float sm_scale,
+               void* stream, bool append);
+}
+
 int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
                       const void* q, const int32_t* cu_seqlens, void* out, float* lse,
                       float sm_scale, void* stream) {
+    return chunk_call(c, k, v, util_logits, q, cu_seqlens, out, lse, sm_scale, stream, true);
+}
+
+int spkv_score_chunk(spkv_cache_t* c, const void* k, const void* v, const void* q,
+                     const int32_t* cu_seqlens, void* out, float* lse, float sm_scale, void* stream) {
+    return chunk_call(c, k, v, nullptr, q, cu_seqlens, out, lse, sm_scale, stream, false);
+}
+
+namespace {
+int chunk_call(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
+               const void* q, const int32_t* cu_seqlens, void* out, float* lse, float sm_scale,
+               void* stream, bool append) {
     if (c == nullptr || cu_seqlens == nullptr) return SPKV_E_INVAL;
     const int B = c->cfg.batch, G = c->carve.G;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -553,9 +571,10 @@ int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float
         n_max = std::max(n_max, (int)n);
     }
     if (n_max == 0) return SPKV_OK;
-    if (k == nullptr || v == nullptr || util_logits == nullptr || q == nullptr || out == nullptr)
+    if (k == nullptr || v == nullptr || (append && util_logits == nullptr) || q == nullptr ||
+        out == nullptr)
         return SPKV_E_INVAL;
-    if (!aligned16(k) || !aligned16(v) || !aligned16(util_logits) || !aligned16(q) ||
+    if (!aligned16(k) || !aligned16(v) || (append && !aligned16(util_logits)) || !aligned16(q) ||
         !aligned16(out) || (lse != nullptr && !aligned16(lse)))
         return SPKV_E_INVAL;
     if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
@@ -563,8 +582,10 @@ int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float
         const int rc = refresh_bound(c, s, nullptr);
         if (rc != SPKV_OK) return rc;
     }
-    const int rc = reserve_capacity(c, cu_seqlens, s);
-    if (rc != SPKV_OK) return rc;
+    if (append) {
+        const int rc = reserve_capacity(c, cu_seqlens, s);
+        if (rc != SPKV_OK) return rc;
+    }
 
     const int cols = n_max * G;
     const int groups = cols <= 16 ? 1 : (cols <= 32 ? 2 : 4);
@@ -589,6 +610,7 @@ int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float
                                  static_cast<uint16_t*>(out), lse, sm_scale, c->split, cu, groups,
                                  s) != hipSuccess)
         return SPKV_E_HIP;
+    if (!append) return SPKV_OK;
     const hipError_t e = (n_max == 1)
                              ? spkv_launch_append_step(c->view, kk, vv, util_logits, cu, s)
                              : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, nullptr, s);
@@ -597,6 +619,7 @@ int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float
     if (n_max > 1) c->bound_is_loose = true;
     return SPKV_OK;
 }
+}  // namespace
 
 namespace {
 // Few spans (short chunks, small batch) leave most of the chip idle while each workgroup

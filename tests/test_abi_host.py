@@ -88,6 +88,7 @@ def test_stateless_size_queries_and_null_handles():
     assert lib.spkv_append(None, None, None, None, cu, None) == -1
     assert lib.spkv_decode_step(None, None, None, None, None, None, None, 0.0, None) == -1
     assert lib.spkv_decode_chunk(None, None, None, None, None, cu, None, None, 0.0, None) == -1
+    assert lib.spkv_score_chunk(None, None, None, None, cu, None, None, 0.0, None) == -1
     assert lib.spkv_prefill_attention(None, None, None, None, None, cu, None, None, 0.0, None, 0, None) == -1
     assert lib.spkv_decode_step_predict(None, None, None, None, None, None, 128, 16, None, None, None,
                                         None, None, None, None, 0, 0.0, None) == -1

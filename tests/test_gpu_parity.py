@@ -158,6 +158,59 @@ def test_split_count_invariance():
         assert (o - outs[0]).abs().max().item() <= 2e-2 * max(1.0, outs[0].abs().max().item())
 
 
+@pytest.mark.parametrize("D,Hq,Hk,w", [(128, 8, 2, 32), (64, 4, 2, 128), (128, 16, 4, 16), (128, 4, 4, 64)])
+def test_score_chunk_then_append_of_the_accepted_drafts(D, Hq, Hk, w):
+    """Speculative decoding rounds: spkv_score_chunk returns what spkv_decode_chunk would for
+    the drafts and leaves the cache bit for bit as it was; the accepted prefixes then go in by
+    spkv_append, and the next round (and a plain decode step) see exactly that cache."""
+    import copy
+    B = 3
+    G = Hq // Hk
+    wl = small_workload("spec", B, Hq, Hk, D, [700, 90, 0], 0.4, window=w, seed=61 + D + w)
+    stream = TokenStream(wl, device="cuda")
+    cache = H.make_cache(wl, pool_tokens=(900 + 64) * Hk * B, extra_context=200)
+    oracle = H.make_oracle(wl)
+    H.prefill(cache, oracle, stream, wl, 4096)
+    rng = np.random.default_rng(D + w)
+    n_cap = min(16, w, 64 // G)
+    for rnd in range(6):
+        counts = [int(rng.integers(0 if rnd else 1, n_cap + 1)) for _ in range(B)]
+        total = sum(counts)
+        if total == 0:
+            continue
+        k, v, f, cu = stream.next_tokens(counts)
+        q = stream.next_query(rows=total)
+        before = cache.stats(with_kept_len=True)
+        out, lse = cache.score_chunk(k, v, q, cu, want_lse=True)
+        # the oracle's view: what the outputs would be had the drafts been appended
+        trial = copy.deepcopy(oracle)
+        trial.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        ref_out, ref_lse = trial.decode_chunk(to_numpy_f32(q), counts)
+        H.check_output(out, ref_out, f"round {rnd} {counts}")
+        H.check_lse(lse, ref_lse, f"round {rnd} {counts}")
+        after = cache.stats(with_kept_len=True)
+        assert before[1] == after[1] and before[0].total_tokens == after[0].total_tokens
+        H.check_state(cache, oracle, wl, label=f"round {rnd}: cache untouched by scoring")
+        # accept a prefix of every sequence's drafts
+        acc = [int(rng.integers(0, c + 1)) for c in counts]
+        if sum(acc):
+            rows = torch.cat([torch.arange(cu[b], cu[b] + acc[b]) for b in range(B)]).to(k.device)
+            acu = [0]
+            for a in acc:
+                acu.append(acu[-1] + a)
+            ka, va, fa = k[rows].contiguous(), v[rows].contiguous(), f[rows].contiguous()
+            cache.append(ka, va, fa, acu)
+            oracle.append(to_numpy_f32(ka), to_numpy_f32(va), to_numpy_f32(fa), acu)
+        H.check_state(cache, oracle, wl, label=f"round {rnd}: after accepting {acc}")
+    k, v, f, cu = stream.next_tokens([1] * B)
+    q = stream.next_query()
+    out = cache.decode_step(k, v, f, q)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    H.check_output(out, oracle.decode(to_numpy_f32(q))[0], "decode after the rounds")
+    H.check_state(cache, oracle, wl, label="end")
+    cache.close()
+
+
 @pytest.mark.parametrize("D,Hq,Hk", [(128, 8, 2), (64, 4, 1), (128, 16, 1)])
 def test_fused_steps_with_many_items_per_pair(D, Hq, Hk):
     """More than 32 work items per (sequence, head): the merges run in 16-wave workgroups
