@@ -1,7 +1,7 @@
 """Random sequences of every state-changing call against the fp64 oracle: bulk and single
 appends, fused steps (with the logits passed in, and with the predictor inside the step),
-multi-token steps, prefill attention, sequence release, threshold
-changes and capacity growth, on random small shapes.  After every call that returns outputs
+multi-token steps, draft scoring (which must change nothing), prefill attention, sequence
+release, threshold changes and capacity growth, on random small shapes.  After every call that returns outputs
 they are compared element by element; after every call the cache state is compared bit for
 bit (kept lengths, kept positions, statistics)."""
 
@@ -57,8 +57,8 @@ def test_random_call_sequences(trial):
             return call()
 
     for step in range(18):
-        op = rng.choice(["bulk", "single", "fused", "fused_pred", "chunk", "prefill", "release", "tau"],
-                        p=[0.2, 0.1, 0.1, 0.1, 0.15, 0.2, 0.1, 0.05])
+        op = rng.choice(["bulk", "single", "fused", "fused_pred", "chunk", "score", "prefill", "release", "tau"],
+                        p=[0.15, 0.1, 0.1, 0.1, 0.12, 0.08, 0.2, 0.1, 0.05])
         log.append(str(op))
         if op == "release":
             b = int(rng.integers(0, B))
@@ -73,7 +73,7 @@ def test_random_call_sequences(trial):
                 counts = [int(rng.integers(0, 180)) for _ in range(B)]
             elif op in ("single", "fused", "fused_pred"):
                 counts = [1] * B
-            elif op == "chunk":
+            elif op in ("chunk", "score"):
                 n_cap = min(16, w, 64 // G)
                 counts = [int(rng.integers(0, n_cap + 1)) for _ in range(B)]
             else:
@@ -103,6 +103,12 @@ def test_random_call_sequences(trial):
                 assert (f - spkv.utility_logits(x, w1, b1, w2, b2)).abs().max().item() <= 1e-4
                 oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
                 ref = oracle.decode(to_numpy_f32(q))[0]
+            elif op == "score":                      # drafts scored, none accepted
+                import copy
+                out = cache.score_chunk(k, v, q, cu)
+                trial = copy.deepcopy(oracle)
+                trial.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+                ref = trial.decode_chunk(to_numpy_f32(q), counts)[0]
             elif op == "chunk":
                 out = with_growth(lambda: cache.decode_chunk(k, v, f, q, cu))
                 oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
