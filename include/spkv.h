@@ -343,9 +343,18 @@ int spkv_cache_threshold_logit(const spkv_cache_t* cache, float* theta);
  * discussion of the appendix).  The window ring stores every pair's logit, so the new
  * threshold applies to every pair that leaves the window in calls issued after this one,
  * including pairs appended under the old value; decisions already taken stand (dropped
- * pairs are gone, kept pairs stay).  Host-side only: nothing is launched, calls already
+ * pairs are gone, kept pairs stay until spkv_cache_prune).  Host-side only: nothing is launched, calls already
  * enqueued keep the threshold they were issued with.  SPKV_E_INVAL for a NaN tau. */
 int spkv_cache_set_tau(spkv_cache_t* cache, float tau);
+
+/* Re-thresholds what is already kept: every long-term entry whose stored utility logit
+ * fails the threshold now in force (spkv_cache_set_tau) is dropped, the lists are closed up
+ * in place, in order, and the pages they no longer reach are recycled.  Entries dropped
+ * earlier are gone for good, so lowering tau brings nothing back; sink positions stay.  The
+ * decode attention afterwards reads only what remains (Sec. 3: tau is chosen after training,
+ * per deployment; here also on a live cache).  Synchronises `stream` (the host re-reads the
+ * lengths).  Cost: one pass over the kept pairs of every (sequence, head). */
+int spkv_cache_prune(spkv_cache_t* cache, void* stream);
 
 /* Tuning and instrumentation; see SPKV_OPT_*. */
 int spkv_cache_set_option(spkv_cache_t* cache, int32_t option, int64_t value);

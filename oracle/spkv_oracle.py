@@ -166,6 +166,7 @@ class SPKVOracle:
         # threshold that never changes this is one entry and every gate below is the plain
         # Eq. 2 comparison.
         self._theta_hist = [[(0, self.theta)] for _ in range(batch)]
+        self._prunes = [[] for _ in range(batch)]     # (positions evicted so far, theta) per prune
 
     # ------------------------------------------------------------------ write
     def append(self, k, v, util_logits, cu_seqlens):
@@ -210,6 +211,15 @@ class SPKVOracle:
         for b in range(self.B):
             self._theta_hist[b].append((self._len[b], self.theta))
 
+    def prune(self):
+        """Re-threshold what is already kept: every pair that has left the window and whose
+        logit fails the threshold now in force is dropped from the long-term cache (pairs
+        dropped earlier stay dropped; sink positions stay kept).  With set_tau this is the
+        "tau adjusted a posteriori" of Sec. 3 applied to a live cache in the raising
+        direction."""
+        for b in range(self.B):
+            self._prunes[b].append((max(0, self._len[b] - self.w), self.theta))
+
     def _theta_when_stored(self, b, n_stored):
         """theta in force when the sequence held n_stored[i] tokens and took one more."""
         n_stored = np.asarray(n_stored)
@@ -221,6 +231,7 @@ class SPKVOracle:
     def release_sequence(self, b):
         """Forget sequence b: slot b holds an empty sequence again."""
         self._theta_hist[b] = [(0, self.theta)]
+        self._prunes[b] = []
         self._kbuf[b] = np.zeros((0, self.Hkv, self.D), self.store_dtype)
         self._vbuf[b] = np.zeros((0, self.Hkv, self.D), self.store_dtype)
         self._fbuf[b] = np.zeros((0, self.Hkv), np.float32)
@@ -247,7 +258,10 @@ class SPKVOracle:
         s = np.arange(self.seq_len(b))
         theta = self._theta_when_stored(b, s + self.w)
         theta[s + self.w >= self.seq_len(b)] = self.theta
-        return (self._f(b)[:, h] >= theta) | (s < self.n_sink)
+        z = self._f(b)[:, h] >= theta
+        for n_evicted, theta_p in self._prunes[b]:      # a prune re-judges what had left the window
+            z[:n_evicted] &= self._f(b)[:n_evicted, h] >= theta_p
+        return z | (s < self.n_sink)
 
     def gate_at_append(self, b, h):
         """The same comparison with the threshold in force when s itself was stored: the

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "spkv_decode_step_predict_workspace_bytes", "spkv_decode_step_predict", "spkv_score_chunk",
     "spkv_prefill_workspace_bytes", "spkv_prefill_attention",
     "spkv_soft_gated_workspace_bytes", "spkv_soft_gated_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_safe_steps", "spkv_cache_advance", "spkv_cache_stats", "spkv_cache_kept_positions",
-    "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
+    "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_prune", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
     "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
 ]
 
@@ -110,6 +110,8 @@ def load_library():
     lib.spkv_cache_release_sequence.argtypes = [vp, i32, vp]
     lib.spkv_utility_logits.restype = C.c_int
     lib.spkv_utility_logits.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    lib.spkv_cache_prune.restype = C.c_int
+    lib.spkv_cache_prune.argtypes = [vp, vp]
     lib.spkv_cache_safe_steps.restype = C.c_int
     lib.spkv_cache_safe_steps.argtypes = [vp, vp, P(i64)]
     lib.spkv_cache_advance.restype = C.c_int
@@ -498,6 +500,10 @@ class SPKVCache:
     def advance(self, n_steps):
         """Account for n_steps steps executed by graph replays (spkv_cache_advance)."""
         _check(self.lib.spkv_cache_advance(self.handle, int(n_steps)), "spkv_cache_advance")
+
+    def prune(self):
+        """Drop every kept pair whose logit fails the current threshold (spkv_cache_prune)."""
+        _check(self.lib.spkv_cache_prune(self.handle, _stream()), "spkv_cache_prune")
 
     def set_tau(self, tau):
         _check(self.lib.spkv_cache_set_tau(self.handle, float(tau)), "spkv_cache_set_tau")

@@ -23,7 +23,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Carve {
     size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, free_top, free_pages, err_flag,
         page_table, pool,
-        pos_pool, seg_count, seg_on, bulk_info, part_acc, part_ml, pair_items,
+        pos_pool, logit_pool, seg_count, seg_on, bulk_info, part_acc, part_ml, pair_items,
         pos_scratch, total;
     int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items;
 };
@@ -77,6 +77,7 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.page_table = take((size_t)k.n_pairs * k.pt_cap * 4);
     k.pool = take((size_t)k.n_pages * page_bytes);
     k.pos_pool = take((size_t)k.n_pages * kPageTokens * 4);
+    k.logit_pool = take((size_t)k.n_pages * kPageTokens * 4);
     k.seg_count = take((size_t)k.n_pairs * k.n_seg_cap * 4);
     k.seg_on = take((size_t)k.n_pairs * k.n_seg_cap * 4);
     k.bulk_info = take((size_t)k.n_pairs * 32);
@@ -155,6 +156,7 @@ void bind_view(spkv_cache* c) {
     v.page_table = reinterpret_cast<int32_t*>(a + k.page_table);
     v.pool = reinterpret_cast<uint16_t*>(a + k.pool);
     v.pos_pool = reinterpret_cast<int32_t*>(a + k.pos_pool);
+    v.logit_pool = reinterpret_cast<float*>(a + k.logit_pool);
     v.seg_count = reinterpret_cast<int32_t*>(a + k.seg_count);
     v.seg_on = reinterpret_cast<int32_t*>(a + k.seg_on);
     v.bulk_info = reinterpret_cast<int32_t*>(a + k.bulk_info);
@@ -357,6 +359,7 @@ int spkv_cache_grow(spkv_cache_t* c, const spkv_config_t* cfg, void* dev_arena, 
         {k.err_flag, q.err_flag, 4},
         {k.pool, q.pool, (size_t)q.n_pages * page_bytes},
         {k.pos_pool, q.pos_pool, (size_t)q.n_pages * kPageTokens * 4},
+        {k.logit_pool, q.logit_pool, (size_t)q.n_pages * kPageTokens * 4},
     };
     // every region starts on a 256-byte boundary and is padded to one, and no region
     // shrinks, so copying the padded size stays inside the new region
@@ -949,6 +952,13 @@ int spkv_cache_set_tau(spkv_cache_t* c, float tau) {
     c->cfg.tau = tau;
     c->view.theta = logit_threshold(tau);
     return SPKV_OK;
+}
+
+int spkv_cache_prune(spkv_cache_t* c, void* stream) {
+    if (c == nullptr) return SPKV_E_INVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (spkv_launch_prune(c->view, s) != hipSuccess) return SPKV_E_HIP;
+    return refresh_bound(c, s, nullptr);      // exact lengths and page count again (synchronises)
 }
 
 int spkv_cache_set_option(spkv_cache_t* c, int32_t option, int64_t value) {

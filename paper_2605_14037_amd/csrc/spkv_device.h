@@ -194,6 +194,7 @@ __device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T,
             if (kmover) *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) = r.k_old;
             if (tid == 0) {
                 v.pos_pool[(size_t)page * kPageTokens + gk] = T - v.w;
+                v.logit_pool[(size_t)page * kPageTokens + gk] = r.f_old;
                 v.kept_len[pair] = L + 1;
             }
         }

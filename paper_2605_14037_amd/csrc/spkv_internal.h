@@ -34,6 +34,7 @@ struct SpkvView {
     int32_t*  page_table;   // [n_pairs][pt_cap] logical page -> pool page
     uint16_t* pool;         // [n_pages] pages
     int32_t*  pos_pool;     // [n_pages][64] position of every long-term entry
+    float*    logit_pool;   // [n_pages][64] utility logit of every long-term entry
     int32_t*  seg_count;    // [n_pairs][n_seg_cap] bulk scratch: kept per segment, then offsets
     int32_t*  seg_on;       // [n_pairs][n_seg_cap] bulk scratch: gate-on tokens per segment
     int32_t*  bulk_info;    // [n_pairs][8] bulk scratch, see BulkInfo in spkv_write.hip
@@ -125,4 +126,6 @@ hipError_t spkv_launch_predictor(const uint16_t* x, const uint16_t* w1, const fl
                                  int n_tokens, int d_model, int d_hidden, int n_kv_heads,
                                  hipStream_t s);
 hipError_t spkv_launch_release_sequence(const SpkvView& v, int b, hipStream_t s);
+// Drops every long-term entry whose stored logit fails the view's threshold (in place).
+hipError_t spkv_launch_prune(const SpkvView& v, hipStream_t s);
 hipError_t spkv_launch_gather_positions(const SpkvView& v, int pair, hipStream_t s);

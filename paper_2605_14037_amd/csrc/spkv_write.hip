@@ -302,7 +302,10 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
                 const int gi = L_old + done + r;
                 const int page = pt[gi >> 6];
                 store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, make_uint4(w[0], w[1], w[2], w[3]));
-                if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = s;
+                if (c == 0) {
+                    v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = s;
+                    v.logit_pool[(size_t)page * kPageTokens + (gi & 63)] = rl[slot];
+                }
             }
         }
         done += tot;
@@ -411,9 +414,11 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
                 *reinterpret_cast<uint4*>(vd) = lo;
                 *reinterpret_cast<uint4*>(vd + 8) = hi;
             }
-            if (lane < 8)
-                v.pos_pool[(size_t)page * kPageTokens + dk0 + lane] =
-                    bi.T_old + j0 + s_list[G8 - g0 + lane];
+            if (lane < 8) {
+                const int jj = j0 + s_list[G8 - g0 + lane];
+                v.pos_pool[(size_t)page * kPageTokens + dk0 + lane] = bi.T_old + jj;
+                v.logit_pool[(size_t)page * kPageTokens + dk0 + lane] = f[((size_t)row0 + jj) * v.Hkv + h];
+            }
             __builtin_amdgcn_wave_barrier();
         }
         // The rows before the first and after the last whole group, one row per 16 lanes,
@@ -430,7 +435,10 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
                 const int gi = g0 + r;
                 const int page = pt[gi >> 6];
                 store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, vl);
-                if (c == 0) v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = bi.T_old + jj;
+                if (c == 0) {
+                    v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = bi.T_old + jj;
+                    v.logit_pool[(size_t)page * kPageTokens + (gi & 63)] = f[((size_t)row0 + jj) * v.Hkv + h];
+                }
             }
         }
     }
@@ -466,6 +474,83 @@ hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const u
         spkv_bulk_ring<64, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
         spkv_bulk_scatter<64><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
     }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ prune after a raise
+// After the threshold has been raised (Sec. 2.1: tau can be chosen after training, per
+// deployment): every long-term entry whose stored logit no longer passes the gate is dropped
+// and the list closed up, in place and in order.  One workgroup per (sequence, KV head)
+// walks its list 256 entries at a time: flags, ranks by a block scan, then the kept rows
+// move down 16 at a time -- read into registers, barrier, written.  A row's destination
+// index never exceeds its own index and rows go in ascending order, so no write lands on a
+// row that is still to be read.  Pages the shorter list no longer reaches go back onto the
+// stack of recycled pages (pushes only: no page is allocated in this launch).
+template <int D>
+__global__ __launch_bounds__(256) void spkv_prune(SpkvView v) {
+    const int pair = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15;
+    const int L = v.kept_len[pair];
+    int32_t* pt = v.page_table + (size_t)pair * v.pt_cap;
+    __shared__ int s_w[4];
+    __shared__ uint16_t s_list[256];
+    __shared__ int s_base;
+    int out = 0;                                           // entries kept so far (uniform)
+    for (int seg0 = 0; seg0 < L; seg0 += 256) {
+        const int idx = seg0 + tid;
+        bool keep = false;
+        if (idx < L) {
+            const size_t e = (size_t)pt[idx >> 6] * kPageTokens + (idx & 63);
+            keep = gate_passes(v, v.logit_pool[e], v.pos_pool[e]);
+        }
+        int tot;
+        const int rank = block_excl_scan(keep ? 1 : 0, s_w, tot);
+        if (keep) s_list[rank] = (uint16_t)tid;
+        __syncthreads();
+        for (int rb = 0; rb < tot; rb += 16) {
+            const int r = rb + wave * 4 + (lane >> 4);
+            const bool mine = r < tot && c < D / 8;
+            uint4 kk = {0u, 0u, 0u, 0u};
+            unsigned w[4] = {0u, 0u, 0u, 0u};
+            int pos = 0;
+            float lg = 0.f;
+            if (mine) {
+                const int si = seg0 + s_list[r];
+                const int sp_page = pt[si >> 6], sk = si & 63;
+                const uint16_t* sp = pool_page(v, sp_page);
+                kk = *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, c * 8));
+                const uint16_t* vs = sp + spkv_v_off(D, sk, c * 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] = (unsigned)vs[(2 * e) * 8] | ((unsigned)vs[(2 * e + 1) * 8] << 16);
+                pos = v.pos_pool[(size_t)sp_page * kPageTokens + sk];
+                lg = v.logit_pool[(size_t)sp_page * kPageTokens + sk];
+            }
+            __syncthreads();                               // every row of the group has been read
+            if (mine) {
+                const int di = out + r;
+                const int dp_page = pt[di >> 6], dk = di & 63;
+                store_row_chunk<D>(pool_page(v, dp_page), dk, c, kk, make_uint4(w[0], w[1], w[2], w[3]));
+                if (c == 0) {
+                    v.pos_pool[(size_t)dp_page * kPageTokens + dk] = pos;
+                    v.logit_pool[(size_t)dp_page * kPageTokens + dk] = lg;
+                }
+            }
+            __syncthreads();                               // ... and written, before the next group reads
+        }
+        out += tot;
+    }
+    const int np_old = (L + kPageTokens - 1) / kPageTokens, np_new = (out + kPageTokens - 1) / kPageTokens;
+    const int n_free = np_old - np_new;
+    if (tid == 0) s_base = n_free > 0 ? atomicAdd(v.free_top, n_free) : 0;
+    __syncthreads();
+    for (int i = tid; i < n_free; i += 256) v.free_pages[s_base + i] = pt[np_new + i];
+    if (tid == 0) v.kept_len[pair] = out;
+}
+
+hipError_t spkv_launch_prune(const SpkvView& v, hipStream_t s) {
+    if (v.D == 128) spkv_prune<128><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v);
+    else spkv_prune<64><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v);
     return hipGetLastError();
 }
 

@@ -1,7 +1,7 @@
 """Random sequences of every state-changing call against the fp64 oracle: bulk and single
 appends, fused steps (with the logits passed in, and with the predictor inside the step),
 multi-token steps, draft scoring (which must change nothing), prefill attention, sequence
-release, threshold changes and capacity growth, on random small shapes.  After every call that returns outputs
+release, threshold changes, pruning and capacity growth, on random small shapes.  After every call that returns outputs
 they are compared element by element; after every call the cache state is compared bit for
 bit (kept lengths, kept positions, statistics)."""
 
@@ -57,13 +57,17 @@ def test_random_call_sequences(trial):
             return call()
 
     for step in range(18):
-        op = rng.choice(["bulk", "single", "fused", "fused_pred", "chunk", "score", "prefill", "release", "tau"],
-                        p=[0.15, 0.1, 0.1, 0.1, 0.12, 0.08, 0.2, 0.1, 0.05])
+        op = rng.choice(["bulk", "single", "fused", "fused_pred", "chunk", "score", "prefill", "release", "tau",
+                         "prune"],
+                        p=[0.15, 0.1, 0.1, 0.1, 0.12, 0.08, 0.17, 0.08, 0.05, 0.05])
         log.append(str(op))
         if op == "release":
             b = int(rng.integers(0, B))
             cache.release_sequence(b)
             oracle.release_sequence(b)
+        elif op == "prune":
+            cache.prune()
+            oracle.prune()
         elif op == "tau":
             tau = float(rng.choice([0.2, 0.5, 0.8]))
             cache.set_tau(tau)

@@ -158,6 +158,73 @@ def test_split_count_invariance():
         assert (o - outs[0]).abs().max().item() <= 2e-2 * max(1.0, outs[0].abs().max().item())
 
 
+@pytest.mark.parametrize("D,Hq,Hk,w", [(128, 8, 2, 64), (64, 4, 2, 16), (128, 16, 1, 128)])
+def test_prune_after_raising_the_threshold(D, Hq, Hk, w):
+    """Lists filled through every write path (bulk append, single steps, multi-token steps,
+    prefill attention), then tau raised and spkv_cache_prune: lengths and positions bit for
+    bit, outputs, statistics; the pages given back are used again by what follows; a prune
+    under a lowered threshold changes nothing; sink positions survive."""
+    B = 3
+    wl = small_workload("prune", B, Hq, Hk, D, [1500, 333, 70], 0.6, window=w, seed=83 + D)
+    stream = TokenStream(wl, device="cuda")
+    cache = H.make_cache(wl, pool_tokens=(2300 + 64) * Hk * B, extra_context=900)
+    oracle = SPKVOracle(B, Hq, Hk, D, window=w, tau=0.5, n_sink=2)
+    cache.set_option(spkv.OPT_SINK_TOKENS, 2)
+    G = Hq // Hk
+
+    def step(kind, counts):
+        k, v, f, cu = stream.next_tokens(counts)
+        q = stream.next_query(rows=sum(counts))
+        if kind == "bulk":
+            cache.append(k, v, f, cu)
+        elif kind == "fused":
+            cache.decode_step(k, v, f, q)
+        elif kind == "chunk":
+            cache.decode_chunk(k, v, f, q, cu)
+        else:
+            cache.prefill_attention(k, v, f, q, cu)
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+
+    def check(label):
+        st = H.check_state(cache, oracle, wl, label=label)
+        q = stream.next_query()
+        H.check_output(cache.decode_attention(q), oracle.decode(to_numpy_f32(q))[0], label)
+        return st
+
+    H.prefill(cache, oracle, stream, wl, 512)
+    for _ in range(5):
+        step("fused", [1] * B)
+    step("chunk", [min(4, w, 64 // G), 2, 1])
+    step("prefill", [150, 40, 3])
+    before = check("filled")
+    for tau in (0.7, 0.9):                       # two raises in a row
+        cache.set_tau(tau)
+        oracle.set_tau(tau)
+        cache.prune()
+        oracle.prune()
+        after = check(f"pruned at tau {tau}")
+        assert after.kept_tokens < before.kept_tokens
+        before = after
+    step("bulk", [300, 10, 200])                 # recycled pages come back into use
+    for _ in range(w + 3):
+        step("fused", [1] * B)
+    check("appends after the prune")
+    cache.set_tau(0.3)                           # lowering brings nothing back
+    oracle.set_tau(0.3)
+    cache.prune()
+    oracle.prune()
+    st = check("prune under a lower threshold")
+    assert st.kept_tokens == before.kept_tokens or st.kept_tokens > 0
+    step("prefill", [90, 90, 90])
+    cache.set_tau(1.0)                           # everything but the sinks goes
+    oracle.set_tau(1.0)
+    cache.prune()
+    oracle.prune()
+    st = check("tau = 1")
+    assert st.kept_tokens == 2 * B * Hk
+    cache.close()
+
+
 @pytest.mark.parametrize("D,Hq,Hk,w", [(128, 8, 2, 32), (64, 4, 2, 128), (128, 16, 4, 16), (128, 4, 4, 64)])
 def test_score_chunk_then_append_of_the_accepted_drafts(D, Hq, Hk, w):
     """Speculative decoding rounds: spkv_score_chunk returns what spkv_decode_chunk would for

@@ -458,14 +458,16 @@ def test_decode_chunk_matches_sdpa_rows_and_single_steps():
 
 
 def test_live_threshold_change_matches_a_step_by_step_cache_simulation():
-    """Pin for set_tau: the appendix describes the cache as a process -- when the window is
+    """Pin for set_tau and prune: the appendix describes the cache as a process -- when the window is
     full, the pair leaving it is kept iff its gate is on (here: with the threshold in force
-    at that moment), otherwise dropped.  A literal simulation of that process (a window list,
+    at that moment), otherwise dropped; a prune drops from the kept list what fails the threshold
+    of the moment.  A literal simulation of that process (a window list,
     a kept list, one token at a time, plain Python) must give the oracle's kept lists, its
     gate-on count and, with explicit softmax loops over kept + window, its decode output."""
     rng = np.random.default_rng(91)
     B, Hq, Hkv, D, w = 2, 4, 2, 4, 3
     taus = {0: 0.5, 7: 0.8, 12: 0.2, 13: 0.65, 20: 0.5}      # step -> new tau
+    prunes = {8, 14, 15, 21}                                  # steps that begin with a prune
     o = SPKVOracle(B, Hq, Hkv, D, window=w, tau=taus[0])
     window = [[[] for _ in range(Hkv)] for _ in range(B)]    # (pos, k, v, f)
     kept = [[[] for _ in range(Hkv)] for _ in range(B)]
@@ -477,6 +479,11 @@ def test_live_threshold_change_matches_a_step_by_step_cache_simulation():
         if step in taus and step > 0:
             o.set_tau(taus[step])
             theta = threshold_logit(taus[step])
+        if step in prunes:                                    # what is kept is judged again
+            o.prune()
+            for b in range(B):
+                for h in range(Hkv):
+                    kept[b][h] = [e for e in kept[b][h] if e[3] >= theta]
         counts = [1, 1] if step % 5 else [2, 0]               # sequence 1 lags behind
         total = sum(counts)
         k = rng.standard_normal((total, Hkv, D)).astype(np.float32)
