@@ -197,6 +197,8 @@ def test_prune_after_raising_the_threshold(D, Hq, Hk, w):
     step("chunk", [min(4, w, 64 // G), 2, 1])
     step("prefill", [150, 40, 3])
     before = check("filled")
+    # the logits travel with the pairs when the cache moves into a larger arena
+    cache.grow(max_context=wl.max_context + 2000, max_total_kept_tokens=(4000 + 64) * Hk * B)
     for tau in (0.7, 0.9):                       # two raises in a row
         cache.set_tau(tau)
         oracle.set_tau(tau)
