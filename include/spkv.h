@@ -89,7 +89,7 @@ typedef struct spkv_stats {
 
 /* Options for spkv_cache_set_option. */
 #define SPKV_OPT_ITEM_TARGET    1  /* split-K work items to aim for per decode, 1..32768;
-                                      0 (default) = chosen from the cache size              */
+                                      0 (default) = as many as the chip runs at once        */
 #define SPKV_OPT_KERNEL_TIMING  2  /* 1: bracket every split-K kernel launch with HIP events */
 #define SPKV_OPT_SPLIT_ONLY     3  /* 1: spkv_decode_attention launches the split-K kernel
                                       only (no combine, `out` and `lse` left untouched):
@@ -183,8 +183,9 @@ int spkv_decode_step(spkv_cache_t* cache, const void* k, const void* v, const fl
  * the attention output of each of them, computed as if the tokens had been appended and
  * decoded one at a time: token i of the chunk (position T_b + i) attends to the positions
  * s <= T_b + i that are inside its window or pass the gate (Eq. 3-5; the rows T_b .. of the
- * masked attention of the listing appendix).  Uses: verification of speculative tokens,
- * prompt feed in 16-token chunks (the chunk size of the paper's chunked-prefill protocol).
+ * masked attention of the listing appendix).  Use: prompt feed in 16-token chunks (the chunk
+ * size of the paper's chunked-prefill protocol); for draft tokens that may be rejected see
+ * spkv_score_chunk.
  *   k, v         device bf16 [total, n_kv_heads, head_dim]    util_logits device fp32 [total, n_kv_heads]
  *   q, out       device bf16 [total, n_q_heads, head_dim]     lse device fp32 [total, n_q_heads] or NULL
  *   cu_seqlens   host int32 [batch + 1]
