@@ -189,3 +189,74 @@ def test_cfg2_prefill_attention_last_chunks():
     st = H.check_state(cache, gates, wl, label="prefill full size")
     assert st.total_tokens == wl.batch * ctx
     cache.close()
+
+
+def test_arena_above_4_gib_sequences_with_identical_tokens():
+    """Page addresses beyond 2^32 bytes (and element offsets beyond 2^31): 40 sequences receive
+    the same tokens, six of the eight KV heads keep every pair and two keep about a third,
+    so more than 4 GiB of pages are in use and most sequences live in pages whose byte offset
+    does not fit 32 bits.  Equal inputs cut into equal work items give equal arithmetic, so every
+    sequence's outputs must equal sequence 0's bit for bit, and sequence 0 is checked against
+    the oracle: the last 1024 prompt tokens through spkv_prefill_attention (sampled rows), then
+    three fused decode steps and one append + decode."""
+    B, Hq, Hkv, D, w = 40, 32, 8, 128, 128
+    ctx, chunk, tail = 40960, 4096, 1024
+    cache = spkv.SPKVCache(B, Hq, Hkv, D, max_context=ctx + 64,
+                           max_total_kept_tokens=B * Hkv * (ctx + 64), window=w, tau=0.5)
+    oracle = SPKVOracle(1, Hq, Hkv, D, window=w, tau=0.5)
+    g = torch.Generator(device="cuda").manual_seed(4099)
+
+    def tokens(n):
+        k1 = torch.randn(n, Hkv, D, generator=g, device="cuda").to(torch.bfloat16)
+        v1 = torch.randn(n, Hkv, D, generator=g, device="cuda").to(torch.bfloat16)
+        f1 = torch.randn(n, Hkv, generator=g, device="cuda")
+        f1[:, :6] = f1[:, :6].abs() + 0.25          # kept whatever the draw
+        f1[:, 6:] -= 0.45                           # about a third kept
+        oracle.append(to_numpy_f32(k1), to_numpy_f32(v1), to_numpy_f32(f1), [0, n])
+        cu = [b * n for b in range(B + 1)]
+        return k1.repeat(B, 1, 1), v1.repeat(B, 1, 1), f1.repeat(B, 1).contiguous(), cu
+
+    def queries(n):
+        q1 = torch.randn(n, Hq, D, generator=g, device="cuda").to(torch.bfloat16)
+        return q1, q1.repeat(B, 1, 1)
+
+    def same_in_every_sequence(t, n, what):
+        t = t.reshape(B, n, *t.shape[1:])
+        assert torch.equal(t, t[:1].expand_as(t)), f"{what}: sequences differ"
+
+    for _ in range((ctx - tail) // chunk):
+        cache.append(*tokens(chunk))
+    cache.append(*tokens((ctx - tail) % chunk))
+    # the last prompt tokens with their attention
+    k, v, f, cu = tokens(tail)
+    q1, q = queries(tail)
+    out, lse = cache.prefill_attention(k, v, f, q, cu, want_lse=True)
+    same_in_every_sequence(out, tail, "prefill out")
+    same_in_every_sequence(lse, tail, "prefill lse")
+    pick = sorted({0, 1, tail // 2, tail - 1} | set(np.random.default_rng(5).choice(tail, 12).tolist()))
+    ref_out, ref_lse = oracle.decode_chunk(to_numpy_f32(q1), [tail], rows=set(pick))
+    H.check_output(out[(B - 1) * tail:][pick], ref_out[pick], "prefill, last sequence")
+    H.check_lse(lse[(B - 1) * tail:][pick], ref_lse[pick], "prefill, last sequence")
+    for step in range(4):
+        k, v, f, cu = tokens(1)
+        q1, q = queries(1)
+        if step < 3:
+            out, lse = cache.decode_step(k, v, f, q, want_lse=True)
+        else:
+            cache.append(k, v, f, cu)
+            out, lse = cache.decode_attention(q, want_lse=True)
+        same_in_every_sequence(out, 1, f"step {step} out")
+        same_in_every_sequence(lse, 1, f"step {step} lse")
+        ref_out, ref_lse = oracle.decode(to_numpy_f32(q1))
+        H.check_output(out[B - 1:], ref_out, f"step {step}, last sequence")
+        H.check_lse(lse[B - 1:], ref_lse, f"step {step}, last sequence")
+    st, kept = cache.stats(with_kept_len=True)
+    assert st.device_error == 0
+    assert st.kept_kv_bytes > 1 << 32
+    kept = np.array(kept, dtype=np.int64).reshape(B, Hkv)
+    assert np.array_equal(kept, np.broadcast_to(oracle.kept_len().reshape(1, Hkv), (B, Hkv)))
+    for b in (0, B - 1):
+        for h in (0, 7):
+            assert cache.kept_positions(b, h) == oracle.kept_positions(0, h).tolist()
+    print(f"arena test: {st.kept_kv_bytes / 2**30:.2f} GiB of kept K/V in use", flush=True)
+    cache.close()
