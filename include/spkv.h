@@ -89,7 +89,10 @@ typedef struct spkv_stats {
 
 /* Options for spkv_cache_set_option. */
 #define SPKV_OPT_ITEM_TARGET    1  /* split-K work items to aim for per decode, 1..32768;
-                                      0 (default) = as many as the chip runs at once        */
+                                      0 (default) = as many as the chip runs at once.  Items
+                                      come in workgroups of up to four (SPKV_OPT_MERGE_WAVES),
+                                      so a call may use up to four per (sequence, KV head)
+                                      even for a target of 1                                 */
 #define SPKV_OPT_KERNEL_TIMING  2  /* 1: bracket every split-K kernel launch with HIP events */
 #define SPKV_OPT_SPLIT_ONLY     3  /* 1: spkv_decode_attention launches the split-K kernel
                                       only (no combine, `out` and `lse` left untouched):
@@ -99,6 +102,10 @@ typedef struct spkv_stats {
                                       (attention sinks, an ablation variant in the paper; the
                                       default 0 is the paper's method).  Only while the cache is
                                       empty (after create or reset): SPKV_E_STATE otherwise. */
+#define SPKV_OPT_MERGE_WAVES    5  /* work items per workgroup of the single-token decode kernels
+                                      (they merge their results before anything is stored):
+                                      1, 2 or 4; 0 (default) = chosen per call from the number
+                                      of (sequence, KV head) pairs and their lengths           */
 
 /* Bytes of device arena a cache with this configuration needs (0 if cfg is invalid).
  * Host-only; touches no device.  Capacity rule: the long-term cache can hold

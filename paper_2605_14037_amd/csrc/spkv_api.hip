@@ -112,6 +112,7 @@ struct spkv_cache {
     int64_t pages_ub;             // sum of pages_for(L_ub): upper bound of pool pages in use
     bool bound_is_loose;          // a bulk append grew L_ub by far more than the truth
     int item_target;
+    int merge_waves;              // SPKV_OPT_MERGE_WAVES (0 = per call)
     int n_sink;                   // always-kept first positions (SPKV_OPT_SINK_TOKENS)
     int one_round_items;          // items the chip runs in one resident round, with a margin
     int chunk_round_items[3];     // the same for the chunk kernel with 1, 2, 4 column groups
@@ -189,7 +190,9 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // about (all half-pages / item_target) half-pages, and enough slots per pair for the
 // longest pair.  The kernels apply it to the exact device-side lengths, which never
 // exceed the bound, so every pair fits its slots.
-SpkvSplit choose_split(const spkv_cache* c, int one_round_items, int64_t slots_total_cap) {
+// mw: work items per workgroup and partial slot; the target counts items either way.
+SpkvSplit choose_split_mw(const spkv_cache* c, int one_round_items, int64_t slots_total_cap, int mw,
+                          int64_t* n_items = nullptr) {
     const int n_pairs = c->carve.n_pairs, Hkv = c->cfg.n_kv_heads;
     std::vector<int64_t> hp(n_pairs);
     int64_t sum_hp = 0, max_hp = 1;
@@ -207,21 +210,50 @@ SpkvSplit choose_split(const spkv_cache* c, int one_round_items, int64_t slots_t
     int64_t target = c->item_target;
     if (target <= 0) target = one_round_items;
     target = std::max<int64_t>(1, std::min<int64_t>(target, slots_total_cap - n_pairs));
-    int64_t per = std::max<int64_t>(1, (sum_hp + target - 1) / target);
-    // Every pair rounds its item count up; keep the total within the target, because one
-    // item more than the chip holds at once costs a whole second round of the longest items.
+    const int64_t groups_target = std::max<int64_t>(1, target / mw);
+    int64_t per = std::max<int64_t>(1, (sum_hp + groups_target * mw - 1) / (groups_target * mw));
+    // Every pair rounds its workgroup count up; keep the total within the target, because one
+    // more than the chip holds at once costs a whole second round of the longest items.
     for (int guard = 0; guard < 64; ++guard) {
-        int64_t items = 0;
-        for (int p = 0; p < n_pairs; ++p) items += (hp[p] + per - 1) / per;
-        if (items <= target || items <= n_pairs) break;
+        int64_t groups = 0;
+        for (int p = 0; p < n_pairs; ++p) groups += (hp[p] + per * mw - 1) / (per * mw);
+        if (groups <= groups_target || groups <= n_pairs) break;
         per += std::max<int64_t>(1, per / 16);
     }
     const int64_t slots_cap = std::max<int64_t>(1, slots_total_cap / n_pairs - 1);
-    if ((max_hp + per - 1) / per > slots_cap) per = (max_hp + slots_cap - 1) / slots_cap;
+    if ((max_hp + per * mw - 1) / (per * mw) > slots_cap) per = (max_hp + slots_cap * mw - 1) / (slots_cap * mw);
     SpkvSplit sp;
     sp.hp_per_item = (int32_t)per;
-    sp.slots = (int32_t)((max_hp + per - 1) / per) | 1;   // odd: see spkv_decode_split
+    sp.slots = (int32_t)((max_hp + per * mw - 1) / (per * mw)) | 1;   // odd: see spkv_decode_split
+    sp.mw = mw;
+    if (n_items != nullptr) {
+        *n_items = 0;
+        for (int p = 0; p < n_pairs; ++p)
+            *n_items += std::min<int64_t>((hp[p] + per * mw - 1) / (per * mw) * mw, hp[p]);
+    }
     return sp;
+}
+
+// Single-token decode: workgroups of 4 or 2 items when the cache has few pairs and the
+// whole-workgroup rounding per pair neither lengthens the items nor leaves fewer of them than
+// one item per workgroup would.  Measured (step time, 32 query / 8 KV heads of 128, keep rates
+// drawn per pair): one sequence of 128k tokens 26 -> 22 us, 4 of 128k 39 -> 38, 3 of 64k
+// 47 -> 44, equal lists of 1 to 4 sequences 1 to 2.5 us less, two of twelve shapes 1.5 us
+// more; but 16 sequences of 32k (128 pairs of about 23 items) 78 -> 92 at the same item
+// length, and 64 sequences of 1k-64k 459 -> 540.  Hence the limit of kMergePairs pairs.
+constexpr int kMergePairs = 32;
+SpkvSplit choose_split(const spkv_cache* c, int one_round_items, int64_t slots_total_cap) {
+    int64_t items_one = 0;
+    const SpkvSplit one = choose_split_mw(c, one_round_items, slots_total_cap, 1, &items_one);
+    if (c->merge_waves == 1) return one;
+    if (c->merge_waves > 1) return choose_split_mw(c, one_round_items, slots_total_cap, c->merge_waves);
+    if (c->carve.n_pairs > kMergePairs) return one;
+    for (int mw = 4; mw > 1; mw >>= 1) {
+        int64_t items = 0;
+        const SpkvSplit sp = choose_split_mw(c, one_round_items, slots_total_cap, mw, &items);
+        if (sp.hp_per_item <= one.hp_per_item && items >= items_one) return sp;
+    }
+    return one;
 }
 
 SpkvSplit choose_split(const spkv_cache* c) {
@@ -304,6 +336,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->pages_ub = 0;
     c->bound_is_loose = false;
     c->item_target = 0;
+    c->merge_waves = 0;
     c->n_sink = 0;
     {
         // Measured on MI355X: up to 94 % of the resident slots run in one round; at 99 % some
@@ -312,7 +345,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
         c->one_round_items = resident > 0 ? resident - resident / 24 : kFallbackItems;
         c->chunk_round_items[0] = c->chunk_round_items[1] = c->chunk_round_items[2] = 0;
     }
-    c->split = SpkvSplit{1, 1};
+    c->split = SpkvSplit{1, 1, 1};
     c->timing = false;
     c->split_only = false;
     c->n_timed = 0;
@@ -602,8 +635,8 @@ int chunk_call(spkv_cache_t* c, const void* k, const void* v, const float* util_
     // With two or four column groups a wave needs most of the register file and only one or
     // two fit a SIMD; one resident round of such items then reads too little at a time, and
     // about 1 800 items (two rounds of the widest kernel) measured 12-15 % faster.
-    c->split = choose_split(c, std::max(c->chunk_round_items[gi], groups > 1 ? c->one_round_items * 5 / 8 : 0),
-                            slot_cap);
+    c->split = choose_split_mw(c, std::max(c->chunk_round_items[gi], groups > 1 ? c->one_round_items * 5 / 8 : 0),
+                               slot_cap, 1);
 
     SpkvCu cu;
     std::memcpy(cu.v, cu_seqlens, (size_t)(B + 1) * 4);
@@ -897,7 +930,8 @@ int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void*
     for (int p = 0; p < n_pairs; ++p) {
         const int Tw = std::min(c->T[p / Hkv], w);
         const int64_t hp = (len[p] + kHalfTokens - 1) / kHalfTokens + (Tw + kHalfTokens - 1) / kHalfTokens;
-        n_items += std::min<int64_t>((hp + sp.hp_per_item - 1) / sp.hp_per_item, sp.slots);
+        const int64_t per = (int64_t)sp.hp_per_item * sp.mw;
+        n_items += std::min<int64_t>(std::min<int64_t>((hp + per - 1) / per, sp.slots) * sp.mw, hp);
     }
     st->n_work_items = (int32_t)n_items;
     if (kept_len != nullptr) std::memcpy(kept_len, len.data(), (size_t)n_pairs * 4);
@@ -970,6 +1004,10 @@ int spkv_cache_set_option(spkv_cache_t* c, int32_t option, int64_t value) {
             return SPKV_OK;
         case SPKV_OPT_SPLIT_ONLY:
             c->split_only = value != 0;
+            return SPKV_OK;
+        case SPKV_OPT_MERGE_WAVES:
+            if (value != 0 && value != 1 && value != 2 && value != 4) return SPKV_E_INVAL;
+            c->merge_waves = (int)value;
             return SPKV_OK;
         case SPKV_OPT_SINK_TOKENS:
             if (value < 0 || value > c->cfg.max_context) return SPKV_E_INVAL;

@@ -11,7 +11,13 @@
 // One wavefront per work item.  The G <= 16 query heads of the GQA group are the N = 16
 // columns of every MFMA, so each K/V tile is read exactly once per group.  Every wave-wide
 // load is 1 KB contiguous.
-// Block id = pair * slots + j with an odd slot count: workgroups go round-robin to the 8
+// MW = sp.mw consecutive items of a pair form a workgroup.  With MW > 1 the waves work
+// independently and meet once, at the end, to merge their (max, sum, acc) triples in LDS, so
+// that one partial per workgroup goes to memory (the partial stores sit in the tail of every
+// wave; a quarter of them measured 1.5-2 us less per launch) and the merge launch has a
+// quarter to fold.  The host picks MW > 1 only when packing the items of every pair into whole
+// workgroups does not lengthen the items (few pairs with long lists).
+// Block id = pair * slots + jj with an odd slot count: workgroups go round-robin to the 8
 // XCDs, so the items of every pair -- long or short -- spread evenly over all of them
 // (heads differ in kept length by several times; pinning a head to one XCD would leave
 // the others idle), and the odd stride keeps the per-pair remainders from piling up on
@@ -23,21 +29,32 @@
 // the pair in it passes the gate (it is the pair leaving the window: kept -> it stays
 // attended, as the next long-term entry; dropped -> it is gone), and publishes every
 // pair's item count for spkv_combine_append, which adds the new token's own term.
-template <int D, bool FUSED>
+constexpr int kMergePad = 16;    // floats between the rows of the LDS copy: no bank conflicts for G = 4
+
+static size_t split_lds_bytes(int mw, int group, int head_dim) {
+    if (mw == 1) return 0;
+    return ((size_t)mw * group * (head_dim + kMergePad) + 2 * mw * 16) * sizeof(float);
+}
+
+template <int D, bool FUSED, int MW>
 __device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint16_t* __restrict__ q,
-                                                  float scale_log2e, SpkvSplit sp, int item) {
+                                                  float scale_log2e, SpkvSplit sp, int wg, float* s_mem) {
     constexpr int NS = D / 32;   // head-dim slabs of one K tile
     constexpr int NB = D / 16;   // 16-wide output blocks
-    const int pair = item / sp.slots;
-    const int j = item - pair * sp.slots;
+    const int pair = wg / sp.slots;
+    const int jj = wg - pair * sp.slots;
     const PairSplit ps = pair_split(v, pair, sp);
-    if (FUSED && j == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.items;
-    if (j >= ps.items) return;
+    if (FUSED && jj == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.groups;
+    if (jj >= ps.groups) return;          // the whole workgroup
+    const int wave = MW == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int j = jj * MW + wave;
+    // a wave past the pair's last item takes an empty range and joins the merge with weight 0
+    const bool has_item = j < ps.items;
     const int hbase = ps.nhp / ps.items, hrem = ps.nhp - hbase * ps.items;
-    const int hp0 = j * hbase + min(j, hrem);
-    const int hp1 = hp0 + hbase + (j < hrem ? 1 : 0);
+    const int hp0 = has_item ? j * hbase + min(j, hrem) : 0;
+    const int hp1 = has_item ? hp0 + hbase + (j < hrem ? 1 : 0) : 0;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
-    const int lane = threadIdx.x, kc = lane >> 4, n = lane & 15;
+    const int lane = threadIdx.x & 63, kc = lane >> 4, n = lane & 15;
 
     bf16x8 qb[NS];
     {
@@ -112,15 +129,58 @@ __device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint1
 
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
+    const size_t slot = (size_t)pair * sp.slots + jj;
+    if (MW == 1) {
+        if (n < v.G) {
+            float* pa = v.part_acc + (slot * v.G + n) * D + kc * 4;
+#pragma unroll
+            for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[db];
+            if (kc == 0) {
+                float* pm = v.part_ml + (slot * v.G + n) * 2;
+                pm[0] = m;
+                pm[1] = l;
+            }
+        }
+        return;
+    }
+    // the workgroup's waves meet: acc[wave][head][d] (rows kMergePad floats apart), m, l
+    constexpr int kRow = D + kMergePad;
+    float* s_acc = s_mem;
+    float* s_m = s_mem + MW * v.G * kRow;
+    float* s_l = s_m + MW * 16;
     if (n < v.G) {
-        const size_t slot = (size_t)pair * sp.slots + j;
-        float* pa = v.part_acc + (slot * v.G + n) * D + kc * 4;
+        float* pa = s_acc + (wave * v.G + n) * kRow + kc * 4;
 #pragma unroll
         for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[db];
         if (kc == 0) {
-            float* pm = v.part_ml + (slot * v.G + n) * 2;
-            pm[0] = m;
-            pm[1] = l;
+            s_m[wave * 16 + n] = m;
+            s_l[wave * 16 + n] = l;
+        }
+    }
+    __syncthreads();
+    // one partial per workgroup: with M the largest reference of the waves,
+    // acc = sum_w 2^(m_w - M) acc_w,  l = sum_w 2^(m_w - M) l_w
+    for (int e = threadIdx.x; e < v.G * D; e += 64 * MW) {
+        const int g = e / D, d = e - g * D;
+        float mw[MW], M = SPKV_NEG_INF;
+#pragma unroll
+        for (int w = 0; w < MW; ++w) {
+            mw[w] = s_m[w * 16 + g];
+            M = fmaxf(M, mw[w]);
+        }
+        const float m_ref = (M == SPKV_NEG_INF) ? 0.f : M;      // no key at all: every weight 0
+        float a = 0.f, lsum = 0.f;
+#pragma unroll
+        for (int w = 0; w < MW; ++w) {
+            const float sc = __builtin_amdgcn_exp2f(mw[w] - m_ref);
+            a += sc * s_acc[(w * v.G + g) * kRow + d];
+            lsum += sc * s_l[w * 16 + g];
+        }
+        v.part_acc[(slot * v.G + g) * D + d] = a;
+        if (d == 0) {
+            float* pm = v.part_ml + (slot * v.G + g) * 2;
+            pm[0] = M;
+            pm[1] = lsum;
         }
     }
 }
@@ -132,33 +192,38 @@ static bool wide_merge(const SpkvView& v, const SpkvSplit& sp) {
     return sp.slots > 32 && v.n_pairs * v.G <= 256;
 }
 
-template <int D, bool FUSED>
-__global__ __launch_bounds__(64) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
-                                                        float scale_log2e, SpkvSplit sp) {
-    decode_split_item<D, FUSED>(v, q, scale_log2e, sp, blockIdx.x);
+template <int D, bool FUSED, int MW>
+__global__ __launch_bounds__(64 * MW) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
+                                                             float scale_log2e, SpkvSplit sp) {
+    extern __shared__ __attribute__((aligned(16))) float s_split[];
+    decode_split_item<D, FUSED, MW>(v, q, scale_log2e, sp, blockIdx.x, s_split);
 }
 
 // Fused step with the utility predictor (Eq. 1; the appendix builds it as Linear - SiLU -
 // Linear per token): the hidden layer rides in the split launch, the output layer in the
 // append workgroups of the second launch, so the gate logits of the new tokens cost no
-// launch of their own.  The first pr.n_blocks one-wave workgroups of this launch compute
-// partial sums of the hidden layer: workgroup (jb, tb, ks) takes 16 hidden units, 16 tokens
-// and the ks-th of kPredictSplit ranges of d_model on MFMA 16x16x32 (W1 rows as A operand,
-// tokens as the 16 columns) and stores part[ks][token][unit], without bias.  The other
-// workgroups are the work items of spkv_decode_split<D, true>.
-template <int D>
-__global__ __launch_bounds__(64) void spkv_decode_split_predict(SpkvView v,
+// launch of their own.  The waves of the first ceil(pr.n_blocks / MW) workgroups of
+// this launch compute partial sums of the hidden layer: wave (jb, tb, ks) takes 16 hidden
+// units, 16 tokens and the ks-th of kPredictSplit ranges of d_model on MFMA 16x16x32 (W1 rows
+// as A operand, tokens as the 16 columns) and stores part[ks][token][unit], without bias.
+// The other workgroups are those of spkv_decode_split<D, true>.
+template <int D, int MW>
+__global__ __launch_bounds__(64 * MW) void spkv_decode_split_predict(SpkvView v,
                                                                 const uint16_t* __restrict__ q,
                                                                 float scale_log2e, SpkvSplit sp,
                                                                 SpkvPredict pr) {
-    if ((int)blockIdx.x >= pr.n_blocks) {
-        decode_split_item<D, true>(v, q, scale_log2e, sp, (int)blockIdx.x - pr.n_blocks);
+    extern __shared__ __attribute__((aligned(16))) float s_split[];
+    const int n_pred_wg = (pr.n_blocks + MW - 1) / MW;
+    if ((int)blockIdx.x >= n_pred_wg) {
+        decode_split_item<D, true, MW>(v, q, scale_log2e, sp, (int)blockIdx.x - n_pred_wg, s_split);
         return;
     }
+    const int unit = (int)blockIdx.x * MW + ((int)threadIdx.x >> 6);
+    if (unit >= pr.n_blocks) return;
     const int n_jb = pr.d_hidden / 16;
-    const int ks = blockIdx.x % kPredictSplit, rest = blockIdx.x / kPredictSplit;
+    const int ks = unit % kPredictSplit, rest = unit / kPredictSplit;
     const int jb = rest % n_jb, tb = rest / n_jb;
-    const int lane = threadIdx.x, kc = lane >> 4, n = lane & 15;
+    const int lane = threadIdx.x & 63, kc = lane >> 4, n = lane & 15;
     const int kq = pr.d_model / kPredictSplit;            // a multiple of 32
     const int tok = tb * 16 + n;
     const bool tok_ok = tok < v.B;
@@ -234,7 +299,7 @@ __global__ __launch_bounds__(64 * NWM) void spkv_decode_combine(SpkvView v, uint
     const int pair = blockIdx.x / v.G, g = blockIdx.x - pair * v.G;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int items = pair_split(v, pair, sp).items;
+    const int items = pair_split(v, pair, sp).groups;
     const size_t slot0 = (size_t)pair * sp.slots;
     __shared__ float s_m[NWM];
     __shared__ float s_den[NWM];
@@ -639,17 +704,36 @@ int spkv_chunk_resident_items(int head_dim, int col_groups) {
     return per_cu * cus;
 }
 
+// Launch of the split kernel for the call's merge width (1, 2 or 4 waves per workgroup).
+template <int D, bool FUSED>
+static void launch_split(const SpkvView& v, const uint16_t* q, float scale_log2e, SpkvSplit sp,
+                         hipStream_t s) {
+    const dim3 grid((unsigned)v.n_pairs * (unsigned)sp.slots);
+    const size_t lds = split_lds_bytes(sp.mw, v.G, D);
+    if (sp.mw == 4) spkv_decode_split<D, FUSED, 4><<<grid, dim3(256), lds, s>>>(v, q, scale_log2e, sp);
+    else if (sp.mw == 2) spkv_decode_split<D, FUSED, 2><<<grid, dim3(128), lds, s>>>(v, q, scale_log2e, sp);
+    else spkv_decode_split<D, FUSED, 1><<<grid, dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+}
+
+template <int D>
+static void launch_split_predict(const SpkvView& v, const uint16_t* q, float scale_log2e,
+                                 SpkvSplit sp, const SpkvPredict& pr, hipStream_t s) {
+    const dim3 grid((unsigned)((pr.n_blocks + sp.mw - 1) / sp.mw) + (unsigned)v.n_pairs * (unsigned)sp.slots);
+    const size_t lds = split_lds_bytes(sp.mw, v.G, D);
+    if (sp.mw == 4) spkv_decode_split_predict<D, 4><<<grid, dim3(256), lds, s>>>(v, q, scale_log2e, sp, pr);
+    else if (sp.mw == 2) spkv_decode_split_predict<D, 2><<<grid, dim3(128), lds, s>>>(v, q, scale_log2e, sp, pr);
+    else spkv_decode_split_predict<D, 1><<<grid, dim3(64), 0, s>>>(v, q, scale_log2e, sp, pr);
+}
+
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
                               float sm_scale, SpkvSplit sp, bool split_only, hipEvent_t ev0,
                               hipEvent_t ev1, hipStream_t s) {
     const float scale_log2e = sm_scale * 1.4426950408889634f;
-    const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
+    if (sp.mw != 1 && sp.mw != 2 && sp.mw != 4) return hipErrorInvalidValue;
     hipError_t e;
     if (ev0 != nullptr && (e = hipEventRecord(ev0, s)) != hipSuccess) return e;
-    if (v.D == 128)
-        spkv_decode_split<128, false><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
-    else
-        spkv_decode_split<64, false><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+    if (v.D == 128) launch_split<128, false>(v, q, scale_log2e, sp, s);
+    else launch_split<64, false>(v, q, scale_log2e, sp, s);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
     if (split_only) return hipSuccess;
@@ -664,14 +748,16 @@ hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* ou
     return hipGetLastError();
 }
 
+// One-wave work items the device holds at once (the registers decide, so the count is the
+// same for every merge width).
 int spkv_split_resident_items(int head_dim) {
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
     const hipError_t e =
         head_dim == 128
-            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<128, false>, 64, 0)
-            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<64, false>, 64, 0);
+            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<128, false, 1>, 64, 0)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<64, false, 1>, 64, 0);
     if (e != hipSuccess || per_cu <= 0 || cus <= 0) return 0;
     return per_cu * cus;
 }
@@ -680,16 +766,16 @@ hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const u
                                    const float* f, const uint16_t* q, uint16_t* out, float* lse,
                                    float sm_scale, SpkvSplit sp, hipStream_t s) {
     const float scale_log2e = sm_scale * 1.4426950408889634f;
-    const unsigned grid = (unsigned)v.n_pairs * (unsigned)sp.slots;
+    if (sp.mw != 1 && sp.mw != 2 && sp.mw != 4) return hipErrorInvalidValue;
     const SpkvPredict none = {};
     const dim3 grid2(v.n_pairs * v.G + v.n_pairs);
     const bool wide = wide_merge(v, sp);
     if (v.D == 128) {
-        spkv_decode_split<128, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+        launch_split<128, true>(v, q, scale_log2e, sp, s);
         if (wide) spkv_combine_append<128, false, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
         else spkv_combine_append<128, false, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
     } else {
-        spkv_decode_split<64, true><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+        launch_split<64, true>(v, q, scale_log2e, sp, s);
         if (wide) spkv_combine_append<64, false, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
         else spkv_combine_append<64, false, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
     }
@@ -705,19 +791,18 @@ hipError_t spkv_launch_decode_step_predict(const SpkvView& v, const uint16_t* k,
                                            float sm_scale, SpkvSplit sp, SpkvPredict pr,
                                            hipStream_t s) {
     const float scale_log2e = sm_scale * 1.4426950408889634f;
+    if (sp.mw != 1 && sp.mw != 2 && sp.mw != 4) return hipErrorInvalidValue;
     pr.n_blocks = spkv_predict_blocks(v.B, pr.d_hidden);
-    const unsigned grid = (unsigned)pr.n_blocks + (unsigned)v.n_pairs * (unsigned)sp.slots;
     const dim3 grid2(v.n_pairs * v.G + v.n_pairs);
     const bool wide = wide_merge(v, sp);
     if (v.D == 128) {
-        spkv_decode_split_predict<128><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp, pr);
+        launch_split_predict<128>(v, q, scale_log2e, sp, pr, s);
         if (wide) spkv_combine_append<128, true, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
         else spkv_combine_append<128, true, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
     } else {
-        spkv_decode_split_predict<64><<<dim3(grid), dim3(64), 0, s>>>(v, q, scale_log2e, sp, pr);
+        launch_split_predict<64>(v, q, scale_log2e, sp, pr, s);
         if (wide) spkv_combine_append<64, true, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
         else spkv_combine_append<64, true, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, nullptr, q, scale_log2e, pr);
     }
     return hipGetLastError();
 }
-

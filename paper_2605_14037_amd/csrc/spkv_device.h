@@ -215,9 +215,14 @@ __device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T,
 // pair; every pair is then cut evenly into ceil(n / hp_per_item) items from its exact
 // device-side lengths, so that the split-K grid is balanced over the kept lengths
 // whatever their spread.  Both decode kernels derive the same partition from (L, T).
+//
+// With sp.mw > 1 (single-token decode kernels only) mw one-wave items share a workgroup and
+// merge their results there: the pair gets min(ceil(n / (mw hp_per_item)), slots) workgroups,
+// one partial slot each, and is cut evenly into min(groups * mw, n) items.
 struct PairSplit {
     int nhp;    // half-pages of the pair
     int ghp;    // of which long-term
+    int groups; // partial slots in use (= items for mw = 1)
     int items;  // work items the pair is cut into
     int L, T, Tw;
 };
@@ -229,7 +234,9 @@ __device__ __forceinline__ PairSplit pair_split(const SpkvView& v, int pair, Spk
     r.Tw = min(r.T, v.w);
     r.ghp = (r.L + kHalfTokens - 1) >> 5;
     r.nhp = r.ghp + ((r.Tw + kHalfTokens - 1) >> 5);
-    r.items = min((r.nhp + sp.hp_per_item - 1) / sp.hp_per_item, sp.slots);
+    const int per = sp.hp_per_item * sp.mw;
+    r.groups = min((r.nhp + per - 1) / per, sp.slots);
+    r.items = min(r.groups * sp.mw, r.nhp);
     return r;
 }
 

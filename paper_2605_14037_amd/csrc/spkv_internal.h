@@ -62,10 +62,13 @@ hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const u
                                    hipStream_t s);
 // Split of every (seq, head) list into work items, chosen by the host per decode call:
 // a pair with n half-pages (32 keys each) is cut evenly into min(ceil(n / hp_per_item),
-// slots) items; item j of pair p owns partial slot p * slots + j.
+// slots) items; item j of pair p owns partial slot p * slots + j.  In the single-token
+// decode kernels mw (1, 2 or 4) items share a workgroup and a slot (see pair_split); the
+// multi-token kernels always run with mw = 1.
 struct SpkvSplit {
     int32_t hp_per_item;
     int32_t slots;
+    int32_t mw;
 };
 
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
@@ -118,7 +121,7 @@ struct SpkvPrefillShape {
 SpkvPrefillShape spkv_prefill_shape(int group, int n_max);   // for chunks of at most n_max tokens
 int spkv_prefill_spans(int n_pairs, int group, int n_max);
 size_t spkv_prefill_partial_bytes(int spans, int ks, SpkvPrefillShape sh, int head_dim);
-// One-wave workgroups of the split-K kernel the current device holds at once (occupancy x
+// One-wave work items of the split-K kernel the current device holds at once (occupancy x
 // compute units); 0 if the runtime cannot tell.
 int spkv_split_resident_items(int head_dim);
 hipError_t spkv_launch_predictor(const uint16_t* x, const uint16_t* w1, const float* b1,

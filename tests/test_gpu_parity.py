@@ -149,13 +149,64 @@ def test_split_count_invariance():
         out = cache.decode_attention(q)
         st = H.check_state(cache, oracle, wl, label=f"target {target}")
         assert st.n_work_items >= wl.batch * wl.n_kv_heads
-        if target == 1:
-            assert st.n_work_items == wl.batch * wl.n_kv_heads
+        if target == 1:      # the fewest: one workgroup of four one-wave items per pair
+            assert st.n_work_items == 4 * wl.batch * wl.n_kv_heads
         H.check_output(out, ref, f"target {target}")
         outs.append(out.float())
         cache.close()
     for o in outs[1:]:
         assert (o - outs[0]).abs().max().item() <= 2e-2 * max(1.0, outs[0].abs().max().item())
+
+
+@pytest.mark.parametrize("merge", [1, 2, 4])
+@pytest.mark.parametrize("D,Hq,Hk", [(128, 8, 2), (64, 16, 1), (128, 4, 4)])
+def test_every_merge_width_in_every_single_token_entry_point(merge, D, Hq, Hk):
+    """One, two or four work items per workgroup (forced; by default the library picks per
+    call): plain decode, fused step and step with the predictor against the oracle, with lists
+    of 1 to about 60 half-pages so that some workgroups have waves without an item, and with
+    item targets from one workgroup per pair to one item per half-page."""
+    from oracle.spkv_oracle import utility_logits as oracle_logits
+    B = 3
+    wl = small_workload("merge", B, Hq, Hk, D, [1900, 40, 700], [[0.9] * Hk, [0.5] * Hk, [0.1] * Hk],
+                        seed=300 + merge + D + Hq)
+    g = torch.Generator(device="cuda").manual_seed(9)
+    dm, dh = 128, 16
+    w1 = (torch.randn(dh, dm, generator=g, device="cuda") / dm ** 0.5).to(torch.bfloat16)
+    w2 = (torch.randn(Hk, dh, generator=g, device="cuda") / dh ** 0.5).to(torch.bfloat16)
+    for target in (1, 13, 32768, 0):
+        stream = TokenStream(wl, device="cuda")
+        cache = H.make_cache(wl, pool_tokens=(2700 + 64) * Hk + 128 * B * Hk, extra_context=16)
+        oracle = H.make_oracle(wl)
+        cache.set_option(spkv.OPT_MERGE_WAVES, merge)
+        cache.set_option(spkv.OPT_ITEM_TARGET, target)
+        H.prefill(cache, oracle, stream, wl, 1024)
+        for i in range(3):
+            k, v, f, cu = stream.next_tokens([1] * B)
+            q = stream.next_query()
+            if i == 0:
+                out, lse = cache.decode_step(k, v, f, q, want_lse=True)
+            elif i == 1:
+                x = torch.randn(B, dm, generator=g, device="cuda").to(torch.bfloat16)
+                out, lse, f = cache.decode_step_predict(x, w1, None, w2, None, k, v, q, want_lse=True)
+                ref_f = oracle_logits(to_numpy_f32(x), to_numpy_f32(w1), None, to_numpy_f32(w2), None)
+                assert np.abs(f.cpu().numpy() - ref_f).max() <= 1e-4 + 1e-4 * np.abs(ref_f).max()
+            else:
+                cache.append(k, v, f, cu)
+                out, lse = cache.decode_attention(q, want_lse=True)
+            oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+            ref_out, ref_lse = oracle.decode(to_numpy_f32(q))
+            H.check_output(out, ref_out, f"merge {merge} target {target} step {i}")
+            H.check_lse(lse, ref_lse, f"merge {merge} target {target} step {i}")
+        st = H.check_state(cache, oracle, wl, label=f"merge {merge} target {target}")
+        if target == 1:
+            assert st.n_work_items <= merge * B * Hk
+        cache.close()
+    with pytest.raises(spkv.SPKVError):
+        c = H.make_cache(wl)
+        try:
+            c.set_option(spkv.OPT_MERGE_WAVES, 3)
+        finally:
+            c.close()
 
 
 @pytest.mark.parametrize("D,Hq,Hk,w", [(128, 8, 2, 64), (64, 4, 2, 16), (128, 16, 1, 128)])
@@ -282,13 +333,14 @@ def test_score_chunk_then_append_of_the_accepted_drafts(D, Hq, Hk, w):
 
 @pytest.mark.parametrize("D,Hq,Hk", [(128, 8, 2), (64, 4, 1), (128, 16, 1)])
 def test_fused_steps_with_many_items_per_pair(D, Hq, Hk):
-    """More than 32 work items per (sequence, head): the merges run in 16-wave workgroups
-    (fused step, step with the predictor, and the plain decode)."""
+    """More than 32 workgroups of four work items per (sequence, head) for the longer
+    sequence: the merges run in 16-wave workgroups (fused step, step with the predictor, and
+    the plain decode)."""
     from oracle.spkv_oracle import utility_logits as oracle_logits
     B = 2
-    wl = small_workload("wide", B, Hq, Hk, D, [5000, 900], 0.5, seed=77 + D + Hq)
+    wl = small_workload("wide", B, Hq, Hk, D, [12000, 900], 0.5, seed=77 + D + Hq)
     stream = TokenStream(wl, device="cuda")
-    cache = H.make_cache(wl, pool_tokens=(5900 + 64) * Hk + 128 * B * Hk, extra_context=16)
+    cache = H.make_cache(wl, pool_tokens=(12900 + 64) * Hk + 128 * B * Hk, extra_context=16)
     oracle = H.make_oracle(wl)
     cache.set_option(spkv.OPT_ITEM_TARGET, 32768)         # one item per half-page
     H.prefill(cache, oracle, stream, wl, 4096)
@@ -312,7 +364,7 @@ def test_fused_steps_with_many_items_per_pair(D, Hq, Hk):
         oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
         H.check_output(out, oracle.decode(to_numpy_f32(q))[0], f"step {i}")
         st = H.check_state(cache, oracle, wl, label=f"step {i}")
-    assert st.n_work_items > 32 * B * Hk
+    assert st.n_work_items > 4 * 32 * Hk
     cache.close()
 
 
