@@ -508,6 +508,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--instances", type=int, default=0, help="cache instances to rotate (0 = auto)")
     ap.add_argument("--item-target", type=int, default=0)
+    ap.add_argument("--merge-waves", type=int, default=0,
+                    help="work items per workgroup of the split-K kernel (0 = chosen per call)")
     ap.add_argument("--chunk", type=int, default=1024, help="prefill chunk (tokens per sequence)")
     ap.add_argument("--two-call", action="store_true",
                     help="time spkv_append + spkv_decode_attention (3 launches) as the step "
@@ -582,6 +584,8 @@ def main():
                            oracle_seqs=cpu_seqs, time_prefill=(r == R - 1))
         if args.item_target:
             c.set_option(spkv.OPT_ITEM_TARGET, args.item_target)
+        if args.merge_waves:
+            c.set_option(spkv.OPT_MERGE_WAVES, args.merge_waves)
         caches.append(c)
         streams.append(s)
 

@@ -240,7 +240,11 @@ SpkvSplit choose_split_mw(const spkv_cache* c, int one_round_items, int64_t slot
 // drawn per pair): one sequence of 128k tokens 26 -> 22 us, 4 of 128k 39 -> 38, 3 of 64k
 // 47 -> 44, equal lists of 1 to 4 sequences 1 to 2.5 us less, two of twelve shapes 1.5 us
 // more; but 16 sequences of 32k (128 pairs of about 23 items) 78 -> 92 at the same item
-// length, and 64 sequences of 1k-64k 459 -> 540.  Hence the limit of kMergePairs pairs.
+// length, and 64 sequences of 1k-64k 459 -> 540: workgroup ids go round-robin to the 8 XCDs,
+// pair p's run starts at id p * slots, and when the lengths repeat from sequence to sequence
+// (keep rates that depend on the head) every sequence adds the same uneven pattern -- in
+// units of whole workgroups -- until some XCD is handed more waves than it holds and runs
+// the surplus in a second round.  Hence the limit of kMergePairs pairs.
 constexpr int kMergePairs = 32;
 SpkvSplit choose_split(const spkv_cache* c, int one_round_items, int64_t slots_total_cap) {
     int64_t items_one = 0;
