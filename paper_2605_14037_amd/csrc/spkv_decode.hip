@@ -185,11 +185,12 @@ __device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint1
     }
 }
 
-// Merge workgroups of 16 waves instead of 4: when pairs are cut into more than 32 items and
-// the merge launch has at most one workgroup per compute unit (few long sequences; measured
-// on 4 sequences of 128k: 1.1 us less per step; with 512 merge workgroups, 3 us more).
+// Merge workgroups of 16 waves instead of 4: when pairs have more than 64 partials and the
+// merge launch has at most one workgroup per compute unit (few long sequences; measured on
+// 4 sequences of 128k with about 150 partials per pair: 1.1 us less per step; with 39 per
+// pair, 0.5 us more; with 512 merge workgroups, 3 us more).
 static bool wide_merge(const SpkvView& v, const SpkvSplit& sp) {
-    return sp.slots > 32 && v.n_pairs * v.G <= 256;
+    return sp.slots > 64 && v.n_pairs * v.G <= 256;
 }
 
 template <int D, bool FUSED, int MW>

@@ -333,9 +333,9 @@ def test_score_chunk_then_append_of_the_accepted_drafts(D, Hq, Hk, w):
 
 @pytest.mark.parametrize("D,Hq,Hk", [(128, 8, 2), (64, 4, 1), (128, 16, 1)])
 def test_fused_steps_with_many_items_per_pair(D, Hq, Hk):
-    """More than 32 workgroups of four work items per (sequence, head) for the longer
-    sequence: the merges run in 16-wave workgroups (fused step, step with the predictor, and
-    the plain decode)."""
+    """More than 64 partials per (sequence, head) for the longer sequence (one work item per
+    half-page and per workgroup): the merges run in 16-wave workgroups (fused step, step with
+    the predictor, and the plain decode)."""
     from oracle.spkv_oracle import utility_logits as oracle_logits
     B = 2
     wl = small_workload("wide", B, Hq, Hk, D, [12000, 900], 0.5, seed=77 + D + Hq)
@@ -343,6 +343,7 @@ def test_fused_steps_with_many_items_per_pair(D, Hq, Hk):
     cache = H.make_cache(wl, pool_tokens=(12900 + 64) * Hk + 128 * B * Hk, extra_context=16)
     oracle = H.make_oracle(wl)
     cache.set_option(spkv.OPT_ITEM_TARGET, 32768)         # one item per half-page
+    cache.set_option(spkv.OPT_MERGE_WAVES, 1)
     H.prefill(cache, oracle, stream, wl, 4096)
     g = torch.Generator(device="cuda").manual_seed(3)
     dm, dh = 256, 32
@@ -364,7 +365,7 @@ def test_fused_steps_with_many_items_per_pair(D, Hq, Hk):
         oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
         H.check_output(out, oracle.decode(to_numpy_f32(q))[0], f"step {i}")
         st = H.check_state(cache, oracle, wl, label=f"step {i}")
-    assert st.n_work_items > 4 * 32 * Hk
+    assert st.n_work_items > 64 * Hk
     cache.close()
 
 
