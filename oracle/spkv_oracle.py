@@ -38,8 +38,11 @@ Pins (tests/test_oracle_pins.py): hand-derived rational-weight examples
 torch.nn.functional.scaled_dot_product_attention in fp64 under the explicit
 mask, tau = -inf == dense causal attention, tau = +inf == sliding-window
 attention, closed forms (identical keys -> mean of V, constant V, one dominant
-key), the count invariant, and mutation checks showing that each planted
-mistake is caught by at least one pin.
+key), the count invariant (both densities of Eq. 8 included), a literal
+step-by-step simulation of the cache process of the appendix (window list, kept
+list; threshold changes, prunes, sequence release and refill, sinks) that pins
+set_tau, prune, release_sequence and n_sink, and mutation checks showing that
+each planted mistake is caught by at least one pin.
 """
 
 from __future__ import annotations

@@ -122,6 +122,17 @@ def pin_brute_force(cls):
 
 
 # ------------------------- pin 3: library routine under the paper's mask (SDPA)
+def _availability(T, w, gate=None):
+    """[T, T] boolean matrix of Eq. 3-4 from the distance d = t - s of every (query, key):
+    a key is visible iff it is not in the future (d >= 0) and is either inside the window
+    (d < w) or gated on.  gate: None (window only) or bool [T] per key."""
+    d = np.subtract.outer(np.arange(T), np.arange(T))
+    near = (d >= 0) & (d < w)
+    if gate is None:
+        return near
+    return near | ((d >= 0) & np.asarray(gate, bool)[None, :])
+
+
 def _sdpa_last_row(q_last, k, v, gate, w, scale, Hq, Hkv, mode):
     """Full T x T masked attention with torch's fp64 SDPA for one sequence;
     returns the last query row.  mode: 'gated' (window OR gate, causal),
@@ -136,15 +147,11 @@ def _sdpa_last_row(q_last, k, v, gate, w, scale, Hq, Hkv, mode):
     if mode == "causal":
         o = F.scaled_dot_product_attention(qt, kt, vt, is_causal=True, scale=scale)
     else:
-        qi = torch.arange(T)[:, None]
-        ki = torch.arange(T)[None, :]
-        causal = ki <= qi
-        in_window = causal & ((qi - ki) < w)
         if mode == "window":
-            mask = in_window[None, None].expand(1, Hq, T, T)
+            mask = torch.from_numpy(_availability(T, w))[None, None].expand(1, Hq, T, T)
         else:
-            gt = torch.from_numpy(gate).T.repeat_interleave(G, dim=0)   # [Hq, T] bool
-            mask = (in_window[None] | (causal[None] & gt[:, None, :]))[None]
+            per_head = np.stack([_availability(T, w, gate[:, j // G]) for j in range(Hq)])
+            mask = torch.from_numpy(per_head)[None]
         o = F.scaled_dot_product_attention(qt, kt, vt, attn_mask=mask, scale=scale)
     return o[0, :, T - 1, :].numpy()
 
@@ -251,6 +258,8 @@ def pin_count_invariant(cls):
         assert st["evicted_tokens"] == sum(max(0, n - w) for n in lens) * Hkv
         assert st["window_tokens"] == sum(min(n, w) for n in lens) * Hkv
         assert abs(st["density_all"] - gate_on / (sum(lens) * Hkv)) < 1e-15     # Eq. 8
+        # the density the text reports: long-term entries over pairs that have left the window
+        assert st["density_evicted"] == float(Fraction(int(kl.sum()), st["evicted_tokens"]))
         assert st["kept_kv_bytes"] == (st["kept_tokens"] + st["window_tokens"]) * 4 * D
         assert st["dense_kv_bytes"] == sum(lens) * Hkv * 4 * D
 
@@ -358,8 +367,15 @@ class _ThresholdSignFlipped(SPKVOracle):         # theta with the wrong sign
         self._theta_hist = [[(0, self.theta)] for _ in range(self.B)]
 
 
+class _DensityOverAllTokens(SPKVOracle):         # Eq. 8's reported density with the wrong denominator
+    def stats(self):
+        st = super().stats()
+        st["density_evicted"] = st["kept_tokens"] / max(1, st["total_tokens"] * self.Hkv)
+        return st
+
+
 MUTANTS = [_WindowOffByOne, _StrictGate, _NoScale, _KeptOffByOne, _GateIgnored,
-           _WrongGroup, _TransposedPV, _ThresholdSignFlipped]
+           _WrongGroup, _TransposedPV, _ThresholdSignFlipped, _DensityOverAllTokens]
 
 
 @pytest.mark.parametrize("mutant", MUTANTS, ids=lambda m: m.__name__)
@@ -403,19 +419,15 @@ def test_utility_logits_against_torch_modules_and_closed_forms():
 # ------------------------------------------------ multi-token step (chunk of queries)
 def _sdpa_rows(q_rows, k, v, gate, w, scale, Hq, Hkv, first_row):
     """Rows first_row.. of the full masked attention of one sequence by torch's fp64 SDPA
-    (mask as in the paper's listing: window -> 0, causal non-window -> gate, future -> -inf)."""
+    under the availability mask of Eq. 3-4 (window or gate, never the future)."""
     T, D = k.shape[0], k.shape[2]
     G = Hq // Hkv
     kt = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
     vt = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
     qt = torch.zeros(1, Hq, T, D, dtype=torch.float64)
     qt[0, :, first_row:, :] = torch.from_numpy(q_rows).permute(1, 0, 2)
-    qi = torch.arange(T)[:, None]
-    ki = torch.arange(T)[None, :]
-    causal = ki <= qi
-    in_window = causal & ((qi - ki) < w)
-    gt = torch.from_numpy(gate).T.repeat_interleave(G, dim=0)
-    mask = (in_window[None] | (causal[None] & gt[:, None, :]))[None]
+    per_head = np.stack([_availability(T, w, gate[:, j // G]) for j in range(Hq)])
+    mask = torch.from_numpy(per_head)[None]
     o = F.scaled_dot_product_attention(qt, kt, vt, attn_mask=mask, scale=scale)
     return o[0, :, first_row:, :].permute(1, 0, 2).numpy()
 
@@ -457,25 +469,35 @@ def test_decode_chunk_matches_sdpa_rows_and_single_steps():
                 np.testing.assert_allclose(l1[b], lse[qoff[b] + i], rtol=1e-12, atol=1e-13)
 
 
-def test_live_threshold_change_matches_a_step_by_step_cache_simulation():
-    """Pin for set_tau and prune: the appendix describes the cache as a process -- when the window is
-    full, the pair leaving it is kept iff its gate is on (here: with the threshold in force
-    at that moment), otherwise dropped; a prune drops from the kept list what fails the threshold
-    of the moment.  A literal simulation of that process (a window list,
-    a kept list, one token at a time, plain Python) must give the oracle's kept lists, its
-    gate-on count and, with explicit softmax loops over kept + window, its decode output."""
-    rng = np.random.default_rng(91)
+def _cache_process(cls, n_sink=0, release=None, n_steps=34, seed=91):
+    """Pin for set_tau, prune, release_sequence and the sinks: the appendix describes the cache
+    as a process -- when the window is full, the pair leaving it is kept iff its gate is on
+    (here: with the threshold in force at that moment, or when it is one of the first n_sink
+    positions of its sequence), otherwise dropped; a prune drops from the kept list what fails
+    the threshold of the moment (never a sink); a release empties the slot.  A literal
+    simulation of that process (a window list, a kept list, one token at a time, plain Python)
+    must give the oracle's kept lists, its counts, both densities of Eq. 8 and, with explicit
+    softmax loops over kept + window, its decode output.  release: {step: sequence}."""
+    rng = np.random.default_rng(seed)
+    release = release or {}
     B, Hq, Hkv, D, w = 2, 4, 2, 4, 3
-    taus = {0: 0.5, 7: 0.8, 12: 0.2, 13: 0.65, 20: 0.5}      # step -> new tau
-    prunes = {8, 14, 15, 21}                                  # steps that begin with a prune
-    o = SPKVOracle(B, Hq, Hkv, D, window=w, tau=taus[0])
+    taus = {0: 0.5, 7: 0.8, 12: 0.2, 13: 0.65, 20: 0.5, 27: 0.75}    # step -> new tau
+    prunes = {8, 14, 15, 21, 28}                                      # steps that begin with a prune
+    o = cls(B, Hq, Hkv, D, window=w, tau=taus[0], n_sink=n_sink)
     window = [[[] for _ in range(Hkv)] for _ in range(B)]    # (pos, k, v, f)
     kept = [[[] for _ in range(Hkv)] for _ in range(B)]
     n_tok = [0] * B
-    gate_on = 0
+    gate_on = [0] * B
     theta = threshold_logit(taus[0])
     scale = 1.0 / math.sqrt(D)
-    for step in range(26):
+    for step in range(n_steps):
+        if step in release:                                   # the request in this slot ends
+            b = release[step]
+            o.release_sequence(b)
+            window[b] = [[] for _ in range(Hkv)]
+            kept[b] = [[] for _ in range(Hkv)]
+            n_tok[b] = 0
+            gate_on[b] = 0
         if step in taus and step > 0:
             o.set_tau(taus[step])
             theta = threshold_logit(taus[step])
@@ -483,7 +505,7 @@ def test_live_threshold_change_matches_a_step_by_step_cache_simulation():
             o.prune()
             for b in range(B):
                 for h in range(Hkv):
-                    kept[b][h] = [e for e in kept[b][h] if e[3] >= theta]
+                    kept[b][h] = [e for e in kept[b][h] if e[3] >= theta or e[0] < n_sink]
         counts = [1, 1] if step % 5 else [2, 0]               # sequence 1 lags behind
         total = sum(counts)
         k = rng.standard_normal((total, Hkv, D)).astype(np.float32)
@@ -496,15 +518,24 @@ def test_live_threshold_change_matches_a_step_by_step_cache_simulation():
                 for h in range(Hkv):
                     if len(window[b][h]) == w:                # window full: one pair leaves
                         old = window[b][h].pop(0)
-                        if old[3] >= theta:
+                        if old[3] >= theta or old[0] < n_sink:
                             kept[b][h].append(old)
                     window[b][h].append((n_tok[b], k[r, h], v[r, h], f[r, h]))
-                    gate_on += int(f[r, h] >= theta)
+                    gate_on[b] += int(f[r, h] >= theta or n_tok[b] < n_sink)
                 n_tok[b] += 1
         for b in range(B):
+            assert o.seq_len(b) == n_tok[b]
             for h in range(Hkv):
                 assert o.kept_positions(b, h).tolist() == [e[0] for e in kept[b][h]], (step, b, h)
-        assert o.stats()["gate_on_tokens"] == gate_on
+        st = o.stats()
+        n_kept = sum(len(kept[b][h]) for b in range(B) for h in range(Hkv))
+        n_left = sum(max(0, n - w) for n in n_tok) * Hkv
+        assert st["gate_on_tokens"] == sum(gate_on)
+        assert st["kept_tokens"] == n_kept and st["evicted_tokens"] == n_left
+        assert st["total_tokens"] == sum(n_tok)
+        # Eq. 8 as the text reports it (kept over what has left the window) and literally
+        assert st["density_evicted"] == (float(Fraction(n_kept, n_left)) if n_left else 0.0)
+        assert st["density_all"] == float(Fraction(sum(gate_on), sum(n_tok) * Hkv))
         if all(n_tok):
             q = rng.standard_normal((B, Hq, D)).astype(np.float32)
             out, lse = o.decode(q)
@@ -522,6 +553,92 @@ def test_live_threshold_change_matches_a_step_by_step_cache_simulation():
                             ref = math.fsum(a * float(e[2][d]) for a, e in zip(wt, entries)) / z
                             assert abs(out[b, j, d] - ref) < 1e-12
                         assert abs(lse[b, j] - (mx + math.log(z))) < 1e-12
+
+
+def pin_cache_process(cls):
+    _cache_process(cls)
+
+
+def pin_cache_process_with_release(cls):
+    # sequence 0 ends after thresholds 0.8 / 0.2 / 0.65 and three prunes have gone by; its
+    # successor in the slot lives through a lower threshold, a prune, a higher one, a prune
+    _cache_process(cls, release={16: 0, 24: 1})
+
+
+def pin_cache_process_with_sinks(cls):
+    # the sinks' logits are ordinary draws: several fail the thresholds of the prunes
+    _cache_process(cls, n_sink=2)
+    _cache_process(cls, n_sink=2, release={16: 0}, seed=92)
+
+
+PROCESS_PINS = [pin_cache_process, pin_cache_process_with_release, pin_cache_process_with_sinks]
+
+
+@pytest.mark.parametrize("pin", PROCESS_PINS, ids=lambda p: p.__name__)
+def test_process_pin(pin):
+    pin(SPKVOracle)
+
+
+# Mistakes in the parts only the process pins reach.
+class _ReleaseKeepsThresholdHistory(SPKVOracle):   # a released slot remembers old thresholds
+    def release_sequence(self, b):
+        hist = self._theta_hist[b]
+        super().release_sequence(b)
+        self._theta_hist[b] = hist
+
+
+class _ReleaseKeepsPrunes(SPKVOracle):             # ... or old prunes
+    def release_sequence(self, b):
+        pr = self._prunes[b]
+        super().release_sequence(b)
+        self._prunes[b] = pr
+
+
+class _PruneDropsSinks(SPKVOracle):                # a prune judges the sinks by their logits
+    def gate(self, b, h):
+        s = np.arange(self.seq_len(b))
+        theta = self._theta_when_stored(b, s + self.w)
+        theta[s + self.w >= self.seq_len(b)] = self.theta
+        z = (self._f(b)[:, h] >= theta) | (s < self.n_sink)
+        for n_evicted, theta_p in self._prunes[b]:
+            z[:n_evicted] &= self._f(b)[:n_evicted, h] >= theta_p
+        return z
+
+
+class _WrongDensityDenominator(SPKVOracle):        # kept / all tokens instead of kept / evicted
+    def stats(self):
+        st = super().stats()
+        tot = st["total_tokens"] * self.Hkv
+        st["density_evicted"] = st["kept_tokens"] / tot if tot else 0.0
+        return st
+
+
+class _PruneIgnored(SPKVOracle):                   # prune does nothing
+    def prune(self):
+        pass
+
+
+class _SetTauRewritesHistory(SPKVOracle):          # a new tau re-judges pairs that already left
+    def set_tau(self, tau):
+        super().set_tau(tau)
+        self._theta_hist = [[(0, self.theta)] for _ in range(self.B)]
+
+
+PROCESS_MUTANTS = {
+    _ReleaseKeepsThresholdHistory: "pin_cache_process_with_release",
+    _ReleaseKeepsPrunes: "pin_cache_process_with_release",
+    _PruneDropsSinks: "pin_cache_process_with_sinks",
+    _WrongDensityDenominator: "pin_cache_process",
+    _PruneIgnored: "pin_cache_process",
+    _SetTauRewritesHistory: "pin_cache_process",
+}
+
+
+@pytest.mark.parametrize("mutant", list(PROCESS_MUTANTS), ids=lambda m: m.__name__)
+def test_planted_process_mistake_is_caught_by_its_named_pin(mutant):
+    by_name = {p.__name__: p for p in PROCESS_PINS}
+    with pytest.raises(AssertionError):
+        by_name[PROCESS_MUTANTS[mutant]](mutant)
 
 
 def test_sinks_pinned_to_sdpa_with_the_sink_columns_unmasked():
@@ -577,15 +694,16 @@ def test_soft_gated_attention_pins():
             T = hi - lo
             if T == 0:
                 continue
-            qi = torch.arange(T).unsqueeze(1)
-            ki = torch.arange(T).unsqueeze(0)
-            causal = ki <= qi
-            in_window = causal & ((qi - ki) < window)
+            dist = np.subtract.outer(np.arange(T), np.arange(T))           # t - s
             for j in range(Hq):
                 h = j // (Hq // Hkv)
-                u = torch.sigmoid(torch.from_numpy(fl[lo:hi, h]).double())
-                gate = torch.log(u + eps)
-                mask = torch.where(in_window, 0.0, torch.where(causal, gate[None, :], float("-inf")))
+                # Eq. 6 as an additive bias: nothing inside the window, log u_s behind it,
+                # -inf on the future
+                with np.errstate(over="ignore", divide="ignore"):      # f = -1e4: u = 0, log u = -inf
+                    u = 1.0 / (1.0 + np.exp(-fl[lo:hi, h].astype(np.float64)))
+                    bias = np.where(dist >= window, np.log(u + eps)[None, :], 0.0)
+                bias[dist < 0] = -np.inf
+                mask = torch.from_numpy(bias)
                 o = torch.nn.functional.scaled_dot_product_attention(
                     torch.from_numpy(q[lo:hi, j]).double()[None, None],
                     torch.from_numpy(k[lo:hi, h]).double()[None, None],
