@@ -85,6 +85,11 @@ typedef struct spkv_stats {
     int64_t arena_bytes;
     int32_t device_error;      /* nonzero if a kernel ever flagged an inconsistency         */
     int32_t n_work_items;      /* split-K work items the next decode call would launch      */
+    int32_t n_work_items_last_call; /* the same lists cut by the partition the most recent
+                                  decode call used (it is chosen from the host's upper bound
+                                  of the lengths; far fewer items than n_work_items would mean
+                                  that bound has drifted)                                   */
+    int32_t reserved_;
 } spkv_stats_t;
 
 /* Options for spkv_cache_set_option. */
@@ -108,7 +113,8 @@ typedef struct spkv_stats {
                                       of (sequence, KV head) pairs and their lengths           */
 
 /* Bytes of device arena a cache with this configuration needs (0 if cfg is invalid).
- * Host-only; touches no device.  Capacity rule: the long-term cache can hold
+ * Host-only; touches no device.  Capacity rule (appendix "Inference Kernels": pages are
+ * given out from a pool with headroom): the long-term cache can hold
  * max_total_kept_tokens pairs in total plus one partly filled page per (seq, head). */
 size_t spkv_cache_required_bytes(const spkv_config_t* cfg);
 
@@ -338,7 +344,9 @@ int spkv_cache_advance(spkv_cache_t* cache, int64_t n_steps);
  * [batch * n_kv_heads], or NULL) receives the long-term length of every (seq, head). */
 int spkv_cache_stats(spkv_cache_t* cache, spkv_stats_t* stats, int32_t* kept_len, void* stream);
 
-/* Positions held by the long-term cache of (sequence b, KV head h), ascending, into
+/* The long-term region of one head (appendix "Inference Kernels": the pairs that left the
+ * window with their gate on, Eq. 2-4), as positions:
+ * Positions held by the long-term cache of (sequence b, KV head h), ascending, into
  * pos (host int32 [cap]); *n receives the count (the call fails with SPKV_E_INVAL if
  * cap is too small, after setting *n).  Synchronises `stream`. */
 int spkv_cache_kept_positions(spkv_cache_t* cache, int32_t b, int32_t h, int32_t* pos,
@@ -383,6 +391,24 @@ int64_t spkv_debug_layout_offset(int32_t head_dim, int32_t is_v, int32_t kidx, i
  * aligned, not overlapping) by a simple grid-stride kernel: a kernel of exactly known HBM
  * traffic (bytes read + bytes written) against which profiler byte counters are scaled. */
 int spkv_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/* Plain streaming read of exactly known traffic with the launch shape and access pattern of
+ * the split-K decode kernel (one-wave workgroups, 16 KB chunks read as sixteen non-temporal
+ * 1 KB wave-wide loads, 1 KB stored per workgroup at the end) and no arithmetic: the read
+ * ceiling of this memory system for such a launch, against which the decode kernel's
+ * bandwidth is put (the measurement protocol asks for the fraction of a measured streaming
+ * read ceiling beside the fraction of the vendor peak).
+ *   src           device, 16-byte aligned, region_bytes bytes, seen as runs of run_bytes
+ *                 (a multiple of 16384; 32768 = one cache page: pages of a list are scattered
+ *                 over the pool, bytes inside a page are contiguous)
+ *   first_run, n_runs, stride   the launch reads the runs ((first_run + i) * stride) mod
+ *                 (region_bytes / run_bytes), i = 0 .. n_runs - 1; a stride coprime to the
+ *                 run count makes successive launches read distinct scattered runs
+ *   n_workgroups  one-wave workgroups; each reads an equal share of the launch's chunks
+ *   sink          device, n_workgroups * 1024 bytes, written
+ * SPKV_E_INVAL for arguments out of range (nothing is launched). */
+int spkv_debug_read(const void* src, size_t region_bytes, int32_t run_bytes, int64_t first_run,
+                    int64_t n_runs, int64_t stride, int32_t n_workgroups, void* sink, void* stream);
 
 /* Static text for an error code. */
 const char* spkv_strerror(int code);

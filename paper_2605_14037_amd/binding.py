@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = [
     "spkv_prefill_workspace_bytes", "spkv_prefill_attention",
     "spkv_soft_gated_workspace_bytes", "spkv_soft_gated_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_safe_steps", "spkv_cache_advance", "spkv_cache_stats", "spkv_cache_kept_positions",
     "spkv_cache_threshold_logit", "spkv_cache_set_tau", "spkv_cache_prune", "spkv_cache_set_option", "spkv_cache_read_kernel_timing",
-    "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_strerror",
+    "spkv_debug_layout_offset", "spkv_debug_copy", "spkv_debug_read", "spkv_strerror",
 ]
 
 
@@ -44,7 +44,8 @@ class SPKVStats(C.Structure):
                 ("density_all", C.c_double), ("kept_kv_bytes", C.c_int64),
                 ("dense_kv_bytes", C.c_int64), ("pool_pages_used", C.c_int64),
                 ("pool_pages_total", C.c_int64), ("arena_bytes", C.c_int64),
-                ("device_error", C.c_int32), ("n_work_items", C.c_int32)]
+                ("device_error", C.c_int32), ("n_work_items", C.c_int32),
+                ("n_work_items_last_call", C.c_int32), ("reserved_", C.c_int32)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -132,6 +133,8 @@ def load_library():
     lib.spkv_debug_layout_offset.argtypes = [i32, i32, i32, i32]
     lib.spkv_debug_copy.restype = C.c_int
     lib.spkv_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.spkv_debug_read.restype = C.c_int
+    lib.spkv_debug_read.argtypes = [vp, C.c_size_t, i32, i64, i64, i64, i32, vp, vp]
     lib.spkv_strerror.restype = C.c_char_p
     lib.spkv_strerror.argtypes = [C.c_int]
     _LIB = lib
@@ -158,6 +161,17 @@ def debug_copy(dst: torch.Tensor, src: torch.Tensor):
         raise ValueError("debug_copy: need contiguous cuda tensors of equal byte size")
     _check(load_library().spkv_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
                                           nbytes, _stream()), "spkv_debug_copy")
+
+
+def debug_read(src: torch.Tensor, run_bytes, first_run, n_runs, stride, n_workgroups, sink):
+    """Plain streaming read with the decode kernel's launch shape (spkv_debug_read)."""
+    if not (src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.is_contiguous()
+            and sink.numel() * sink.element_size() >= n_workgroups * 1024):
+        raise ValueError("debug_read: need contiguous cuda tensors, sink of n_workgroups KB")
+    _check(load_library().spkv_debug_read(C.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                                          int(run_bytes), int(first_run), int(n_runs), int(stride),
+                                          int(n_workgroups), C.c_void_p(sink.data_ptr()), _stream()),
+           "spkv_debug_read")
 
 
 def soft_gated_attention(q, k, v, util_logits, cu_seqlens, window=128, sm_scale=0.0, out=None,

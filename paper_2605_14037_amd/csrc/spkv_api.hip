@@ -7,6 +7,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -57,7 +58,11 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.n_seg_cap = (int)(((int64_t)c->max_context + kSegTokens - 1) / kSegTokens) + 1;
     // Work-item slots: 128 per pair leaves room for a pair 40 times longer than the mean at
     // the default item count; at least enough for the largest item target on one pair.
+    // The multi-token kernels store 16, 32 or 64 columns per slot instead of G: two slots of
+    // 64 columns per pair must fit whatever the shape (only caches of thousands of pairs
+    // with small groups reach this term).
     k.max_items = std::max(kMaxItemTarget + k.n_pairs, std::min(k.n_pairs * 128, 1 << 17));
+    k.max_items = std::max(k.max_items, (k.n_pairs * 128 + k.G - 1) / k.G);
     const size_t page_bytes = (size_t)spkv_page_elems(c->head_dim) * 2;
     size_t off = 0;
     auto take = [&off](size_t bytes) {
@@ -111,6 +116,16 @@ struct spkv_cache {
     std::vector<int32_t> L_ub;    // per (seq, head): upper bound of the long-term length
     int64_t pages_ub;             // sum of pages_for(L_ub): upper bound of pool pages in use
     bool bound_is_loose;          // a bulk append grew L_ub by far more than the truth
+    // Single-token steps add one to L_ub per pair and step although only the keep rate's share
+    // is kept, so the bound drifts away from the lengths and the work partition derived from
+    // it would come out too coarse.  `slack` counts what was added since the bound was last
+    // exact; past 1/16 of the bound the lengths are copied to pinned host memory behind the
+    // step just issued (no wait) and adopted by the first later call that finds the copy done.
+    int64_t slack;
+    int32_t* snap_host;           // pinned, [n_pairs]; null if the allocation failed
+    hipEvent_t snap_event;
+    bool snap_pending;
+    std::vector<int32_t> snap_ev; // per sequence: pairs pushed out of the window since the copy
     int item_target;
     int merge_waves;              // SPKV_OPT_MERGE_WAVES (0 = per call)
     int n_sink;                   // always-kept first positions (SPKV_OPT_SINK_TOKENS)
@@ -180,8 +195,54 @@ int refresh_bound(spkv_cache* c, hipStream_t s, int32_t* kept_len_out) {
     }
     c->pages_ub = pages;
     c->bound_is_loose = false;
+    c->slack = 0;
+    c->snap_pending = false;      // a copy still on its way is older than what was just read
     if (kept_len_out != nullptr) std::memcpy(kept_len_out, len.data(), len.size() * 4);
     return SPKV_OK;
+}
+
+// Keeps the host's bound of the lengths close to the truth during long runs of single-token
+// steps without ever waiting: adopts a finished copy of the device lengths (plus whatever has
+// left the windows since it was enqueued: still an upper bound), and enqueues a new copy when
+// the slack has grown past 1/16 of the bound.  Never while the stream is being captured (the
+// copy would become a graph node and the host would read it at the wrong time).
+void tighten_bound(spkv_cache* c, hipStream_t s) {
+    if (c->snap_host == nullptr) return;
+    const int n_pairs = c->carve.n_pairs, Hkv = c->cfg.n_kv_heads;
+    if (c->snap_pending) {
+        const hipError_t q = hipEventQuery(c->snap_event);
+        if (q == hipSuccess) {
+            int64_t pages = 0, slack = 0;
+            for (int p = 0; p < n_pairs; ++p) {
+                const int64_t L = (int64_t)c->snap_host[p] + c->snap_ev[p / Hkv];
+                if (L < c->L_ub[p]) c->L_ub[p] = (int32_t)L;
+                pages += pages_for(c->L_ub[p]);
+                slack += c->snap_ev[p / Hkv];
+            }
+            c->pages_ub = pages;
+            c->slack = slack;
+            c->snap_pending = false;
+        } else {
+            (void)hipGetLastError();      // "not ready" is not an error of the next launch
+            return;
+        }
+    }
+    int64_t sum = 0;
+    for (int p = 0; p < n_pairs; ++p) sum += c->L_ub[p] + std::min(c->T[p / Hkv], c->cfg.window);
+    if (c->slack * 16 <= sum) return;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        return;
+    }
+    if (hipMemcpyAsync(c->snap_host, c->view.kept_len, (size_t)n_pairs * 4, hipMemcpyDeviceToHost, s) !=
+            hipSuccess ||
+        hipEventRecord(c->snap_event, s) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+    }
+    std::fill(c->snap_ev.begin(), c->snap_ev.end(), 0);
+    c->snap_pending = true;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -307,6 +368,8 @@ void commit_lengths(spkv_cache* c, const int32_t* cu) {
             c->pages_ub += pages_for(L + ev) - pages_for(L);
             L += (int32_t)ev;
         }
+        c->slack += ev * Hkv;
+        c->snap_ev[b] += (int32_t)ev;
     }
 }
 
@@ -339,6 +402,11 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->L_ub.assign(k.n_pairs, 0);
     c->pages_ub = 0;
     c->bound_is_loose = false;
+    c->slack = 0;
+    c->snap_host = nullptr;
+    c->snap_event = nullptr;
+    c->snap_pending = false;
+    c->snap_ev.assign(cfg->batch, 0);
     c->item_target = 0;
     c->merge_waves = 0;
     c->n_sink = 0;
@@ -358,6 +426,17 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
         hipSuccess) {
         delete c;
         return SPKV_E_HIP;
+    }
+    // pinned host buffer for the length snapshots (see tighten_bound); the cache works
+    // without it, with a coarser partition on very long generations
+    void* pinned = nullptr;
+    if (hipHostMalloc(&pinned, (size_t)k.n_pairs * 4, hipHostMallocDefault) == hipSuccess &&
+        hipEventCreateWithFlags(&c->snap_event, hipEventDisableTiming) == hipSuccess) {
+        c->snap_host = static_cast<int32_t*>(pinned);
+    } else {
+        if (pinned != nullptr) (void)hipHostFree(pinned);
+        c->snap_event = nullptr;
+        (void)hipGetLastError();
     }
     *out = c;
     return SPKV_OK;
@@ -421,6 +500,11 @@ int spkv_cache_grow(spkv_cache_t* c, const spkv_config_t* cfg, void* dev_arena, 
 int spkv_cache_destroy(spkv_cache_t* c) {
     if (c == nullptr) return SPKV_E_INVAL;
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+    if (c->snap_host != nullptr) {
+        (void)hipEventSynchronize(c->snap_event);      // a copy may still be writing the buffer
+        (void)hipEventDestroy(c->snap_event);
+        (void)hipHostFree(c->snap_host);
+    }
     delete c;
     return SPKV_OK;
 }
@@ -432,6 +516,9 @@ int spkv_cache_reset(spkv_cache_t* c, void* stream) {
     std::fill(c->T.begin(), c->T.end(), 0);
     std::fill(c->L_ub.begin(), c->L_ub.end(), 0);
     c->pages_ub = 0;
+    c->bound_is_loose = false;
+    c->slack = 0;
+    c->snap_pending = false;
     return SPKV_OK;
 }
 
@@ -480,6 +567,7 @@ int spkv_decode_step(spkv_cache_t* c, const void* k, const void* v, const float*
         const int rc = refresh_bound(c, s, nullptr);
         if (rc != SPKV_OK) return rc;
     }
+    tighten_bound(c, s);
     const int rc = reserve_capacity(c, nullptr, s);
     if (rc != SPKV_OK) return rc;
     c->split = choose_split(c);          // partition of the state BEFORE the append
@@ -519,6 +607,7 @@ int spkv_decode_step_predict(spkv_cache_t* c, const void* hidden, const void* w1
         const int rc = refresh_bound(c, s, nullptr);
         if (rc != SPKV_OK) return rc;
     }
+    tighten_bound(c, s);
     const int rc = reserve_capacity(c, nullptr, s);
     if (rc != SPKV_OK) return rc;
     // the predictor's workgroups share the launch: leave them room in the resident round
@@ -556,6 +645,7 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
         const int rc = refresh_bound(c, s, nullptr);
         if (rc != SPKV_OK) return rc;
     }
+    tighten_bound(c, s);
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (c->timing && c->n_timed < kMaxTimedLaunches) {
         if ((size_t)(2 * c->n_timed + 2) > c->events.size()) {
@@ -641,6 +731,11 @@ int chunk_call(spkv_cache_t* c, const void* k, const void* v, const float* util_
     // about 1 800 items (two rounds of the widest kernel) measured 12-15 % faster.
     c->split = choose_split_mw(c, std::max(c->chunk_round_items[gi], groups > 1 ? c->one_round_items * 5 / 8 : 0),
                                slot_cap, 1);
+
+    // every slot the launch may write must lie inside the partial buffers (they are sized
+    // for this at create; checked again here because an overrun would be a wild device write)
+    if ((int64_t)c->carve.n_pairs * c->split.slots * groups * 16 > (int64_t)c->carve.max_items * G)
+        return SPKV_E_CAPACITY;
 
     SpkvCu cu;
     std::memcpy(cu.v, cu_seqlens, (size_t)(B + 1) * 4);
@@ -893,6 +988,8 @@ int spkv_cache_advance(spkv_cache_t* c, int64_t n_steps) {
             c->pages_ub += pages_for((int64_t)L + ev) - pages_for(L);
             L += (int32_t)ev;
         }
+        c->slack += ev * Hkv;
+        c->snap_ev[b] += (int32_t)ev;
     }
     return SPKV_OK;
 }
@@ -938,6 +1035,17 @@ int spkv_cache_stats(spkv_cache_t* c, spkv_stats_t* st, int32_t* kept_len, void*
         n_items += std::min<int64_t>(std::min<int64_t>((hp + per - 1) / per, sp.slots) * sp.mw, hp);
     }
     st->n_work_items = (int32_t)n_items;
+    {   // the same count under the partition the most recent decode call actually used
+        const SpkvSplit lp = c->split;
+        int64_t n_last = 0;
+        for (int p = 0; p < n_pairs; ++p) {
+            const int Tw = std::min(c->T[p / Hkv], w);
+            const int64_t hp = (len[p] + kHalfTokens - 1) / kHalfTokens + (Tw + kHalfTokens - 1) / kHalfTokens;
+            const int64_t per = (int64_t)lp.hp_per_item * lp.mw;
+            n_last += std::min<int64_t>(std::min<int64_t>((hp + per - 1) / per, lp.slots) * lp.mw, hp);
+        }
+        st->n_work_items_last_call = (int32_t)n_last;
+    }
     if (kept_len != nullptr) std::memcpy(kept_len, len.data(), (size_t)n_pairs * 4);
     return err ? SPKV_E_DEVICE : SPKV_OK;
 }
@@ -1076,6 +1184,21 @@ int spkv_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
     if (dst == nullptr || src == nullptr || (bytes & 15u) != 0 || !aligned16(dst) || !aligned16(src))
         return SPKV_E_INVAL;
     return spkv_launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? SPKV_OK
+               : SPKV_E_HIP;
+}
+
+int spkv_debug_read(const void* src, size_t region_bytes, int32_t run_bytes, int64_t first_run,
+                    int64_t n_runs, int64_t stride, int32_t n_workgroups, void* sink, void* stream) {
+    if (src == nullptr || sink == nullptr || !aligned16(src) || !aligned16(sink)) return SPKV_E_INVAL;
+    if (run_bytes < 16384 || run_bytes % 16384 != 0) return SPKV_E_INVAL;
+    const int64_t total_runs = (int64_t)(region_bytes / (size_t)run_bytes);
+    if (total_runs < 1 || n_runs < 1 || n_runs > total_runs || first_run < 0 || stride < 1 ||
+        stride > ((int64_t)1 << 31) || first_run > ((int64_t)1 << 31) || total_runs > ((int64_t)1 << 31))
+        return SPKV_E_INVAL;               // (first_run + i) * stride stays below 2^64
+    if (n_workgroups < 1 || n_workgroups > (1 << 20)) return SPKV_E_INVAL;
+    return spkv_launch_read(src, total_runs, run_bytes / 16384, first_run, n_runs, stride, n_workgroups,
+                            sink, static_cast<hipStream_t>(stream)) == hipSuccess
                ? SPKV_OK
                : SPKV_E_HIP;
 }

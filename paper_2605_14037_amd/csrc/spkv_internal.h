@@ -51,6 +51,11 @@ struct SpkvCu {
 
 hipError_t spkv_launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// Streaming read of n_runs runs (chunks_per_run chunks of 16 KB each) of a region of
+// total_runs runs by n_workgroups one-wave workgroups; sink: n_workgroups KB.
+hipError_t spkv_launch_read(const void* src, long long total_runs, int chunks_per_run,
+                            long long first_run, long long n_runs, long long stride,
+                            int n_workgroups, void* sink, hipStream_t s);
 // rows rows of src_width int32 into the first columns of rows of dst_width (>= src_width).
 hipError_t spkv_launch_copy_rows(int32_t* dst, const int32_t* src, int rows, int src_width,
                                  int dst_width, hipStream_t s);

@@ -42,6 +42,47 @@ hipError_t spkv_launch_copy(void* dst, const void* src, size_t bytes, hipStream_
     return hipGetLastError();
 }
 
+// ------------------------------------------------- plain streaming read (reference)
+// The memory side of the decode kernel and nothing else: one-wave workgroups, each reading
+// its share of the launch's 16 KB chunks with sixteen non-temporal 1 KB wave-wide loads per
+// chunk (the half-page access pattern) and storing 1 KB at the end (as a work item stores its
+// partial result).  Chunk c of the launch lies in run c / chunks_per_run; run i of the launch
+// is run ((first_run + i) * stride) mod total_runs of the region, so with a stride coprime to
+// total_runs successive launches read distinct, scattered runs.
+__global__ __launch_bounds__(64) void spkv_plain_read(const uint16_t* __restrict__ src,
+                                                      long long total_runs, int chunks_per_run,
+                                                      long long first_run, long long n_chunks,
+                                                      long long stride, uint4* __restrict__ sink) {
+    const long long g = blockIdx.x, n = gridDim.x;
+    const long long c0 = g * n_chunks / n, c1 = (g + 1) * n_chunks / n;
+    const int lane = threadIdx.x;
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (long long c = c0; c < c1; ++c) {
+        const long long i = c / chunks_per_run;
+        const int within = (int)(c - i * chunks_per_run);
+        const long long run = (long long)(((unsigned long long)(first_run + i) * (unsigned long long)stride) %
+                                          (unsigned long long)total_runs);
+        const uint16_t* base = src + ((size_t)run * chunks_per_run + within) * 8192 + lane * 8;
+        u32x4 x[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t)
+            x[t] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + t * 512));
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc ^= x[t];
+    }
+    sink[(size_t)g * 64 + lane] = make_uint4(acc.x, acc.y, acc.z, acc.w);
+}
+
+hipError_t spkv_launch_read(const void* src, long long total_runs, int chunks_per_run,
+                            long long first_run, long long n_runs, long long stride,
+                            int n_workgroups, void* sink, hipStream_t s) {
+    spkv_plain_read<<<dim3((unsigned)n_workgroups), dim3(64), 0, s>>>(
+        static_cast<const uint16_t*>(src), total_runs, chunks_per_run, first_run,
+        n_runs * chunks_per_run, stride, static_cast<uint4*>(sink));
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void spkv_copy_rows(int32_t* __restrict__ dst,
                                                       const int32_t* __restrict__ src, int rows,
                                                       int src_width, int dst_width) {

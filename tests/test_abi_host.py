@@ -130,3 +130,32 @@ def test_page_layout_is_a_bijection_in_mfma_operand_order(D):
                     assert voff[half * 32 + 8 * kc + e, 16 * db + dr] == tile + lane * 8 + e
     assert spkv.layout_offset(D, 0, 64, 0) == -1 and spkv.layout_offset(D, 1, 0, D) == -1
     assert spkv.layout_offset(96, 0, 0, 0) == -1
+
+
+def test_debug_read_rejects_bad_arguments_before_any_launch():
+    lib = spkv.load_library()
+    ok_ptr = C.c_void_p(4096)
+    # null pointers, misaligned pointers, a run size that is no multiple of 16 KB, more runs
+    # than the region holds, no workgroups
+    assert lib.spkv_debug_read(None, 1 << 20, 32768, 0, 1, 1, 1, ok_ptr, None) == -1
+    assert lib.spkv_debug_read(ok_ptr, 1 << 20, 32768, 0, 1, 1, 1, None, None) == -1
+    assert lib.spkv_debug_read(C.c_void_p(4100), 1 << 20, 32768, 0, 1, 1, 1, ok_ptr, None) == -1
+    assert lib.spkv_debug_read(ok_ptr, 1 << 20, 1000, 0, 1, 1, 1, ok_ptr, None) == -1
+    assert lib.spkv_debug_read(ok_ptr, 1 << 20, 32768, 0, 33, 1, 1, ok_ptr, None) == -1
+    assert lib.spkv_debug_read(ok_ptr, 1 << 20, 32768, 0, 1, 0, 1, ok_ptr, None) == -1
+    assert lib.spkv_debug_read(ok_ptr, 1 << 20, 32768, 0, 1, 1, 0, ok_ptr, None) == -1
+
+
+@pytest.mark.parametrize("batch,hq,hkv,D", [(512, 17, 17, 128), (512, 32, 32, 64), (512, 96, 32, 128),
+                                            (300, 54, 18, 64)])
+def test_arena_holds_the_multi_token_partials_of_extreme_shapes(batch, hq, hkv, D):
+    """The multi-token kernels write 16, 32 or 64 columns of partial results per slot and at
+    least one slot per (sequence, KV head): the arena of the largest valid shapes must have
+    room for two slots of 64 columns per pair (the slot arithmetic of the host keeps one
+    spare), whatever the group size."""
+    pairs = batch * hkv
+    need = pairs * 128 * (D + 2) * 4
+    got = spkv.required_bytes(_cfg(batch=batch, n_q_heads=hq, n_kv_heads=hkv, head_dim=D,
+                                   window=8, max_context=64, max_total_kept_tokens=0))
+    ring = pairs * 2 * 64 * D * 2                 # one 64-pair ring page (K and V) per pair
+    assert got >= need + ring

@@ -562,6 +562,62 @@ def test_largest_batch():
     H.run_workload(wl, chunk=4096, state_pairs=[(1, 1), (510, 6)], fused=True)
 
 
+def test_multi_token_step_on_thousands_of_pairs():
+    """512 sequences x 17 KV heads = 8704 pairs, group size 1: more pairs than a quarter of
+    the work-item slots, the shape at which the partial buffers of the multi-token kernels
+    were once too small for one slot per pair."""
+    B = 512
+    rng = np.random.default_rng(5)
+    lens = rng.integers(0, 30, size=B).tolist()
+    wl = small_workload("manypairs", B, 17, 17, 64, lens, 0.4, window=8, seed=23)
+    stream = TokenStream(wl, device="cuda")
+    cache = H.make_cache(wl, extra_context=16)
+    oracle = H.make_oracle(wl)
+    H.prefill(cache, oracle, stream, wl, 4096)
+    for counts in ([4] * B, rng.integers(0, 5, size=B).tolist()):
+        k, v, f, cu = stream.next_tokens(counts)
+        q = stream.next_query(rows=sum(counts))
+        out, lse = cache.decode_chunk(k, v, f, q, cu, want_lse=True)
+        oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+        ref_out, ref_lse = oracle.decode_chunk(to_numpy_f32(q), counts)
+        H.check_output(out, ref_out, "chunk")
+        H.check_lse(lse, ref_lse, "chunk")
+        H.check_state(cache, oracle, wl, [(0, 0), (511, 16), (200, 9), (37, 3)], "chunk")
+    cache.close()
+
+
+def test_partition_follows_the_lengths_over_thousands_of_steps():
+    """Every single-token step adds one to the host's upper bound of every long-term length
+    although only the keep rate's share is kept.  The work partition is derived from that
+    bound, so it must be brought back to the device's lengths now and then (without waiting):
+    after 3000 fused steps at keep rate 0.1 the partition of the last call must still cut the
+    lists into about as many items as the exact lengths would give."""
+    wl = small_workload("drift", 2, 8, 2, 128, [600, 300], 0.1, window=64, seed=77)
+    stream = TokenStream(wl, device="cuda")
+    n_steps = 3000
+    cache = H.make_cache(wl, pool_tokens=2 * 2 * (900 + n_steps), extra_context=n_steps + 8)
+    cache.set_option(spkv.OPT_ITEM_TARGET, 24)
+    oracle = H.make_oracle(wl)
+    H.prefill(cache, oracle, stream, wl, 4096)
+    ins = []
+    for _ in range(8):
+        k, v, f, cu = stream.next_tokens([1, 1])
+        q = stream.next_query()
+        ins.append((k, v, f, cache.make_cu(cu), q, to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu))
+    out = torch.empty_like(ins[0][4])
+    for i in range(n_steps):
+        k, v, f, cuc, q, kn, vn, fn, cu = ins[i % 8]
+        cache.decode_step(k, v, f, q, out=out)
+        oracle.append(kn, vn, fn, cu)
+        if i % 500 == 499:
+            torch.cuda.synchronize()
+            H.check_output(out, oracle.decode(to_numpy_f32(q))[0], f"step {i}")
+    st = H.check_state(cache, oracle, wl, label="after the run")
+    assert st.kept_tokens < 0.2 * st.evicted_tokens          # the bound would be 5-10x the truth
+    assert st.n_work_items_last_call >= 0.85 * st.n_work_items, (st.n_work_items_last_call, st.n_work_items)
+    cache.close()
+
+
 def test_release_and_reuse_sequences():
     """Continuous batching: sequences finish, their slots are released and refilled; pages
     are recycled (the pool would overflow without it) and every state check stays exact."""
