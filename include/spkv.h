@@ -175,6 +175,27 @@ int spkv_append(spkv_cache_t* cache, const void* k, const void* v, const float* 
 int spkv_decode_attention(spkv_cache_t* cache, const void* q, void* out, float* lse,
                           float sm_scale, void* stream);
 
+/* spkv_decode_attention for callers that cannot allocate -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc -- and do not want the split-K
+ * partial results in their arena either: the same kernels, with the partials in a 16 MiB
+ * array that is part of the library's device image (one copy per GPU, held until the process
+ * ends) instead of the cache's arena.  The call allocates nothing, on the host's device side
+ * or through any library, and never waits for the device.  Inputs, outputs and result as
+ * for spkv_decode_attention (the work partition is fitted to the slots the array holds, so
+ * results can differ from spkv_decode_attention's in the last bits, as between any two
+ * partitions).
+ * The array keeps the last call's contents; every slot a call reads it has written before,
+ * so nothing needs clearing.  All caches on a GPU share it: calls that overlap on one GPU
+ * (different streams) race -- issue them on one stream, or order them with events.
+ * Errors: SPKV_E_CAPACITY if the array cannot hold two partial slots per (sequence, KV head)
+ * -- batch * n_kv_heads above 16 MiB / (8 * group size * (head_dim + 2)) -- checked first;
+ * SPKV_E_STATE if some sequence holds no token, or if a multi-token append has been issued
+ * since the lengths were last read back (spkv_decode_attention, spkv_cache_safe_steps and
+ * spkv_cache_stats read them; this call will not wait for them); SPKV_E_HIP if the array's
+ * address cannot be obtained. */
+int spkv_decode_attention_static(spkv_cache_t* cache, const void* q, void* out, float* lse,
+                                 float sm_scale, void* stream);
+
 /* One whole decode step in two kernel launches instead of three: the same result and the
  * same cache state as
  *     spkv_append(cache, k, v, util_logits, {0, 1, .., batch}, stream);

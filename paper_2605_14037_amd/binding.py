@@ -21,7 +21,8 @@ MAX_BATCH, PAGE_TOKENS = 512, 64
 EXPORTED_SYMBOLS = [
     "spkv_cache_required_bytes", "spkv_cache_create", "spkv_cache_destroy", "spkv_cache_grow",
     "spkv_cache_reset",
-    "spkv_append", "spkv_decode_attention", "spkv_decode_step", "spkv_decode_chunk",
+    "spkv_append", "spkv_decode_attention", "spkv_decode_attention_static", "spkv_decode_step",
+    "spkv_decode_chunk",
     "spkv_decode_step_predict_workspace_bytes", "spkv_decode_step_predict", "spkv_score_chunk",
     "spkv_prefill_workspace_bytes", "spkv_prefill_attention",
     "spkv_soft_gated_workspace_bytes", "spkv_soft_gated_attention", "spkv_cache_release_sequence", "spkv_utility_logits", "spkv_cache_safe_steps", "spkv_cache_advance", "spkv_cache_stats", "spkv_cache_kept_positions",
@@ -87,6 +88,8 @@ def load_library():
     lib.spkv_append.argtypes = [vp, vp, vp, vp, P(i32), vp]
     lib.spkv_decode_attention.restype = C.c_int
     lib.spkv_decode_attention.argtypes = [vp, vp, vp, vp, f32, vp]
+    lib.spkv_decode_attention_static.restype = C.c_int
+    lib.spkv_decode_attention_static.argtypes = [vp, vp, vp, vp, f32, vp]
     lib.spkv_decode_step.restype = C.c_int
     lib.spkv_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, vp]
     lib.spkv_decode_step_predict_workspace_bytes.restype = C.c_size_t
@@ -320,6 +323,18 @@ class SPKVCache:
         _check(self.lib.spkv_decode_attention(self.handle, qp, op, lp, float(sm_scale), _stream()),
                "spkv_decode_attention")
         return (out, lse) if lse is not None else out
+
+    def decode_attention_static(self, q, out, lse=None, sm_scale=0.0):
+        """spkv_decode_attention_static: partials in the library's static device array; the
+        caller passes every buffer (nothing is allocated here either)."""
+        cfg = self.cfg
+        shape = (cfg.batch, cfg.n_q_heads, cfg.head_dim)
+        qp = _dev_ptr(q, torch.bfloat16, shape, "q")
+        op = _dev_ptr(out, torch.bfloat16, shape, "out")
+        lp = _dev_ptr(lse, torch.float32, shape[:2], "lse") if lse is not None else None
+        _check(self.lib.spkv_decode_attention_static(self.handle, qp, op, lp, float(sm_scale),
+                                                     _stream()), "spkv_decode_attention_static")
+        return out
 
     def decode_step(self, k, v, util_logits, q, out=None, lse=None, sm_scale=0.0, want_lse=False):
         """Append one token per sequence and decode, fused (spkv_decode_step)."""

@@ -106,6 +106,36 @@ int64_t pages_for(int64_t len) { return (len + kPageTokens - 1) / kPageTokens; }
 
 }  // namespace
 
+// Scratch for spkv_decode_attention_static: the split-K partials of callers that cannot
+// allocate.  One copy per GPU the library runs on, held until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels get the address
+// that call returns for the current device.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up once per device);
+// null if the runtime cannot tell.
+void* static_scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
 struct spkv_cache {
     spkv_config_t cfg;
     Carve carve;
@@ -427,6 +457,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
         delete c;
         return SPKV_E_HIP;
     }
+    (void)static_scratch_of_current_device();     // set-up for spkv_decode_attention_static
     // pinned host buffer for the length snapshots (see tighten_bound); the cache works
     // without it, with a coarser partition on very long generations
     void* pinned = nullptr;
@@ -665,6 +696,33 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
     c->split = choose_split(c);
     if (spkv_launch_decode(c->view, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
                            lse, sm_scale, c->split, c->split_only, ev0, ev1, s) != hipSuccess)
+        return SPKV_E_HIP;
+    return SPKV_OK;
+}
+
+int spkv_decode_attention_static(spkv_cache_t* c, const void* q, void* out, float* lse,
+                                 float sm_scale, void* stream) {
+    if (c == nullptr || q == nullptr || out == nullptr) return SPKV_E_INVAL;
+    if (!aligned16(q) || !aligned16(out) || (lse != nullptr && !aligned16(lse))) return SPKV_E_INVAL;
+    // partial slots the scratch holds for this shape: [cap][G][D] sums, then [cap][G][2]
+    const int G = c->carve.G, D = c->cfg.head_dim;
+    const int64_t cap = (int64_t)((kStaticScratchBytes - kAlign) / ((size_t)G * (D + 2) * sizeof(float)));
+    if (cap < 2 * (int64_t)c->carve.n_pairs) return SPKV_E_CAPACITY;
+    for (int b = 0; b < c->cfg.batch; ++b)
+        if (c->T[b] == 0) return SPKV_E_STATE;
+    if (c->bound_is_loose) return SPKV_E_STATE;      // would have to wait for the device
+    char* base = static_cast<char*>(static_scratch_of_current_device());
+    if (base == nullptr) return SPKV_E_HIP;
+    if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)D);
+    SpkvView v = c->view;
+    v.part_acc = reinterpret_cast<float*>(base);
+    v.part_ml = reinterpret_cast<float*>(base + align_up((size_t)cap * G * D * sizeof(float)));
+    v.max_items = (int32_t)std::min<int64_t>(cap, INT32_MAX);
+    c->split = choose_split(c, c->one_round_items, cap);
+    if ((int64_t)c->carve.n_pairs * c->split.slots > cap) return SPKV_E_CAPACITY;
+    if (spkv_launch_decode(v, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out), lse,
+                           sm_scale, c->split, false, nullptr, nullptr,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
         return SPKV_E_HIP;
     return SPKV_OK;
 }
