@@ -465,10 +465,11 @@ def layered_bench(wl, args):
     print(json.dumps(result))
 
 
-def read_traffic_summary():
-    """HBM bytes per launch of the split-K kernel from the committed rocprofv3 --pmc
-    summary (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size), if present."""
-    path = os.path.join(ROOT, "profiles", "decode_split_cfg2_pmc.txt")
+def read_traffic_summary(wl_name):
+    """HBM bytes per launch of the decode kernel of this workload from the committed rocprofv3
+    --pmc summary (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size); None when
+    no summary of this workload is committed."""
+    path = os.path.join(ROOT, "profiles", f"decode_step_{wl_name}_pmc.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch="):
@@ -478,7 +479,7 @@ def read_traffic_summary():
     return None
 
 
-def cpu_baseline(wl, oracle, q, seqs, kept_bytes_sample, repeats=3):
+def cpu_baseline(wl, oracle, q, seqs, kept_bytes_sample, repeats=2):
     from oracle.spkv_oracle import SPKVOracle  # noqa: F401  (the oracle is only used here)
     workers = max(1, min(16, os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16"))))
     qn = to_numpy_f32(q[:seqs])
@@ -491,13 +492,228 @@ def cpu_baseline(wl, oracle, q, seqs, kept_bytes_sample, repeats=3):
     return {
         "value": kept_bytes_sample / best / 1e9, "unit": "GB/s", "cores": workers,
         "kind": "oracle",
-        "sample": (f"fp64 oracle, one decode step (attention over the dense history under the "
-                   f"explicit mask) for the first {seqs} of {wl.batch} sequences x {wl.n_kv_heads} "
-                   f"KV heads of instance 0, best of {repeats}; GB/s counts the same kept-KV bytes "
-                   f"as the GPU figure for those sequences"),
+        "sample": (f"fp64 oracle (numpy, {workers} threads over (sequence, KV head) pairs), one decode "
+                   f"step (attention over the dense history under the explicit mask) for the first "
+                   f"{seqs} of {wl.batch} sequences x {wl.n_kv_heads} KV heads of instance 0, best of "
+                   f"{repeats}; GB/s counts the same kept-KV bytes as the GPU figure for those sequences"),
         "seconds_per_step_sample": best,
-        "us_per_step_extrapolated": best * wl.batch / seqs * 1e6,
+        "us_per_step_extrapolated_from_sample_x%d" % (wl.batch // seqs): best * wl.batch / seqs * 1e6,
     }
+
+
+def events_per_launch(fn, n):
+    """Average milliseconds of n calls of fn issued back to back, by HIP events on the
+    launch stream (torch's current stream is the stream the binding launches on)."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(n):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
+def read_ceiling_leg(nbytes, n_workgroups, launches):
+    """A plain streaming read (spkv_debug_read) of the same number of bytes, in scattered 32 KB
+    runs (the cache's page size), by as many one-wave workgroups as the decode launch has work
+    items, back to back over a 3 GiB region so that every launch reads cold memory."""
+    region = 3 << 30
+    run_bytes = 32768
+    src = torch.empty(region, dtype=torch.uint8, device="cuda")
+    src.zero_()
+    sink = torch.empty(max(1, n_workgroups) * 1024, dtype=torch.uint8, device="cuda")
+    total_runs = region // run_bytes
+    n_runs = max(1, min(int(nbytes) // run_bytes, total_runs // 2))
+    state = {"first": 0}
+
+    def launch(_):
+        spkv.debug_read(src, run_bytes, state["first"], n_runs, 1000003, n_workgroups, sink)
+        state["first"] = (state["first"] + n_runs) % (total_runs - n_runs)
+
+    for i in range(5):
+        launch(i)
+    ms = events_per_launch(launch, launches)
+    del src, sink
+    torch.cuda.empty_cache()
+    gbps = n_runs * run_bytes / (ms * 1e-3) / 1e9
+    return {"what": "spkv_debug_read: non-temporal 16 KB chunk reads in scattered 32 KB runs, one-wave "
+                    "workgroups, no arithmetic; same bytes and workgroup count as the decode launch",
+            "bytes_per_launch": n_runs * run_bytes, "workgroups": n_workgroups, "us_per_launch": ms * 1e3,
+            "GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "launches_timed": launches}
+
+
+def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, cpu_repeats=2):
+    """One workload through the decode path: fused step (host clock and HIP events), the same
+    step replayed from a HIP graph, the split-K part alone, the other launch count, the read
+    ceiling, the dense-cache baseline and the CPU oracle.  Kept bytes are counted right before
+    and right after the timed steps (mean of the two)."""
+    exp_bytes = (wl.expected_kept_tokens() + wl.batch * wl.n_kv_heads * wl.window) * 4 * wl.head_dim
+    R = args.instances or max(2, int(np.ceil(2.5e9 / exp_bytes)))
+    cpu_seqs = min(cpu_seqs, wl.batch)
+    oracle = None
+    if cpu_seqs > 0:
+        from oracle.spkv_oracle import SPKVOracle
+        oracle = SPKVOracle(cpu_seqs, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
+                            window=wl.window, tau=wl.tau)
+    caches, streams = [], []
+    for r in range(R):
+        c, s = build_cache(wl, r, args.chunk, oracle=oracle if r == 0 else None,
+                           oracle_seqs=cpu_seqs, time_prefill=(keep_caches and r == R - 1))
+        if args.item_target:
+            c.set_option(spkv.OPT_ITEM_TARGET, args.item_target)
+        if args.merge_waves:
+            c.set_option(spkv.OPT_MERGE_WAVES, args.merge_waves)
+        if args.step_launches:
+            c.set_option(spkv.OPT_STEP_LAUNCHES, args.step_launches)
+        caches.append(c)
+        streams.append(s)
+
+    # Per-step inputs, resident before timing (a ring of distinct steps).
+    steps_in = []
+    for j in range(max(64, R)):
+        k, v, f, cu = streams[j % R].next_tokens([1] * wl.batch)
+        q = streams[j % R].next_query()
+        steps_in.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
+
+    fused = not args.two_call
+    timed_steps(caches, steps_in, W, 0, fused=fused)
+    before = [c.stats() for c in caches]
+    dt = timed_steps(caches, steps_in, K, W, fused=fused)
+    after = [c.stats() for c in caches]
+    host_issue_us = HOST_ISSUE_S[-1] * 1e6
+    assert all(s.device_error == 0 for s in after)
+    kept_bytes = float(np.mean([s.kept_kv_bytes for s in before + after]))
+    dense_bytes = float(np.mean([s.dense_kv_bytes for s in before + after]))
+    density = float(np.mean([s.density_evicted for s in after]))
+    work_items = int(after[0].n_work_items)
+
+    # K back-to-back steps between two HIP events on the launch stream.  (One event pair per
+    # launch would put a ~5 us barrier packet in front of every kernel.)
+    def step(i):
+        k, v, f, cu, q, out = steps_in[i % len(steps_in)]
+        caches[i % R].decode_step(k, v, f, q, out=out)
+    for i in range(R):
+        step(i)
+    step_events_ms = events_per_launch(step, K)
+
+    # The same step captured once per cache instance into one HIP graph and replayed: what a
+    # serving loop sees when the host's per-call work (argument checks, the capacity bound, the
+    # launch itself) is off the path.
+    graph = None
+    n_rep = max(1, K // R)
+    if min(c.safe_steps() for c in caches) > n_rep + 2:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for r in range(R):
+                k, v, f, cu, q, out = steps_in[r]
+                caches[r].decode_step(k, v, f, q, out=out)
+        g.replay()                                   # the step the captured calls accounted for
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_rep):
+            for c in caches:
+                c.advance(1)
+            g.replay()
+        torch.cuda.synchronize()
+        gus = (time.perf_counter() - t0) / (n_rep * R) * 1e6
+        graph = {"what": f"one graph of {R} captured steps (one per cache instance), replayed {n_rep} "
+                         "times; host bookkeeping by spkv_cache_advance",
+                 "us_per_step": gus, "GBps": kept_bytes / gus / 1e3,
+                 "frac_of_hbm_peak_step": kept_bytes / gus / 1e3 / HBM_PEAK_GBPS}
+        del g
+
+    # the other launch count, and the split-K part alone (no merge, no append)
+    other = 2 if args.step_launches == 1 else 1        # the library's default is two
+    for c in caches:
+        c.set_option(spkv.OPT_STEP_LAUNCHES, other)
+    timed_steps(caches, steps_in, max(W, R), 0, fused=True)
+    dt_other = timed_steps(caches, steps_in, K, W, fused=True)
+    for c in caches:
+        c.set_option(spkv.OPT_STEP_LAUNCHES, args.step_launches)
+        c.set_option(spkv.OPT_SPLIT_ONLY, 1)
+    timed_steps(caches, steps_in, max(W, R), 0, do_append=False)
+    split_ms = events_per_launch(
+        lambda i: caches[i % R].decode_attention(steps_in[i % len(steps_in)][4],
+                                                 out=steps_in[i % len(steps_in)][5]), K)
+    for c in caches:
+        c.set_option(spkv.OPT_SPLIT_ONLY, 0)
+
+    # With two launches per step the dominant kernel is the split-K launch, timed alone above;
+    # with one launch it is the step itself.
+    kern_avg_ms = step_events_ms if args.step_launches == 1 else split_ms
+    achieved = kept_bytes / (kern_avg_ms * 1e-3) / 1e9
+    res = {
+        "workload": f"{wl.name}: batch {wl.batch}, {wl.n_q_heads}q/{wl.n_kv_heads}kv heads, "
+                    f"head_dim {wl.head_dim}, ctx {min(wl.ctx_lens)}..{max(wl.ctx_lens)}, "
+                    f"window {wl.window}, tau {wl.tau}, target keep rates "
+                    f"{wl.keep.min():.2f}..{wl.keep.max():.2f} ({wl.note})",
+        "cache_instances_rotated": R,
+        "kept_kv_bytes_per_step": kept_bytes, "dense_kv_bytes_per_step": dense_bytes,
+        "density_evicted": density, "work_items": work_items,
+        "us_per_step": dt / K * 1e6, "steps_timed": K,
+        "GBps_step": kept_bytes / (dt / K) / 1e9,
+        "frac_of_hbm_peak_step": kept_bytes / (dt / K) / 1e9 / HBM_PEAK_GBPS,
+        "host_issue_us_per_step": host_issue_us,
+        "hip_graph_replay": graph,
+        f"us_per_step_with_{other}_launch{'es' if other > 1 else ''}": dt_other / K * 1e6,
+        "roofline": {
+            "bound": "hbm",
+            "kernel": (f"spkv_decode_split<{wl.head_dim}>: split-K over the kept lists (the first of the "
+                       "step's two launches; the second, spkv_combine_append, merges and appends)"
+                       if args.step_launches != 1 else
+                       f"spkv_decode_split<{wl.head_dim}, step>: split-K + merge + append in one launch"),
+            "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": read_traffic_summary(wl.name),
+            "algorithmic_bytes_per_launch": kept_bytes,
+            "kernel_avg_us": kern_avg_ms * 1e3, "launches_timed": K,
+            "timing": "HIP events around K back-to-back launches of this kernel alone on the launch stream",
+            "us_per_step_by_events": step_events_ms * 1e3,
+        },
+    }
+    ceiling = read_ceiling_leg(kept_bytes, work_items, K)
+    ceiling["kernel_over_read_ceiling"] = ceiling["us_per_launch"] / (kern_avg_ms * 1e3)
+    ceiling["step_over_read_ceiling"] = ceiling["us_per_launch"] / (dt / K * 1e6)
+    res["read_ceiling"] = ceiling
+
+    state = (caches, streams, steps_in, R, dt)
+    if not keep_caches:
+        for c in caches:
+            c.close()
+        caches, streams = [], []
+        state = None
+        torch.cuda.empty_cache()
+    if with_dense and not args.no_dense:
+        dc, ds = build_cache(wl, 1000, args.chunk, tau=0.0)
+        Kd = max(10, K // 4)
+        timed_steps([dc], steps_in, 5, 0, fused=fused)
+        ddt = timed_steps([dc], steps_in, Kd, 5, fused=fused)
+        dst = dc.stats()
+        res["dense_cache"] = {
+            "what": "same library, tau = 0 (every pair kept): dense-cache decode on the same GPU",
+            "us_per_step": ddt / Kd * 1e6, "kv_bytes_per_step": dst.kept_kv_bytes,
+            "GBps": dst.kept_kv_bytes / (ddt / Kd) / 1e9,
+            "speedup_of_spkv": (ddt / Kd) / (dt / K)}
+        dc.close()
+        del dc, ds
+        torch.cuda.empty_cache()
+    res["_oracle"] = (oracle, steps_in[0], cpu_seqs, cpu_repeats)
+    return res, state
+
+
+def finish_cpu(res, wl):
+    """CPU baseline of a leg, run after every GPU timing (a long host-only phase lets the GPU
+    clocks drop): the oracle mirrors the first sequences of instance 0 up to the end of the
+    prefill; give it one more step of instance 0 and time its decode."""
+    oracle, step0, cpu_seqs, repeats = res.pop("_oracle")
+    if oracle is None:
+        res["cpu_baseline"] = None
+        return
+    k, v, f, cu, q, out = step0
+    n = cu[cpu_seqs]
+    oracle.append(to_numpy_f32(k[:n]), to_numpy_f32(v[:n]), to_numpy_f32(f[:n]), list(cu[:cpu_seqs + 1]))
+    res["cpu_baseline"] = cpu_baseline(wl, oracle, q, cpu_seqs, oracle.stats()["kept_kv_bytes"], repeats)
 
 
 def main():
@@ -506,16 +722,25 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--configs", default=None,
+                    help="further configurations measured into the line's `configs` object, comma "
+                         "separated (default: cfg3,cfg4,cfg5 beside cfg2, none beside any other "
+                         "workload; cfg5 here is one of its 32 layers); 'none' for none")
     ap.add_argument("--instances", type=int, default=0, help="cache instances to rotate (0 = auto)")
     ap.add_argument("--item-target", type=int, default=0)
     ap.add_argument("--merge-waves", type=int, default=0,
                     help="work items per workgroup of the split-K kernel (0 = chosen per call)")
+    ap.add_argument("--step-launches", type=int, default=0,
+                    help="kernel launches per step: 1 (merge and append by the last workgroup of "
+                         "every pair), 2 (a merge launch), 0 = chosen by the library")
     ap.add_argument("--chunk", type=int, default=1024, help="prefill chunk (tokens per sequence)")
     ap.add_argument("--two-call", action="store_true",
-                    help="time spkv_append + spkv_decode_attention (3 launches) as the step "
-                         "instead of the fused spkv_decode_step (2 launches)")
+                    help="time spkv_append + spkv_decode_attention as the step instead of the fused "
+                         "spkv_decode_step")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the legs beyond the decode step (predictor, multi-token, prefill)")
     ap.add_argument("--cpu-seqs", type=int, default=4)
     ap.add_argument("--scaling", action="store_true",
                     help="run the keep-rate and context sweeps instead of the benchmark")
@@ -569,210 +794,135 @@ def main():
     if wl.n_layers > 1:
         layered_bench(wl, args)
         return
-    exp_bytes = (wl.expected_kept_tokens() + wl.batch * wl.n_kv_heads * wl.window) * 4 * wl.head_dim
-    R = args.instances or max(2, int(np.ceil(2.5e9 / exp_bytes)))
-    cpu_seqs = min(args.cpu_seqs, wl.batch)
-
-    oracle = None
-    if not args.no_cpu:
-        from oracle.spkv_oracle import SPKVOracle
-        oracle = SPKVOracle(cpu_seqs, wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
-                            window=wl.window, tau=wl.tau)
-    caches, streams = [], []
-    for r in range(R):
-        c, s = build_cache(wl, r, args.chunk, oracle=oracle if r == 0 else None,
-                           oracle_seqs=cpu_seqs, time_prefill=(r == R - 1))
-        if args.item_target:
-            c.set_option(spkv.OPT_ITEM_TARGET, args.item_target)
-        if args.merge_waves:
-            c.set_option(spkv.OPT_MERGE_WAVES, args.merge_waves)
-        caches.append(c)
-        streams.append(s)
-
-    # Per-step inputs, resident before timing (a ring of 64 distinct steps).
-    steps_in = []
-    for j in range(64):
-        k, v, f, cu = streams[j % R].next_tokens([1] * wl.batch)
-        q = streams[j % R].next_query()
-        out = torch.empty_like(q)
-        steps_in.append((k, v, f, caches[0].make_cu(cu), q, out))
 
     W, K = args.warmup, args.steps
+    cpu_seqs = 0 if args.no_cpu else args.cpu_seqs
+    extras = not args.no_extras
+    res, state = decode_leg(wl, args, K, W, cpu_seqs=cpu_seqs, keep_caches=extras)
     fused = not args.two_call
-    timed_steps(caches, steps_in, W, 0, fused=fused)
-    dt = timed_steps(caches, steps_in, K, W, fused=fused)
-    ms_per_step = dt / K * 1e3
-    host_issue_us = HOST_ISSUE_S[-1] * 1e6
-    # the other way of taking the same step, for reference
-    timed_steps(caches, steps_in, max(W, R), 0, fused=not fused)
-    dt_other = timed_steps(caches, steps_in, K, W, fused=not fused)
 
-    # Roofline of the dominant kernel: K launches of the split-K kernel alone, back to back
-    # on the launch stream (same rotation over the cache instances), between two HIP events.
-    # (One event pair per launch would put a ~5 us barrier packet in front of every kernel
-    # and inflate each sample by that much; it is reported below for reference.)
-    for c in caches:
-        c.set_option(spkv.OPT_SPLIT_ONLY, 1)
-    timed_steps(caches, steps_in, max(W, R), 0, do_append=False)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(K):
-        caches[i % R].decode_attention(steps_in[i % len(steps_in)][4], out=steps_in[i % len(steps_in)][5])
-    e1.record()
-    torch.cuda.synchronize()
-    kern_avg_ms = e0.elapsed_time(e1) / K
-    for c in caches:
-        c.set_option(spkv.OPT_SPLIT_ONLY, 0)
-        c.set_option(spkv.OPT_KERNEL_TIMING, 1)
-    dt_ev = timed_steps(caches, steps_in, K, W + K)
-    kern_ms = []
-    for c in caches:
-        kern_ms += c.read_kernel_timing()
-        c.set_option(spkv.OPT_KERNEL_TIMING, 0)
-    dt_dec = timed_steps(caches, steps_in, K, W + 2 * K, do_append=False)
-    dt_app = timed_steps(caches, steps_in, K, W + 3 * K, do_decode=False)
-    # The same step on ONE cache instance, step after step, as a serving loop runs it: what
-    # the chip's last-level cache (256 MB) holds of the kept K/V from the step before is not
-    # fetched from HBM again.  The headline figure is the cold one (rotation).
-    timed_steps(caches[:1], steps_in, max(W, 10), 0, fused=fused)
-    dt_hot = timed_steps(caches[:1], steps_in, K, W, fused=fused)
+    extra = {}
+    if extras:
+        caches, streams, steps_in, R, dt = state
+        # the step as two calls (spkv_append + spkv_decode_attention), and its halves
+        timed_steps(caches, steps_in, max(W, R), 0, fused=not fused)
+        dt_other = timed_steps(caches, steps_in, K, W, fused=not fused)
+        dt_dec = timed_steps(caches, steps_in, K, W + K, do_append=False)
+        dt_app = timed_steps(caches, steps_in, K, W + 2 * K, do_decode=False)
+        # The same step on ONE cache instance, step after step, as a serving loop runs it: what
+        # the chip's last-level cache (256 MB) holds of the kept K/V from the step before is not
+        # fetched from HBM again.  The headline figure is the cold one (rotation).
+        timed_steps(caches[:1], steps_in, max(W, 10), 0, fused=fused)
+        dt_hot = timed_steps(caches[:1], steps_in, K, W, fused=fused)
+        extra["us_per_step_other_entry"] = dt_other / K * 1e6
+        extra["us_per_step_one_instance_warm_cache"] = dt_hot / K * 1e6
+        extra["decode_only_us"] = dt_dec / K * 1e6
+        extra["append_only_us"] = dt_app / K * 1e6
+        extra["step_with_predictor"] = predictor_step_leg(caches, steps_in, wl, K)
 
-    predictor_leg = predictor_step_leg(caches, steps_in, wl, K)
-
-    # Multi-token steps: 4 and 16 new tokens per sequence per call, through
-    # spkv_decode_chunk and through spkv_prefill_attention (which hands the shortest chunks
-    # to the former itself).
-    chunk_legs = {}
-    for n_tok in (4, 16):
-        if n_tok * (wl.n_q_heads // wl.n_kv_heads) > 64:
-            continue
-        ins = []
-        for j in range(2 * R):
-            k, v, f, cu = streams[j % R].next_tokens([n_tok] * wl.batch)
-            q = streams[j % R].next_query(rows=n_tok * wl.batch)
-            ins.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
-        ws = torch.empty(caches[0].prefill_workspace_bytes(n_tok, n_tok * wl.batch),
-                         dtype=torch.uint8, device="cuda")
-        Kc = max(R, K // 8)
-        leg = {"calls_timed": Kc}
-        for name in ("decode_chunk", "prefill_attention"):
-            def call(j):
-                k, v, f, cu, q, o = ins[j % len(ins)]
-                if name == "decode_chunk":
-                    caches[j % R].decode_chunk(k, v, f, q, cu, out=o)
-                else:
-                    caches[j % R].prefill_attention(k, v, f, q, cu, workspace=ws, out=o)
-            for j in range(R):
-                call(j)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for j in range(Kc):
-                call(j)
-            torch.cuda.synchronize()
-            dtc = (time.perf_counter() - t0) / Kc
-            leg[f"us_per_call_{name}"] = dtc * 1e6
-        leg["us_per_token_position"] = min(leg["us_per_call_decode_chunk"],
-                                           leg["us_per_call_prefill_attention"]) / n_tok
-        chunk_legs[f"{n_tok}_tokens_per_sequence"] = leg
-
-    stats = [c.stats() for c in caches]
-    kept_bytes = float(np.mean([s.kept_kv_bytes for s in stats]))
-    dense_bytes = float(np.mean([s.dense_kv_bytes for s in stats]))
-    density = float(np.mean([s.density_evicted for s in stats]))
-    assert all(s.device_error == 0 for s in stats)
-    achieved = kept_bytes / (kern_avg_ms * 1e-3) / 1e9
-
-    dense = None
-    if not args.no_dense:
-        for c in caches[2:]:
-            c.close()
-        del caches[2:]
-        torch.cuda.empty_cache()
-        dc, ds = build_cache(wl, 1000, args.chunk, tau=0.0)
-        Kd = max(10, K // 4)
-        timed_steps([dc], steps_in, 5, 0, fused=fused)
-        ddt = timed_steps([dc], steps_in, Kd, 5, fused=fused)
-        dst = dc.stats()
-        dense = {
-            "what": "same library, tau = 0 (every pair kept): dense-cache decode on the same GPU",
-            "us_per_step": ddt / Kd * 1e6,
-            "kv_bytes_per_step": dst.kept_kv_bytes,
-            "GBps": dst.kept_kv_bytes / (ddt / Kd) / 1e9,
-            "speedup_of_spkv": (ddt / Kd) / (dt / K),
-        }
-        dc.close()
-
-    # Prefill attention: the last two 2048-token chunks of the prompt on a fresh cache.
-    prefill_attn = None
-    if min(wl.ctx_lens) >= 4096:
+        # Multi-token steps: 4 and 16 new tokens per sequence per call, through
+        # spkv_decode_chunk and through spkv_prefill_attention (which hands the shortest chunks
+        # to the former itself).
+        chunk_legs = {}
+        for n_tok in (4, 16):
+            if n_tok * (wl.n_q_heads // wl.n_kv_heads) > 64:
+                continue
+            ins = []
+            for j in range(2 * R):
+                k, v, f, cu = streams[j % R].next_tokens([n_tok] * wl.batch)
+                q = streams[j % R].next_query(rows=n_tok * wl.batch)
+                ins.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
+            ws = torch.empty(caches[0].prefill_workspace_bytes(n_tok, n_tok * wl.batch),
+                             dtype=torch.uint8, device="cuda")
+            Kc = max(R, K // 8)
+            leg = {"calls_timed": Kc}
+            for name in ("decode_chunk", "prefill_attention"):
+                def call(j):
+                    k, v, f, cu, q, o = ins[j % len(ins)]
+                    if name == "decode_chunk":
+                        caches[j % R].decode_chunk(k, v, f, q, cu, out=o)
+                    else:
+                        caches[j % R].prefill_attention(k, v, f, q, cu, workspace=ws, out=o)
+                for j in range(R):
+                    call(j)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for j in range(Kc):
+                    call(j)
+                torch.cuda.synchronize()
+                leg[f"us_per_call_{name}"] = (time.perf_counter() - t0) / Kc * 1e6
+            leg["us_per_token_position"] = min(leg["us_per_call_decode_chunk"],
+                                               leg["us_per_call_prefill_attention"]) / n_tok
+            chunk_legs[f"{n_tok}_tokens_per_sequence"] = leg
+        extra["multi_token_step"] = chunk_legs
+        extra["prefill_append"] = dict(PREFILL_TIMING)
         for c in caches:
             c.close()
-        caches = []
+        caches, state = [], None
+        del streams
         torch.cuda.empty_cache()
-        prefill_attn = prefill_attention_leg(wl, 2048, 2)
+        # Prefill attention: the last two 2048-token chunks of the prompt on a fresh cache.
+        if min(wl.ctx_lens) >= 4096:
+            extra["prefill_attention"] = prefill_attention_leg(wl, 2048, 2)
 
-    # CPU baseline last (a long host-only phase lets the GPU clocks drop, so it must not
-    # precede a timed region): the oracle mirrors the first sequences of instance 0 up to
-    # the end of prefill; give it one more step of instance 0 and time its decode.
-    cpu = None
-    if oracle is not None:
-        k, v, f, cu, q, out = steps_in[0]
-        n = cu[cpu_seqs]
-        oracle.append(to_numpy_f32(k[:n]), to_numpy_f32(v[:n]), to_numpy_f32(f[:n]),
-                      list(cu[:cpu_seqs + 1]))
-        ost = oracle.stats()
-        cpu = cpu_baseline(wl, oracle, q, cpu_seqs, ost["kept_kv_bytes"])
-        oracle = None
+    # further configurations, each a decode leg of its own
+    names = args.configs
+    if names is None:
+        names = "cfg3,cfg4,cfg5" if args.workload == "cfg2" else "none"
+    others = {}
+    other_wl = {}
+    if names != "none":
+        import dataclasses
+        for name in [n for n in names.split(",") if n and n != args.workload]:
+            w2 = workload(name)
+            label = name
+            if w2.n_layers > 1:       # one layer of the layered configuration, gate logits passed in
+                w2 = dataclasses.replace(w2, n_layers=1, note=w2.note + "; ONE of its 32 layers")
+                label = name + "_one_layer"
+            K2 = max(20, K // 2) if w2.expected_kept_tokens() * 4 * w2.head_dim > 1.5e9 else K
+            others[label], _ = decode_leg(w2, args, K2, W, cpu_seqs=cpu_seqs, cpu_repeats=1)
+            other_wl[label] = w2
+
+    # CPU baselines last
+    finish_cpu(res, wl)
+    for label, r in others.items():
+        finish_cpu(r, other_wl[label])
 
     result = {
         "metric": "sp-kv decode step (append + decode attention): achieved HBM GB/s on kept-KV bytes",
-        "value": kept_bytes / (dt / K) / 1e9,
+        "value": res["GBps_step"],
         "unit": "GB/s",
         "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": ms_per_step,
-        "us_per_step": ms_per_step * 1e3,
+        "ms_per_step": res["us_per_step"] / 1e3,
+        "us_per_step": res["us_per_step"],
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"{wl.name}: batch {wl.batch}, {wl.n_q_heads}q/{wl.n_kv_heads}kv heads, "
-                        f"head_dim {wl.head_dim}, ctx {min(wl.ctx_lens)}..{max(wl.ctx_lens)}, "
-                        f"window {wl.window}, tau {wl.tau}, target keep rates "
-                        f"{wl.keep.min():.2f}..{wl.keep.max():.2f} ({wl.note})",
-            "cache_instances_rotated": R,
-            "kept_kv_bytes_per_step": kept_bytes,
-            "dense_kv_bytes_per_step": dense_bytes,
-            "density_evicted": density,
-            "work_items": int(stats[0].n_work_items),
+            "workload": res["workload"],
+            "cache_instances_rotated": res["cache_instances_rotated"],
+            "kept_kv_bytes_per_step": res["kept_kv_bytes_per_step"],
+            "dense_kv_bytes_per_step": res["dense_kv_bytes_per_step"],
+            "density_evicted": res["density_evicted"],
+            "work_items": res["work_items"],
         },
-        "step_entry": ("spkv_decode_step (fused append + decode, 2 launches)" if fused else
-                       "spkv_append + spkv_decode_attention (3 launches)"),
-        "us_per_step_other_entry": dt_other / K * 1e6,
-        "us_per_step_one_instance_warm_cache": dt_hot / K * 1e6,
-        "step_with_predictor": predictor_leg,
-        "host_issue_us_per_step": host_issue_us,
-        "decode_only_us": dt_dec / K * 1e6,
-        "append_only_us": dt_app / K * 1e6,
-        "frac_of_hbm_peak_step": kept_bytes / (dt / K) / 1e9 / HBM_PEAK_GBPS,
-        "dense_cache": dense,
-        "prefill_append": dict(PREFILL_TIMING),
-        "multi_token_step": chunk_legs,
-        "prefill_attention": prefill_attn,
-        "roofline": {
-            "bound": "hbm", "kernel": "spkv_decode_split<128>",
-            "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": read_traffic_summary(),
-            "algorithmic_bytes_per_launch": kept_bytes,
-            "kernel_avg_us": kern_avg_ms * 1e3,
-            "launches_timed": K,
-            "timing": "HIP events around K back-to-back launches of the split-K kernel alone",
-            "kernel_avg_us_event_pair_per_launch": float(np.mean(kern_ms)) * 1e3,
-            "us_per_step_with_event_pair_per_launch": dt_ev / K * 1e6,
-        },
-        "cpu_baseline": cpu,
+        "step_entry": ("spkv_decode_step (fused append + decode)" if fused else
+                       "spkv_append + spkv_decode_attention"),
+        "frac_of_hbm_peak_step": res["frac_of_hbm_peak_step"],
+        "host_issue_us_per_step": res["host_issue_us_per_step"],
+        "hip_graph_replay": res["hip_graph_replay"],
     }
+    for key in res:
+        if key.startswith("us_per_step_with_"):
+            result[key] = res[key]
+    result.update(extra)
+    result["dense_cache"] = res.get("dense_cache")
+    result["roofline"] = res["roofline"]
+    result["read_ceiling"] = res["read_ceiling"]
+    result["cpu_baseline"] = res["cpu_baseline"]
+    if others:
+        result["configs"] = others
     print(json.dumps(result))
 
 

@@ -112,6 +112,13 @@ typedef struct spkv_stats {
                                       1, 2 or 4; 0 (default) = chosen per call from the number
                                       of (sequence, KV head) pairs and their lengths           */
 
+#define SPKV_OPT_STEP_LAUNCHES  6  /* kernel launches of spkv_decode_step and spkv_decode_attention:
+                                      1: one -- the last workgroup of every (sequence, KV head) to
+                                      finish merges the pair's partial results and, in the step,
+                                      performs the pair's append; 2: a second launch merges (and
+                                      appends); 0 (default) = chosen per call.  Same results up to
+                                      the order of fp32 sums                                       */
+
 /* Bytes of device arena a cache with this configuration needs (0 if cfg is invalid).
  * Host-only; touches no device.  Capacity rule (appendix "Inference Kernels": pages are
  * given out from a pool with headroom): the long-term cache can hold
@@ -196,8 +203,8 @@ int spkv_decode_attention(spkv_cache_t* cache, const void* q, void* out, float* 
 int spkv_decode_attention_static(spkv_cache_t* cache, const void* q, void* out, float* lse,
                                  float sm_scale, void* stream);
 
-/* One whole decode step in two kernel launches instead of three: the same result and the
- * same cache state as
+/* One whole decode step in one kernel launch (or two, SPKV_OPT_STEP_LAUNCHES) instead of
+ * three: the same result and the same cache state as
  *     spkv_append(cache, k, v, util_logits, {0, 1, .., batch}, stream);
  *     spkv_decode_attention(cache, q, out, lse, sm_scale, stream);
  * (appendix "Inference Kernels" for the write, Eq. 3-5 for the read), for the case of exactly
@@ -205,10 +212,12 @@ int spkv_decode_attention_static(spkv_cache_t* cache, const void* q, void* out, 
  *   k, v         device bf16 [batch, n_kv_heads, head_dim]   (the new token's pair)
  *   util_logits  device fp32 [batch, n_kv_heads]
  *   q, out, lse, sm_scale as for spkv_decode_attention
- * The split-K kernel attends to the cache as it stands plus the new pair read from k / v,
- * leaving out the pair the new token pushes out of the window unless it passes the gate;
- * the second kernel merges the partials and then performs the append.  Sequences may be
- * empty before the call.  Errors as for spkv_append (SPKV_E_CAPACITY before any launch). */
+ * The split-K kernel attends to the cache as it stands, leaving out the pair the new token
+ * pushes out of the window unless it passes the gate; the merge of the partial results adds
+ * the new pair's own term, read from k / v, and the append follows it -- both by the last
+ * workgroup of every (sequence, KV head) to finish (appendix "Inference Kernels": one fused
+ * kernel per step), or by a second launch.  Sequences may be empty before the call.  Errors
+ * as for spkv_append (SPKV_E_CAPACITY before any launch). */
 int spkv_decode_step(spkv_cache_t* cache, const void* k, const void* v, const float* util_logits,
                      const void* q, void* out, float* lse, float sm_scale, void* stream);
 

@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     SPKVCache, SPKVConfig, SPKVStats, SPKVError, load_library, library_path,
     required_bytes, strerror, layout_offset, debug_copy, debug_read, utility_logits, soft_gated_attention,
     EXPORTED_SYMBOLS,
-    OPT_ITEM_TARGET, OPT_KERNEL_TIMING, OPT_SPLIT_ONLY, OPT_SINK_TOKENS, OPT_MERGE_WAVES,
+    OPT_ITEM_TARGET, OPT_KERNEL_TIMING, OPT_SPLIT_ONLY, OPT_SINK_TOKENS, OPT_MERGE_WAVES, OPT_STEP_LAUNCHES,
 )

@@ -16,6 +16,7 @@ _LIB = None
 
 OK, E_INVAL, E_STATE, E_CAPACITY, E_HIP, E_NOMEM, E_DEVICE = 0, -1, -2, -3, -4, -5, -6
 OPT_ITEM_TARGET, OPT_KERNEL_TIMING, OPT_SPLIT_ONLY, OPT_SINK_TOKENS, OPT_MERGE_WAVES = 1, 2, 3, 4, 5
+OPT_STEP_LAUNCHES = 6
 MAX_BATCH, PAGE_TOKENS = 512, 64
 
 EXPORTED_SYMBOLS = [

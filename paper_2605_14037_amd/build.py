@@ -21,7 +21,7 @@ FLAGS = [
 # Waves per SIMD the decode kernels are expected to reach (registers decide it, and the
 # register count depends on how the compiler schedules loads against MFMAs): the library
 # adapts its work-item count to whatever the runtime reports, but a drop costs bandwidth.
-EXPECTED_OCCUPANCY = {"spkv_decode_splitILi128ELb0": 3, "spkv_decode_splitILi128ELb1": 3}
+EXPECTED_OCCUPANCY = {"spkv_decode_splitILi128E": 3}      # every mode and merge width at head_dim 128
 
 
 def _check_occupancy(remarks: str) -> list:

@@ -25,7 +25,7 @@ struct Carve {
     size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, free_top, free_pages, err_flag,
         page_table, pool,
         pos_pool, logit_pool, seg_count, seg_on, bulk_info, part_acc, part_ml, pair_items,
-        pos_scratch, total;
+        pair_ticket, pos_scratch, total;
     int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items;
 };
 
@@ -89,6 +89,7 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.part_acc = take((size_t)k.max_items * k.G * c->head_dim * 4);
     k.part_ml = take((size_t)k.max_items * k.G * 2 * 4);
     k.pair_items = take((size_t)k.n_pairs * 4);
+    k.pair_ticket = take((size_t)k.n_pairs * 4);
     k.pos_scratch = take((size_t)k.pt_cap * kPageTokens * 4);
     k.total = off;
     *out = k;
@@ -158,6 +159,7 @@ struct spkv_cache {
     std::vector<int32_t> snap_ev; // per sequence: pairs pushed out of the window since the copy
     int item_target;
     int merge_waves;              // SPKV_OPT_MERGE_WAVES (0 = per call)
+    int step_launches;            // SPKV_OPT_STEP_LAUNCHES (0 = per call)
     int n_sink;                   // always-kept first positions (SPKV_OPT_SINK_TOKENS)
     int one_round_items;          // items the chip runs in one resident round, with a margin
     int chunk_round_items[3];     // the same for the chunk kernel with 1, 2, 4 column groups
@@ -209,6 +211,7 @@ void bind_view(spkv_cache* c) {
     v.part_acc = reinterpret_cast<float*>(a + k.part_acc);
     v.part_ml = reinterpret_cast<float*>(a + k.part_ml);
     v.pair_items = reinterpret_cast<int32_t*>(a + k.pair_items);
+    v.pair_ticket = reinterpret_cast<int32_t*>(a + k.pair_ticket);
     v.pos_scratch = reinterpret_cast<int32_t*>(a + k.pos_scratch);
 }
 
@@ -355,6 +358,13 @@ SpkvSplit choose_split(const spkv_cache* c) {
     return choose_split(c, c->one_round_items, c->carve.max_items);
 }
 
+// One launch (merge and append by the last workgroup of every pair) or two (a merge launch)
+// for the single-token decode calls.
+bool one_launch(const spkv_cache* c) {
+    if (c->step_launches != 0) return c->step_launches == 1;
+    return false;
+}
+
 // Tokens sequence b receives in a call: from cu_seqlens, or one each (cu == nullptr).
 int tokens_for(const int32_t* cu, int b) { return cu == nullptr ? 1 : cu[b + 1] - cu[b]; }
 
@@ -439,6 +449,7 @@ int spkv_cache_create(const spkv_config_t* cfg, void* dev_arena, size_t arena_by
     c->snap_ev.assign(cfg->batch, 0);
     c->item_target = 0;
     c->merge_waves = 0;
+    c->step_launches = 0;
     c->n_sink = 0;
     {
         // Measured on MI355X: up to 94 % of the resident slots run in one round; at 99 % some
@@ -605,7 +616,7 @@ int spkv_decode_step(spkv_cache_t* c, const void* k, const void* v, const float*
     if (spkv_launch_decode_step(c->view, static_cast<const uint16_t*>(k),
                                 static_cast<const uint16_t*>(v), util_logits,
                                 static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out), lse,
-                                sm_scale, c->split, s) != hipSuccess)
+                                sm_scale, c->split, one_launch(c), s) != hipSuccess)
         return SPKV_E_HIP;
     commit_lengths(c, nullptr);
     return SPKV_OK;
@@ -695,7 +706,7 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
     }
     c->split = choose_split(c);
     if (spkv_launch_decode(c->view, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
-                           lse, sm_scale, c->split, c->split_only, ev0, ev1, s) != hipSuccess)
+                           lse, sm_scale, c->split, c->split_only, one_launch(c), ev0, ev1, s) != hipSuccess)
         return SPKV_E_HIP;
     return SPKV_OK;
 }
@@ -721,7 +732,7 @@ int spkv_decode_attention_static(spkv_cache_t* c, const void* q, void* out, floa
     c->split = choose_split(c, c->one_round_items, cap);
     if ((int64_t)c->carve.n_pairs * c->split.slots > cap) return SPKV_E_CAPACITY;
     if (spkv_launch_decode(v, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out), lse,
-                           sm_scale, c->split, false, nullptr, nullptr,
+                           sm_scale, c->split, false, false, nullptr, nullptr,
                            static_cast<hipStream_t>(stream)) != hipSuccess)
         return SPKV_E_HIP;
     return SPKV_OK;
@@ -1178,6 +1189,10 @@ int spkv_cache_set_option(spkv_cache_t* c, int32_t option, int64_t value) {
         case SPKV_OPT_MERGE_WAVES:
             if (value != 0 && value != 1 && value != 2 && value != 4) return SPKV_E_INVAL;
             c->merge_waves = (int)value;
+            return SPKV_OK;
+        case SPKV_OPT_STEP_LAUNCHES:
+            if (value != 0 && value != 1 && value != 2) return SPKV_E_INVAL;
+            c->step_launches = (int)value;
             return SPKV_OK;
         case SPKV_OPT_SINK_TOKENS:
             if (value < 0 || value > c->cfg.max_context) return SPKV_E_INVAL;

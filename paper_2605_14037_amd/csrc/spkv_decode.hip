@@ -29,6 +29,23 @@
 // the pair in it passes the gate (it is the pair leaving the window: kept -> it stays
 // attended, as the next long-term entry; dropped -> it is gone), and publishes every
 // pair's item count for spkv_combine_append, which adds the new token's own term.
+//
+// Modes of the split kernel:
+//   kSplitPlain     partials only (spkv_decode_attention in two launches, split-only timing)
+//   kSplitFusedTwo  first launch of the two-launch fused step (FUSED above)
+//   kSplitMerge     one launch for spkv_decode_attention: every workgroup of a (sequence, KV
+//                   head), with or without work, takes a ticket of the pair once its partial
+//                   (stored through to device scope) has arrived; the one that draws the last
+//                   ticket -- all partials of the pair are then visible to it after a
+//                   device-scope acquire -- merges them and writes `out` / `lse`
+//   kSplitStep      one launch for the whole fused step: kSplitMerge in the state before the
+//                   append (FUSED masking), the merging workgroup adds the new token's own term
+//                   and then performs the pair's append.  Workgroups without work take a
+//                   ticket too because they have read the pair's counters: the append may only
+//                   change them once nobody will read them again in this launch.
+// No workgroup ever waits for another: tickets are a single fetch-and-add, so the launch
+// drains whatever the order in which its workgroups run.
+constexpr int kSplitPlain = 0, kSplitFusedTwo = 1, kSplitMerge = 2, kSplitStep = 3;
 constexpr int kMergePad = 16;    // floats between the rows of the LDS copy: no bank conflicts for G = 4
 
 static size_t split_lds_bytes(int mw, int group, int head_dim) {
@@ -36,16 +53,14 @@ static size_t split_lds_bytes(int mw, int group, int head_dim) {
     return ((size_t)mw * group * (head_dim + kMergePad) + 2 * mw * 16) * sizeof(float);
 }
 
-template <int D, bool FUSED, int MW>
-__device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint16_t* __restrict__ q,
-                                                  float scale_log2e, SpkvSplit sp, int wg, float* s_mem) {
+// The work of one workgroup that has some: MW items of pair `pair`, their partial to slot
+// pair * slots + jj.
+template <int D, bool FUSED, int MW, bool SHARED>
+__device__ __forceinline__ void split_compute(const SpkvView& v, const uint16_t* __restrict__ q,
+                                              float scale_log2e, SpkvSplit sp, const PairSplit& ps,
+                                              int pair, int jj, float* s_mem) {
     constexpr int NS = D / 32;   // head-dim slabs of one K tile
     constexpr int NB = D / 16;   // 16-wide output blocks
-    const int pair = wg / sp.slots;
-    const int jj = wg - pair * sp.slots;
-    const PairSplit ps = pair_split(v, pair, sp);
-    if (FUSED && jj == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.groups;
-    if (jj >= ps.groups) return;          // the whole workgroup
     const int wave = MW == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     const int j = jj * MW + wave;
     // a wave past the pair's last item takes an empty range and joins the merge with weight 0
@@ -130,15 +145,24 @@ __device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint1
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     const size_t slot = (size_t)pair * sp.slots + jj;
+    // SHARED: the partial is read by another workgroup of this launch (see ticket_merge)
     if (MW == 1) {
         if (n < v.G) {
             float* pa = v.part_acc + (slot * v.G + n) * D + kc * 4;
 #pragma unroll
-            for (int db = 0; db < NB; ++db) *reinterpret_cast<f32x4*>(pa + db * 16) = acc[db];
+            for (int db = 0; db < NB; ++db) {
+                if (SHARED) store_device_b128(pa + db * 16, acc[db]);
+                else *reinterpret_cast<f32x4*>(pa + db * 16) = acc[db];
+            }
             if (kc == 0) {
                 float* pm = v.part_ml + (slot * v.G + n) * 2;
-                pm[0] = m;
-                pm[1] = l;
+                if (SHARED) {
+                    store_device_b32(pm, m);
+                    store_device_b32(pm + 1, l);
+                } else {
+                    pm[0] = m;
+                    pm[1] = l;
+                }
             }
         }
         return;
@@ -176,13 +200,205 @@ __device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint1
             a += sc * s_acc[(w * v.G + g) * kRow + d];
             lsum += sc * s_l[w * 16 + g];
         }
-        v.part_acc[(slot * v.G + g) * D + d] = a;
-        if (d == 0) {
-            float* pm = v.part_ml + (slot * v.G + g) * 2;
-            pm[0] = M;
-            pm[1] = lsum;
+        float* pa = v.part_acc + (slot * v.G + g) * D + d;
+        float* pm = v.part_ml + (slot * v.G + g) * 2;
+        if (SHARED) {
+            store_device_b32(pa, a);
+            if (d == 0) {
+                store_device_b32(pm, M);
+                store_device_b32(pm + 1, lsum);
+            }
+        } else {
+            *pa = a;
+            if (d == 0) {
+                pm[0] = M;
+                pm[1] = lsum;
+            }
         }
     }
+}
+
+// Inputs and outputs of the merging workgroup (modes with a ticket).
+struct SpkvStepIO {
+    uint16_t* out;            // [B][Hq][D]
+    float* lse;               // [B][Hq] or null
+    const uint16_t* k_new;    // fused step: the new token's pair and logits
+    const uint16_t* v_new;
+    const float* f_new;
+};
+
+// Ticket and merge.  Every workgroup of the pair calls this once, after its partial (if it
+// had work) has been stored.  In the merging workgroup a thread owns eight consecutive
+// floats of the pair's G x D outputs (a "unit": two float4 of one head); the waves share the
+// partials round-robin, their loads go out eight partials at a time and only the cheap
+// rescaling is chained; with several waves the wave results meet in LDS.
+template <int D, bool STEP, int MW>
+__device__ __forceinline__ void ticket_merge(const SpkvView& v, const uint16_t* __restrict__ q,
+                                             float scale_log2e, SpkvSplit sp, const PairSplit& ps,
+                                             int pair, float* s_mem, int* s_page, const SpkvStepIO& io) {
+    constexpr int NT = 64 * MW, UPH = D / 8, U = 8, kRow = D + kMergePad;
+    const int tid = threadIdx.x;
+    wait_all_vmem();          // this thread's partial stores (written through) have arrived
+    int ticket = 0;
+    if (MW == 1) {
+        if (tid == 0) ticket = atomicAdd(v.pair_ticket + pair, 1);
+        ticket = __builtin_amdgcn_readfirstlane(ticket);
+    } else {
+        int* s_t = reinterpret_cast<int*>(s_mem);
+        __syncthreads();                                     // all threads released; LDS is free
+        if (tid == 0) *s_t = atomicAdd(v.pair_ticket + pair, 1);
+        __syncthreads();
+        ticket = *s_t;
+        __syncthreads();                                     // before LDS is written again
+    }
+    if (ticket != sp.slots - 1) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");       // the others' partials
+    if (tid == 0) v.pair_ticket[pair] = 0;                   // for the next launch
+
+    const int b = pair / v.Hkv, h = pair - b * v.Hkv;
+    const int lane = tid & 63, wave = MW == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid >> 6);
+    const size_t kv_row = ((size_t)b * v.Hkv + h) * D;
+    const int n_part = ps.groups, NU = v.G * UPH;            // units of the pair
+    const size_t slot0 = (size_t)pair * sp.slots;
+    float* s_acc = s_mem;                                    // [MW][G][kRow]   (MW > 1 only)
+    float* s_m = s_mem + MW * v.G * kRow;                    // [MW][16]
+    float* s_l = s_m + MW * 16;
+
+    // The finish of one unit: the new token's own term (step), normalisation, bf16, store.
+    auto finish = [&](int g, int d8, bool ok, float M, float den, const f32x4 (&acc)[2]) {
+        const size_t o_row = (size_t)b * v.Hq + (size_t)h * v.G + g;
+        float Mt = M, w_tok = 0.f;
+        f32x4 vn[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        if (STEP) {
+            // score q . k_new in fp32 (the UPH lanes of a head add up), weight sum 1, value v_new
+            const uint4 qe = *reinterpret_cast<const uint4*>(q + o_row * D + d8 * 8);
+            const uint4 ke = *reinterpret_cast<const uint4*>(io.k_new + kv_row + d8 * 8);
+            const uint4 ve = *reinterpret_cast<const uint4*>(io.v_new + kv_row + d8 * 8);
+            const unsigned qw[4] = {qe.x, qe.y, qe.z, qe.w}, kw[4] = {ke.x, ke.y, ke.z, ke.w};
+            const unsigned vw[4] = {ve.x, ve.y, ve.z, ve.w};
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dot += __builtin_bit_cast(float, qw[e] << 16) * __builtin_bit_cast(float, kw[e] << 16);
+                dot += __builtin_bit_cast(float, qw[e] & 0xffff0000u) * __builtin_bit_cast(float, kw[e] & 0xffff0000u);
+                vn[e >> 1][(e & 1) * 2] = __builtin_bit_cast(float, vw[e] << 16);
+                vn[e >> 1][(e & 1) * 2 + 1] = __builtin_bit_cast(float, vw[e] & 0xffff0000u);
+            }
+            if (!ok) dot = 0.f;
+#pragma unroll
+            for (int o = UPH / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+            const float m_tok = dot * scale_log2e;
+            Mt = fmaxf(M, m_tok);
+            w_tok = __builtin_amdgcn_exp2f(m_tok - Mt);
+        }
+        const float m_ref = (Mt == SPKV_NEG_INF) ? 0.f : Mt;
+        const float sc = __builtin_amdgcn_exp2f(M - m_ref);
+        const float dsum = den * sc + w_tok;
+        if (ok) {
+            unsigned pk[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float x0 = (acc[e >> 1][(e & 1) * 2] * sc + vn[e >> 1][(e & 1) * 2] * w_tok) / dsum;
+                const float x1 = (acc[e >> 1][(e & 1) * 2 + 1] * sc + vn[e >> 1][(e & 1) * 2 + 1] * w_tok) / dsum;
+                const __bf16 r0 = (__bf16)x0, r1 = (__bf16)x1;
+                pk[e] = (unsigned)__builtin_bit_cast(uint16_t, r0) | ((unsigned)__builtin_bit_cast(uint16_t, r1) << 16);
+            }
+            *reinterpret_cast<uint4*>(io.out + o_row * D + d8 * 8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            if (io.lse != nullptr && d8 == 0) io.lse[o_row] = (Mt + log2f(dsum)) * 0.6931471805599453f;
+        }
+    };
+
+    AppendRegs<D, NT> ar;
+    if (STEP)      // the append's loads travel while the partials are merged
+        ar = append_load<D, NT>(v, pair, h, b, ps.T, ps.L, io.k_new, io.v_new,
+                                io.f_new[(size_t)b * v.Hkv + h], tid);
+
+    for (int u0 = 0; u0 < NU; u0 += 64) {        // every wave: all units, its share of the partials
+        const int unit = u0 + lane;
+        const bool ok = unit < NU;
+        const int g = ok ? unit / UPH : 0, d8 = ok ? unit - g * UPH : 0;
+        float M = SPKV_NEG_INF, den = 0.f;
+        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        for (int i0 = wave; i0 < n_part; i0 += U * MW) {
+            f32x4 a[U][2];
+            float2 ml[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t row = (slot0 + min(i0 + u * MW, n_part - 1)) * v.G + g;   // past the end: re-read, ignored
+                const float* pa = v.part_acc + row * D + d8 * 8;
+                a[u][0] = *reinterpret_cast<const f32x4*>(pa);
+                a[u][1] = *reinterpret_cast<const f32x4*>(pa + 4);
+                ml[u] = *reinterpret_cast<const float2*>(v.part_ml + row * 2);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (i0 + u * MW < n_part) {
+                    const float m_new = fmaxf(M, ml[u].x);
+                    const float m_ref = (m_new == SPKV_NEG_INF) ? 0.f : m_new;   // partials with no key: weight 0
+                    const float so = __builtin_amdgcn_exp2f(M - m_ref);
+                    const float si = __builtin_amdgcn_exp2f(ml[u].x - m_ref);
+                    den = den * so + ml[u].y * si;
+                    acc[0] = acc[0] * so + a[u][0] * si;
+                    acc[1] = acc[1] * so + a[u][1] * si;
+                    M = m_new;
+                }
+            }
+        }
+        if (MW == 1) {
+            finish(g, d8, ok, M, den, acc);
+        } else if (ok) {
+            float* pa = s_acc + (wave * v.G + g) * kRow + d8 * 8;
+            *reinterpret_cast<f32x4*>(pa) = acc[0];
+            *reinterpret_cast<f32x4*>(pa + 4) = acc[1];
+            if (d8 == 0) {
+                s_m[wave * 16 + g] = M;
+                s_l[wave * 16 + g] = den;
+            }
+        }
+    }
+    if (MW > 1) {
+        __syncthreads();
+        for (int u0 = 0; u0 < NU; u0 += NT) {
+            const int unit = u0 + tid;
+            const bool ok = unit < NU;
+            const int g = ok ? unit / UPH : 0, d8 = ok ? unit - g * UPH : 0;
+            float mw[MW], M = SPKV_NEG_INF;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) {
+                mw[w] = s_m[w * 16 + g];
+                M = fmaxf(M, mw[w]);
+            }
+            const float m_ref = (M == SPKV_NEG_INF) ? 0.f : M;
+            float den = 0.f;
+            f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int w = 0; w < MW; ++w) {
+                const float sc = __builtin_amdgcn_exp2f(mw[w] - m_ref);
+                const float* pa = s_acc + (w * v.G + g) * kRow + d8 * 8;
+                acc[0] += *reinterpret_cast<const f32x4*>(pa) * sc;
+                acc[1] += *reinterpret_cast<const f32x4*>(pa + 4) * sc;
+                den += s_l[w * 16 + g] * sc;
+            }
+            finish(g, d8, ok, M, den, acc);
+        }
+    }
+    if (STEP) append_store<D, NT>(v, pair, ps.T, ps.L, ar, tid, s_page);
+}
+
+template <int D, int MODE, int MW>
+__device__ __forceinline__ void decode_split_item(const SpkvView& v, const uint16_t* __restrict__ q,
+                                                  float scale_log2e, SpkvSplit sp, int wg, float* s_mem,
+                                                  int* s_page, const SpkvStepIO& io) {
+    constexpr bool FUSED = MODE == kSplitFusedTwo || MODE == kSplitStep;
+    const int pair = wg / sp.slots;
+    const int jj = wg - pair * sp.slots;
+    const PairSplit ps = pair_split(v, pair, sp);
+    if (MODE == kSplitFusedTwo && jj == 0 && threadIdx.x == 0) v.pair_items[pair] = ps.groups;
+    constexpr bool TICKET = MODE == kSplitMerge || MODE == kSplitStep;
+    if (jj < ps.groups)       // the whole workgroup
+        split_compute<D, FUSED, MW, TICKET>(v, q, scale_log2e, sp, ps, pair, jj, s_mem);
+    if (MODE == kSplitMerge || MODE == kSplitStep)
+        ticket_merge<D, MODE == kSplitStep, MW>(v, q, scale_log2e, sp, ps, pair, s_mem, s_page, io);
 }
 
 // Merge workgroups of 16 waves instead of 4: when pairs have more than 64 partials and the
@@ -193,11 +409,12 @@ static bool wide_merge(const SpkvView& v, const SpkvSplit& sp) {
     return sp.slots > 64 && v.n_pairs * v.G <= 256;
 }
 
-template <int D, bool FUSED, int MW>
+template <int D, int MODE, int MW>
 __global__ __launch_bounds__(64 * MW) void spkv_decode_split(SpkvView v, const uint16_t* __restrict__ q,
-                                                             float scale_log2e, SpkvSplit sp) {
+                                                             float scale_log2e, SpkvSplit sp, SpkvStepIO io) {
     extern __shared__ __attribute__((aligned(16))) float s_split[];
-    decode_split_item<D, FUSED, MW>(v, q, scale_log2e, sp, blockIdx.x, s_split);
+    __shared__ int s_page;
+    decode_split_item<D, MODE, MW>(v, q, scale_log2e, sp, blockIdx.x, s_split, &s_page, io);
 }
 
 // Fused step with the utility predictor (Eq. 1; the appendix builds it as Linear - SiLU -
@@ -216,7 +433,9 @@ __global__ __launch_bounds__(64 * MW) void spkv_decode_split_predict(SpkvView v,
     extern __shared__ __attribute__((aligned(16))) float s_split[];
     const int n_pred_wg = (pr.n_blocks + MW - 1) / MW;
     if ((int)blockIdx.x >= n_pred_wg) {
-        decode_split_item<D, true, MW>(v, q, scale_log2e, sp, (int)blockIdx.x - n_pred_wg, s_split);
+        const SpkvStepIO none = {};
+        decode_split_item<D, kSplitFusedTwo, MW>(v, q, scale_log2e, sp, (int)blockIdx.x - n_pred_wg,
+                                                 s_split, nullptr, none);
         return;
     }
     const int unit = (int)blockIdx.x * MW + ((int)threadIdx.x >> 6);
@@ -706,14 +925,14 @@ int spkv_chunk_resident_items(int head_dim, int col_groups) {
 }
 
 // Launch of the split kernel for the call's merge width (1, 2 or 4 waves per workgroup).
-template <int D, bool FUSED>
+template <int D, int MODE>
 static void launch_split(const SpkvView& v, const uint16_t* q, float scale_log2e, SpkvSplit sp,
-                         hipStream_t s) {
+                         const SpkvStepIO& io, hipStream_t s) {
     const dim3 grid((unsigned)v.n_pairs * (unsigned)sp.slots);
     const size_t lds = split_lds_bytes(sp.mw, v.G, D);
-    if (sp.mw == 4) spkv_decode_split<D, FUSED, 4><<<grid, dim3(256), lds, s>>>(v, q, scale_log2e, sp);
-    else if (sp.mw == 2) spkv_decode_split<D, FUSED, 2><<<grid, dim3(128), lds, s>>>(v, q, scale_log2e, sp);
-    else spkv_decode_split<D, FUSED, 1><<<grid, dim3(64), 0, s>>>(v, q, scale_log2e, sp);
+    if (sp.mw == 4) spkv_decode_split<D, MODE, 4><<<grid, dim3(256), lds, s>>>(v, q, scale_log2e, sp, io);
+    else if (sp.mw == 2) spkv_decode_split<D, MODE, 2><<<grid, dim3(128), lds, s>>>(v, q, scale_log2e, sp, io);
+    else spkv_decode_split<D, MODE, 1><<<grid, dim3(64), 0, s>>>(v, q, scale_log2e, sp, io);
 }
 
 template <int D>
@@ -727,14 +946,24 @@ static void launch_split_predict(const SpkvView& v, const uint16_t* q, float sca
 }
 
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
-                              float sm_scale, SpkvSplit sp, bool split_only, hipEvent_t ev0,
-                              hipEvent_t ev1, hipStream_t s) {
+                              float sm_scale, SpkvSplit sp, bool split_only, bool one_launch,
+                              hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
     const float scale_log2e = sm_scale * 1.4426950408889634f;
     if (sp.mw != 1 && sp.mw != 2 && sp.mw != 4) return hipErrorInvalidValue;
     hipError_t e;
+    if (one_launch && !split_only) {
+        const SpkvStepIO io = {out, lse, nullptr, nullptr, nullptr};
+        if (ev0 != nullptr && (e = hipEventRecord(ev0, s)) != hipSuccess) return e;
+        if (v.D == 128) launch_split<128, kSplitMerge>(v, q, scale_log2e, sp, io, s);
+        else launch_split<64, kSplitMerge>(v, q, scale_log2e, sp, io, s);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
+        return hipSuccess;
+    }
+    const SpkvStepIO none = {};
     if (ev0 != nullptr && (e = hipEventRecord(ev0, s)) != hipSuccess) return e;
-    if (v.D == 128) launch_split<128, false>(v, q, scale_log2e, sp, s);
-    else launch_split<64, false>(v, q, scale_log2e, sp, s);
+    if (v.D == 128) launch_split<128, kSplitPlain>(v, q, scale_log2e, sp, none, s);
+    else launch_split<64, kSplitPlain>(v, q, scale_log2e, sp, none, s);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ev1 != nullptr && (e = hipEventRecord(ev1, s)) != hipSuccess) return e;
     if (split_only) return hipSuccess;
@@ -757,26 +986,33 @@ int spkv_split_resident_items(int head_dim) {
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
     const hipError_t e =
         head_dim == 128
-            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<128, false, 1>, 64, 0)
-            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<64, false, 1>, 64, 0);
+            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<128, kSplitStep, 1>, 64, 0)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, spkv_decode_split<64, kSplitStep, 1>, 64, 0);
     if (e != hipSuccess || per_cu <= 0 || cus <= 0) return 0;
     return per_cu * cus;
 }
 
 hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const uint16_t* q, uint16_t* out, float* lse,
-                                   float sm_scale, SpkvSplit sp, hipStream_t s) {
+                                   float sm_scale, SpkvSplit sp, bool one_launch, hipStream_t s) {
     const float scale_log2e = sm_scale * 1.4426950408889634f;
     if (sp.mw != 1 && sp.mw != 2 && sp.mw != 4) return hipErrorInvalidValue;
+    if (one_launch) {
+        const SpkvStepIO io = {out, lse, k, vv, f};
+        if (v.D == 128) launch_split<128, kSplitStep>(v, q, scale_log2e, sp, io, s);
+        else launch_split<64, kSplitStep>(v, q, scale_log2e, sp, io, s);
+        return hipGetLastError();
+    }
+    const SpkvStepIO no_io = {};
     const SpkvPredict none = {};
     const dim3 grid2(v.n_pairs * v.G + v.n_pairs);
     const bool wide = wide_merge(v, sp);
     if (v.D == 128) {
-        launch_split<128, true>(v, q, scale_log2e, sp, s);
+        launch_split<128, kSplitFusedTwo>(v, q, scale_log2e, sp, no_io, s);
         if (wide) spkv_combine_append<128, false, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
         else spkv_combine_append<128, false, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
     } else {
-        launch_split<64, true>(v, q, scale_log2e, sp, s);
+        launch_split<64, kSplitFusedTwo>(v, q, scale_log2e, sp, no_io, s);
         if (wide) spkv_combine_append<64, false, 16><<<grid2, dim3(1024), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
         else spkv_combine_append<64, false, 4><<<grid2, dim3(256), 0, s>>>(v, out, lse, sp, k, vv, f, q, scale_log2e, none);
     }

@@ -28,6 +28,22 @@ __device__ __forceinline__ bf16x8 load_stream_b128(const uint16_t* p) {
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// Stores that other compute dies (each has its own L2) may read later in the SAME launch:
+// written through to device scope, so that waiting for the wave's outstanding stores is all
+// it takes to make them visible -- no write-back of the whole L2 (a device-scope release fence
+// costs that, and thousands of them per launch were measured at +200 us).
+// (The s_nop: a store of more than 8 bytes reads its data registers up to two cycles after it
+// issues, and the compiler, which keeps that distance for its own stores, does not look into
+// an asm statement -- without it the next instruction may overwrite the data.)
+__device__ __forceinline__ void store_device_b128(float* p, f32x4 x) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(x) : "memory");
+}
+__device__ __forceinline__ void store_device_b32(float* p, float x) {
+    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Waits for every vector memory operation of this wave, the stores above included.
+__device__ __forceinline__ void wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+
 __device__ __forceinline__ int mbcnt64(unsigned long long mask) {
     return __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
                                      __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
@@ -127,23 +143,27 @@ __device__ __forceinline__ f32x4 predictor_contract(const uint16_t* __restrict__
 // halves so that a caller can put other work between the loads and the stores.
 // `row` indexes the new token in k/vv, f_new is its logit for this head; T and L are the
 // pair's counters as read by every thread before any of them is updated.
-template <int D>
+// NT = threads that take part (a multiple of 64); thread tid moves V elements tid,
+// tid + NT, ... (one per thread when NT >= D).
+template <int D, int NT = D>
 struct AppendRegs {
+    static constexpr int VPT = (D + NT - 1) / NT;
     float f_old, f_new;
     int page_entry;
-    uint16_t v_new, v_old;
+    uint16_t v_new[VPT], v_old[VPT];
     uint4 k_new, k_old;
 };
 
 // Everything the counters address, issued together (the outgoing row is read before it is
 // known whether it is kept: 2 + 16 bytes per thread).
-template <int D>
-__device__ __forceinline__ AppendRegs<D> append_load(const SpkvView& v, int pair, int h, int row,
-                                                     int T, int L, const uint16_t* __restrict__ k,
-                                                     const uint16_t* __restrict__ vv,
-                                                     float f_new, int tid) {
-    AppendRegs<D> r;
-    const bool mover = tid < D, kmover = tid < D / 8;
+template <int D, int NT = D>
+__device__ __forceinline__ AppendRegs<D, NT> append_load(const SpkvView& v, int pair, int h, int row,
+                                                         int T, int L, const uint16_t* __restrict__ k,
+                                                         const uint16_t* __restrict__ vv,
+                                                         float f_new, int tid) {
+    AppendRegs<D, NT> r;
+    constexpr int VPT = AppendRegs<D, NT>::VPT;
+    const bool kmover = tid < D / 8;
     const int slot = T % v.w;
     const uint16_t* rp = ring_page(v, pair, slot >> 6);
     const int rk = slot & 63;
@@ -153,23 +173,30 @@ __device__ __forceinline__ AppendRegs<D> append_load(const SpkvView& v, int pair
     r.f_old = full ? v.ring_logit[(size_t)pair * v.w + slot] : 0.f;
     r.page_entry = (gk != 0 && lp < v.pt_cap) ? v.page_table[(size_t)pair * v.pt_cap + lp] : -1;
     r.f_new = f_new;
-    r.v_new = 0;
-    r.v_old = 0;
     r.k_new = make_uint4(0u, 0u, 0u, 0u);
     r.k_old = make_uint4(0u, 0u, 0u, 0u);
-    if (mover) r.v_new = vv[src + tid];
-    if (kmover) r.k_new = *reinterpret_cast<const uint4*>(k + src + tid * 8);
-    if (full) {
-        if (mover) r.v_old = rp[spkv_v_off(D, rk, tid)];
-        if (kmover) r.k_old = *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const int d = tid + j * NT;
+        r.v_new[j] = 0;
+        r.v_old[j] = 0;
+        if (d < D) {
+            r.v_new[j] = vv[src + d];
+            if (full) r.v_old[j] = rp[spkv_v_off(D, rk, d)];
+        }
+    }
+    if (kmover) {
+        r.k_new = *reinterpret_cast<const uint4*>(k + src + tid * 8);
+        if (full) r.k_old = *reinterpret_cast<const uint4*>(rp + spkv_k_off(D, rk, tid * 8));
     }
     return r;
 }
 
-template <int D>
+template <int D, int NT = D>
 __device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T, int L,
-                                             const AppendRegs<D>& r, int tid, int* s_page) {
-    const bool mover = tid < D, kmover = tid < D / 8;
+                                             const AppendRegs<D, NT>& r, int tid, int* s_page) {
+    constexpr int VPT = AppendRegs<D, NT>::VPT;
+    const bool kmover = tid < D / 8;
     const int slot = T % v.w;
     uint16_t* rp = ring_page(v, pair, slot >> 6);
     const int rk = slot & 63;
@@ -190,7 +217,11 @@ __device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T,
         }
         if (page >= 0) {
             uint16_t* gp = pool_page(v, page);
-            if (mover) gp[spkv_v_off(D, gk, tid)] = r.v_old;
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) {
+                const int d = tid + j * NT;
+                if (d < D) gp[spkv_v_off(D, gk, d)] = r.v_old[j];
+            }
             if (kmover) *reinterpret_cast<uint4*>(gp + spkv_k_off(D, gk, tid * 8)) = r.k_old;
             if (tid == 0) {
                 v.pos_pool[(size_t)page * kPageTokens + gk] = T - v.w;
@@ -199,7 +230,11 @@ __device__ __forceinline__ void append_store(const SpkvView& v, int pair, int T,
             }
         }
     }
-    if (mover) rp[spkv_v_off(D, rk, tid)] = r.v_new;
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const int d = tid + j * NT;
+        if (d < D) rp[spkv_v_off(D, rk, d)] = r.v_new[j];
+    }
     if (kmover) *reinterpret_cast<uint4*>(rp + spkv_k_off(D, rk, tid * 8)) = r.k_new;
     if (tid == 0) {
         v.ring_logit[(size_t)pair * v.w + slot] = r.f_new;

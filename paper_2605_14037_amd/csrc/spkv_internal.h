@@ -41,6 +41,7 @@ struct SpkvView {
     float*    part_acc;     // [max_items][G][D] un-normalised partial outputs
     float*    part_ml;      // [max_items][G][2] running max (log2 domain) and sum
     int32_t*  pair_items;   // [n_pairs] fused step: item count of every pair, split -> combine
+    int32_t*  pair_ticket;  // [n_pairs] one-launch decode: workgroups of the pair that are done (0 between launches)
     int32_t*  pos_scratch;  // [pt_cap * 64] gather buffer for kept positions
 };
 
@@ -76,12 +77,14 @@ struct SpkvSplit {
     int32_t mw;
 };
 
+// one_launch: the last workgroup of every pair merges (and, in the step, appends) inside the
+// split launch; otherwise a second launch does.
 hipError_t spkv_launch_decode(const SpkvView& v, const uint16_t* q, uint16_t* out, float* lse,
-                              float sm_scale, SpkvSplit split, bool split_only, hipEvent_t ev0,
-                              hipEvent_t ev1, hipStream_t s);
+                              float sm_scale, SpkvSplit split, bool split_only, bool one_launch,
+                              hipEvent_t ev0, hipEvent_t ev1, hipStream_t s);
 hipError_t spkv_launch_decode_step(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const uint16_t* q, uint16_t* out, float* lse,
-                                   float sm_scale, SpkvSplit split, hipStream_t s);
+                                   float sm_scale, SpkvSplit split, bool one_launch, hipStream_t s);
 // Utility predictor riding in the fused step (Eq. 1): inputs, the fp32 partial sums of the
 // hidden layer between the two launches, and the logits it leaves for the caller.
 constexpr int kPredictSplit = 4;      // ranges d_model is cut into

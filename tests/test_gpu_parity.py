@@ -158,11 +158,13 @@ def test_split_count_invariance():
         assert (o - outs[0]).abs().max().item() <= 2e-2 * max(1.0, outs[0].abs().max().item())
 
 
+@pytest.mark.parametrize("launches", [1, 2])
 @pytest.mark.parametrize("merge", [1, 2, 4])
 @pytest.mark.parametrize("D,Hq,Hk", [(128, 8, 2), (64, 16, 1), (128, 4, 4)])
-def test_every_merge_width_in_every_single_token_entry_point(merge, D, Hq, Hk):
+def test_every_merge_width_in_every_single_token_entry_point(merge, D, Hq, Hk, launches):
     """One, two or four work items per workgroup (forced; by default the library picks per
-    call): plain decode, fused step and step with the predictor against the oracle, with lists
+    call), merged by the last workgroup of every pair inside the launch or by a second launch:
+    plain decode, fused step and step with the predictor against the oracle, with lists
     of 1 to about 60 half-pages so that some workgroups have waves without an item, and with
     item targets from one workgroup per pair to one item per half-page."""
     from oracle.spkv_oracle import utility_logits as oracle_logits
@@ -179,6 +181,7 @@ def test_every_merge_width_in_every_single_token_entry_point(merge, D, Hq, Hk):
         oracle = H.make_oracle(wl)
         cache.set_option(spkv.OPT_MERGE_WAVES, merge)
         cache.set_option(spkv.OPT_ITEM_TARGET, target)
+        cache.set_option(spkv.OPT_STEP_LAUNCHES, launches)
         H.prefill(cache, oracle, stream, wl, 1024)
         for i in range(3):
             k, v, f, cu = stream.next_tokens([1] * B)
@@ -207,6 +210,41 @@ def test_every_merge_width_in_every_single_token_entry_point(merge, D, Hq, Hk):
             c.set_option(spkv.OPT_MERGE_WAVES, 3)
         finally:
             c.close()
+
+
+@pytest.mark.parametrize("D,G,Hk", [(128, 1, 2), (128, 2, 3), (128, 3, 1), (128, 4, 2), (128, 8, 1),
+                                    (128, 16, 1), (64, 1, 1), (64, 4, 2), (64, 5, 1), (64, 16, 2)])
+def test_one_launch_merge_for_every_group_size(D, G, Hk):
+    """The merge by the last workgroup of a pair maps threads to the pair's G x D outputs in
+    units of eight floats: every group size from 1 to 16 at both head sizes, every merge
+    width, from one partial per pair to dozens, sequences that start empty, many consecutive
+    fused steps (tickets must be back at zero after every launch), then plain decode."""
+    B = 3
+    wl = small_workload("onelaunch", B, G * Hk, Hk, D, [2100, 0, 333], [[0.8] * Hk, [0.5] * Hk, [0.2] * Hk],
+                        window=48, seed=7 * D + G)
+    for merge, target in ((1, 0), (2, 40), (4, 0), (1, 1), (4, 3)):
+        stream = TokenStream(wl, device="cuda")
+        cache = H.make_cache(wl, extra_context=32)
+        oracle = H.make_oracle(wl)
+        cache.set_option(spkv.OPT_MERGE_WAVES, merge)
+        cache.set_option(spkv.OPT_ITEM_TARGET, target)
+        cache.set_option(spkv.OPT_STEP_LAUNCHES, 1)
+        H.prefill(cache, oracle, stream, wl, 1024)
+        for i in range(12):
+            k, v, f, cu = stream.next_tokens([1] * B)
+            q = stream.next_query()
+            if i < 10:
+                out, lse = cache.decode_step(k, v, f, q, want_lse=True)
+                oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+            else:
+                H.feed(cache, oracle, k, v, f, cu)
+                out, lse = cache.decode_attention(q, want_lse=True)
+            if i in (0, 1, 5, 9, 10, 11):
+                ref_out, ref_lse = oracle.decode(to_numpy_f32(q))
+                H.check_output(out, ref_out, f"G {G} merge {merge} target {target} step {i}")
+                H.check_lse(lse, ref_lse, f"G {G} merge {merge} target {target} step {i}")
+        H.check_state(cache, oracle, wl, label=f"G {G} merge {merge} target {target}")
+        cache.close()
 
 
 @pytest.mark.parametrize("D,Hq,Hk,w", [(128, 8, 2, 64), (64, 4, 2, 16), (128, 16, 1, 128)])
@@ -968,7 +1006,8 @@ def test_sink_tokens_every_entry_point(n_sink, w):
 
 
 # ------------------------------------------------------------- replay from a HIP graph
-def test_decode_step_replayed_from_a_hip_graph():
+@pytest.mark.parametrize("launches", [1, 2])
+def test_decode_step_replayed_from_a_hip_graph(launches):
     """The fused step captured once into a HIP graph and replayed with new inputs in the same
     buffers: every replay (with eager copies, checks and synchronisations between them) must
     equal the oracle's step, the host's bookkeeping is carried by spkv_cache_advance, and the
@@ -976,6 +1015,7 @@ def test_decode_step_replayed_from_a_hip_graph():
     wl = small_workload("graph", 3, 8, 2, 128, [700, 300, 40], [[0.4, 0.1]], window=64, seed=61)
     stream = TokenStream(wl, device="cuda")
     cache = H.make_cache(wl, pool_tokens=3 * 2 * 900, extra_context=200)
+    cache.set_option(spkv.OPT_STEP_LAUNCHES, launches)
     oracle = H.make_oracle(wl)
     H.prefill(cache, oracle, stream, wl, 4096)
 
@@ -997,7 +1037,7 @@ def test_decode_step_replayed_from_a_hip_graph():
         dst.copy_(src)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):                     # records the two launches; runs nothing
+    with torch.cuda.graph(graph):                     # records the launches; runs nothing
         cache.decode_step(ks, vs, fs, qs, out=outs)
     n_replays = 70                                    # crosses page boundaries of the short lists
     for i in range(n_replays):
