@@ -517,9 +517,10 @@ def events_per_launch(fn, n):
 def read_ceiling_leg(nbytes, n_workgroups, launches):
     """A plain streaming read (spkv_debug_read) of the same number of bytes, in scattered 32 KB
     runs (the cache's page size), by as many one-wave workgroups as the decode launch has work
-    items, back to back over a 3 GiB region so that every launch reads cold memory."""
-    region = 3 << 30
+    items, back to back over a region of at least 3 GiB (twice the bytes of a launch) so that
+    every launch reads cold memory."""
     run_bytes = 32768
+    region = max(3 << 30, (2 * int(nbytes) + (1 << 30)) // run_bytes * run_bytes)
     src = torch.empty(region, dtype=torch.uint8, device="cuda")
     src.zero_()
     sink = torch.empty(max(1, n_workgroups) * 1024, dtype=torch.uint8, device="cuda")
@@ -550,7 +551,7 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
     and right after the timed steps (mean of the two)."""
     exp_bytes = (wl.expected_kept_tokens() + wl.batch * wl.n_kv_heads * wl.window) * 4 * wl.head_dim
     R = args.instances or max(2, int(np.ceil(2.5e9 / exp_bytes)))
-    cpu_seqs = min(cpu_seqs, wl.batch)
+    cpu_seqs = min(cpu_seqs, max(1, wl.batch // 4))      # a bounded sample: a quarter of the batch at most
     oracle = None
     if cpu_seqs > 0:
         from oracle.spkv_oracle import SPKVOracle

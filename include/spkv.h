@@ -234,8 +234,12 @@ int spkv_decode_step(spkv_cache_t* cache, const void* k, const void* v, const fl
  *   cu_seqlens   host int32 [batch + 1]
  * Afterwards the cache holds the chunk exactly as after spkv_append of the same tokens.
  * One pass over the cache serves all tokens of a chunk (each K/V tile is read once per
- * (sequence, KV head)).  Needs no workspace.  For chunks of more than 16 / group-size tokens
- * spkv_prefill_attention is the faster call (it picks this one itself for shorter chunks).
+ * (sequence, KV head)).  Needs no workspace.  Two kernels stand behind the multi-token calls
+ * and each shape has one owner: chunks that fit one group of 16 query columns
+ * (n_b * group size <= 16 for every b) run on the split-K kernel of the decode step with the
+ * columns (token, head); wider chunks run on the kernels of spkv_prefill_attention, here with
+ * the staging rows in the cache's own arena.  spkv_prefill_attention routes the same way, so
+ * the two calls cost the same on the shapes both accept.
  * Errors as for spkv_append; SPKV_E_INVAL if a chunk is too long. */
 int spkv_decode_chunk(spkv_cache_t* cache, const void* k, const void* v, const float* util_logits,
                       const void* q, const int32_t* cu_seqlens, void* out, float* lse,

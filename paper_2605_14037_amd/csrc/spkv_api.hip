@@ -25,8 +25,8 @@ struct Carve {
     size_t ring, ring_logit, t_pair, kept_len, gate_on, pool_next, free_top, free_pages, err_flag,
         page_table, pool,
         pos_pool, logit_pool, seg_count, seg_on, bulk_info, part_acc, part_ml, pair_items,
-        pair_ticket, pos_scratch, total;
-    int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items;
+        pair_ticket, pos_scratch, chunk_stage, chunk_prefix, total;
+    int n_pairs, G, n_ring_pages, pt_cap, n_pages, n_seg_cap, max_items, chunk_shp;
 };
 
 bool config_ok(const spkv_config_t* c) {
@@ -91,6 +91,12 @@ bool carve(const spkv_config_t* c, Carve* out) {
     k.pair_items = take((size_t)k.n_pairs * 4);
     k.pair_ticket = take((size_t)k.n_pairs * 4);
     k.pos_scratch = take((size_t)k.pt_cap * kPageTokens * 4);
+    // multi-token steps (spkv_decode_chunk) wider than one group of 16 query columns run on the
+    // prefill kernels: staging half-pages for the window plus 16 new rows per pair, and the
+    // per-token prefix counts
+    k.chunk_shp = (int)(((int64_t)c->window + SPKV_MAX_CHUNK_TOKENS + kHalfTokens - 1) / kHalfTokens);
+    k.chunk_stage = take((size_t)k.n_pairs * k.chunk_shp * ((size_t)2 * kHalfTokens * c->head_dim * 2));
+    k.chunk_prefix = take((size_t)c->batch * SPKV_MAX_CHUNK_TOKENS * c->n_kv_heads * 4);
     k.total = off;
     *out = k;
     return true;
@@ -591,7 +597,7 @@ int spkv_append(spkv_cache_t* c, const void* k, const void* v, const float* util
                        : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, nullptr, s);
     if (e != hipSuccess) return SPKV_E_HIP;
     commit_lengths(c, cu_seqlens);
-    if (n_max > 1) c->bound_is_loose = true;
+    if (n_max > SPKV_MAX_CHUNK_TOKENS) c->bound_is_loose = true;   // short chunks: see tighten_bound
     return SPKV_OK;
 }
 
@@ -742,6 +748,10 @@ namespace {
 int chunk_call(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
                const void* q, const int32_t* cu_seqlens, void* out, float* lse, float sm_scale,
                void* stream, bool append);
+int prefill_core(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
+                 const void* q, const int32_t* cu_seqlens, int n_max, void* out, float* lse,
+                 float sm_scale, uint16_t* stage, int32_t* prefix, int shp, float* part,
+                 size_t part_bytes, bool exact_fit, hipStream_t s);
 }
 
 int spkv_decode_chunk(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
@@ -777,7 +787,20 @@ int chunk_call(spkv_cache_t* c, const void* k, const void* v, const float* util_
         !aligned16(out) || (lse != nullptr && !aligned16(lse)))
         return SPKV_E_INVAL;
     if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
-    if (c->bound_is_loose) {
+    if (!c->bound_is_loose) tighten_bound(c, s);
+    const int cols = n_max * G;
+    const int groups = cols <= 16 ? 1 : (cols <= 32 ? 2 : 4);
+    if (append && groups > 1) {
+        // More than one group of 16 query columns: the prefill kernels (tiles shared by a
+        // workgroup through LDS) are the faster way to the same result; their staging rows and
+        // prefix counts live in the cache's arena, the split-K partials in its partial buffers.
+        return prefill_core(c, k, v, util_logits, q, cu_seqlens, n_max, out, lse, sm_scale,
+                            reinterpret_cast<uint16_t*>(c->arena + c->carve.chunk_stage),
+                            reinterpret_cast<int32_t*>(c->arena + c->carve.chunk_prefix),
+                            c->carve.chunk_shp, c->view.part_acc,
+                            (size_t)c->carve.max_items * G * c->cfg.head_dim * sizeof(float), false, s);
+    }
+    if (c->bound_is_loose) {       // the split-K partition below wants the exact lengths
         const int rc = refresh_bound(c, s, nullptr);
         if (rc != SPKV_OK) return rc;
     }
@@ -786,8 +809,6 @@ int chunk_call(spkv_cache_t* c, const void* k, const void* v, const float* util_
         if (rc != SPKV_OK) return rc;
     }
 
-    const int cols = n_max * G;
-    const int groups = cols <= 16 ? 1 : (cols <= 32 ? 2 : 4);
     const int gi = groups == 1 ? 0 : (groups == 2 ? 1 : 2);
     if (c->chunk_round_items[gi] == 0) {
         const int resident = spkv_chunk_resident_items(c->cfg.head_dim, groups);
@@ -820,7 +841,7 @@ int chunk_call(spkv_cache_t* c, const void* k, const void* v, const float* util_
                              : spkv_launch_append_bulk(c->view, kk, vv, util_logits, cu, n_max, nullptr, s);
     if (e != hipSuccess) return SPKV_E_HIP;
     commit_lengths(c, cu_seqlens);
-    if (n_max > 1) c->bound_is_loose = true;
+    if (n_max > SPKV_MAX_CHUNK_TOKENS) c->bound_is_loose = true;   // short chunks: see tighten_bound
     return SPKV_OK;
 }
 }  // namespace
@@ -856,6 +877,42 @@ size_t spkv_prefill_workspace_bytes(const spkv_cache_t* c, int32_t max_tokens_pe
     return prefix + align_up((size_t)c->carve.n_pairs * shp * half_bytes) + partial;
 }
 
+namespace {
+// Prefill attention + append of a call whose arguments have been checked: staging rows,
+// prefix counts and split-K partials in the buffers given (part_bytes: what `part` holds; the
+// number of key ranges per span is cut down to what fits).  exact_fit: fail instead.
+int prefill_core(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
+                 const void* q, const int32_t* cu_seqlens, int n_max, void* out, float* lse,
+                 float sm_scale, uint16_t* stage, int32_t* prefix, int shp, float* part,
+                 size_t part_bytes, bool exact_fit, hipStream_t s) {
+    const int B = c->cfg.batch;
+    const int rc = reserve_capacity(c, cu_seqlens, s);
+    if (rc != SPKV_OK) return rc;
+    SpkvCu cu;
+    std::memcpy(cu.v, cu_seqlens, (size_t)(B + 1) * 4);
+    // split-K over every span's tiles when the spans alone would not fill the chip; each
+    // range keeps at least a few tiles (lengths from the host's upper bound)
+    const int spans = spkv_prefill_spans(c->carve.n_pairs, c->carve.G, n_max);
+    int64_t tiles = 0;
+    for (int p = 0; p < c->carve.n_pairs; ++p) tiles = std::max<int64_t>(tiles, c->L_ub[p] / kHalfTokens);
+    tiles += (c->cfg.window + 64) / kHalfTokens;
+    const SpkvPrefillShape sh = spkv_prefill_shape(c->carve.G, n_max);
+    int ks = (int)std::max<int64_t>(1, std::min<int64_t>(prefill_split_cap(spans, sh.nw), tiles / 4));
+    // exactly what this call writes must fit
+    while (spkv_prefill_partial_bytes(spans, ks, sh, c->cfg.head_dim) > part_bytes) {
+        if (exact_fit) return SPKV_E_INVAL;
+        ks -= 1;                    // ks = 1 writes no partials
+    }
+    if (spkv_launch_prefill(c->view, static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
+                            util_logits, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
+                            lse, sm_scale, cu, n_max, stage, prefix, shp, ks, part, s) != hipSuccess)
+        return SPKV_E_HIP;
+    commit_lengths(c, cu_seqlens);
+    if (n_max > SPKV_MAX_CHUNK_TOKENS) c->bound_is_loose = true;   // short chunks: see tighten_bound
+    return SPKV_OK;
+}
+}  // namespace
+
 int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const float* util_logits,
                            const void* q, const int32_t* cu_seqlens, void* out, float* lse,
                            float sm_scale, void* workspace, size_t workspace_bytes, void* stream) {
@@ -890,37 +947,16 @@ int spkv_prefill_attention(spkv_cache_t* c, const void* k, const void* v, const 
         return SPKV_E_INVAL;
     if (cu_seqlens[B] <= 0) return SPKV_E_INVAL;
     if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt((float)c->cfg.head_dim);
-    const int rc = reserve_capacity(c, cu_seqlens, s);
-    if (rc != SPKV_OK) return rc;
-
-    SpkvCu cu;
-    std::memcpy(cu.v, cu_seqlens, (size_t)(B + 1) * 4);
     char* ws = static_cast<char*>(workspace);
     const size_t prefix_bytes = align_up((size_t)cu_seqlens[B] * c->cfg.n_kv_heads * 4);
     const int shp = (c->cfg.window + n_max + kHalfTokens - 1) / kHalfTokens;
     const size_t stage_bytes =
         align_up((size_t)c->carve.n_pairs * shp * ((size_t)2 * kHalfTokens * c->cfg.head_dim * 2));
-    // split-K over every span's tiles when the spans alone would not fill the chip; each
-    // range keeps at least a few tiles (lengths from the host's upper bound)
-    const int spans = spkv_prefill_spans(c->carve.n_pairs, c->carve.G, n_max);
-    int64_t tiles = 0;
-    for (int p = 0; p < c->carve.n_pairs; ++p) tiles = std::max<int64_t>(tiles, c->L_ub[p] / kHalfTokens);
-    tiles += (c->cfg.window + 64) / kHalfTokens;
-    const SpkvPrefillShape sh = spkv_prefill_shape(c->carve.G, n_max);
-    const int ks = (int)std::max<int64_t>(1, std::min<int64_t>(prefill_split_cap(spans, sh.nw), tiles / 4));
-    // exactly what this call writes must fit the workspace
-    if (prefix_bytes + stage_bytes + spkv_prefill_partial_bytes(spans, ks, sh, c->cfg.head_dim) >
-        workspace_bytes)
-        return SPKV_E_INVAL;
-    if (spkv_launch_prefill(c->view, static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
-                            util_logits, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
-                            lse, sm_scale, cu, n_max, reinterpret_cast<uint16_t*>(ws + prefix_bytes),
-                            reinterpret_cast<int32_t*>(ws), shp, ks,
-                            reinterpret_cast<float*>(ws + prefix_bytes + stage_bytes), s) != hipSuccess)
-        return SPKV_E_HIP;
-    commit_lengths(c, cu_seqlens);
-    c->bound_is_loose = true;
-    return SPKV_OK;
+    if (prefix_bytes + stage_bytes > workspace_bytes) return SPKV_E_INVAL;
+    return prefill_core(c, k, v, util_logits, q, cu_seqlens, n_max, out, lse, sm_scale,
+                        reinterpret_cast<uint16_t*>(ws + prefix_bytes), reinterpret_cast<int32_t*>(ws), shp,
+                        reinterpret_cast<float*>(ws + prefix_bytes + stage_bytes),
+                        workspace_bytes - prefix_bytes - stage_bytes, true, s);
 }
 
 namespace {

@@ -222,7 +222,12 @@ __device__ __forceinline__ int block_excl_scan(int x, int* s_w, int& total) {
 // within the call and this launch is the whole append: it also counts the gate-on tokens from
 // the logits (stage 1's job otherwise) and, once the kept rows have left the ring, writes
 // the new tokens into it (stage 3's job otherwise).
-template <int D, bool SMALL>
+//
+// COUNT: chunks of at most kCountSegs segments per sequence -- this launch also does stage 1's
+// job for its pair (the per-segment counts from the logits, every wave's popcounts parked in
+// LDS and summed after one barrier), so that the call is two launches instead of three.
+constexpr int kCountSegs = 16;
+template <int D, bool SMALL, bool COUNT>
 __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int32_t* prefix,
                                                       const uint16_t* __restrict__ k,
                                                       const uint16_t* __restrict__ vv,
@@ -243,12 +248,46 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
     __shared__ int s_w[4];
     __shared__ BulkInfo s_bi;
     __shared__ uint16_t s_list[256];
+    __shared__ int s_seg[COUNT ? kCountSegs : 1][4][2];
+
+    // the ring logits of the first 256 leaving positions travel with the segments' logits
+    const float rl_first = tid < nr ? rl[(r0 + tid) % v.w] : 0.f;
+    if (COUNT) {          // stage 1 for this pair: per segment and wave, kept-and-leaving / gate-on
+        const int hh = pair - b * v.Hkv, nseg_all = (n + kSegTokens - 1) / kSegTokens;
+        float fv[kCountSegs];           // every segment's logit of this thread, loads issued together
+#pragma unroll
+        for (int sg = 0; sg < kCountSegs; ++sg) {
+            const int j = sg * kSegTokens + tid;
+            fv[sg] = (sg < nseg_all && j < n) ? f[((size_t)cu.v[b] + j) * v.Hkv + hh] : 0.f;
+        }
+#pragma unroll
+        for (int sg = 0; sg < kCountSegs; ++sg) {
+            if (sg < nseg_all) {
+                const int j = sg * kSegTokens + tid;
+                const bool on = j < n && gate_passes(v, fv[sg], T_old + j);
+                const int c_on = __popcll(__ballot(on));
+                const int c_ev = __popcll(__ballot(on && j < n_ev));
+                if (lane == 0) {
+                    s_seg[sg][wave][0] = c_ev;
+                    s_seg[sg][wave][1] = c_on;
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < nseg_all) {
+            sc[tid] = s_seg[tid][0][0] + s_seg[tid][1][0] + s_seg[tid][2][0] + s_seg[tid][3][0];
+            v.seg_on[(size_t)pair * v.n_seg_cap + tid] =
+                s_seg[tid][0][1] + s_seg[tid][1][1] + s_seg[tid][2][1] + s_seg[tid][3][1];
+        }
+        __threadfence_block();
+        __syncthreads();
+    }
 
     // (a) how many ring pairs are kept
     int cnt = 0;
     for (int base = 0; base < nr; base += 256) {
         const int idx = base + tid;
-        const bool flag = idx < nr && gate_passes(v, rl[(r0 + idx) % v.w], r0 + idx);
+        const bool flag = idx < nr && gate_passes(v, base == 0 ? rl_first : rl[(r0 + idx) % v.w], r0 + idx);
         cnt += __popcll(__ballot(flag));
     }
     if (lane == 0) s_w[wave] = cnt;
@@ -317,7 +356,7 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
     int done = 0;
     for (int base = 0; base < nr; base += 256) {
         const int idx = base + tid;
-        const bool flag = idx < nr && gate_passes(v, rl[(r0 + idx) % v.w], r0 + idx);
+        const bool flag = idx < nr && gate_passes(v, base == 0 ? rl_first : rl[(r0 + idx) % v.w], r0 + idx);
         int tot;
         const int rank = block_excl_scan(flag ? 1 : 0, s_w, tot);
         if (flag) s_list[rank] = (uint16_t)tid;
@@ -327,25 +366,41 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
         }
         __syncthreads();
         const int c = lane & 15;
-        for (int rb = wave * 4; rb < tot; rb += 16) {
-            const int r = rb + (lane >> 4);
-            if (r < tot && c < D / 8) {
-                const int s = r0 + base + s_list[r];
-                const int slot = s % v.w;
-                const uint16_t* sp = ring_page(v, pair, slot >> 6);
-                const int sk = slot & 63;
-                const uint4 kk = *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, c * 8));
-                const uint16_t* vs = sp + spkv_v_off(D, sk, c * 8);
-                unsigned w[4];
+        // four rows per lane at a time: all their loads go out before the first store
+        for (int rb = wave * 4; rb < tot; rb += 64) {
+            uint4 kk[4], vl[4];
+            int sv[4], page[4];
+            float lg[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    w[e] = (unsigned)vs[(2 * e) * 8] | ((unsigned)vs[(2 * e + 1) * 8] << 16);
-                const int gi = L_old + done + r;
-                const int page = pt[gi >> 6];
-                store_row_chunk<D>(pool_page(v, page), gi & 63, c, kk, make_uint4(w[0], w[1], w[2], w[3]));
-                if (c == 0) {
-                    v.pos_pool[(size_t)page * kPageTokens + (gi & 63)] = s;
-                    v.logit_pool[(size_t)page * kPageTokens + (gi & 63)] = rl[slot];
+            for (int u = 0; u < 4; ++u) {
+                const int r = rb + u * 16 + (lane >> 4);
+                sv[u] = -1;
+                if (r < tot && c < D / 8) {
+                    const int s = r0 + base + s_list[r];
+                    const int slot = s % v.w;
+                    const uint16_t* sp = ring_page(v, pair, slot >> 6);
+                    const int sk = slot & 63;
+                    kk[u] = *reinterpret_cast<const uint4*>(sp + spkv_k_off(D, sk, c * 8));
+                    const uint16_t* vs = sp + spkv_v_off(D, sk, c * 8);
+                    unsigned w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        w[e] = (unsigned)vs[(2 * e) * 8] | ((unsigned)vs[(2 * e + 1) * 8] << 16);
+                    vl[u] = make_uint4(w[0], w[1], w[2], w[3]);
+                    page[u] = pt[(L_old + done + r) >> 6];
+                    lg[u] = rl[slot];
+                    sv[u] = s;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (sv[u] >= 0) {
+                    const int gi = L_old + done + rb + u * 16 + (lane >> 4);
+                    store_row_chunk<D>(pool_page(v, page[u]), gi & 63, c, kk[u], vl[u]);
+                    if (c == 0) {
+                        v.pos_pool[(size_t)page[u] * kPageTokens + (gi & 63)] = sv[u];
+                        v.logit_pool[(size_t)page[u] * kPageTokens + (gi & 63)] = lg[u];
+                    }
                 }
             }
         }
@@ -374,17 +429,78 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
 // stage 2); the kept tokens' indices are compacted into LDS and their rows moved in groups
 // of eight consecutive destination rows (whole 16-byte V units, transposed through LDS),
 // stragglers row by row; the last min(n, w) tokens of the call are written into the ring.
+// The last min(n, w) tokens of the call go into the ring: workgroup rb of the ring part takes
+// the ring slots [32 rb, 32 rb + 32), a wave eight consecutive slots -- one 16-byte V unit per
+// head-dim element.  Slot s receives the newest position p < T_new with p mod w = s if the call
+// brought it (p >= T_new - min(n, w)).  A unit whose eight slots are all written goes out as
+// whole 16-byte units, transposed through LDS; otherwise the written rows go one by one.
+template <int D>
+__device__ __forceinline__ void bulk_ring_rows(const SpkvView& v, const uint16_t* __restrict__ k,
+                                               const uint16_t* __restrict__ vv,
+                                               const float* __restrict__ f, int pair, int h, int row0,
+                                               int n, int T_old, int rb, uint16_t (*s_rows)[D],
+                                               int lane, int wave) {
+    const int s0 = rb * kHalfTokens + wave * 8;
+    if (s0 >= v.w) return;
+    const int T_new = T_old + n, m = min(n, v.w), c = lane & 15;
+    // token index (row of the call) landing in slot s, or -1
+    auto token_of = [&](int s) -> int {
+        if (s >= v.w) return -1;
+        const int p = T_new - 1 - ((T_new - 1 - s) % v.w + v.w) % v.w;
+        return p >= T_new - m ? p - T_old : -1;
+    };
+    bool all = true;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) all = all && token_of(s0 + r) >= 0;
+    uint16_t* dp = ring_page(v, pair, s0 >> 6);
+    const int dk0 = s0 & 63;
+    uint4 kk[2], vl[2];
+    int jj[2];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        jj[pass] = token_of(s0 + pass * 4 + (lane >> 4));
+        kk[pass] = make_uint4(0u, 0u, 0u, 0u);
+        vl[pass] = make_uint4(0u, 0u, 0u, 0u);
+        if (jj[pass] >= 0 && c < D / 8) {
+            const size_t src = ((size_t)(row0 + jj[pass]) * v.Hkv + h) * D + c * 8;
+            kk[pass] = *reinterpret_cast<const uint4*>(k + src);
+            vl[pass] = *reinterpret_cast<const uint4*>(vv + src);
+        }
+    }
+    if (lane < 8) {
+        const int j = token_of(s0 + lane);
+        if (j >= 0) v.ring_logit[(size_t)pair * v.w + s0 + lane] = f[((size_t)row0 + j) * v.Hkv + h];
+    }
+    if (all) {
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const int row = pass * 4 + (lane >> 4);
+            if (c < D / 8) {
+                *reinterpret_cast<uint4*>(dp + spkv_k_off(D, dk0 + row, c * 8)) = kk[pass];
+                *reinterpret_cast<uint4*>(&s_rows[row][c * 8]) = vl[pass];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        store_v_units<D>(dp, dk0, s_rows, lane);
+    } else {
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass)
+            if (jj[pass] >= 0 && c < D / 8)
+                store_row_chunk<D>(dp, dk0 + pass * 4 + (lane >> 4), c, kk[pass], vl[pass]);
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint16_t* __restrict__ k,
                                                          const uint16_t* __restrict__ vv,
                                                          const float* __restrict__ f, SpkvCu cu,
-                                                         int32_t* prefix) {
+                                                         int32_t* prefix, int segs_all) {
     const int pair = blockIdx.y, seg = blockIdx.x;
     const int b = pair / v.Hkv, h = pair - b * v.Hkv;
     const int row0 = cu.v[b];
     const int n = cu.v[b + 1] - row0;
     const int j0 = seg * kSegTokens;
-    if (j0 >= n) return;
+    if (n == 0 || (seg < segs_all && j0 >= n)) return;
     const BulkInfo bi = *reinterpret_cast<const BulkInfo*>(v.bulk_info + (size_t)pair * 8);
     if (bi.ok == 0) return;
     const int n_ev = max(0, n - v.w);
@@ -392,6 +508,10 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
     __shared__ int s_cnt[4];
     __shared__ uint16_t s_list[256];
     __shared__ __attribute__((aligned(16))) uint16_t s_v[4][8][D];
+    if (seg >= segs_all) {      // the ring part of the grid: independent of the segments
+        bulk_ring_rows<D>(v, k, vv, f, pair, h, row0, n, bi.T_old, seg - segs_all, s_v[wave], lane, wave);
+        return;
+    }
 
     const int j = j0 + tid;
     const bool on = j < n && gate_passes(v, f[((size_t)row0 + j) * v.Hkv + h], bi.T_old + j);
@@ -483,37 +603,29 @@ __global__ __launch_bounds__(256) void spkv_bulk_scatter(SpkvView v, const uint1
             }
         }
     }
-    const int ja = max(j0, n_ev), jb = min(n, j0 + kSegTokens);
-    for (int rb = ja + wave * 4; rb < jb; rb += 16) {
-        const int jj = rb + (lane >> 4);
-        if (jj < jb && c < D / 8) {
-            const int slot = (bi.T_old + jj) % v.w;
-            const size_t src = ((size_t)(row0 + jj) * v.Hkv + h) * D + c * 8;
-            const uint4 kk = *reinterpret_cast<const uint4*>(k + src);
-            const uint4 vl = *reinterpret_cast<const uint4*>(vv + src);
-            store_row_chunk<D>(ring_page(v, pair, slot >> 6), slot & 63, c, kk, vl);
-            if (c == 0)
-                v.ring_logit[(size_t)pair * v.w + slot] = f[((size_t)row0 + jj) * v.Hkv + h];
-        }
-    }
 }
 
 hipError_t spkv_launch_append_bulk(const SpkvView& v, const uint16_t* k, const uint16_t* vv,
                                    const float* f, const SpkvCu& cu, int n_max, int32_t* prefix,
                                    hipStream_t s) {
     if (n_max <= v.w && n_max <= kSegTokens) {      // short chunks: one launch
-        if (v.D == 128) spkv_bulk_ring<128, true><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
-        else spkv_bulk_ring<64, true><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
+        if (v.D == 128) spkv_bulk_ring<128, true, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
+        else spkv_bulk_ring<64, true, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
         return hipGetLastError();
     }
     const int segs_all = (n_max + kSegTokens - 1) / kSegTokens;
-    spkv_bulk_count<<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, f, cu);
+    const int ring_blocks = (v.w + kHalfTokens - 1) / kHalfTokens;
+    const dim3 grid3(segs_all + ring_blocks, v.n_pairs);
+    const bool fold = segs_all <= kCountSegs;       // the per-pair launch counts for itself
+    if (!fold) spkv_bulk_count<<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, f, cu);
     if (v.D == 128) {
-        spkv_bulk_ring<128, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
-        spkv_bulk_scatter<128><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
+        if (fold) spkv_bulk_ring<128, false, true><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
+        else spkv_bulk_ring<128, false, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
+        spkv_bulk_scatter<128><<<grid3, dim3(256), 0, s>>>(v, k, vv, f, cu, prefix, segs_all);
     } else {
-        spkv_bulk_ring<64, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
-        spkv_bulk_scatter<64><<<dim3(segs_all, v.n_pairs), dim3(256), 0, s>>>(v, k, vv, f, cu, prefix);
+        if (fold) spkv_bulk_ring<64, false, true><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
+        else spkv_bulk_ring<64, false, false><<<dim3(v.n_pairs), dim3(256), 0, s>>>(v, cu, prefix, k, vv, f);
+        spkv_bulk_scatter<64><<<grid3, dim3(256), 0, s>>>(v, k, vv, f, cu, prefix, segs_all);
     }
     return hipGetLastError();
 }
