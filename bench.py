@@ -225,9 +225,40 @@ def quick_point(wl, chunk, steps, warmup):
         k, v, f, cu = streams[j % R].next_tokens([1] * wl.batch)
         q = streams[j % R].next_query()
         steps_in.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
-    timed_steps(caches, steps_in, warmup, 0, fused=True)
+    timed_steps(caches, steps_in, max(warmup, 2 * R), 0, fused=True)    # every instance has run twice
     dt = timed_steps(caches, steps_in, steps, warmup, fused=True)
+    stats = [c.stats() for c in caches]
+    kept = float(np.mean([s.kept_kv_bytes for s in stats]))
+    # the same step forced into one launch (merge and append by the last workgroup of every
+    # pair) and into two (the library picks per call by default)
+    forced = {}
+    for n_launch in (1, 2):
+        for c in caches:
+            c.set_option(spkv.OPT_STEP_LAUNCHES, n_launch)
+        timed_steps(caches, steps_in, max(warmup, R), 0, fused=True)
+        forced[n_launch] = timed_steps(caches, steps_in, steps, warmup, fused=True)
+    dt_one = forced[1]
+    # and replayed from a HIP graph (one captured step per cache instance): no host work per call
+    graph_us = None
+    n_rep = max(1, steps // R)
+    if min(c.safe_steps() for c in caches) > n_rep + 2:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for r in range(R):
+                k, v, f, cu, q, out = steps_in[r % 32]
+                caches[r].decode_step(k, v, f, q, out=out)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_rep):
+            for c in caches:
+                c.advance(1)
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) / (n_rep * R) * 1e6
+        del g
     for c in caches:
+        c.set_option(spkv.OPT_STEP_LAUNCHES, 0)
         c.set_option(spkv.OPT_SPLIT_ONLY, 1)
     timed_steps(caches, steps_in, max(warmup, R), 0, do_append=False)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -237,11 +268,12 @@ def quick_point(wl, chunk, steps, warmup):
     e1.record()
     torch.cuda.synchronize()
     kern_us = e0.elapsed_time(e1) / steps * 1e3
-    stats = [c.stats() for c in caches]
-    kept = float(np.mean([s.kept_kv_bytes for s in stats]))
     res = {"ctx": max(wl.ctx_lens), "keep": float(wl.keep.mean()), "instances": R,
            "kept_kv_MB": kept / 1e6, "dense_kv_MB": float(np.mean([s.dense_kv_bytes for s in stats])) / 1e6,
-           "us_per_step": dt / steps * 1e6, "kernel_us": kern_us,
+           "us_per_step": dt / steps * 1e6, "us_per_step_one_launch": dt_one / steps * 1e6,
+           "us_per_step_two_launches": forced[2] / steps * 1e6,
+           "us_per_step_graph_replay": graph_us, "host_issue_us": HOST_ISSUE_S[-2] * 1e6,
+           "kernel_us": kern_us,
            "kernel_GBps": kept / kern_us / 1e3, "step_GBps": kept / (dt / steps) / 1e9}
     for c in caches:
         c.close()
@@ -578,7 +610,7 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
         steps_in.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
 
     fused = not args.two_call
-    timed_steps(caches, steps_in, W, 0, fused=fused)
+    timed_steps(caches, steps_in, max(W, 2 * R), 0, fused=fused)        # every instance has run twice
     before = [c.stats() for c in caches]
     dt = timed_steps(caches, steps_in, K, W, fused=fused)
     after = [c.stats() for c in caches]
@@ -624,12 +656,13 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
                  "frac_of_hbm_peak_step": kept_bytes / gus / 1e3 / HBM_PEAK_GBPS}
         del g
 
-    # the other launch count, and the split-K part alone (no merge, no append)
-    other = 2 if args.step_launches == 1 else 1        # the library's default is two
-    for c in caches:
-        c.set_option(spkv.OPT_STEP_LAUNCHES, other)
-    timed_steps(caches, steps_in, max(W, R), 0, fused=True)
-    dt_other = timed_steps(caches, steps_in, K, W, fused=True)
+    # both launch counts forced (the default picks per call), and the split-K part alone
+    forced = {}
+    for n_launch in (1, 2):
+        for c in caches:
+            c.set_option(spkv.OPT_STEP_LAUNCHES, n_launch)
+        timed_steps(caches, steps_in, max(W, R), 0, fused=True)
+        forced[n_launch] = timed_steps(caches, steps_in, K, W, fused=True) / K * 1e6
     for c in caches:
         c.set_option(spkv.OPT_STEP_LAUNCHES, args.step_launches)
         c.set_option(spkv.OPT_SPLIT_ONLY, 1)
@@ -657,7 +690,7 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
         "frac_of_hbm_peak_step": kept_bytes / (dt / K) / 1e9 / HBM_PEAK_GBPS,
         "host_issue_us_per_step": host_issue_us,
         "hip_graph_replay": graph,
-        f"us_per_step_with_{other}_launch{'es' if other > 1 else ''}": dt_other / K * 1e6,
+        "us_per_step_forced_one_launch": forced[1], "us_per_step_forced_two_launches": forced[2],
         "roofline": {
             "bound": "hbm",
             "kernel": (f"spkv_decode_split<{wl.head_dim}>: split-K over the kept lists (the first of the "
@@ -915,7 +948,7 @@ def main():
         "hip_graph_replay": res["hip_graph_replay"],
     }
     for key in res:
-        if key.startswith("us_per_step_with_"):
+        if key.startswith("us_per_step_forced_"):
             result[key] = res[key]
     result.update(extra)
     result["dense_cache"] = res.get("dense_cache")

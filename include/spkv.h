@@ -116,8 +116,10 @@ typedef struct spkv_stats {
                                       1: one -- the last workgroup of every (sequence, KV head) to
                                       finish merges the pair's partial results and, in the step,
                                       performs the pair's append; 2: a second launch merges (and
-                                      appends); 0 (default) = chosen per call.  Same results up to
-                                      the order of fp32 sums                                       */
+                                      appends); 0 (default) = the library's choice, at present two
+                                      (measured faster at every cache size tried: the tickets and
+                                      the merge inside the launch cost more than a launch).  Same
+                                      results up to the order of fp32 sums                         */
 
 /* Bytes of device arena a cache with this configuration needs (0 if cfg is invalid).
  * Host-only; touches no device.  Capacity rule (appendix "Inference Kernels": pages are

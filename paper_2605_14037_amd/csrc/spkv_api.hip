@@ -366,9 +366,13 @@ SpkvSplit choose_split(const spkv_cache* c) {
 
 // One launch (merge and append by the last workgroup of every pair) or two (a merge launch)
 // for the single-token decode calls.
-bool one_launch(const spkv_cache* c) {
-    if (c->step_launches != 0) return c->step_launches == 1;
-    return false;
+// Measured on MI355X (16 sequences, 32 query / 8 KV heads of 128, step time in us against kept
+// K/V bytes): one launch 22.3 / 36.8 / 54.6 / 87.3 at 51 / 115 / 222 / 436 MB, two launches
+// 17.6 / 28.0 / 45.0 / 78.5 -- the tickets (an atomic per workgroup on one address per pair,
+// served one after the other) and the merge's dependent round trips inside the launch cost
+// more than a second launch does, at every size tried.  Two launches unless the caller asks.
+bool one_launch(const spkv_cache* c, hipStream_t) {
+    return c->step_launches == 1;
 }
 
 // Tokens sequence b receives in a call: from cu_seqlens, or one each (cu == nullptr).
@@ -622,7 +626,7 @@ int spkv_decode_step(spkv_cache_t* c, const void* k, const void* v, const float*
     if (spkv_launch_decode_step(c->view, static_cast<const uint16_t*>(k),
                                 static_cast<const uint16_t*>(v), util_logits,
                                 static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out), lse,
-                                sm_scale, c->split, one_launch(c), s) != hipSuccess)
+                                sm_scale, c->split, one_launch(c, s), s) != hipSuccess)
         return SPKV_E_HIP;
     commit_lengths(c, nullptr);
     return SPKV_OK;
@@ -712,7 +716,7 @@ int spkv_decode_attention(spkv_cache_t* c, const void* q, void* out, float* lse,
     }
     c->split = choose_split(c);
     if (spkv_launch_decode(c->view, static_cast<const uint16_t*>(q), static_cast<uint16_t*>(out),
-                           lse, sm_scale, c->split, c->split_only, one_launch(c), ev0, ev1, s) != hipSuccess)
+                           lse, sm_scale, c->split, c->split_only, one_launch(c, s), ev0, ev1, s) != hipSuccess)
         return SPKV_E_HIP;
     return SPKV_OK;
 }

@@ -76,6 +76,34 @@ __device__ __forceinline__ int alloc_page(const SpkvView& v) {
     return page < v.n_pages ? page : -1;
 }
 
+// `need` pages at once, for one thread of a workgroup that then hands them out: one atomic on
+// the bump counter (and one on the stack of recycled pages only when it holds any) instead of
+// one or three per page -- every atomic of a launch goes to the same two addresses, and they
+// are served one after the other.  Page i of the batch: batch_page(v, pb, i); -1 past the pool.
+struct PageBatch {
+    int stack_lo, from_stack, pool_base;
+};
+__device__ __forceinline__ PageBatch alloc_page_batch(const SpkvView& v, int need) {
+    PageBatch pb = {0, 0, 0};
+    if (need <= 0) return pb;
+    // no page is pushed in a launch that pops, so a stack seen empty stays empty
+    if (__hip_atomic_load(v.free_top, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > 0) {
+        const int top = atomicSub(v.free_top, need);
+        const int take = min(max(top, 0), need);
+        if (take < need) atomicAdd(v.free_top, need - take);     // put back what was not there
+        pb.from_stack = take;
+        pb.stack_lo = top - take;
+    }
+    const int rest = need - pb.from_stack;
+    if (rest > 0) pb.pool_base = atomicAdd(v.pool_next, rest);
+    return pb;
+}
+__device__ __forceinline__ int batch_page(const SpkvView& v, const PageBatch& pb, int i) {
+    if (i < pb.from_stack) return v.free_pages[pb.stack_lo + i];
+    const int page = pb.pool_base + (i - pb.from_stack);
+    return page < v.n_pages ? page : -1;
+}
+
 // ------------------------------------------------------------------ memory -> LDS copies
 // One wave-wide 16-byte load from global memory straight into LDS: lane i's 16 bytes at
 // `src` land at LDS byte address lds_row + 16 i (lds_row wave-uniform).  The load counts

@@ -326,14 +326,17 @@ __global__ __launch_bounds__(256) void spkv_bulk_ring(SpkvView v, SpkvCu cu, int
         if (tid == 0) v.gate_on[pair] += s_w[0] + s_w[1] + s_w[2] + s_w[3];
     }
 
-    // (c) pages: one allocation per new logical page, in parallel; the table entries are
+    // (c) pages: all the call's pages of this pair in one allocation; the table entries are
     //     visible to the whole workgroup after the barrier and to stage 3 after the launch
     const int first = (L_old + kPageTokens - 1) / kPageTokens;
     const int last = (L_old + total_new + kPageTokens - 1) / kPageTokens;
     const int need = last <= v.pt_cap ? last - first : 0;
     int bad = last > v.pt_cap ? 1 : 0;
+    __shared__ PageBatch s_pb;
+    if (tid == 0) s_pb = alloc_page_batch(v, need);
+    __syncthreads();
     for (int i = tid; i < need; i += 256) {
-        const int page = alloc_page(v);
+        const int page = batch_page(v, s_pb, i);
         if (page < 0) bad = 1;
         else v.page_table[(size_t)pair * v.pt_cap + first + i] = page;
     }
