@@ -63,8 +63,11 @@ def build_cache(wl: Workload, instance: int, chunk: int, tau=None, oracle=None, 
         dt = time.perf_counter() - t0
         st = cache.stats()
         moved = st.dense_kv_bytes + (st.kept_tokens + st.window_tokens) * 4 * wl.head_dim
+        if PREFILL_TIMING and PREFILL_TIMING["ms"] <= dt * 1e3:
+            return cache, stream          # keep the faster of the instances timed
         PREFILL_TIMING.update({
-            "what": "spkv_append over the whole prompt, inputs resident, chunked",
+            "what": "spkv_append over the whole prompt, inputs resident, chunked (a single pass "
+                    "per cache instance: the faster of the last two instances built)",
             "chunk_tokens_per_sequence": chunk, "calls": len(chunks), "ms": dt * 1e3,
             "tokens_per_s": st.total_tokens / dt,
             "GBps_read_new_kv_plus_written_kept": moved / dt / 1e9})
@@ -227,6 +230,7 @@ def quick_point(wl, chunk, steps, warmup):
         steps_in.append((k, v, f, caches[0].make_cu(cu), q, torch.empty_like(q)))
     timed_steps(caches, steps_in, max(warmup, 2 * R), 0, fused=True)    # every instance has run twice
     dt = timed_steps(caches, steps_in, steps, warmup, fused=True)
+    host_us = HOST_ISSUE_S[-1] * 1e6
     stats = [c.stats() for c in caches]
     kept = float(np.mean([s.kept_kv_bytes for s in stats]))
     # the same step forced into one launch (merge and append by the last workgroup of every
@@ -238,6 +242,19 @@ def quick_point(wl, chunk, steps, warmup):
         timed_steps(caches, steps_in, max(warmup, R), 0, fused=True)
         forced[n_launch] = timed_steps(caches, steps_in, steps, warmup, fused=True)
     dt_one = forced[1]
+    for c in caches:
+        c.set_option(spkv.OPT_STEP_LAUNCHES, 0)
+        c.set_option(spkv.OPT_SPLIT_ONLY, 1)
+    timed_steps(caches, steps_in, max(warmup, R), 0, do_append=False)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        caches[i % R].decode_attention(steps_in[i % 32][4], out=steps_in[i % 32][5])
+    e1.record()
+    torch.cuda.synchronize()
+    kern_us = e0.elapsed_time(e1) / steps * 1e3
+    for c in caches:
+        c.set_option(spkv.OPT_SPLIT_ONLY, 0)
     # and replayed from a HIP graph (one captured step per cache instance): no host work per call
     graph_us = None
     n_rep = max(1, steps // R)
@@ -257,22 +274,11 @@ def quick_point(wl, chunk, steps, warmup):
         torch.cuda.synchronize()
         graph_us = (time.perf_counter() - t0) / (n_rep * R) * 1e6
         del g
-    for c in caches:
-        c.set_option(spkv.OPT_STEP_LAUNCHES, 0)
-        c.set_option(spkv.OPT_SPLIT_ONLY, 1)
-    timed_steps(caches, steps_in, max(warmup, R), 0, do_append=False)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(steps):
-        caches[i % R].decode_attention(steps_in[i % 32][4], out=steps_in[i % 32][5])
-    e1.record()
-    torch.cuda.synchronize()
-    kern_us = e0.elapsed_time(e1) / steps * 1e3
     res = {"ctx": max(wl.ctx_lens), "keep": float(wl.keep.mean()), "instances": R,
            "kept_kv_MB": kept / 1e6, "dense_kv_MB": float(np.mean([s.dense_kv_bytes for s in stats])) / 1e6,
            "us_per_step": dt / steps * 1e6, "us_per_step_one_launch": dt_one / steps * 1e6,
            "us_per_step_two_launches": forced[2] / steps * 1e6,
-           "us_per_step_graph_replay": graph_us, "host_issue_us": HOST_ISSUE_S[-2] * 1e6,
+           "us_per_step_graph_replay": graph_us, "host_issue_us": host_us,
            "kernel_us": kern_us,
            "kernel_GBps": kept / kern_us / 1e3, "step_GBps": kept / (dt / steps) / 1e9}
     for c in caches:
@@ -567,8 +573,8 @@ def read_ceiling_leg(nbytes, n_workgroups, launches):
     for i in range(5):
         launch(i)
     ms = events_per_launch(launch, launches)
-    del src, sink
-    torch.cuda.empty_cache()
+    del src, sink          # (no empty_cache here: handing gigabytes back to the driver right before
+    #                         the next timed leg was measured to slow that leg by 3-4 %)
     gbps = n_runs * run_bytes / (ms * 1e-3) / 1e9
     return {"what": "spkv_debug_read: non-temporal 16 KB chunk reads in scattered 32 KB runs, one-wave "
                     "workgroups, no arithmetic; same bytes and workgroup count as the decode launch",
@@ -592,7 +598,7 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
     caches, streams = [], []
     for r in range(R):
         c, s = build_cache(wl, r, args.chunk, oracle=oracle if r == 0 else None,
-                           oracle_seqs=cpu_seqs, time_prefill=(keep_caches and r == R - 1))
+                           oracle_seqs=cpu_seqs, time_prefill=(keep_caches and r >= max(1, R - 2)))
         if args.item_target:
             c.set_option(spkv.OPT_ITEM_TARGET, args.item_target)
         if args.merge_waves:
@@ -628,33 +634,8 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
         caches[i % R].decode_step(k, v, f, q, out=out)
     for i in range(R):
         step(i)
-    step_events_ms = events_per_launch(step, K)
-
-    # The same step captured once per cache instance into one HIP graph and replayed: what a
-    # serving loop sees when the host's per-call work (argument checks, the capacity bound, the
-    # launch itself) is off the path.
-    graph = None
-    n_rep = max(1, K // R)
-    if min(c.safe_steps() for c in caches) > n_rep + 2:
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            for r in range(R):
-                k, v, f, cu, q, out = steps_in[r]
-                caches[r].decode_step(k, v, f, q, out=out)
-        g.replay()                                   # the step the captured calls accounted for
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(n_rep):
-            for c in caches:
-                c.advance(1)
-            g.replay()
-        torch.cuda.synchronize()
-        gus = (time.perf_counter() - t0) / (n_rep * R) * 1e6
-        graph = {"what": f"one graph of {R} captured steps (one per cache instance), replayed {n_rep} "
-                         "times; host bookkeeping by spkv_cache_advance",
-                 "us_per_step": gus, "GBps": kept_bytes / gus / 1e3,
-                 "frac_of_hbm_peak_step": kept_bytes / gus / 1e3 / HBM_PEAK_GBPS}
-        del g
+    Kk = max(K, 100)       # the legs below time single kernels: enough launches for a stable mean
+    step_events_ms = events_per_launch(step, Kk)
 
     # both launch counts forced (the default picks per call), and the split-K part alone
     forced = {}
@@ -669,7 +650,7 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
     timed_steps(caches, steps_in, max(W, R), 0, do_append=False)
     split_ms = events_per_launch(
         lambda i: caches[i % R].decode_attention(steps_in[i % len(steps_in)][4],
-                                                 out=steps_in[i % len(steps_in)][5]), K)
+                                                 out=steps_in[i % len(steps_in)][5]), Kk)
     for c in caches:
         c.set_option(spkv.OPT_SPLIT_ONLY, 0)
 
@@ -689,7 +670,7 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
         "GBps_step": kept_bytes / (dt / K) / 1e9,
         "frac_of_hbm_peak_step": kept_bytes / (dt / K) / 1e9 / HBM_PEAK_GBPS,
         "host_issue_us_per_step": host_issue_us,
-        "hip_graph_replay": graph,
+        "hip_graph_replay": None,
         "us_per_step_forced_one_launch": forced[1], "us_per_step_forced_two_launches": forced[2],
         "roofline": {
             "bound": "hbm",
@@ -701,15 +682,43 @@ def decode_leg(wl, args, K, W, with_dense=True, cpu_seqs=0, keep_caches=False, c
             "frac": achieved / HBM_PEAK_GBPS,
             "traffic": read_traffic_summary(wl.name),
             "algorithmic_bytes_per_launch": kept_bytes,
-            "kernel_avg_us": kern_avg_ms * 1e3, "launches_timed": K,
+            "kernel_avg_us": kern_avg_ms * 1e3, "launches_timed": Kk,
             "timing": "HIP events around K back-to-back launches of this kernel alone on the launch stream",
             "us_per_step_by_events": step_events_ms * 1e3,
         },
     }
-    ceiling = read_ceiling_leg(kept_bytes, work_items, K)
+    ceiling = read_ceiling_leg(kept_bytes, work_items, Kk)
     ceiling["kernel_over_read_ceiling"] = ceiling["us_per_launch"] / (kern_avg_ms * 1e3)
     ceiling["step_over_read_ceiling"] = ceiling["us_per_launch"] / (dt / K * 1e6)
     res["read_ceiling"] = ceiling
+
+    # The same step captured once per cache instance into one HIP graph and replayed: what a
+    # serving loop sees when the host's per-call work (argument checks, the capacity bound, the
+    # launch itself) is off the path.
+    graph = None
+    n_rep = max(1, Kk // R)
+    if min(c.safe_steps() for c in caches) > n_rep + 2:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for r in range(R):
+                k, v, f, cu, q, out = steps_in[r]
+                caches[r].decode_step(k, v, f, q, out=out)
+        g.replay()                                   # the step the captured calls accounted for
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_rep):
+            for c in caches:
+                c.advance(1)
+            g.replay()
+        torch.cuda.synchronize()
+        gus = (time.perf_counter() - t0) / (n_rep * R) * 1e6
+        graph = {"what": f"one graph of {R} captured steps (one per cache instance), replayed {n_rep} "
+                         "times; host bookkeeping by spkv_cache_advance",
+                 "us_per_step": gus, "GBps": kept_bytes / gus / 1e3,
+                 "frac_of_hbm_peak_step": kept_bytes / gus / 1e3 / HBM_PEAK_GBPS}
+        del g      # (last in the leg: giving a graph's memory pool back slows what is timed next)
+
+    res["hip_graph_replay"] = graph
 
     state = (caches, streams, steps_in, R, dt)
     if not keep_caches:
@@ -839,7 +848,7 @@ def main():
     if extras:
         caches, streams, steps_in, R, dt = state
         # the step as two calls (spkv_append + spkv_decode_attention), and its halves
-        timed_steps(caches, steps_in, max(W, R), 0, fused=not fused)
+        timed_steps(caches, steps_in, max(W, R, 200), 0, fused=not fused)
         dt_other = timed_steps(caches, steps_in, K, W, fused=not fused)
         dt_dec = timed_steps(caches, steps_in, K, W + K, do_append=False)
         dt_app = timed_steps(caches, steps_in, K, W + 2 * K, do_decode=False)
