@@ -109,6 +109,46 @@ def test_incremental_equals_bulk():
         c.close()
 
 
+@pytest.mark.parametrize("w", [128, 40, 300])
+def test_bulk_append_chunk_sizes_around_the_launch_paths(w):
+    """The bulk append has three launch shapes: one launch (chunks within the window and one
+    256-token segment), two (up to 16 segments per sequence: the per-pair stage counts for
+    itself), three (longer chunks: a count launch first).  Chunks on both sides of every limit,
+    ragged across the batch, windows that are no multiple of 8 or 32 (ring rows written as
+    whole 16-byte units only where all eight slots are covered), prefill attention on top."""
+    B = 3
+    wl = small_workload("paths", B, 8, 2, 128, [0, 0, 0], [[0.35, 0.1]], window=w, seed=900 + w)
+    stream = TokenStream(wl, device="cuda")
+    plan = [[5, 0, 200], [256, 257, 40], [4096, 1000, 4097], [9000, 0, 3], [1, 4100, 5000],
+            [w, w + 1, w - 1], [300, 300, 300]]
+    total = [sum(c[b] for c in plan) for b in range(B)]
+    cache = spkv.SPKVCache(B, 8, 2, 128, max_context=max(total) + 600,
+                           max_total_kept_tokens=sum(total) * 2 + 2000, window=w)
+    oracle = H.make_oracle(wl)
+    for counts in plan:
+        k, v, f, cu = stream.next_tokens(counts)
+        H.feed(cache, oracle, k, v, f, cu)
+        H.check_state(cache, oracle, wl, label=f"after {counts}")
+    counts = [500, 17, 300]                        # a prefill-attention call on the same state
+    k, v, f, cu = stream.next_tokens(counts)
+    q = stream.next_query(rows=sum(counts))
+    out, lse = cache.prefill_attention(k, v, f, q, cu, want_lse=True)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    rows = sorted(set(range(0, sum(counts), 37)) | {sum(counts) - 1, 499, 500, 516, 517})
+    ref_out, ref_lse = oracle.decode_chunk(to_numpy_f32(q), counts, rows=set(rows))
+    H.check_output(out[rows], ref_out[rows], "prefill rows")
+    H.check_lse(lse[rows], ref_lse[rows], "prefill rows")
+    H.check_state(cache, oracle, wl, label="after prefill attention")
+    k, v, f, cu = stream.next_tokens([1] * B)
+    qd = stream.next_query()
+    o2, l2 = cache.decode_step(k, v, f, qd, want_lse=True)
+    oracle.append(to_numpy_f32(k), to_numpy_f32(v), to_numpy_f32(f), cu)
+    ro, rl = oracle.decode(to_numpy_f32(qd))
+    H.check_output(o2, ro, "decode after the chunks")
+    H.check_lse(l2, rl, "decode after the chunks")
+    cache.close()
+
+
 def test_sequences_that_skip_a_step():
     """cu_seqlens may give a sequence no token in a step."""
     wl = small_workload("skip", 3, 4, 2, 64, [140, 150, 160], 0.5, seed=3)
