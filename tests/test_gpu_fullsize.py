@@ -39,13 +39,16 @@ def _rows_of(cu, seqs):
     return torch.cat(idx), sub_cu
 
 
-def _run_full(name, chunk=1024, layer=0, logits_fn=None, predictor=None):
+def _run_full(name, chunk=1024, layer=0, logits_fn=None, predictor=None, fused=False, launches=0):
+    """fused: the step bench.py times (spkv_decode_step) instead of spkv_append +
+    spkv_decode_attention; launches: SPKV_OPT_STEP_LAUNCHES."""
     wl = workload(name)
     seqs = _sample_sequences(wl)
     print(f"{name}: sampled sequences {seqs}", flush=True)
     stream = TokenStream(wl, device="cuda", layer=layer)
     pool = int(wl.expected_kept_tokens() * 1.08) + wl.batch * wl.n_kv_heads * (chunk + 256)
     cache = H.make_cache(wl, pool_tokens=pool, extra_context=64)
+    cache.set_option(spkv.OPT_STEP_LAUNCHES, launches)
     gates = SPKVOracle(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, window=wl.window,
                        tau=wl.tau, track_kv=False)
     sub = SPKVOracle(len(seqs), wl.n_q_heads, wl.n_kv_heads, wl.head_dim, window=wl.window,
@@ -71,8 +74,12 @@ def _run_full(name, chunk=1024, layer=0, logits_fn=None, predictor=None):
     else:
         if logits_fn is not None:
             f = logits_fn(stream)
-        feed(k, v, f, cu)
-        out, lse = cache.decode_attention(q, want_lse=True)
+        if fused:
+            out, lse = cache.decode_step(k, v, f, q, want_lse=True)
+            feed(k, v, f, cu, to_cache=False)
+        else:
+            feed(k, v, f, cu)
+            out, lse = cache.decode_attention(q, want_lse=True)
 
     # every (sequence, head): lengths, positions, statistics -- bit exact
     st = H.check_state(cache, gates, wl, label=name)
@@ -103,6 +110,14 @@ def test_cfg3_full():
 
 def test_cfg4_full():
     st = _run_full("cfg4")
+    assert st.kept_tokens > 0
+
+
+@pytest.mark.parametrize("name,launches", [("cfg2", 0), ("cfg3", 0), ("cfg4", 0), ("cfg3", 1), ("cfg2", 1)])
+def test_fused_step_full(name, launches):
+    """The fused step -- the entry point bench.py times -- at full size, as the library launches
+    it by default and forced into one launch."""
+    st = _run_full(name, fused=True, launches=launches)
     assert st.kept_tokens > 0
 
 
